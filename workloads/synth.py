@@ -1,0 +1,97 @@
+"""Seeded generators for the synthetic tensors of a layer window.
+
+Every tensor is drawn from its own Philox stream keyed by
+(BASE_SEED, config_id, layer, tensor_id), so any tensor can be regenerated on
+its own (one layer at a time for the large windows) and the result does not
+depend on the order of generation.
+
+A Q4_K tensor is produced as raw bytes: every 6-bit and 4-bit field of a
+super-block is uniform over its whole range, so filling bytes 4..143 of each
+144-byte super-block with uniform random bytes gives exactly that
+distribution whatever the bit packing is; only the two fp16 values at bytes
+0..3 (d, dmin uniform in [1e-3, 4e-3]) are written as numbers.  No packing or
+decoding logic lives here.
+"""
+import numpy as np
+
+BASE_SEED = 0x5052494D41  # fixed
+QK = 256                  # weights per super-block
+BLOCK_BYTES = 144
+
+TENSOR_IDS = {
+    "wq": 0, "wk": 1, "wv": 2, "wo": 3, "wgate": 4, "wup": 5, "wdown": 6,
+    "g_attn": 7, "g_ffn": 8, "k_cache": 9, "v_cache": 10, "x_in": 11,
+    "g_final": 12, "w_lm": 13, "q": 14,
+}
+
+
+def _rng(config_id, layer, tensor):
+    tid = TENSOR_IDS[tensor] if isinstance(tensor, str) else int(tensor)
+    ss = np.random.SeedSequence([BASE_SEED, int(config_id), int(layer), tid])
+    return np.random.Generator(np.random.Philox(ss))
+
+
+def q4k_tensor(config_id, layer, tensor, n_rows, n_cols):
+    """uint8 [n_rows, n_cols/256, 144]: row-major rows of 144-byte super-blocks."""
+    assert n_cols % QK == 0
+    nb = n_rows * (n_cols // QK)
+    rng = _rng(config_id, layer, tensor)
+    n64 = nb * BLOCK_BYTES // 8
+    raw = rng.bit_generator.random_raw(n64).view(np.uint8).reshape(nb, BLOCK_BYTES)
+    u = rng.random((nb, 2), dtype=np.float32)
+    dd = (np.float32(1e-3) + np.float32(3e-3) * u).astype(np.float16)
+    raw[:, 0:4] = dd.view(np.uint8).reshape(nb, 4)
+    return raw.reshape(n_rows, n_cols // QK, BLOCK_BYTES)
+
+
+def normal_f32(config_id, layer, tensor, shape):
+    """fp32 N(0,1)."""
+    return _rng(config_id, layer, tensor).standard_normal(shape, dtype=np.float64).astype(np.float32)
+
+
+def gain_f32(config_id, layer, tensor, n):
+    """RMSNorm gain 1 + N(0, 0.1), fp32."""
+    z = _rng(config_id, layer, tensor).standard_normal(n, dtype=np.float64)
+    return (1.0 + 0.1 * z).astype(np.float32)
+
+
+def kv_cache_f16(config_id, layer, tensor, n_kv_heads, kv_cap, head_dim, n_past):
+    """fp16 [n_kv_heads, kv_cap, head_dim]; rows < n_past ~ N(0,1), the rest zero."""
+    out = np.zeros((n_kv_heads, kv_cap, head_dim), dtype=np.float16)
+    if n_past > 0:
+        z = _rng(config_id, layer, tensor).standard_normal((n_kv_heads, n_past, head_dim), dtype=np.float32)
+        out[:, :n_past, :] = z.astype(np.float16)
+    return out
+
+
+def layer_tensors(cfg, layer, kv_cap=None):
+    """All tensors of one decoder layer of window `cfg` as a dict of numpy arrays."""
+    d = cfg.dims
+    cid = cfg.config_id
+    cap = kv_cap if kv_cap is not None else cfg.n_past + cfg.T
+    return {
+        "wq": q4k_tensor(cid, layer, "wq", d.qd, d.e),
+        "wk": q4k_tensor(cid, layer, "wk", d.kvd, d.e),
+        "wv": q4k_tensor(cid, layer, "wv", d.kvd, d.e),
+        "wo": q4k_tensor(cid, layer, "wo", d.e, d.qd),
+        "wgate": q4k_tensor(cid, layer, "wgate", d.ffn, d.e),
+        "wup": q4k_tensor(cid, layer, "wup", d.ffn, d.e),
+        "wdown": q4k_tensor(cid, layer, "wdown", d.e, d.ffn),
+        "g_attn": gain_f32(cid, layer, "g_attn", d.e),
+        "g_ffn": gain_f32(cid, layer, "g_ffn", d.e),
+        "k_cache": kv_cache_f16(cid, layer, "k_cache", d.n_kv_heads, cap, d.head_dim, cfg.n_past),
+        "v_cache": kv_cache_f16(cid, layer, "v_cache", d.n_kv_heads, cap, d.head_dim, cfg.n_past),
+    }
+
+
+def window_input(cfg):
+    """x_in fp32 [T, e] ~ N(0,1)."""
+    return normal_f32(cfg.config_id, 0, "x_in", (cfg.T, cfg.dims.e))
+
+
+def output_layer_tensors(cfg):
+    d = cfg.dims
+    return {
+        "g_final": gain_f32(cfg.config_id, 0, "g_final", d.e),
+        "w_lm": q4k_tensor(cfg.config_id, 0, "w_lm", cfg.vocab, d.e),
+    }
