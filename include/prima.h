@@ -1,0 +1,150 @@
+/*
+ * prima.h - C ABI of the MI355X (gfx950) decode hot path of a prima.cpp layer window.
+ *
+ * A device in the pipelined ring receives e FP32 values per token from its predecessor,
+ * advances its window of consecutive decoder layers and forwards e FP32 values
+ * (arXiv 2504.08791, Sec. 3.1 and App. A.3 "network communication latency").  Weights stay in
+ * Q4_K and are never expanded in memory (App. A.9); the KV cache is fp16 and lives with its
+ * layers, one cache per request (App. A.3 "memory access latency", App. A.10); several draft
+ * tokens are verified in one batch with unchanged outputs (App. A.12).
+ *
+ * Conventions for every entry point
+ *  - All pointers are DEVICE pointers unless a parameter says "host".  The caller owns every
+ *    buffer; the library allocates and frees nothing on these paths, never synchronises the
+ *    device and never changes the current device.
+ *  - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
+ *    stream).  Results are ready when that stream has drained.
+ *  - Arguments are validated on the host before anything is launched; a bad argument returns
+ *    a status code and launches nothing.  A fault inside a kernel surfaces at the caller's
+ *    next synchronisation; PRIMA_E_DEVICE reports launch-time failures only.
+ *  - Q4_K tensors: row-major by output row; a row is n_cols/256 consecutive 144-byte
+ *    super-blocks; base pointer 16-byte aligned.  Super-block layout (version 1):
+ *      bytes 0-1 d (binary16 LE), 2-3 dmin, 4-15 a 96-bit little-endian bit stream of sixteen
+ *      6-bit fields (field i at bits [6i,6i+6): 0-7 sub-scales sc_s, 8-15 sub-mins m_s),
+ *      16-143 quants (weight t in byte 16 + t/2, low nibble when t is even);
+ *      w[t] = d*sc_s*q[t] - dmin*m_s with s = t/32.
+ *  - T (tokens advanced jointly) must satisfy 1 <= T <= PRIMA_MAX_TOK.
+ */
+#ifndef PRIMA_H
+#define PRIMA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PRIMA_ABI_VERSION 1
+#define PRIMA_MAX_TOK 16
+
+typedef enum {
+    PRIMA_OK = 0,
+    PRIMA_E_NULL = 1,      /* a required pointer is NULL */
+    PRIMA_E_SHAPE = 2,     /* a dimension is not supported (e.g. n_cols % 256 != 0) */
+    PRIMA_E_ALIGN = 3,     /* a pointer or leading dimension is misaligned */
+    PRIMA_E_RANGE = 4,     /* T, n_past or kv_cap out of range */
+    PRIMA_E_WORKSPACE = 5, /* workspace too small */
+    PRIMA_E_DEVICE = 6     /* a launch failed */
+} prima_status;
+
+/* Model dimensions (plain data, passed by pointer to host memory). */
+typedef struct {
+    int32_t e;          /* hidden size, multiple of 256 */
+    int32_t n_q_heads;  /* multiple of n_kv_heads */
+    int32_t n_kv_heads;
+    int32_t head_dim;   /* 64 or 128 */
+    int32_t ffn;        /* multiple of 256 */
+    float rope_theta;
+    float rms_eps;
+    int32_t rope_mode;  /* 0: rotate pairs (i, i + D/2); 1: pairs (2i, 2i + 1) */
+} prima_dims;
+
+/* One decoder layer: device pointers.  Read-only except rows [n_past, n_past+T) of the caches. */
+typedef struct {
+    const void *wq, *wk, *wv, *wo, *wgate, *wup, *wdown; /* Q4_K */
+    const float *g_attn, *g_ffn;                         /* fp32 [e] RMSNorm gains */
+    void *k_cache, *v_cache;                             /* fp16 [n_kv_heads][kv_cap][head_dim] */
+} prima_layer;
+
+/*
+ * Dequantised mat-vec (the seven projections of a layer; App. A.3 counts their bytes as b):
+ *     y[t*ldy + r] = sum_c W[r][c] * x[t*ldx + c],  r < n_rows, t < T.
+ * W: Q4_K, n_rows x n_cols, n_cols % 256 == 0.  x: fp32, ldx >= n_cols.  y: fp32, ldy >= n_rows.
+ * workspace: scratch of at least prima_gemv_workspace_bytes(n_rows, n_cols, T) bytes, 256-byte aligned.
+ */
+prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols,
+                            const float *x, int64_t ldx, int32_t T,
+                            float *y, int64_t ldy,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t prima_gemv_workspace_bytes(int64_t n_rows, int64_t n_cols, int32_t T);
+
+/*
+ * Test hook: out[r*n_cols + c] = fp32 value of weight (r, c).  The value is the fp32 number
+ * nearest to the exact d*sc*q - dmin*m (both products are exact in fp32); results are
+ * bit-exact by contract.
+ */
+prima_status prima_q4k_dequant(const void *W, int64_t n_rows, int64_t n_cols, float *out,
+                               void *hip_stream);
+
+/*
+ * GQA decode attention over an fp16 KV cache (App. A.3: 2(h_k e_k + h_v e_v) n_kv bytes read per
+ * layer per step):
+ *     o[t][h][:] = sum_{p <= n_past+t} softmax_p( q[t][h] . K[h/G][p] / sqrt(D) ) V[h/G][p],
+ *     G = n_q_heads / n_kv_heads.
+ * q, o: fp32 [T][n_q_heads][head_dim].  k_cache, v_cache: fp16 [n_kv_heads][kv_cap][head_dim];
+ * rows 0 .. n_past+T-1 must be valid (the T new rows already appended).  n_past >= 0,
+ * n_past + T <= kv_cap.  workspace >= prima_attn_workspace_bytes(d, kv_cap, T).
+ */
+prima_status prima_attn_decode(const prima_dims *d, const float *q,
+                               const void *k_cache, const void *v_cache,
+                               int32_t kv_cap, int32_t n_past, int32_t T, float *o,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t prima_attn_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
+
+/*
+ * Advance a window of L consecutive decoder layers by T tokens (Sec. 3.1, Def. 1: the layer
+ * window; App. A.12: T > 1 is speculative verification with a causal mask among the T tokens).
+ * Per layer: RMSNorm, Q/K/V projections, RoPE at positions n_past+t, append fp16 K/V rows
+ * n_past..n_past+T-1 (2(h_k e_k + h_v e_v) bytes per token), attention over rows 0..n_past+t,
+ * output projection + residual, RMSNorm, SwiGLU feed-forward + residual.
+ * layers: HOST array of L descriptors.  x_in, x_out: fp32 [T][e]; x_out may alias x_in.
+ * The library keeps no position state: the caller advances n_past (by fewer than T after a
+ * rejection; stale rows are overwritten by the next step, never read).
+ * workspace >= prima_workspace_bytes(d, kv_cap, T), 256-byte aligned.
+ */
+prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *layers, int32_t L,
+                                       int32_t kv_cap, int32_t n_past, int32_t T,
+                                       const float *x_in, float *x_out,
+                                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Test hook: one layer as above, additionally copying intermediates to caller buffers (each may be
+ * NULL): tap_q [T][n_q_heads*head_dim] rotated queries, tap_o same shape attention output,
+ * tap_h [T][e] hidden state after the attention residual, tap_a [T][ffn] SwiGLU output.
+ */
+prima_status prima_layer_decode_taps(const prima_dims *d, const prima_layer *layer,
+                                     int32_t kv_cap, int32_t n_past, int32_t T,
+                                     const float *x_in, float *x_out,
+                                     float *tap_q, float *tap_o, float *tap_h, float *tap_a,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Output layer (App. A.3: b_o bytes): logits[t][v] = W_lm . rmsnorm(x[t]; g_final).
+ * w_lm: Q4_K [vocab][e].  x: fp32 [T][e].  logits: fp32 [T][vocab].
+ * workspace >= prima_workspace_bytes(d, 0, T).
+ */
+prima_status prima_lm_head(const prima_dims *d, const float *g_final, const void *w_lm, int64_t vocab,
+                           const float *x, int32_t T, float *logits,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of scratch the window / output-layer calls need for up to T tokens and kv_cap cache rows. */
+size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
+
+const char *prima_status_str(prima_status s);
+int prima_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRIMA_H */

@@ -1,0 +1,163 @@
+"""MI355X decode hot path of a prima.cpp layer window: thin Python binding.
+
+Every function marshals torch CUDA tensors (device memory and streams only) into the C ABI of
+include/prima.h; all computation happens in the HIP library.  There is no CPU path.
+"""
+import ctypes as C
+
+import torch
+
+from . import _ffi
+from ._ffi import Dims, Layer, PrimaError, MAX_TOK  # noqa: F401
+
+_WEIGHTS = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _need(t, dtype, name):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous CUDA tensor of {dtype}")
+    return t
+
+
+def make_dims(d):
+    """ModelDims-like object (fields e, n_q_heads, n_kv_heads, head_dim, ffn, rope_theta, rms_eps, rope_mode)."""
+    if isinstance(d, Dims):
+        return d
+    return Dims(d.e, d.n_q_heads, d.n_kv_heads, d.head_dim, d.ffn, d.rope_theta, d.rms_eps, d.rope_mode)
+
+
+def abi_version():
+    return _ffi.lib().prima_abi_version()
+
+
+def q4k_dequant(W):
+    """W uint8 [rows, cols/256, 144] -> float32 [rows, cols]."""
+    _need(W, torch.uint8, "W")
+    rows, nb = W.shape[0], W.shape[1]
+    out = torch.empty((rows, nb * 256), dtype=torch.float32, device=W.device)
+    _ffi.check(_ffi.lib().prima_q4k_dequant(_ptr(W), rows, nb * 256, _ptr(out), _stream()), "prima_q4k_dequant")
+    return out
+
+
+def gemv_workspace_bytes(rows, cols, T):
+    return _ffi.lib().prima_gemv_workspace_bytes(rows, cols, T)
+
+
+def q4k_gemv(W, x, y=None, workspace=None):
+    """y[t, r] = sum_c W[r, c] x[t, c];  W uint8 [rows, cols/256, 144], x float32 [T, cols]."""
+    _need(W, torch.uint8, "W")
+    _need(x, torch.float32, "x")
+    rows, cols = W.shape[0], W.shape[1] * 256
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, rows), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(256, gemv_workspace_bytes(rows, cols, T)), dtype=torch.uint8, device=x.device)
+    _ffi.check(_ffi.lib().prima_q4k_gemv(_ptr(W), rows, cols, _ptr(x), x.stride(0), T, _ptr(y), y.stride(0),
+                                         _ptr(workspace), workspace.numel(), _stream()), "prima_q4k_gemv")
+    return y
+
+
+def attn_workspace_bytes(dims, kv_cap, T):
+    d = make_dims(dims)
+    return _ffi.lib().prima_attn_workspace_bytes(C.byref(d), kv_cap, T)
+
+
+def attn_decode(dims, q, k_cache, v_cache, n_past, o=None, workspace=None):
+    """q float32 [T, Hq, D]; caches float16 [Hkv, cap, D] with rows < n_past + T valid -> o like q."""
+    d = make_dims(dims)
+    _need(q, torch.float32, "q")
+    _need(k_cache, torch.float16, "k_cache")
+    _need(v_cache, torch.float16, "v_cache")
+    T, cap = q.shape[0], k_cache.shape[1]
+    if o is None:
+        o = torch.empty_like(q)
+    if workspace is None:
+        workspace = torch.empty(max(256, attn_workspace_bytes(d, cap, T)), dtype=torch.uint8, device=q.device)
+    _ffi.check(_ffi.lib().prima_attn_decode(C.byref(d), _ptr(q), _ptr(k_cache), _ptr(v_cache), cap, n_past, T, _ptr(o),
+                                            _ptr(workspace), workspace.numel(), _stream()), "prima_attn_decode")
+    return o
+
+
+def workspace_bytes(dims, kv_cap, T):
+    d = make_dims(dims)
+    return _ffi.lib().prima_workspace_bytes(C.byref(d), kv_cap, T)
+
+
+class Window:
+    """A window of decoder layers resident in HBM: keeps the tensors alive, the descriptor array
+    and a workspace, so that a step is a single C call."""
+
+    def __init__(self, dims, layers, kv_cap, T_max=MAX_TOK):
+        self.dims = make_dims(dims)
+        self.layers = layers
+        self.kv_cap = kv_cap
+        self.T_max = T_max
+        arr = (Layer * len(layers))()
+        for i, t in enumerate(layers):
+            for k in _WEIGHTS:
+                _need(t[k], torch.uint8, k)
+            _need(t["g_attn"], torch.float32, "g_attn")
+            _need(t["g_ffn"], torch.float32, "g_ffn")
+            _need(t["k_cache"], torch.float16, "k_cache")
+            _need(t["v_cache"], torch.float16, "v_cache")
+            if t["k_cache"].shape[1] != kv_cap or t["v_cache"].shape[1] != kv_cap:
+                raise ValueError("kv_cap does not match the cache tensors")
+            for k in _WEIGHTS + ("g_attn", "g_ffn", "k_cache", "v_cache"):
+                setattr(arr[i], k, t[k].data_ptr())
+        self._arr = arr
+        dev = layers[0]["wq"].device
+        self.workspace = torch.empty(max(256, workspace_bytes(self.dims, kv_cap, T_max)), dtype=torch.uint8, device=dev)
+
+    def decode(self, x_in, n_past, x_out=None):
+        """Advance all layers by T = x_in.shape[0] tokens; returns x_out float32 [T, e]."""
+        _need(x_in, torch.float32, "x_in")
+        T = x_in.shape[0]
+        if x_out is None:
+            x_out = torch.empty_like(x_in)
+        _ffi.check(_ffi.lib().prima_layer_window_decode(C.byref(self.dims), self._arr, len(self.layers), self.kv_cap,
+                                                        n_past, T, _ptr(x_in), _ptr(x_out), _ptr(self.workspace),
+                                                        self.workspace.numel(), _stream()), "prima_layer_window_decode")
+        return x_out
+
+    def decode_layer_taps(self, layer_index, x_in, n_past):
+        """Test hook: one layer with intermediates (q, o, h, a)."""
+        d = self.dims
+        T = x_in.shape[0]
+        dev = x_in.device
+        qd = d.n_q_heads * d.head_dim
+        taps = {"q": torch.empty((T, qd), dtype=torch.float32, device=dev),
+                "o": torch.empty((T, qd), dtype=torch.float32, device=dev),
+                "h": torch.empty((T, d.e), dtype=torch.float32, device=dev),
+                "a": torch.empty((T, d.ffn), dtype=torch.float32, device=dev)}
+        x_out = torch.empty_like(x_in)
+        one = C.cast(C.byref(self._arr, layer_index * C.sizeof(Layer)), C.POINTER(Layer))
+        _ffi.check(_ffi.lib().prima_layer_decode_taps(C.byref(d), one, self.kv_cap, n_past, T, _ptr(x_in), _ptr(x_out),
+                                                      _ptr(taps["q"]), _ptr(taps["o"]), _ptr(taps["h"]), _ptr(taps["a"]),
+                                                      _ptr(self.workspace), self.workspace.numel(), _stream()),
+                   "prima_layer_decode_taps")
+        return x_out, taps
+
+
+def lm_head(dims, g_final, w_lm, x, logits=None, workspace=None):
+    """logits[t, v] = W_lm . rmsnorm(x[t]; g_final)."""
+    d = make_dims(dims)
+    _need(g_final, torch.float32, "g_final")
+    _need(w_lm, torch.uint8, "w_lm")
+    _need(x, torch.float32, "x")
+    T, vocab = x.shape[0], w_lm.shape[0]
+    if logits is None:
+        logits = torch.empty((T, vocab), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(256, workspace_bytes(d, 0, T)), dtype=torch.uint8, device=x.device)
+    _ffi.check(_ffi.lib().prima_lm_head(C.byref(d), _ptr(g_final), _ptr(w_lm), vocab, _ptr(x), T, _ptr(logits),
+                                        _ptr(workspace), workspace.numel(), _stream()), "prima_lm_head")
+    return logits

@@ -1,0 +1,69 @@
+"""ctypes view of the C ABI declared in include/prima.h.  No arithmetic lives here."""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libprima_hip.so")
+
+MAX_TOK = 16
+STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIGN", 4: "PRIMA_E_RANGE",
+          5: "PRIMA_E_WORKSPACE", 6: "PRIMA_E_DEVICE"}
+
+EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", "prima_attn_decode",
+           "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_decode_taps",
+           "prima_lm_head", "prima_workspace_bytes", "prima_status_str", "prima_abi_version"]
+
+
+class Dims(C.Structure):
+    _fields_ = [("e", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("rope_mode", C.c_int32)]
+
+
+class Layer(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown",
+                                          "g_attn", "g_ffn", "k_cache", "v_cache")]
+
+
+class PrimaError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {STATUS.get(code, code)}")
+
+
+_lib = None
+
+
+def lib():
+    """The HIP library.  There is no fallback: a missing build is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        dp, lp = C.POINTER(Dims), C.POINTER(Layer)
+        L.prima_q4k_gemv.argtypes = [vp, i64, i64, vp, i64, i32, vp, i64, vp, sz, vp]
+        L.prima_gemv_workspace_bytes.argtypes = [i64, i64, i32]
+        L.prima_gemv_workspace_bytes.restype = sz
+        L.prima_q4k_dequant.argtypes = [vp, i64, i64, vp, vp]
+        L.prima_attn_decode.argtypes = [dp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.prima_attn_workspace_bytes.argtypes = [dp, i32, i32]
+        L.prima_attn_workspace_bytes.restype = sz
+        L.prima_layer_window_decode.argtypes = [dp, lp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.prima_layer_decode_taps.argtypes = [dp, lp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.prima_lm_head.argtypes = [dp, vp, vp, i64, vp, i32, vp, vp, sz, vp]
+        L.prima_workspace_bytes.argtypes = [dp, i32, i32]
+        L.prima_workspace_bytes.restype = sz
+        L.prima_status_str.argtypes = [C.c_int]
+        L.prima_status_str.restype = C.c_char_p
+        L.prima_abi_version.restype = C.c_int
+        for name in ("prima_q4k_gemv", "prima_q4k_dequant", "prima_attn_decode", "prima_layer_window_decode",
+                     "prima_layer_decode_taps", "prima_lm_head"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def check(code, where):
+    if code != 0:
+        raise PrimaError(code, where)

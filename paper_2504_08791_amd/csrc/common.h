@@ -1,0 +1,85 @@
+// Shared declarations of the HIP decode path (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "prima.h"
+
+namespace prima {
+
+constexpr int QK = 256;          // weights per Q4_K super-block
+constexpr int BLOCK_BYTES = 144; // bytes per super-block
+constexpr int WAVE = 64;
+
+inline prima_status last_launch_status()
+{
+    return hipGetLastError() == hipSuccess ? PRIMA_OK : PRIMA_E_DEVICE;
+}
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- Q4_K header decoding (layout version 1, see prima.h) ----
+// hdr = the first 16 bytes of a super-block as four little-endian dwords:
+// hdr.x = d | dmin << 16, hdr.y/z/w = bits 0-31 / 32-63 / 64-95 of the field stream.
+__device__ __forceinline__ float hdr_d(const uint4 &hdr)
+{
+    return __half2float(__ushort_as_half(static_cast<unsigned short>(hdr.x & 0xffffu)));
+}
+__device__ __forceinline__ float hdr_dmin(const uint4 &hdr)
+{
+    return __half2float(__ushort_as_half(static_cast<unsigned short>(hdr.x >> 16)));
+}
+// 6-bit field i (0..15): i < 8 sub-scale sc_i, otherwise sub-min m_{i-8}
+__device__ __forceinline__ uint32_t hdr_field(const uint4 &hdr, int i)
+{
+    const int bit = 6 * i, w = bit >> 5, sh = bit & 31;
+    const uint32_t lo = w == 0 ? hdr.y : (w == 1 ? hdr.z : hdr.w);
+    const uint32_t hi = w == 0 ? hdr.z : (w == 1 ? hdr.w : 0u);
+    const uint64_t two = static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32);
+    return static_cast<uint32_t>(two >> sh) & 63u;
+}
+
+// ---- launchers implemented in the .hip files (host side, all asynchronous on `st`) ----
+
+struct GemvSeg {
+    const uint8_t *W;   // Q4_K matrix of this segment
+    float *y;           // fp32 output [T][ldy]
+    const float *resid; // optional fp32 [T][ldr] added to the product (may alias y)
+    int64_t n_rows, ldy, ldr;
+};
+
+// up to three matrices with the same n_cols multiplied with the same x in one launch
+struct GemvArgs {
+    GemvSeg seg[3];
+    int nseg;
+    int64_t n_cols;
+    const float *x; // fp32 [T][ldx]
+    int64_t ldx;
+    int T;
+};
+
+prima_status launch_dequant(const uint8_t *W, int64_t n_rows, int64_t n_cols, float *out, hipStream_t st);
+prima_status launch_gemv(const GemvArgs &a, void *ws, size_t ws_bytes, hipStream_t st);
+size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T);
+// single-token path on the matrix cores (q4k_gemv_mfma.hip)
+prima_status launch_gemv_t1(const GemvArgs &a, void *ws, size_t ws_bytes, hipStream_t st);
+size_t gemv_t1_ws_bytes(int64_t n_rows_total, int64_t n_cols);
+extern bool g_force_rowwave; // debugging aid: route every mat-vec through the row-per-wave kernel
+
+prima_status launch_rmsnorm(const float *x, const float *g, float *out, int T, int n, float eps, hipStream_t st);
+prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
+// rotate q in place; rotate k and store k, v as fp16 rows n_past.. of the caches
+prima_status launch_rope_kv_append(const prima_dims &d, float *q, const float *k, const float *v,
+                                   const float *rope_tab, __half *k_cache, __half *v_cache,
+                                   int kv_cap, int n_past, int T, hipStream_t st);
+prima_status launch_swiglu(const float *g, const float *u, float *a, int64_t n, hipStream_t st);
+
+int attn_num_splits(const prima_dims &d, int n_total, int T);
+size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);
+prima_status launch_attn(const prima_dims &d, const float *q, const __half *K, const __half *V,
+                         int kv_cap, int n_past, int T, float *o, void *ws, hipStream_t st);
+
+} // namespace prima

@@ -1,0 +1,102 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/prima.h declares,
+and rejects bad arguments before launching anything (no GPU needed: validation is host code)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2504_08791_amd import _ffi
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "prima.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(prima_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert "prima_q4k_gemv" in names and "prima_attn_decode" in names and "prima_layer_window_decode" in names
+    L = _ffi.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(_ffi.EXPORTS) == names
+
+
+def test_abi_version_and_status_strings():
+    L = _ffi.lib()
+    assert L.prima_abi_version() == 1
+    for code in range(7):
+        assert L.prima_status_str(code)
+
+
+def _dims(**kw):
+    d = dict(e=512, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=768, rope_theta=1e4, rms_eps=1e-5, rope_mode=0)
+    d.update(kw)
+    return _ffi.Dims(**d)
+
+
+FAKE = 0x7f0000001000  # never dereferenced: every call below must fail validation first
+
+
+def test_gemv_argument_errors():
+    L = _ffi.lib()
+    f = lambda W=FAKE, rows=8, cols=512, x=FAKE, ldx=512, T=1, y=FAKE, ldy=8, ws=FAKE, wsb=1 << 20: \
+        L.prima_q4k_gemv(W, rows, cols, x, ldx, T, y, ldy, ws, wsb, None)
+    assert f(W=None) == 1 and f(x=None) == 1 and f(y=None) == 1 and f(ws=None) == 1
+    assert f(cols=300) == 2 and f(ldx=256) == 2 and f(ldy=4) == 2
+    assert f(T=0) == 4 and f(T=17) == 4
+    assert f(W=FAKE + 8) == 3 and f(x=FAKE + 4) == 3 and f(ldx=514) == 3 and f(ws=FAKE + 16) == 3
+    assert f(wsb=0) == 5
+
+
+def test_dequant_argument_errors():
+    L = _ffi.lib()
+    assert L.prima_q4k_dequant(None, 1, 256, FAKE, None) == 1
+    assert L.prima_q4k_dequant(FAKE, 1, 100, FAKE, None) == 2
+    assert L.prima_q4k_dequant(FAKE + 2, 1, 256, FAKE, None) == 3
+
+
+def test_attn_argument_errors():
+    L = _ffi.lib()
+    d = _dims()
+    f = lambda dd=d, q=FAKE, k=FAKE, v=FAKE, cap=64, n_past=10, T=1, o=FAKE, ws=FAKE, wsb=1 << 30: \
+        L.prima_attn_decode(C.byref(dd), q, k, v, cap, n_past, T, o, ws, wsb, None)
+    assert f(q=None) == 1 and f(k=None) == 1 and f(o=None) == 1
+    assert f(dd=_dims(head_dim=96)) == 2 and f(dd=_dims(n_q_heads=5)) == 2
+    assert f(n_past=64) == 4 and f(T=0) == 4 and f(n_past=-1) == 4 and f(T=17) == 4
+    assert f(k=FAKE + 2) == 3
+    assert f(wsb=16) == 5
+
+
+def test_window_argument_errors():
+    L = _ffi.lib()
+    d = _dims()
+    lay = (_ffi.Layer * 1)()
+    for name, _ in _ffi.Layer._fields_:
+        setattr(lay[0], name, FAKE)
+    need = L.prima_workspace_bytes(C.byref(d), 64, 4)
+    assert need > 0
+    f = lambda dd=d, layers=lay, Ln=1, cap=64, n_past=10, T=4, xi=FAKE, xo=FAKE, ws=FAKE, wsb=need: \
+        L.prima_layer_window_decode(C.byref(dd), layers, Ln, cap, n_past, T, xi, xo, ws, wsb, None)
+    assert f(xi=None) == 1 and f(ws=None) == 1 and f(layers=None) == 1
+    assert f(dd=_dims(e=500)) == 2
+    assert f(n_past=61) == 4 and f(Ln=0) == 4 and f(T=17) == 4
+    assert f(xi=FAKE + 4) == 3
+    assert f(wsb=need - 1) == 5
+    bad = (_ffi.Layer * 1)()
+    for name, _ in _ffi.Layer._fields_:
+        setattr(bad[0], name, FAKE)
+    bad[0].wo = None
+    assert f(layers=bad) == 1
+    assert L.prima_workspace_bytes(C.byref(_dims(e=100)), 64, 1) == 0
+
+
+def test_missing_library_is_an_error(monkeypatch, tmp_path):
+    monkeypatch.setattr(_ffi, "_lib", None)
+    monkeypatch.setattr(_ffi, "LIB_PATH", str(tmp_path / "absent.so"))
+    with pytest.raises(ImportError):
+        _ffi.lib()

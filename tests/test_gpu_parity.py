@@ -1,0 +1,250 @@
+"""GPU parity: every step of the HIP path against the CPU oracle on the same seeded inputs.
+
+Bars: dequantisation bit-exact; hidden states / mat-vec outputs max relative error <= 2e-3;
+attention outputs <= 1e-3 (error metric: tests/metrics.rel_err).
+"""
+import copy
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from metrics import rel_err
+from q4k_pack import half_bits, pack_block
+from workloads import synth
+from workloads.configs import TINY, ModelDims
+
+pytestmark = pytest.mark.gpu
+
+HID_TOL = 2e-3
+ATT_TOL = 1e-3
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _rand_q4k(rng, rows, nb):
+    W = rng.integers(0, 256, size=(rows, nb, 144), dtype=np.uint8)
+    dd = (1e-3 + 3e-3 * rng.random((rows * nb, 2), dtype=np.float32)).astype(np.float16)
+    W.reshape(-1, 144)[:, 0:4] = dd.view(np.uint8).reshape(-1, 4)
+    return W
+
+
+def test_dequant_bit_exact_random(gpu_lib):
+    rng = np.random.default_rng(0)
+    for rows, nb in [(1, 1), (37, 3), (300, 5)]:
+        W = _rand_q4k(rng, rows, nb)
+        got = gpu_lib.q4k_dequant(_dev(W)).cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), oracle.dequant(W).view(np.uint32)), (rows, nb)
+
+
+def test_dequant_bit_exact_any_half_scale(gpu_lib):
+    """Arbitrary finite fp16 d / dmin, including subnormals and zero, and extreme fields."""
+    rng = np.random.default_rng(1)
+    W = rng.integers(0, 256, size=(64, 4, 144), dtype=np.uint8)
+    flat = W.reshape(-1, 144)
+    hb = rng.integers(0, 1 << 16, size=(flat.shape[0], 2)).astype(np.uint16)
+    hb[(hb >> 10) & 31 == 31] &= 0x83ff           # no inf / nan
+    flat[:, 0:4] = hb.view(np.uint8).reshape(-1, 4)
+    flat[0] = pack_block(0, 0, [0] * 8, [0] * 8, [0] * 256)
+    flat[1] = pack_block(half_bits(1.0), half_bits(0.5), [63] * 8, [63] * 8, [15] * 256)
+    flat[2] = pack_block(1, 1, [63] * 8, [1] * 8, [15] * 256)      # smallest subnormal scales
+    got = gpu_lib.q4k_dequant(_dev(W)).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), oracle.dequant(W).view(np.uint32))
+
+
+def test_dequant_empty(gpu_lib):
+    W = torch.empty((0, 2, 144), dtype=torch.uint8, device="cuda")
+    assert gpu_lib.q4k_dequant(W).shape == (0, 512)
+
+
+@pytest.mark.parametrize("rows,nb,T", [(1, 1, 1), (7, 2, 1), (100, 5, 1), (257, 16, 1), (1030, 4, 1),
+                                       (64, 3, 2), (100, 5, 4), (33, 6, 5), (96, 2, 8), (50, 3, 16), (130, 9, 3)])
+def test_gemv_vs_oracle(gpu_lib, rows, nb, T):
+    rng = np.random.default_rng(rows * 1000 + nb * 10 + T)
+    W = _rand_q4k(rng, rows, nb)
+    x = rng.standard_normal((T, nb * 256)).astype(np.float32)
+    ref = oracle.gemv(W, x.astype(np.float64))
+    got = gpu_lib.q4k_gemv(_dev(W), _dev(x)).cpu().numpy()
+    assert rel_err(got, ref) < 1e-4, rel_err(got, ref)
+
+
+def test_gemv_wide_dynamic_range(gpu_lib):
+    """Activations like the SwiGLU output of the synthetic models: huge, common-mode, with outliers."""
+    rng = np.random.default_rng(5)
+    W = _rand_q4k(rng, 200, 8)
+    for x in (1e7 * (1 + 0.01 * rng.standard_normal((2, 2048))),
+              rng.standard_normal((2, 2048)) * np.exp(4 * rng.standard_normal((2, 2048))),
+              np.zeros((1, 2048))):
+        x = x.astype(np.float32)
+        ref = oracle.gemv(W, x.astype(np.float64))
+        got = gpu_lib.q4k_gemv(_dev(W), _dev(x)).cpu().numpy()
+        if np.abs(ref).max() == 0:
+            assert np.all(got == 0)
+        else:
+            assert rel_err(got, ref) < HID_TOL, rel_err(got, ref)
+
+
+def test_gemv_integer_exact(gpu_lib):
+    """Power-of-two scales and small integer x: every partial sum is exact in fp32, so any
+    summation order must reproduce the oracle exactly."""
+    rng = np.random.default_rng(3)
+    rows, nb = 48, 4
+    W = rng.integers(0, 256, size=(rows, nb, 144), dtype=np.uint8)
+    for r in range(rows):
+        for b in range(nb):
+            W[r, b, 0:2] = np.frombuffer(int(half_bits(2.0 ** -(r % 3))).to_bytes(2, "little"), dtype=np.uint8)
+            W[r, b, 2:4] = np.frombuffer(int(half_bits(2.0 ** -(b % 2 + 1))).to_bytes(2, "little"), dtype=np.uint8)
+    x = rng.integers(-4, 5, size=(3, nb * 256)).astype(np.float32)
+    ref = oracle.gemv(W, x.astype(np.float64))
+    got = gpu_lib.q4k_gemv(_dev(W), _dev(x)).cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, ref)
+
+
+def test_gemv_strided_io(gpu_lib):
+    rng = np.random.default_rng(9)
+    W = _rand_q4k(rng, 70, 2)
+    xbig = rng.standard_normal((3, 640)).astype(np.float32)
+    x = _dev(xbig)[:, :512]
+    ybig = torch.full((3, 100), -7.0, device="cuda")
+    import ctypes as C
+    from paper_2504_08791_amd import _ffi
+    ws = torch.empty(max(256, gpu_lib.gemv_workspace_bytes(70, 512, 3)), dtype=torch.uint8, device="cuda")
+    Wd = _dev(W)
+    rc = _ffi.lib().prima_q4k_gemv(Wd.data_ptr(), 70, 512, x.data_ptr(), 640, 3, ybig.data_ptr(), 100,
+                                   ws.data_ptr(), ws.numel(), C.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == 0
+    ref = oracle.gemv(W, xbig[:, :512].astype(np.float64))
+    out = ybig.cpu().numpy()
+    assert rel_err(out[:, :70], ref) < 1e-4 and np.all(out[:, 70:] == -7.0)
+
+
+ATT_CASES = [  # Hq, Hkv, D, n_past, T
+    (8, 2, 64, 37, 1), (10, 2, 128, 130, 4), (8, 1, 128, 0, 3), (4, 4, 64, 5, 2), (32, 8, 128, 512, 1),
+    (40, 8, 128, 700, 5), (64, 8, 128, 1000, 1), (64, 8, 128, 300, 8), (8, 1, 128, 0, 1), (16, 2, 128, 2047, 16),
+]
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,n_past,T", ATT_CASES)
+def test_attention_vs_oracle(gpu_lib, Hq, Hkv, D, n_past, T):
+    rng = np.random.default_rng(Hq * 7 + n_past + T)
+    dims = ModelDims(Hq * D, Hq, Hkv, D, 256, 1e4)
+    cap = n_past + T + 2
+    K = rng.standard_normal((Hkv, cap, D)).astype(np.float16)
+    V = rng.standard_normal((Hkv, cap, D)).astype(np.float16)
+    K[:, n_past + T:] = np.float16(300.0)     # rows beyond the step must never be read
+    V[:, n_past + T:] = np.float16(-300.0)
+    q = rng.standard_normal((T, Hq, D)).astype(np.float32)
+    ref = oracle.attn_decode(dims, q.astype(np.float64), K, V, n_past, T)
+    got = gpu_lib.attn_decode(dims, _dev(q), _dev(K), _dev(V), n_past).cpu().numpy()
+    assert rel_err(got.reshape(T, -1), ref.reshape(T, -1)) < ATT_TOL
+
+
+def test_attention_peaked_logits(gpu_lib):
+    """Near one-hot softmax (logit spread of tens to thousands), as inside the synthetic layers."""
+    rng = np.random.default_rng(77)
+    Hq, Hkv, D, n_past, T = 16, 2, 128, 257, 3
+    dims = ModelDims(Hq * D, Hq, Hkv, D, 256, 1e4)
+    K = (rng.standard_normal((Hkv, n_past + T, D)) * 8).astype(np.float16)
+    V = rng.standard_normal((Hkv, n_past + T, D)).astype(np.float16)
+    q = (rng.standard_normal((T, Hq, D)) * 20).astype(np.float32)
+    ref, gap = oracle.attn_decode(dims, q.astype(np.float64), K, V, n_past, T, return_gap=True)
+    got = gpu_lib.attn_decode(dims, _dev(q), _dev(K), _dev(V), n_past).cpu().numpy()
+    print("min top-2 logit gap", gap)
+    assert rel_err(got.reshape(T, -1), ref.reshape(T, -1)) < ATT_TOL
+
+
+def _window(gpu_lib, cfg, cap, layers_host):
+    dev_layers = [{k: _dev(v) for k, v in t.items()} for t in layers_host]
+    return gpu_lib.Window(cfg.dims, dev_layers, cap, T_max=16), dev_layers
+
+
+@pytest.mark.parametrize("name", ["t0", "t1", "t2"])
+def test_layer_taps_vs_oracle(gpu_lib, name):
+    cfg = TINY[name]
+    cap = cfg.n_past + cfg.T
+    host = [synth.layer_tensors(cfg, 0, kv_cap=cap)]
+    win, dev_layers = _window(gpu_lib, cfg, cap, host)
+    x = synth.window_input(cfg)
+    ref, taps = oracle.layer(cfg.dims, host[0], x.astype(np.float64), cfg.n_past, taps=True)
+    y, gt = win.decode_layer_taps(0, _dev(x), cfg.n_past)
+    print(name, "oracle min top-2 gap", taps["min_gap"])
+    assert rel_err(gt["q"].cpu().numpy(), taps["q"]) < HID_TOL
+    assert rel_err(gt["o"].cpu().numpy(), taps["o"]) < ATT_TOL
+    assert rel_err(gt["h"].cpu().numpy(), taps["h"]) < HID_TOL
+    assert rel_err(gt["a"].cpu().numpy(), taps["a"]) < HID_TOL
+    assert rel_err(y.cpu().numpy(), ref) < HID_TOL
+    # appended fp16 rows: identical up to one fp16 ulp (rounding of values that differ in the last fp32 bits)
+    for key in ("k_cache", "v_cache"):
+        g = dev_layers[0][key].cpu().numpy().astype(np.float64)
+        assert rel_err(g[:, cfg.n_past:cap].reshape(1, -1), host[0][key][:, cfg.n_past:cap].astype(np.float64).reshape(1, -1)) < 1e-3
+        assert np.array_equal(g[:, :cfg.n_past], host[0][key][:, :cfg.n_past].astype(np.float64))
+
+
+@pytest.mark.parametrize("name", ["t0", "t1", "t2"])
+def test_window_vs_oracle(gpu_lib, name):
+    cfg = TINY[name]
+    cap = cfg.n_past + cfg.T + 3
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    win, _ = _window(gpu_lib, cfg, cap, host)
+    x = synth.window_input(cfg)
+    ref = oracle.window(cfg.dims, host, x.astype(np.float64), cfg.n_past)
+    xd = _dev(x)
+    y = win.decode(xd, cfg.n_past)
+    assert rel_err(y.cpu().numpy(), ref) < HID_TOL
+    # in place: x_out may alias x_in
+    host2 = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    win2, _ = _window(gpu_lib, cfg, cap, host2)
+    y2 = win2.decode(xd, cfg.n_past, x_out=xd)
+    assert torch.equal(y2, y)
+
+
+def test_joint_equals_sequential_on_gpu(gpu_lib):
+    cfg = TINY["t1"]
+    cap = cfg.n_past + cfg.T
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    wj, _ = _window(gpu_lib, cfg, cap, host)
+    ws, _ = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
+    x = _dev(synth.window_input(cfg))
+    yj = wj.decode(x, cfg.n_past).cpu().numpy()
+    ys = np.stack([ws.decode(x[j:j + 1].contiguous(), cfg.n_past + j).cpu().numpy()[0] for j in range(cfg.T)])
+    assert rel_err(yj, ys) < HID_TOL
+
+
+def test_rewind_on_gpu(gpu_lib):
+    cfg = TINY["t1"]
+    d = cfg.dims
+    cap = cfg.n_past + 8
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(2)]
+    wa, _ = _window(gpu_lib, cfg, cap, host)
+    wb, _ = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
+    x4 = _dev(synth.window_input(cfg))
+    xb = _dev(synth.normal_f32(cfg.config_id, 1, "x_in", (2, d.e)))
+    wa.decode(x4, cfg.n_past)
+    ya = wa.decode(xb, cfg.n_past + 2)
+    wb.decode(x4[:2].contiguous(), cfg.n_past)
+    yb = wb.decode(xb, cfg.n_past + 2)
+    assert torch.equal(ya, yb)
+
+
+def test_rerun_is_bit_identical(gpu_lib):
+    """No float atomics anywhere: the same step twice gives the same bits."""
+    cfg = TINY["t2"]
+    cap = cfg.n_past + cfg.T
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    win, _ = _window(gpu_lib, cfg, cap, host)
+    x = _dev(synth.window_input(cfg))
+    a = win.decode(x, cfg.n_past).clone()
+    b = win.decode(x, cfg.n_past)
+    assert torch.equal(a, b)
+
+
+def test_lm_head_vs_oracle(gpu_lib):
+    cfg = TINY["t0"].with_(vocab=1000)
+    out = synth.output_layer_tensors(cfg)
+    x = synth.window_input(cfg)
+    ref = oracle.lm_head(cfg.dims, out["g_final"], out["w_lm"], x.astype(np.float64))
+    got = gpu_lib.lm_head(cfg.dims, _dev(out["g_final"]), _dev(out["w_lm"]), _dev(x)).cpu().numpy()
+    assert rel_err(got, ref) < HID_TOL
