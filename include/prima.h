@@ -70,7 +70,8 @@ typedef struct {
 /*
  * Dequantised mat-vec (the seven projections of a layer; App. A.3 counts their bytes as b):
  *     y[t*ldy + r] = sum_c W[r][c] * x[t*ldx + c],  r < n_rows, t < T.
- * W: Q4_K, n_rows x n_cols, n_cols % 256 == 0.  x: fp32, ldx >= n_cols.  y: fp32, ldy >= n_rows.
+ * W: Q4_K, n_rows x n_cols, n_cols % 256 == 0.  x: fp32, ldx >= n_cols, ldx % 4 == 0.  y: fp32,
+ * ldy >= n_rows; y must not overlap x.
  * workspace: scratch of at least prima_gemv_workspace_bytes(n_rows, n_cols, T) bytes, 256-byte aligned.
  */
 prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols,

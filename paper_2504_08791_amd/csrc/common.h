@@ -51,7 +51,14 @@ struct GemvSeg {
     int64_t n_rows, ldy, ldr;
 };
 
-// up to three matrices with the same n_cols multiplied with the same x in one launch
+// how the mat-vec obtains its activation vector
+enum XMode {
+    X_PLAIN = 0,   // x as given
+    X_RMSNORM = 1, // x * gain / sqrt(mean(x^2) + eps)
+    X_SWIGLU = 2   // silu(x) * x2
+};
+
+// up to three matrices with the same n_cols multiplied with the same activations in one launch
 struct GemvArgs {
     GemvSeg seg[3];
     int nseg;
@@ -59,23 +66,21 @@ struct GemvArgs {
     const float *x; // fp32 [T][ldx]
     int64_t ldx;
     int T;
+    int xmode;         // XMode
+    const float *x2;   // X_SWIGLU: second operand [T][ldx]
+    const float *gain; // X_RMSNORM: fp32 [n_cols]
+    float eps;         // X_RMSNORM
+    float *x_tap;      // optional fp32 [T][n_cols]: the transformed activations (test hook)
 };
 
 prima_status launch_dequant(const uint8_t *W, int64_t n_rows, int64_t n_cols, float *out, hipStream_t st);
-prima_status launch_gemv(const GemvArgs &a, void *ws, size_t ws_bytes, hipStream_t st);
-size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T);
-// single-token path on the matrix cores (q4k_gemv_mfma.hip)
-prima_status launch_gemv_t1(const GemvArgs &a, void *ws, size_t ws_bytes, hipStream_t st);
-size_t gemv_t1_ws_bytes(int64_t n_rows_total, int64_t n_cols);
-extern bool g_force_rowwave; // debugging aid: route every mat-vec through the row-per-wave kernel
+prima_status launch_gemv_mfma(const GemvArgs &a, hipStream_t st);
 
-prima_status launch_rmsnorm(const float *x, const float *g, float *out, int T, int n, float eps, hipStream_t st);
 prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
 // rotate q in place; rotate k and store k, v as fp16 rows n_past.. of the caches
 prima_status launch_rope_kv_append(const prima_dims &d, float *q, const float *k, const float *v,
                                    const float *rope_tab, __half *k_cache, __half *v_cache,
                                    int kv_cap, int n_past, int T, hipStream_t st);
-prima_status launch_swiglu(const float *g, const float *u, float *a, int64_t n, hipStream_t st);
 
 int attn_num_splits(const prima_dims &d, int n_total, int T);
 size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);

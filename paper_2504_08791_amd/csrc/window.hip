@@ -8,7 +8,7 @@ using namespace prima;
 namespace {
 
 struct WindowWs {
-    size_t n, q, k, v, o, h, g, u, a, xb0, xb1, rope, attn, gemv, total;
+    size_t q, k, v, o, h, g, u, xb0, xb1, rope, attn, total;
 };
 
 bool dims_ok(const prima_dims *d)
@@ -25,7 +25,6 @@ WindowWs carve(const prima_dims &d, int kv_cap, int T)
     auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
     const size_t qd = static_cast<size_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<size_t>(d.n_kv_heads) * d.head_dim;
     const size_t f = sizeof(float);
-    w.n = take(T * static_cast<size_t>(d.e) * f);
     w.q = take(T * qd * f);
     w.k = take(T * kvd * f);
     w.v = take(T * kvd * f);
@@ -33,14 +32,10 @@ WindowWs carve(const prima_dims &d, int kv_cap, int T)
     w.h = take(T * static_cast<size_t>(d.e) * f);
     w.g = take(T * static_cast<size_t>(d.ffn) * f);
     w.u = take(T * static_cast<size_t>(d.ffn) * f);
-    w.a = take(T * static_cast<size_t>(d.ffn) * f);
     w.xb0 = take(T * static_cast<size_t>(d.e) * f);
     w.xb1 = take(T * static_cast<size_t>(d.e) * f);
     w.rope = take(T * static_cast<size_t>(d.head_dim) * f);
     w.attn = take(attn_ws_bytes(d, kv_cap, T));
-    const int64_t max_rows = 2 * static_cast<int64_t>(d.ffn) > static_cast<int64_t>(qd + 2 * kvd) ? 2 * d.ffn : qd + 2 * kvd;
-    const int64_t max_cols = d.ffn > d.e ? d.ffn : d.e;
-    w.gemv = take(gemv_ws_bytes(max_rows, max_cols, T));
     w.total = off;
     return w;
 }
@@ -62,26 +57,33 @@ prima_status check_layer(const prima_layer &l)
     return PRIMA_OK;
 }
 
-// one decoder layer; x -> y (fp32 [T][e]); taps may be null
+GemvArgs gemv_args(int nseg, int64_t n_cols, const float *x, int64_t ldx, int T, int xmode = X_PLAIN,
+                   const float *x2 = nullptr, const float *gain = nullptr, float eps = 0.f, float *x_tap = nullptr)
+{
+    GemvArgs ga{};
+    ga.nseg = nseg; ga.n_cols = n_cols; ga.x = x; ga.ldx = ldx; ga.T = T;
+    ga.xmode = xmode; ga.x2 = x2; ga.gain = gain; ga.eps = eps; ga.x_tap = x_tap;
+    return ga;
+}
+
+// one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Seven launches: Q/K/V projections
+// (RMSNorm fused), RoPE + KV append, attention (two), output projection (+ residual), gate/up
+// projections (RMSNorm fused), down projection (SwiGLU fused, + residual).
 prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
                        const float *x, float *y, void *ws, const WindowWs &w, hipStream_t st,
                        float *tap_q, float *tap_o, float *tap_h, float *tap_a)
 {
     const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
-    float *n = at<float>(ws, w.n), *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
-    float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *g = at<float>(ws, w.g), *u = at<float>(ws, w.u), *a = at<float>(ws, w.a);
-    void *gws = at<char>(ws, w.gemv);
-    const size_t gws_bytes = w.total - w.gemv;
+    float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
+    float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *g = at<float>(ws, w.g), *u = at<float>(ws, w.u);
     prima_status s;
 #define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
-    PRIMA_TRY(launch_rmsnorm(x, L.g_attn, n, T, d.e, d.rms_eps, st));
     {
-        GemvArgs ga{};
+        GemvArgs ga = gemv_args(3, e, x, e, T, X_RMSNORM, nullptr, L.g_attn, d.rms_eps);
         ga.seg[0] = seg(L.wq, q, qd, qd);
         ga.seg[1] = seg(L.wk, k, kvd, kvd);
         ga.seg[2] = seg(L.wv, v, kvd, kvd);
-        ga.nseg = 3; ga.n_cols = e; ga.x = n; ga.ldx = e; ga.T = T;
-        PRIMA_TRY(launch_gemv(ga, gws, gws_bytes, st));
+        PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
     PRIMA_TRY(launch_rope_kv_append(d, q, k, v, at<float>(ws, w.rope), static_cast<__half *>(L.k_cache),
                                     static_cast<__half *>(L.v_cache), kv_cap, n_past, T, st));
@@ -90,27 +92,21 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
                           kv_cap, n_past, T, o, at<char>(ws, w.attn), st));
     if (tap_o && hipMemcpyAsync(tap_o, o, T * qd * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     {
-        GemvArgs ga{};
+        GemvArgs ga = gemv_args(1, qd, o, qd, T);
         ga.seg[0] = seg(L.wo, h, e, e, x, e);
-        ga.nseg = 1; ga.n_cols = qd; ga.x = o; ga.ldx = qd; ga.T = T;
-        PRIMA_TRY(launch_gemv(ga, gws, gws_bytes, st));
+        PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
     if (tap_h && hipMemcpyAsync(tap_h, h, T * e * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
-    PRIMA_TRY(launch_rmsnorm(h, L.g_ffn, n, T, d.e, d.rms_eps, st));
     {
-        GemvArgs ga{};
+        GemvArgs ga = gemv_args(2, e, h, e, T, X_RMSNORM, nullptr, L.g_ffn, d.rms_eps);
         ga.seg[0] = seg(L.wgate, g, F, F);
         ga.seg[1] = seg(L.wup, u, F, F);
-        ga.nseg = 2; ga.n_cols = e; ga.x = n; ga.ldx = e; ga.T = T;
-        PRIMA_TRY(launch_gemv(ga, gws, gws_bytes, st));
+        PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
-    PRIMA_TRY(launch_swiglu(g, u, a, static_cast<int64_t>(T) * F, st));
-    if (tap_a && hipMemcpyAsync(tap_a, a, T * F * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     {
-        GemvArgs ga{};
+        GemvArgs ga = gemv_args(1, F, g, F, T, X_SWIGLU, u, nullptr, 0.f, tap_a);
         ga.seg[0] = seg(L.wdown, y, e, e, h, e);
-        ga.nseg = 1; ga.n_cols = F; ga.x = a; ga.ldx = F; ga.T = T;
-        PRIMA_TRY(launch_gemv(ga, gws, gws_bytes, st));
+        PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
 #undef PRIMA_TRY
     return PRIMA_OK;
@@ -149,8 +145,9 @@ const char *prima_status_str(prima_status s)
 
 prima_status prima_q4k_dequant(const void *W, int64_t n_rows, int64_t n_cols, float *out, void *hip_stream)
 {
-    if (!W || !out) return PRIMA_E_NULL;
     if (n_rows < 0 || n_cols < 0 || n_cols % QK) return PRIMA_E_SHAPE;
+    if (n_rows == 0 || n_cols == 0) return PRIMA_OK; // nothing to do; pointers may be null
+    if (!W || !out) return PRIMA_E_NULL;
     if (!aligned(W, 16) || !aligned(out, 16)) return PRIMA_E_ALIGN;
     return launch_dequant(static_cast<const uint8_t *>(W), n_rows, n_cols, out, static_cast<hipStream_t>(hip_stream));
 }
@@ -158,7 +155,7 @@ prima_status prima_q4k_dequant(const void *W, int64_t n_rows, int64_t n_cols, fl
 size_t prima_gemv_workspace_bytes(int64_t n_rows, int64_t n_cols, int32_t T)
 {
     if (n_rows < 0 || n_cols < 0 || T < 1) return 0;
-    return gemv_ws_bytes(n_rows, n_cols, T);
+    return 256; // the mat-vec keeps its intermediates in LDS; the argument is reserved
 }
 
 prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int32_t T,
@@ -168,11 +165,11 @@ prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols, const
     if (n_rows < 0 || n_cols <= 0 || n_cols % QK || ldx < n_cols || ldy < n_rows) return PRIMA_E_SHAPE;
     if (T < 1 || T > PRIMA_MAX_TOK) return PRIMA_E_RANGE;
     if (!aligned(W, 16) || !aligned(x, 16) || !aligned(y, 4) || ldx % 4 || !aligned(workspace, 256)) return PRIMA_E_ALIGN;
-    if (workspace_bytes < gemv_ws_bytes(n_rows, n_cols, T)) return PRIMA_E_WORKSPACE;
-    GemvArgs ga{};
+    if (workspace_bytes < 256) return PRIMA_E_WORKSPACE;
+    if (n_rows == 0) return PRIMA_OK;
+    GemvArgs ga = gemv_args(1, n_cols, x, ldx, T);
     ga.seg[0] = seg(W, y, n_rows, ldy);
-    ga.nseg = 1; ga.n_cols = n_cols; ga.x = x; ga.ldx = ldx; ga.T = T;
-    return launch_gemv(ga, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+    return launch_gemv_mfma(ga, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t prima_attn_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
@@ -253,13 +250,9 @@ prima_status prima_lm_head(const prima_dims *d, const float *g_final, const void
     const WindowWs w = carve(*d, 0, T);
     if (workspace_bytes < w.total) return PRIMA_E_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    float *n = at<float>(workspace, w.n);
-    prima_status s = launch_rmsnorm(x, g_final, n, T, d->e, d->rms_eps, st);
-    if (s != PRIMA_OK) return s;
-    GemvArgs ga{};
+    GemvArgs ga = gemv_args(1, d->e, x, d->e, T, X_RMSNORM, nullptr, g_final, d->rms_eps);
     ga.seg[0] = seg(w_lm, logits, vocab, vocab);
-    ga.nseg = 1; ga.n_cols = d->e; ga.x = n; ga.ldx = d->e; ga.T = T;
-    return launch_gemv(ga, at<char>(workspace, w.gemv), w.total - w.gemv, st);
+    return launch_gemv_mfma(ga, st);
 }
 
 } // extern "C"

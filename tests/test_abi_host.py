@@ -56,6 +56,7 @@ def test_gemv_argument_errors():
 def test_dequant_argument_errors():
     L = _ffi.lib()
     assert L.prima_q4k_dequant(None, 1, 256, FAKE, None) == 1
+    assert L.prima_q4k_dequant(None, 0, 256, None, None) == 0
     assert L.prima_q4k_dequant(FAKE, 1, 100, FAKE, None) == 2
     assert L.prima_q4k_dequant(FAKE + 2, 1, 256, FAKE, None) == 3
 
