@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Decode throughput of one layer window on one MI355X.
+
+A step = one pass of the whole hot path (every layer of the window: Q4_K projections with fused
+RMSNorm / SwiGLU / residuals, RoPE + fp16 KV append, GQA attention) over one batch of T tokens
+of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="c3")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    import paper_2504_08791_amd as prima
+    from workloads import synth
+    from workloads.configs import CONFIGS
+
+    cfg = CONFIGS[args.config]
+    if args.layers:
+        cfg = cfg.with_(n_layers=args.layers)
+    d = cfg.dims
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cap = cfg.n_past + cfg.T
+    x_host = synth.window_input(cfg)
+
+    # --- build the window in HBM, one layer at a time; the oracle walks the same layers on the host ---
+    want_cpu = not args.no_cpu_baseline
+    if want_cpu:
+        import oracle
+    dev_layers = []
+    h_ref = x_host.astype(np.float64)
+    cpu_seconds = 0.0
+    t_build = time.time()
+    for l in range(cfg.n_layers):
+        t = synth.layer_tensors(cfg, l, kv_cap=cap)
+        dev_layers.append({k: torch.from_numpy(v).to(dev) for k, v in t.items()})
+        if want_cpu:
+            t0 = time.perf_counter()
+            h_ref = oracle.layer(d, t, h_ref, cfg.n_past)     # appends to the host copy of the cache only
+            cpu_seconds += time.perf_counter() - t0
+        del t
+    print(f"[bench] built {cfg.n_layers} layers in {time.time() - t_build:.1f} s "
+          f"(oracle: {cpu_seconds:.1f} s)", file=sys.stderr, flush=True)
+
+    win = prima.Window(d, dev_layers, cap, T_max=cfg.T)
+    x = torch.from_numpy(x_host).to(dev)
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        win.decode(x, cfg.n_past, x_out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        win.decode(x, cfg.n_past, x_out=y)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    tokens_per_s = cfg.T / (ms_per_step * 1e-3)
+    bytes_step = cfg.bytes_per_step()
+
+    # --- dominant kernel (gate/up projections): HIP events around every launch, on the same stream ---
+    n_prof = 5
+    acc = {}
+    for _ in range(n_prof):
+        _, kinds = win.decode_profiled(x, cfg.n_past, x_out=y)
+        for k, (ms, n) in kinds.items():
+            a = acc.setdefault(k, [0.0, 0])
+            a[0] += ms
+            a[1] += n
+    per_launch_us = {k: (v[0] / v[1] * 1e3 if v[1] else 0.0) for k, v in acc.items()}
+    gate_up_bytes = 2 * d.ffn * (d.e // 256) * 144      # algorithmic bytes of one gate/up launch
+    gu_us = per_launch_us["gate_up"]
+    achieved = gate_up_bytes / (gu_us * 1e-6) / 1e9
+
+    out = {
+        "metric": "decode tokens/s per layer window; achieved HBM GB/s vs MI355X peak",
+        "value": round(tokens_per_s, 2),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: {cfg.n_layers}-layer window, e={d.e}, Hq/Hkv={d.n_q_heads}/{d.n_kv_heads}, "
+                        f"ffn={d.ffn}, T={cfg.T}, n_kv={cfg.n_past}, Q4_K weights, fp16 KV",
+            "tokens_per_step": cfg.T,
+            "layers": cfg.n_layers,
+            "kv_context": cfg.n_past,
+        },
+        "window_bytes_per_step": bytes_step,
+        "window_hbm_gbps": round(bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
+        "window_hbm_frac": round(bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "wall_ms_per_step": round(wall_ms / args.steps, 4),
+        "per_launch_us": {k: round(v, 2) for k, v in per_launch_us.items()},
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "gemv_q4k_persistent_kernel<T> (gate/up projections, fused RMSNorm)",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "bytes_per_launch": gate_up_bytes,
+            "avg_launch_us": round(gu_us, 2),
+            "traffic": None,
+        },
+    }
+    if want_cpu:
+        got = y.cpu().numpy().astype(np.float64)
+        rms = np.sqrt((h_ref ** 2).mean(axis=1, keepdims=True))
+        err = float((np.abs(got - h_ref) / np.maximum(np.abs(h_ref), np.maximum(rms, 1e-30))).max())
+        out["max_rel_err_vs_oracle"] = err
+        out["cpu_baseline"] = {
+            "value": round(cfg.T / cpu_seconds, 4),
+            "unit": "tokens/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"the whole {cfg.n_layers}-layer window, {cfg.T} token(s), once ({cpu_seconds:.1f} s of CPU time; "
+                      "tensor generation excluded)",
+        }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

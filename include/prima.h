@@ -120,6 +120,28 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
                                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Measurement hook: the same launches as prima_layer_window_decode, with a HIP event recorded on
+ * `hip_stream` after every launch.  SYNCHRONISES the stream before returning and creates/destroys
+ * events (host-side allocation), so it is not for the serving path.  ms_by_kind and
+ * launches_by_kind are HOST arrays of PRIMA_N_KINDS entries: per kind of launch, the summed time
+ * from the previous launch's completion to this one's (milliseconds) and the number of launches.
+ */
+enum {
+    PRIMA_K_QKV = 0,     /* Q/K/V projections with fused RMSNorm */
+    PRIMA_K_ROPE_KV = 1, /* RoPE + fp16 KV append */
+    PRIMA_K_ATTN = 2,    /* attention (partial + merge) */
+    PRIMA_K_WO = 3,      /* output projection + residual */
+    PRIMA_K_GATE_UP = 4, /* gate/up projections with fused RMSNorm */
+    PRIMA_K_DOWN = 5,    /* down projection with fused SwiGLU + residual */
+    PRIMA_N_KINDS = 6
+};
+prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima_layer *layers, int32_t L,
+                                                int32_t kv_cap, int32_t n_past, int32_t T,
+                                                const float *x_in, float *x_out,
+                                                void *workspace, size_t workspace_bytes, void *hip_stream,
+                                                float *ms_by_kind, int32_t *launches_by_kind);
+
+/*
  * Test hook: one layer as above, additionally copying intermediates to caller buffers (each may be
  * NULL): tap_q [T][n_q_heads*head_dim] rotated queries, tap_o same shape attention output,
  * tap_h [T][e] hidden state after the attention residual, tap_a [T][ffn] SwiGLU output.

@@ -128,6 +128,21 @@ class Window:
                                                         self.workspace.numel(), _stream()), "prima_layer_window_decode")
         return x_out
 
+    def decode_profiled(self, x_in, n_past, x_out=None):
+        """Measurement hook: one step with an event after every launch; synchronises.
+        Returns (x_out, {kind: (milliseconds, launches)})."""
+        _need(x_in, torch.float32, "x_in")
+        T = x_in.shape[0]
+        if x_out is None:
+            x_out = torch.empty_like(x_in)
+        n = len(_ffi.KINDS)
+        ms = (C.c_float * n)()
+        cnt = (C.c_int32 * n)()
+        _ffi.check(_ffi.lib().prima_layer_window_decode_profiled(
+            C.byref(self.dims), self._arr, len(self.layers), self.kv_cap, n_past, T, _ptr(x_in), _ptr(x_out),
+            _ptr(self.workspace), self.workspace.numel(), _stream(), ms, cnt), "prima_layer_window_decode_profiled")
+        return x_out, {k: (ms[i], cnt[i]) for i, k in enumerate(_ffi.KINDS)}
+
     def decode_layer_taps(self, layer_index, x_in, n_past):
         """Test hook: one layer with intermediates (q, o, h, a)."""
         d = self.dims

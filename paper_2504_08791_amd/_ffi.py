@@ -6,11 +6,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libprima_hip.so")
 
 MAX_TOK = 16
+KINDS = ("qkv", "rope_kv", "attn", "wo", "gate_up", "down")
 STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIGN", 4: "PRIMA_E_RANGE",
           5: "PRIMA_E_WORKSPACE", 6: "PRIMA_E_DEVICE"}
 
 EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", "prima_attn_decode",
-           "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_decode_taps",
+           "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_window_decode_profiled", "prima_layer_decode_taps",
            "prima_lm_head", "prima_workspace_bytes", "prima_status_str", "prima_abi_version"]
 
 
@@ -50,6 +51,8 @@ def lib():
         L.prima_attn_workspace_bytes.argtypes = [dp, i32, i32]
         L.prima_attn_workspace_bytes.restype = sz
         L.prima_layer_window_decode.argtypes = [dp, lp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.prima_layer_window_decode_profiled.argtypes = [dp, lp, i32, i32, i32, i32, vp, vp, vp, sz, vp,
+                                                         C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.prima_layer_decode_taps.argtypes = [dp, lp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.prima_lm_head.argtypes = [dp, vp, vp, i64, vp, i32, vp, vp, sz, vp]
         L.prima_workspace_bytes.argtypes = [dp, i32, i32]
@@ -58,6 +61,7 @@ def lib():
         L.prima_status_str.restype = C.c_char_p
         L.prima_abi_version.restype = C.c_int
         for name in ("prima_q4k_gemv", "prima_q4k_dequant", "prima_attn_decode", "prima_layer_window_decode",
+                     "prima_layer_window_decode_profiled",
                      "prima_layer_decode_taps", "prima_lm_head"):
             getattr(L, name).restype = C.c_int
         _lib = L
