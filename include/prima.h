@@ -128,8 +128,8 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
  */
 enum {
     PRIMA_K_QKV = 0,     /* Q/K/V projections with fused RMSNorm */
-    PRIMA_K_ROPE_KV = 1, /* RoPE + fp16 KV append */
-    PRIMA_K_ATTN = 2,    /* attention (partial + merge) */
+    PRIMA_K_ROPE_KV = 1, /* unused: RoPE + fp16 KV append run inside the attention kernel */
+    PRIMA_K_ATTN = 2,    /* attention: partial (with RoPE + KV append) and merge */
     PRIMA_K_WO = 3,      /* output projection + residual */
     PRIMA_K_GATE_UP = 4, /* gate/up projections with fused RMSNorm */
     PRIMA_K_DOWN = 5,    /* down projection with fused SwiGLU + residual */

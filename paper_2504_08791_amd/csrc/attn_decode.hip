@@ -1,119 +1,297 @@
 // GQA decode attention over an fp16 KV cache, split over the KV length, partials merged by
 // log-sum-exp.  Per layer and step it reads 2(h_k e_k + h_v e_v) n_kv bytes (arXiv 2504.08791,
-// App. A.3, device-loading term).
+// App. A.3, device-loading term) and appends 2(h_k e_k + h_v e_v) bytes per token.
 //
-// Work decomposition: the queries that share one KV head (G heads x T tokens) are taken in
-// groups of up to QG; a block handles one (key range, KV head, query group).  Inside a wave a
-// K/V row is spread over D/8 lanes (8 halfs = one 128-bit load per lane), so one wave
-// instruction reads 64/(D/8) consecutive rows, fully coalesced.  Every lane group keeps its own
-// running (max, sum, output) per query; groups, waves and key ranges are merged at the end.
+// One workgroup handles (key range, KV head, group of up to 8 queries that share the head).
+//  * Q.K^T runs on the matrix cores: the fp16 cache rows are MFMA operands as they lie in memory
+//    (lane (n, c) loads 16 bytes of key n), the queries are pre-scaled by a power of two and split
+//    into fp16 high and low parts that occupy rows 0-7 and 8-15 of the A operand, so the logits
+//    carry the queries' full fp32 precision with fp32 accumulation.
+//  * softmax statistics are kept online per 16-key tile in fp32.
+//  * P.V runs on the vector ALUs in fp32: lane (dg, ks) owns 8 output columns for the keys
+//    congruent to ks mod 4 (one 128-bit load of V per key), combined across lanes at the end.
+//  * when asked, the kernel also does the layer's RoPE and KV append: queries are rotated as they
+//    are loaded, and the workgroup whose key range holds the new rows rotates k, rounds k and v to
+//    fp16 (nearest even) and stores them before reading them back like any other row.
 #include "common.h"
 
 namespace prima {
 
-constexpr int QG = 8;        // queries per block
-constexpr int ATT_WAVES = 4; // waves per block
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int QG = 8;        // queries per workgroup
+constexpr int ATT_WAVES = 4; // waves per workgroup
 constexpr int MAX_SPLITS = 64;
 
-__device__ __forceinline__ void unpack8(const uint4 &r, float *f)
+struct AttnArgs {
+    const float *q;       // [T][Hq][D]; rotated already unless rope_tab is set
+    float *q_rot_out;     // optional: rotated queries written back (split 0 only)
+    const float *k_new;   // fused append: un-rotated k [T][Hkv][D], else null
+    const float *v_new;   // fused append: v [T][Hkv][D]
+    const float2 *rope_tab; // [T][D/2] (cos, sin) or null
+    __half *K, *V;        // caches [Hkv][kv_cap][D]
+    float *part;          // [T*Hq][nsplit][2 + D]
+    int Hq, Hkv, kv_cap, n_past, T, nsplit, keys_per_split, rope_mode;
+};
+
+__device__ __forceinline__ void rope_pair_index(int i, int half, int mode, int &ia, int &ib)
 {
-    const __half2 *h = reinterpret_cast<const __half2 *>(&r);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float2 v = __half22float2(h[i]);
-        f[2 * i] = v.x;
-        f[2 * i + 1] = v.y;
-    }
+    ia = mode ? 2 * i : i;
+    ib = mode ? 2 * i + 1 : i + half;
 }
 
-// partial record per (query, split): [0] = running max, [1] = sum of exp, [2..2+D) = unnormalised output
 template <int D>
-__global__ void __launch_bounds__(ATT_WAVES * 64)
-attn_partial_kernel(const float *__restrict__ q, const __half *__restrict__ K, const __half *__restrict__ V,
-                    float *__restrict__ part, int Hq, int Hkv, int kv_cap, int n_past, int T,
-                    int nsplit, int keys_per_split)
+__global__ void __launch_bounds__(ATT_WAVES * 64) attn_partial_kernel(AttnArgs a)
 {
-    constexpr int LPK = D / 8;    // lanes per key row
-    constexpr int KPW = 64 / LPK; // key rows per wave instruction
+    constexpr int NA = D / 32;   // MFMAs (k-steps of 32) per 16-key tile
+    constexpr int DG = D / 8;    // lanes per V row (8 columns each)
+    constexpr int KS = 64 / DG;  // V rows per wave instruction
+    constexpr int VPT = 16 / KS; // V loads per lane per 16-key tile
     const int split = blockIdx.x, kvh = blockIdx.y, qgrp = blockIdx.z;
-    const int G = Hq / Hkv, NQ = G * T; // queries on this KV head, index = t*G + hg
+    const int G = a.Hq / a.Hkv, NQ = G * a.T; // queries on this KV head, index = t*G + hg
     const int q0 = qgrp * QG;
     const int nq = min(QG, NQ - q0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int dl = lane % LPK, kl = lane / LPK;
-    const float scale = rsqrtf(static_cast<float>(D));
+    const int n_total = a.n_past + a.T;
+    const int p_begin = split * a.keys_per_split;
+    const int p_end = min(p_begin + a.keys_per_split, n_total);
 
-    float qr[QG][8], o[QG][8], m[QG], l[QG];
-    int limit[QG]; // last visible cache row per query
-#pragma unroll
-    for (int i = 0; i < QG; ++i) {
-        m[i] = -INFINITY;
-        l[i] = 0.f;
-        limit[i] = -1;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { o[i][e] = 0.f; qr[i][e] = 0.f; }
-        if (i < nq) {
-            const int qi = q0 + i, t = qi / G, hg = qi - t * G;
-            const float *qp = q + (static_cast<int64_t>(t) * Hq + kvh * G + hg) * D + dl * 8;
-            const float4 a = *reinterpret_cast<const float4 *>(qp), b = *reinterpret_cast<const float4 *>(qp + 4);
-            qr[i][0] = a.x * scale; qr[i][1] = a.y * scale; qr[i][2] = a.z * scale; qr[i][3] = a.w * scale;
-            qr[i][4] = b.x * scale; qr[i][5] = b.y * scale; qr[i][6] = b.z * scale; qr[i][7] = b.w * scale;
-            limit[i] = n_past + t;
+    __shared__ __align__(16) _Float16 s_q[16][D + 8];     // rows 0-7 high parts, 8-15 low parts (+8: bank skew)
+    __shared__ float s_fq[QG];                            // per-query logit factor 2^e / sqrt(D)
+    __shared__ int s_limit[QG];                           // last visible cache row per query
+    __shared__ __align__(16) float s_p[ATT_WAVES][16][QG]; // probabilities of the current tile [key][query]
+    __shared__ float s_corr[ATT_WAVES][QG];
+    __shared__ float s_m[ATT_WAVES][QG], s_l[ATT_WAVES][QG];
+    __shared__ __align__(16) float s_o[ATT_WAVES][QG][D];
+
+    __half *Kh = a.K + static_cast<int64_t>(kvh) * a.kv_cap * D;
+    __half *Vh = a.V + static_cast<int64_t>(kvh) * a.kv_cap * D;
+
+    // ---- fused KV append: a workgroup whose range contains new rows writes them first (when several
+    // query groups share the range each writes the same values) ----
+    if (a.k_new && p_end > a.n_past && p_begin < n_total) {
+        for (int idx = threadIdx.x; idx < a.T * (D / 2); idx += blockDim.x) {
+            const int t = idx / (D / 2), i = idx - t * (D / 2);
+            const int row = a.n_past + t;
+            if (row < p_begin || row >= p_end) continue;
+            int ia, ib;
+            rope_pair_index(i, D / 2, a.rope_mode, ia, ib);
+            const float2 cs = a.rope_tab[t * (D / 2) + i];
+            const float *kp = a.k_new + (static_cast<int64_t>(t) * a.Hkv + kvh) * D;
+            const float ka = kp[ia], kb = kp[ib];
+            Kh[static_cast<int64_t>(row) * D + ia] = __float2half_rn(ka * cs.x - kb * cs.y);
+            Kh[static_cast<int64_t>(row) * D + ib] = __float2half_rn(ka * cs.y + kb * cs.x);
+            const float *vp = a.v_new + (static_cast<int64_t>(t) * a.Hkv + kvh) * D;
+            Vh[static_cast<int64_t>(row) * D + 2 * i] = __float2half_rn(vp[2 * i]);
+            Vh[static_cast<int64_t>(row) * D + 2 * i + 1] = __float2half_rn(vp[2 * i + 1]);
         }
+        __threadfence_block();
     }
 
-    const int p_begin = split * keys_per_split;
-    const int p_end = min(p_begin + keys_per_split, n_past + T);
-    const __half *Kh = K + static_cast<int64_t>(kvh) * kv_cap * D;
-    const __half *Vh = V + static_cast<int64_t>(kvh) * kv_cap * D;
-
-    for (int p = p_begin + wave * KPW + kl; p < p_end; p += ATT_WAVES * KPW) {
-        const uint4 kraw = *reinterpret_cast<const uint4 *>(Kh + static_cast<int64_t>(p) * D + dl * 8);
-        const uint4 vraw = *reinterpret_cast<const uint4 *>(Vh + static_cast<int64_t>(p) * D + dl * 8);
-        float kf[8], vf[8];
-        unpack8(kraw, kf);
-        unpack8(vraw, vf);
+    // ---- queries: rotate (if asked), scale by a power of two, split into fp16 high + low ----
+    for (int i = threadIdx.x; i < 16 * (D + 8); i += blockDim.x) (&s_q[0][0])[i] = static_cast<_Float16>(0.f);
+    __syncthreads();
+    if (wave < 2) {
+        // wave w handles queries 4w..4w+3, 16 lanes per query
+        const int qi_l = wave * 4 + (lane >> 4), sub = lane & 15;
+        if (qi_l < nq) {
+            const int qi = q0 + qi_l, t = qi / G, hg = qi - t * G;
+            const int64_t qoff = (static_cast<int64_t>(t) * a.Hq + kvh * G + hg) * D;
+            float v[D / 16];
+            float amax = 0.f;
 #pragma unroll
-        for (int i = 0; i < QG; ++i) {
-            float s = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s += qr[i][e] * kf[e];
-#pragma unroll
-            for (int off = LPK / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-            if (p <= limit[i]) {
-                const float mn = fmaxf(m[i], s);
-                const float corr = __expf(m[i] - mn); // exp(-inf) = 0 on the first key
-                const float pw = __expf(s - mn);
-                l[i] = l[i] * corr + pw;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[i][e] = o[i][e] * corr + pw * vf[e];
-                m[i] = mn;
+            for (int c = 0; c < D / 32; ++c) {
+                // pair index i = sub + 16c  (i < D/2)
+                const int i = sub + 16 * c;
+                int ia, ib;
+                rope_pair_index(i, D / 2, a.rope_mode, ia, ib);
+                float xa = a.q[qoff + ia], xb = a.q[qoff + ib];
+                if (a.rope_tab) {
+                    const float2 cs = a.rope_tab[t * (D / 2) + i];
+                    const float ra = xa * cs.x - xb * cs.y, rb = xa * cs.y + xb * cs.x;
+                    xa = ra;
+                    xb = rb;
+                    if (a.q_rot_out && split == 0) {
+                        a.q_rot_out[qoff + ia] = xa;
+                        a.q_rot_out[qoff + ib] = xb;
+                    }
+                }
+                v[2 * c] = xa;
+                v[2 * c + 1] = xb;
+                amax = fmaxf(amax, fmaxf(fabsf(xa), fabsf(xb)));
             }
+#pragma unroll
+            for (int off = 8; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+            int ex = 0;
+            if (amax > 0.f) frexpf(amax, &ex);  // amax < 2^ex
+            int p = 12 - ex;                    // scaled |q| < 2^12
+            p = p > 100 ? 100 : (p < -100 ? -100 : p);
+            const float S = ldexpf(1.0f, p);
+#pragma unroll
+            for (int c = 0; c < D / 32; ++c) {
+                const int i = sub + 16 * c;
+                int ia, ib;
+                rope_pair_index(i, D / 2, a.rope_mode, ia, ib);
+                const float sa = v[2 * c] * S, sb = v[2 * c + 1] * S;
+                const _Float16 ha = static_cast<_Float16>(sa), hb = static_cast<_Float16>(sb);
+                s_q[qi_l][ia] = ha;
+                s_q[qi_l][ib] = hb;
+                s_q[8 + qi_l][ia] = static_cast<_Float16>(sa - static_cast<float>(ha));
+                s_q[8 + qi_l][ib] = static_cast<_Float16>(sb - static_cast<float>(hb));
+            }
+            if (sub == 0) {
+                s_fq[qi_l] = ldexpf(1.0f, -p) * rsqrtf(static_cast<float>(D));
+                s_limit[qi_l] = a.n_past + t;
+            }
+        } else if (sub == 0 && qi_l < QG) {
+            s_fq[qi_l] = 0.f;
+            s_limit[qi_l] = -1;
         }
     }
+    __syncthreads();
 
-    // merge the KPW lane groups of the wave, then the waves through LDS
-    __shared__ float sm[ATT_WAVES][QG][2 + D];
+    // A operands: lane (m = lane%16, c = lane/16) holds s_q[m][32a + 8c .. +8] for a = 0..NA-1
+    const int mrow = lane & 15, kc = lane >> 4;
+    half8 qa[NA];
 #pragma unroll
-    for (int i = 0; i < QG; ++i) {
-        float mm = m[i];
+    for (int x = 0; x < NA; ++x) qa[x] = *reinterpret_cast<const half8 *>(&s_q[mrow][32 * x + 8 * kc]);
+
+    // softmax bookkeeping for the 4 queries this lane sees in the MFMA result: m = 4*(kc&1) + r
+    const int mq0 = 4 * (kc & 1);
+    float fq[4], m_run[4], l_run[4];
+    int lim[4];
 #pragma unroll
-        for (int off = LPK; off < 64; off <<= 1) mm = fmaxf(mm, __shfl_xor(mm, off, 64));
-        const float w = (m[i] == -INFINITY) ? 0.f : __expf(m[i] - mm);
-        float ll = l[i] * w;
+    for (int r = 0; r < 4; ++r) {
+        fq[r] = s_fq[mq0 + r];
+        lim[r] = s_limit[mq0 + r];
+        m_run[r] = -INFINITY;
+        l_run[r] = 0.f;
+    }
+    // P.V ownership: lane (dg, ks): columns 8dg..8dg+7, keys = tile key 4i + ks (D = 128) or 8i + ks (D = 64)
+    const int dg = lane % DG, ks = lane / DG;
+    float o[QG][8];
 #pragma unroll
-        for (int off = LPK; off < 64; off <<= 1) ll += __shfl_xor(ll, off, 64);
+    for (int i = 0; i < QG; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[i][e] = 0.f;
+
+    const int last_row = n_total - 1;
+    auto load_tile = [&](int key0, half8 *kb, uint4 *vb) {
+        const int krow = min(key0 + mrow, last_row);
+        const __half *kp = Kh + static_cast<int64_t>(krow) * D + 8 * kc;
+#pragma unroll
+        for (int x = 0; x < NA; ++x) kb[x] = *reinterpret_cast<const half8 *>(kp + 32 * x);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int vrow = min(key0 + KS * i + ks, last_row);
+            vb[i] = *reinterpret_cast<const uint4 *>(Vh + static_cast<int64_t>(vrow) * D + 8 * dg);
+        }
+    };
+
+    half8 kb0[NA], kb1[NA];
+    uint4 vb0[VPT], vb1[VPT];
+    const int tile_stride = ATT_WAVES * 16;
+    int key0 = p_begin + wave * 16;
+    if (key0 < p_end) load_tile(key0, kb0, vb0);
+
+    auto process = [&](int k0, const half8 *kb, const uint4 *vb) {
+        // logits of 16 keys x 16 A rows (8 high + 8 low query parts)
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int x = 0; x < NA; ++x) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[x], kb[x], acc, 0, 0, 0);
+        // rows 4kc..4kc+3 of column (key) mrow: add the low-part rows held 32 lanes away
+        float s[4], pr[4], corr[4];
+        const int key = k0 + mrow;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            s[r] = (acc[r] + __shfl_xor(acc[r], 32, 64)) * fq[r];
+            if (key >= p_end || key > lim[r]) s[r] = -INFINITY;
+            float mx = s[r];
+#pragma unroll
+            for (int off = 8; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+            const float mn = fmaxf(m_run[r], mx);
+            corr[r] = (mn == -INFINITY) ? 1.f : __expf(m_run[r] - mn); // exp(-inf) = 0 on the first visible key
+            pr[r] = (s[r] == -INFINITY) ? 0.f : __expf(s[r] - mn);
+            float ps = pr[r];
+#pragma unroll
+            for (int off = 8; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
+            l_run[r] = l_run[r] * corr[r] + ps;
+            m_run[r] = mn;
+        }
+        if (kc < 2) {
+            *reinterpret_cast<float4 *>(&s_p[wave][mrow][mq0]) = make_float4(pr[0], pr[1], pr[2], pr[3]);
+            if (mrow == 0) *reinterpret_cast<float4 *>(&s_corr[wave][mq0]) = make_float4(corr[0], corr[1], corr[2], corr[3]);
+        }
+        __builtin_amdgcn_wave_barrier();
+        // P.V
+        float cr[QG];
+#pragma unroll
+        for (int q = 0; q < QG; q += 4) {
+            const float4 c4 = *reinterpret_cast<const float4 *>(&s_corr[wave][q]);
+            cr[q] = c4.x; cr[q + 1] = c4.y; cr[q + 2] = c4.z; cr[q + 3] = c4.w;
+        }
+#pragma unroll
+        for (int q = 0; q < QG; ++q)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[q][e] *= cr[q];
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int kt = KS * i + ks;
+            const float4 p0 = *reinterpret_cast<const float4 *>(&s_p[wave][kt][0]);
+            const float4 p1 = *reinterpret_cast<const float4 *>(&s_p[wave][kt][4]);
+            const float pw[QG] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+            const __half2 *h = reinterpret_cast<const __half2 *>(&vb[i]);
+            float vf[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float2 f2 = __half22float2(h[e]);
+                vf[2 * e] = f2.x;
+                vf[2 * e + 1] = f2.y;
+            }
+#pragma unroll
+            for (int q = 0; q < QG; ++q)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[q][e] = fmaf(pw[q], vf[e], o[q][e]);
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    // tiles of this wave, double-buffered in registers
+    while (key0 < p_end) {
+        const int next = key0 + tile_stride;
+        if (next < p_end) load_tile(next, kb1, vb1);
+        process(key0, kb0, vb0);
+        key0 = next;
+        if (key0 >= p_end) break;
+        const int next2 = key0 + tile_stride;
+        if (next2 < p_end) load_tile(next2, kb0, vb0);
+        process(key0, kb1, vb1);
+        key0 = next2;
+    }
+
+    // ---- merge the KS lane groups of the wave, then the waves ----
+#pragma unroll
+    for (int q = 0; q < QG; ++q)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float v = o[i][e] * w;
+            float v = o[q][e];
 #pragma unroll
-            for (int off = LPK; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
-            o[i][e] = v;
+            for (int off = DG; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+            o[q][e] = v;
         }
-        if (kl == 0) {
-            if (dl == 0) { sm[wave][i][0] = mm; sm[wave][i][1] = ll; }
+    if (ks == 0) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sm[wave][i][2 + dl * 8 + e] = o[i][e];
+        for (int q = 0; q < QG; ++q) {
+            *reinterpret_cast<float4 *>(&s_o[wave][q][8 * dg]) = make_float4(o[q][0], o[q][1], o[q][2], o[q][3]);
+            *reinterpret_cast<float4 *>(&s_o[wave][q][8 * dg + 4]) = make_float4(o[q][4], o[q][5], o[q][6], o[q][7]);
+        }
+    }
+    if (mrow == 0 && kc < 2) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            s_m[wave][mq0 + r] = m_run[r];
+            s_l[wave][mq0 + r] = l_run[r];
         }
     }
     __syncthreads();
@@ -121,47 +299,68 @@ attn_partial_kernel(const float *__restrict__ q, const __half *__restrict__ K, c
         const int i = idx / D, e = idx - i * D;
         float mm = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < ATT_WAVES; ++w) mm = fmaxf(mm, sm[w][i][0]);
-        float ll = 0.f, acc = 0.f;
+        for (int w = 0; w < ATT_WAVES; ++w) mm = fmaxf(mm, s_m[w][i]);
+        float ll = 0.f, accv = 0.f;
 #pragma unroll
         for (int w = 0; w < ATT_WAVES; ++w) {
-            const float f = (sm[w][i][0] == -INFINITY) ? 0.f : __expf(sm[w][i][0] - mm);
-            ll += sm[w][i][1] * f;
-            acc += sm[w][i][2 + e] * f;
+            const float f = (s_m[w][i] == -INFINITY) ? 0.f : __expf(s_m[w][i] - mm);
+            ll += s_l[w][i] * f;
+            accv += s_o[w][i][e] * f;
         }
         const int qi = q0 + i, t = qi / G, hg = qi - t * G;
-        float *rec = part + ((static_cast<int64_t>(t) * Hq + kvh * G + hg) * nsplit + split) * (2 + D);
+        float *rec = a.part + ((static_cast<int64_t>(t) * a.Hq + kvh * G + hg) * a.nsplit + split) * (2 + D);
         if (e == 0) { rec[0] = mm; rec[1] = ll; }
-        rec[2 + e] = acc;
+        rec[2 + e] = accv;
     }
 }
 
 // o[t][h][:] = sum_i part_i.o * exp(m_i - M) / sum_i part_i.l * exp(m_i - M); a key range that
-// held no visible key has (max, sum) = (-inf, 0) and drops out.
+// held no visible key has (max, sum) = (-inf, 0) and drops out.  One workgroup per (token, head).
 template <int D>
-__global__ void __launch_bounds__(D) attn_merge_kernel(const float *__restrict__ part, float *__restrict__ o, int nsplit)
+__global__ void __launch_bounds__(256) attn_merge_kernel(const float *__restrict__ part, float *__restrict__ o, int nsplit)
 {
+    __shared__ float s_w[MAX_SPLITS];
+    __shared__ float s_red[4][D];
+    __shared__ float s_L;
     const int64_t qh = blockIdx.x;
-    const int e = threadIdx.x;
     const float *rec = part + qh * nsplit * (2 + D);
-    float mm = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) mm = fmaxf(mm, rec[s * (2 + D)]);
-    float ll = 0.f, acc = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        const float ms = rec[s * (2 + D)];
-        const float f = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
-        ll += rec[s * (2 + D) + 1] * f;
-        acc += rec[s * (2 + D) + 2 + e] * f;
+    if (threadIdx.x < 64) {
+        const int s = threadIdx.x;
+        const float ms = s < nsplit ? rec[s * (2 + D)] : -INFINITY;
+        const float ls = s < nsplit ? rec[s * (2 + D) + 1] : 0.f;
+        float mm = ms;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mm = fmaxf(mm, __shfl_xor(mm, off, 64));
+        const float w = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
+        float ll = ls * w;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ll += __shfl_xor(ll, off, 64);
+        s_w[s] = w;
+        if (s == 0) s_L = ll;
     }
-    o[qh * D + e] = acc / ll;
+    __syncthreads();
+    // 256 threads: 256/D groups of splits, D columns
+    constexpr int NG = 256 / D;
+    const int e = threadIdx.x % D, grp = threadIdx.x / D;
+    float acc = 0.f;
+#pragma unroll 8
+    for (int s = grp; s < nsplit; s += NG) acc = fmaf(rec[s * (2 + D) + 2 + e], s_w[s], acc);
+    s_red[grp][e] = acc;
+    __syncthreads();
+    if (grp == 0) {
+        float v = s_red[0][e];
+#pragma unroll
+        for (int g2 = 1; g2 < NG; ++g2) v += s_red[g2][e];
+        o[qh * D + e] = v / s_L;
+    }
 }
 
 int attn_num_splits(const prima_dims &d, int n_total, int T)
 {
     const int G = d.n_q_heads / d.n_kv_heads;
     const int nqg = (G * T + QG - 1) / QG;
-    const int by_len = (n_total + 63) / 64;                       // at least 64 keys per block
-    const int by_grid = (1024 + d.n_kv_heads * nqg - 1) / (d.n_kv_heads * nqg); // about 4 blocks per CU
+    const int by_len = (n_total + 63) / 64;                                     // at least one 16-key tile per wave
+    const int by_grid = (512 + d.n_kv_heads * nqg - 1) / (d.n_kv_heads * nqg);  // about 2 workgroups per CU
     int ns = by_len < by_grid ? by_len : by_grid;
     if (ns < 1) ns = 1;
     if (ns > MAX_SPLITS) ns = MAX_SPLITS;
@@ -173,24 +372,29 @@ size_t attn_ws_bytes(const prima_dims &d, int, int T)
     return round_up(static_cast<size_t>(T) * d.n_q_heads * MAX_SPLITS * (2 + d.head_dim) * sizeof(float), 256);
 }
 
-prima_status launch_attn(const prima_dims &d, const float *q, const __half *K, const __half *V,
-                         int kv_cap, int n_past, int T, float *o, void *ws, hipStream_t st)
+prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
+                         const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
+                         void *ws, hipStream_t st)
 {
     const int n_total = n_past + T;
-    const int nsplit = attn_num_splits(d, n_total, T);
-    const int kps = (n_total + nsplit - 1) / nsplit;
+    AttnArgs a{};
+    a.q = q; a.q_rot_out = q_rot_out; a.k_new = k_new; a.v_new = v_new;
+    a.rope_tab = reinterpret_cast<const float2 *>(rope_tab);
+    a.K = K; a.V = V; a.part = static_cast<float *>(ws);
+    a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.kv_cap = kv_cap; a.n_past = n_past; a.T = T;
+    a.nsplit = attn_num_splits(d, n_total, T);
+    // key ranges are multiples of 16 so that tiles never straddle two workgroups
+    a.keys_per_split = ((n_total + a.nsplit - 1) / a.nsplit + 15) / 16 * 16;
+    a.rope_mode = d.rope_mode;
     const int G = d.n_q_heads / d.n_kv_heads;
     const int nqg = (G * T + QG - 1) / QG;
-    float *part = static_cast<float *>(ws);
-    const dim3 grid(nsplit, d.n_kv_heads, nqg), block(ATT_WAVES * 64);
+    const dim3 grid(a.nsplit, d.n_kv_heads, nqg), block(ATT_WAVES * 64);
     if (d.head_dim == 128) {
-        hipLaunchKernelGGL(attn_partial_kernel<128>, grid, block, 0, st, q, K, V, part, d.n_q_heads, d.n_kv_heads,
-                           kv_cap, n_past, T, nsplit, kps);
-        hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(T * d.n_q_heads), dim3(128), 0, st, part, o, nsplit);
+        hipLaunchKernelGGL(attn_partial_kernel<128>, grid, block, 0, st, a);
+        hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(T * d.n_q_heads), dim3(256), 0, st, a.part, o, a.nsplit);
     } else if (d.head_dim == 64) {
-        hipLaunchKernelGGL(attn_partial_kernel<64>, grid, block, 0, st, q, K, V, part, d.n_q_heads, d.n_kv_heads,
-                           kv_cap, n_past, T, nsplit, kps);
-        hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(T * d.n_q_heads), dim3(64), 0, st, part, o, nsplit);
+        hipLaunchKernelGGL(attn_partial_kernel<64>, grid, block, 0, st, a);
+        hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(T * d.n_q_heads), dim3(256), 0, st, a.part, o, a.nsplit);
     } else {
         return PRIMA_E_SHAPE;
     }

@@ -77,14 +77,12 @@ prima_status launch_dequant(const uint8_t *W, int64_t n_rows, int64_t n_cols, fl
 prima_status launch_gemv_mfma(const GemvArgs &a, hipStream_t st);
 
 prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
-// rotate q in place; rotate k and store k, v as fp16 rows n_past.. of the caches
-prima_status launch_rope_kv_append(const prima_dims &d, float *q, const float *k, const float *v,
-                                   const float *rope_tab, __half *k_cache, __half *v_cache,
-                                   int kv_cap, int n_past, int T, hipStream_t st);
-
 int attn_num_splits(const prima_dims &d, int n_total, int T);
 size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);
-prima_status launch_attn(const prima_dims &d, const float *q, const __half *K, const __half *V,
-                         int kv_cap, int n_past, int T, float *o, void *ws, hipStream_t st);
+// q: [T][Hq][D].  With rope_tab set, q and k_new are un-rotated and the kernel rotates them and
+// appends k_new / v_new to the caches; otherwise q is used as is and the caches are complete.
+prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
+                         const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
+                         void *ws, hipStream_t st);
 
 } // namespace prima

@@ -84,9 +84,9 @@ struct LaunchTimer {
     }
 };
 
-// one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Seven launches: Q/K/V projections
-// (RMSNorm fused), RoPE + KV append, attention (two), output projection (+ residual), gate/up
-// projections (RMSNorm fused), down projection (SwiGLU fused, + residual).
+// one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Six launches: Q/K/V projections
+// (RMSNorm fused), attention partial (RoPE + KV append fused) and merge, output projection
+// (+ residual), gate/up projections (RMSNorm fused), down projection (SwiGLU fused, + residual).
 prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
                        const float *x, float *y, void *ws, const WindowWs &w, hipStream_t st,
                        float *tap_q, float *tap_o, float *tap_h, float *tap_a, LaunchTimer *tm = nullptr)
@@ -105,12 +105,8 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
         PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
     PRIMA_MARK(PRIMA_K_QKV);
-    PRIMA_TRY(launch_rope_kv_append(d, q, k, v, at<float>(ws, w.rope), static_cast<__half *>(L.k_cache),
-                                    static_cast<__half *>(L.v_cache), kv_cap, n_past, T, st));
-    PRIMA_MARK(PRIMA_K_ROPE_KV);
-    if (tap_q && hipMemcpyAsync(tap_q, q, T * qd * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
-    PRIMA_TRY(launch_attn(d, q, static_cast<const __half *>(L.k_cache), static_cast<const __half *>(L.v_cache),
-                          kv_cap, n_past, T, o, at<char>(ws, w.attn), st));
+    PRIMA_TRY(launch_attn(d, q, tap_q, k, v, at<float>(ws, w.rope), static_cast<__half *>(L.k_cache),
+                          static_cast<__half *>(L.v_cache), kv_cap, n_past, T, o, at<char>(ws, w.attn), st));
     PRIMA_MARK(PRIMA_K_ATTN);
     if (tap_o && hipMemcpyAsync(tap_o, o, T * qd * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     {
@@ -213,8 +209,9 @@ prima_status prima_attn_decode(const prima_dims *d, const float *q, const void *
     if (T < 1 || T > PRIMA_MAX_TOK || n_past < 0 || kv_cap < 1 || static_cast<int64_t>(n_past) + T > kv_cap) return PRIMA_E_RANGE;
     if (!aligned(q, 16) || !aligned(o, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(workspace, 256)) return PRIMA_E_ALIGN;
     if (workspace_bytes < attn_ws_bytes(*d, kv_cap, T)) return PRIMA_E_WORKSPACE;
-    return launch_attn(*d, q, static_cast<const __half *>(k_cache), static_cast<const __half *>(v_cache), kv_cap, n_past, T, o,
-                       workspace, static_cast<hipStream_t>(hip_stream));
+    return launch_attn(*d, q, nullptr, nullptr, nullptr, nullptr,
+                       static_cast<__half *>(const_cast<void *>(k_cache)), static_cast<__half *>(const_cast<void *>(v_cache)),
+                       kv_cap, n_past, T, o, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
