@@ -42,7 +42,7 @@ __device__ __forceinline__ void rope_pair_index(int i, int half, int mode, int &
 }
 
 template <int D>
-__global__ void __launch_bounds__(ATT_WAVES * 64) attn_partial_kernel(AttnArgs a)
+__global__ void __launch_bounds__(ATT_WAVES * 64, 2) attn_partial_kernel(AttnArgs a)
 {
     constexpr int NA = D / 32;   // MFMAs (k-steps of 32) per 16-key tile
     constexpr int DG = D / 8;    // lanes per V row (8 columns each)
@@ -92,6 +92,43 @@ __global__ void __launch_bounds__(ATT_WAVES * 64) attn_partial_kernel(AttnArgs a
     // ---- queries: rotate (if asked), scale by a power of two, split into fp16 high + low ----
     for (int i = threadIdx.x; i < 16 * (D + 8); i += blockDim.x) (&s_q[0][0])[i] = static_cast<_Float16>(0.f);
     __syncthreads();
+    // appended rows are visible from here on: request the first tile before staging the queries
+    const int mrow = lane & 15, kc = lane >> 4;
+    // softmax bookkeeping for the 4 queries this lane sees in the MFMA result: m = 4*(kc&1) + r
+    const int mq0 = 4 * (kc & 1);
+    // P.V ownership: lane (dg, ks): columns 8dg..8dg+7, keys = tile key 4i + ks (D = 128) or 8i + ks (D = 64)
+    const int dg = lane % DG, ks = lane / DG;
+    float o[QG][8];
+#pragma unroll
+    for (int i = 0; i < QG; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[i][e] = 0.f;
+
+    const int last_row = n_total - 1;
+    auto load_k = [&](int k0, half8 *kbuf) {
+        const int krow = min(k0 + mrow, last_row);
+        const __half *kp = Kh + static_cast<int64_t>(krow) * D + 8 * kc;
+#pragma unroll
+        for (int x = 0; x < NA; ++x) kbuf[x] = *reinterpret_cast<const half8 *>(kp + 32 * x);
+    };
+    auto load_v = [&](int k0, uint4 *vbuf) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            const int vrow = min(k0 + KS * i + ks, last_row);
+            vbuf[i] = *reinterpret_cast<const uint4 *>(Vh + static_cast<int64_t>(vrow) * D + 8 * dg);
+        }
+    };
+
+    // one K and one V buffer per lane: the next tile's K is requested as soon as the MFMAs have
+    // consumed the current one, the next V as soon as P.V is done
+    half8 kb[NA];
+    uint4 vb[VPT];
+    const int tile_stride = ATT_WAVES * 16;
+    int key0 = p_begin + wave * 16;
+    if (key0 < p_end) {
+        load_k(key0, kb);
+        load_v(key0, vb);
+    }
     if (wave < 2) {
         // wave w handles queries 4w..4w+3, 16 lanes per query
         const int qi_l = wave * 4 + (lane >> 4), sub = lane & 15;
@@ -151,14 +188,11 @@ __global__ void __launch_bounds__(ATT_WAVES * 64) attn_partial_kernel(AttnArgs a
     }
     __syncthreads();
 
+
     // A operands: lane (m = lane%16, c = lane/16) holds s_q[m][32a + 8c .. +8] for a = 0..NA-1
-    const int mrow = lane & 15, kc = lane >> 4;
     half8 qa[NA];
 #pragma unroll
     for (int x = 0; x < NA; ++x) qa[x] = *reinterpret_cast<const half8 *>(&s_q[mrow][32 * x + 8 * kc]);
-
-    // softmax bookkeeping for the 4 queries this lane sees in the MFMA result: m = 4*(kc&1) + r
-    const int mq0 = 4 * (kc & 1);
     float fq[4], m_run[4], l_run[4];
     int lim[4];
 #pragma unroll
@@ -168,73 +202,47 @@ __global__ void __launch_bounds__(ATT_WAVES * 64) attn_partial_kernel(AttnArgs a
         m_run[r] = -INFINITY;
         l_run[r] = 0.f;
     }
-    // P.V ownership: lane (dg, ks): columns 8dg..8dg+7, keys = tile key 4i + ks (D = 128) or 8i + ks (D = 64)
-    const int dg = lane % DG, ks = lane / DG;
-    float o[QG][8];
-#pragma unroll
-    for (int i = 0; i < QG; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[i][e] = 0.f;
 
-    const int last_row = n_total - 1;
-    auto load_tile = [&](int key0, half8 *kb, uint4 *vb) {
-        const int krow = min(key0 + mrow, last_row);
-        const __half *kp = Kh + static_cast<int64_t>(krow) * D + 8 * kc;
-#pragma unroll
-        for (int x = 0; x < NA; ++x) kb[x] = *reinterpret_cast<const half8 *>(kp + 32 * x);
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int vrow = min(key0 + KS * i + ks, last_row);
-            vb[i] = *reinterpret_cast<const uint4 *>(Vh + static_cast<int64_t>(vrow) * D + 8 * dg);
-        }
-    };
-
-    half8 kb0[NA], kb1[NA];
-    uint4 vb0[VPT], vb1[VPT];
-    const int tile_stride = ATT_WAVES * 16;
-    int key0 = p_begin + wave * 16;
-    if (key0 < p_end) load_tile(key0, kb0, vb0);
-
-    auto process = [&](int k0, const half8 *kb, const uint4 *vb) {
+    while (key0 < p_end) {
+        const int next = key0 + tile_stride;
         // logits of 16 keys x 16 A rows (8 high + 8 low query parts)
         v4f acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int x = 0; x < NA; ++x) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qa[x], kb[x], acc, 0, 0, 0);
         // rows 4kc..4kc+3 of column (key) mrow: add the low-part rows held 32 lanes away
-        float s[4], pr[4], corr[4];
-        const int key = k0 + mrow;
+        float pr[4], corr[4];
+        const int key = key0 + mrow;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            s[r] = (acc[r] + __shfl_xor(acc[r], 32, 64)) * fq[r];
-            if (key >= p_end || key > lim[r]) s[r] = -INFINITY;
-            float mx = s[r];
+            float sv = (acc[r] + __shfl_xor(acc[r], 32, 64)) * fq[r];
+            if (key >= p_end || key > lim[r]) sv = -INFINITY;
+            float mx = sv;
 #pragma unroll
             for (int off = 8; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
             const float mn = fmaxf(m_run[r], mx);
             corr[r] = (mn == -INFINITY) ? 1.f : __expf(m_run[r] - mn); // exp(-inf) = 0 on the first visible key
-            pr[r] = (s[r] == -INFINITY) ? 0.f : __expf(s[r] - mn);
+            pr[r] = (sv == -INFINITY) ? 0.f : __expf(sv - mn);
             float ps = pr[r];
 #pragma unroll
             for (int off = 8; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
             l_run[r] = l_run[r] * corr[r] + ps;
             m_run[r] = mn;
         }
+        if (next < p_end) load_k(next, kb);
         if (kc < 2) {
             *reinterpret_cast<float4 *>(&s_p[wave][mrow][mq0]) = make_float4(pr[0], pr[1], pr[2], pr[3]);
             if (mrow == 0) *reinterpret_cast<float4 *>(&s_corr[wave][mq0]) = make_float4(corr[0], corr[1], corr[2], corr[3]);
         }
         __builtin_amdgcn_wave_barrier();
         // P.V
-        float cr[QG];
 #pragma unroll
         for (int q = 0; q < QG; q += 4) {
             const float4 c4 = *reinterpret_cast<const float4 *>(&s_corr[wave][q]);
-            cr[q] = c4.x; cr[q + 1] = c4.y; cr[q + 2] = c4.z; cr[q + 3] = c4.w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                o[q][e] *= c4.x; o[q + 1][e] *= c4.y; o[q + 2][e] *= c4.z; o[q + 3][e] *= c4.w;
+            }
         }
-#pragma unroll
-        for (int q = 0; q < QG; ++q)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[q][e] *= cr[q];
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
             const int kt = KS * i + ks;
@@ -255,19 +263,8 @@ __global__ void __launch_bounds__(ATT_WAVES * 64) attn_partial_kernel(AttnArgs a
                 for (int e = 0; e < 8; ++e) o[q][e] = fmaf(pw[q], vf[e], o[q][e]);
         }
         __builtin_amdgcn_wave_barrier();
-    };
-
-    // tiles of this wave, double-buffered in registers
-    while (key0 < p_end) {
-        const int next = key0 + tile_stride;
-        if (next < p_end) load_tile(next, kb1, vb1);
-        process(key0, kb0, vb0);
+        if (next < p_end) load_v(next, vb);
         key0 = next;
-        if (key0 >= p_end) break;
-        const int next2 = key0 + tile_stride;
-        if (next2 < p_end) load_tile(next2, kb0, vb0);
-        process(key0, kb1, vb1);
-        key0 = next2;
     }
 
     // ---- merge the KS lane groups of the wave, then the waves ----

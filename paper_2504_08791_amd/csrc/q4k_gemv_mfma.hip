@@ -1,42 +1,51 @@
 // Dequant-fused Q4_K mat-vec on the matrix cores with exact integer accumulation (gfx950).
 //
 // The weight stream (the b bytes per layer of arXiv 2504.08791, App. A.3) is what bounds decode;
-// the arithmetic has to hide behind it.  At 8 TB/s a CU receives ~26 four-bit weights per clock
-// but its vector ALUs issue 64 lane-operations per clock, so a multiply-add per weight per token
-// plus the nibble unpacking does not fit.  The multiply-adds run on the MFMA units instead:
+// everything else has to hide behind it.
 //
+// Arithmetic.  At 8 TB/s a CU receives ~26 four-bit weights per clock but its vector ALUs issue 64
+// lane-operations per clock, so a multiply-add per weight per token plus the nibble unpacking does
+// not fit.  The multiply-adds run on the MFMA units instead:
 //  * each activation vector is turned into block fixed point once per mat-vec: x = xfix * 2^-p,
 //    |xfix| < 2^30, split into four signed 8-bit digits (xfix = sum_r digit_r * 256^r);
-//  * a wave owns 16 output rows; lane (j, g) = (lane % 16, lane / 16) loads the 16-byte quant
-//    chunk of row j, sub-block s0+g (128-bit loads; one instruction covers 16 rows x 64 B), splits
-//    it into two int8 vectors with three ALU ops per 8 weights, and feeds them as the B operand of
-//    v_mfma_i32_16x16x32_i8;
+//  * a wave owns 16 output rows; lane (j, g) = (lane % 16, lane / 16) takes the 16-byte quant chunk
+//    of row j, sub-block s0+g, splits it into two int8 vectors with three ALU ops per 8 weights and
+//    feeds them as the B operand of v_mfma_i32_16x16x32_i8;
 //  * the A operand holds the digits, arranged block-diagonally: output slot 4g'+r carries digit r
-//    restricted to k-group g'.  The MFMA result on lane (j, g) is then exactly the four digit
-//    sums of row j with *its own* sub-block s0+g: sum_k q_k * digit_r(x_k);
+//    restricted to k-group g'.  The MFMA result on lane (j, g) is then exactly the four digit sums
+//    of row j with *its own* sub-block s0+g: sum_k q_k * digit_r(x_k);
 //  * the 6-bit sub-scale multiplies these integers (still exact), the four digits are recombined
 //    in fp32, and d (fp16) scales the super-block.  The min term uses per-sub-block sums of xfix:
 //        y = 2^-p * sum_blocks [ d * sum_s sc_s * (q . xfix)_s  -  dmin * sum_s m_s * Xsum_s ].
 //    For T tokens the unpacked weights are reused against each token's digits.
 //
-// Launch shape: one 1024-thread workgroup per compute unit, persistent.  Each workgroup owns a
-// contiguous range of 16-row tiles with all of K, so no result crosses workgroups and every sum
-// has a fixed order (bit-reproducible).  The activations are transformed (RMSNorm or SwiGLU when
-// asked), quantised and laid out in LDS by every workgroup for itself; the 16 waves then stream
-// (tile, K-piece) units, three super-blocks of loads in flight per wave, and leave per-unit
-// partial sums in LDS that the epilogue adds in piece order.
+// Data movement.  One 512-thread workgroup per compute unit, persistent; it owns a contiguous range
+// of 16-row tiles with all of K, so no sum crosses workgroups and every sum has a fixed order.
+// Each wave streams its share of the weights through a private three-stage LDS ring filled by
+// 128-bit global->LDS loads (no VGPR staging): a stage is 16 rows x 2 super-blocks, requested as
+// runs of 288 contiguous bytes per row, laid out with an odd row stride so that the MFMA-order
+// reads (lane (j, g) reads row j) are free of bank conflicts.  Two stages are always in flight
+// per wave while the third is consumed; only s_waitcnt orders them, no barrier.  The activations
+// are transformed (RMSNorm or SwiGLU when asked), quantised and laid out in LDS by every
+// workgroup for itself, slab by slab when K is too long for the LDS left over by the rings.
 #include "common.h"
 
 namespace prima {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int SUB_LDS = 144;   // bytes of LDS per sub-block of digits: 4 digits x 32 B + 16 B skew
-constexpr int MAX_WAVES = 16;
-// workgroup size: 16 waves leave 128 VGPRs per lane, enough for up to 4 tokens' accumulators next to
-// the three load stages; 5..8 tokens run 8 waves with 256 VGPRs
-constexpr int threads_for(int tt) { return tt <= 4 ? 1024 : 512; }
+constexpr int GEMV_THREADS = 512;
+constexpr int GEMV_WAVES = GEMV_THREADS / 64;
+constexpr int NST = 3;                       // ring stages per wave
+constexpr int PBS = 2;                       // super-blocks per stage
+constexpr int RS = 9 * PBS + 1;              // row stride of a stage in 16-byte slots (odd)
+constexpr int STAGE_SLOTS = 16 * RS;         // 304
+constexpr int NI = (STAGE_SLOTS + 63) / 64;  // load instructions per stage (5; the last one uses 48 lanes)
+constexpr int STAGE_BYTES = STAGE_SLOTS * 16;
+constexpr int RING_BYTES = GEMV_WAVES * NST * STAGE_BYTES;
+constexpr int SUB_BYTES = 128;               // digits of one sub-block: 4 digits x 32 values
 constexpr size_t LDS_BUDGET = 160 * 1024;
+constexpr int MAX_T_PASS = 8;                // tokens per pass over the weights
 
 struct PGemvArgs {
     GemvSeg seg[3];
@@ -49,23 +58,29 @@ struct PGemvArgs {
     float eps;
     float *x_tap; // optional [T][K]: transformed fp32 activations (written by workgroup 0)
     // decomposition
-    int pb;          // super-blocks per unit (K-piece)
-    int ppt;         // pieces per tile
-    int pps;         // pieces per slab
-    int n_slabs;     // K slabs staged in LDS one after the other
+    int ksplit;      // waves sharing a tile: unit = (tile, part), part p takes chunks p, p+ksplit, ...
+    int slab_blocks; // super-blocks of activations staged in LDS at a time (even)
+    int n_slabs;
     int units_cap;   // partial-sum slots per workgroup
     int n_wg;
 };
 
-struct BlockRegs {
-    uint4 hdr, qa, qb;
-};
-
-__device__ __forceinline__ void load_block(BlockRegs &r, const uint4 *bp, int g)
+// 16 bytes per lane from global memory straight into LDS: lane l writes bytes [16 l, 16 l + 16) of the
+// 1 KiB at LDS byte address lds_addr (wave-uniform, goes through M0).  Written as inline assembly on
+// purpose: the compiler then does not know these loads write LDS and leaves the ordering against the
+// later LDS reads to the explicit s_waitcnt vmcnt(N) below, which lets newer stages stay in flight
+// (with the builtin it waits for *all* outstanding loads before any LDS read).  Loads complete in
+// order, so loads the compiler does not know about can only make its own waits stricter.
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
 {
-    r.hdr = bp[0];
-    r.qa = bp[1 + g];
-    r.qb = bp[5 + g];
+    // one wait state is required between the SALU write of M0 and the load that reads it; M0 is a reserved
+    // register that nothing else in this file uses
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)); // low half of a flat LDS pointer is the LDS byte address
 }
 
 __device__ __forceinline__ long pack64(uint32_t lo, uint32_t hi)
@@ -73,7 +88,6 @@ __device__ __forceinline__ long pack64(uint32_t lo, uint32_t hi)
     return static_cast<long>(static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32));
 }
 
-template <int GEMV_WAVES>
 __device__ __forceinline__ float wg_reduce(float v, float *red, bool is_max)
 {
 #pragma unroll
@@ -90,8 +104,9 @@ __device__ __forceinline__ float wg_reduce(float v, float *red, bool is_max)
     return r;
 }
 
-// eight consecutive transformed activations of token t starting at column c0
-__device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, float inv_rms, float *f)
+// eight consecutive activations of token t starting at column c0, before the RMSNorm scale:
+// X_PLAIN x, X_RMSNORM x*gain (the 1/rms factor is applied by the caller), X_SWIGLU silu(x)*x2
+__device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, float *f)
 {
     const float *xp = a.x + t * a.ldx + c0;
     const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
@@ -100,7 +115,7 @@ __device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, flo
         const float4 g0 = *reinterpret_cast<const float4 *>(a.gain + c0), g1 = *reinterpret_cast<const float4 *>(a.gain + c0 + 4);
         const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = f[e] * inv_rms * gg[e];
+        for (int e = 0; e < 8; ++e) f[e] *= gg[e];
     } else if (a.xmode == X_SWIGLU) {
         const float *up = a.x2 + t * a.ldx + c0;
         const float4 u0 = *reinterpret_cast<const float4 *>(up), u1 = *reinterpret_cast<const float4 *>(up + 4);
@@ -110,13 +125,18 @@ __device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, flo
     }
 }
 
+// position of a wave in its stream of stages: slab -> unit (tile, part) -> chunk of PBS super-blocks
+struct Cursor {
+    int slab, u, c;
+    bool valid;
+};
+
 template <int TT>
-__global__ void __launch_bounds__(threads_for(TT)) gemv_q4k_persistent_kernel(PGemvArgs a)
+__global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemvArgs a)
 {
-    constexpr int GEMV_THREADS = threads_for(TT);
-    constexpr int GEMV_WAVES = GEMV_THREADS / 64;
     extern __shared__ __align__(16) uint8_t smem[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15, g = lane >> 4;
     const int K = a.nb * QK;
 
@@ -125,94 +145,166 @@ __global__ void __launch_bounds__(threads_for(TT)) gemv_q4k_persistent_kernel(PG
     const int tl1 = static_cast<int>(static_cast<int64_t>(a.n_tiles) * (blockIdx.x + 1) / a.n_wg);
     const int ntl = tl1 - tl0;
     if (ntl == 0) return;
+    const int n_units = ntl * a.ksplit;
 
-    // LDS carve: digits [TT][slab_sub][SUB_LDS] | zeros 32 B | xsum [TT][slab_sub] | partial [units_cap][TT][16] | red[16] | stats
-    const int slab_blocks = a.pps * a.pb;
-    const int slab_sub = slab_blocks * 8;
-    uint8_t *l_dig = smem;
-    const int dig_t_stride = slab_sub * SUB_LDS;
-    const int zero_off = TT * dig_t_stride;
-    float *l_xs = reinterpret_cast<float *>(smem + zero_off + 32);
+    // LDS carve: rings | 32 zero bytes | digits [TT][slab_sub][128] | xsum [TT][slab_sub] | partial [units_cap][TT][16] | red[16] | stats [3 TT]
+    const int slab_sub = a.slab_blocks * 8;
+    uint8_t *l_ring = smem + wave * (NST * STAGE_BYTES);
+    uint8_t *l_zero = smem + RING_BYTES;      // 32 zero bytes: the A operand of lanes that carry no digits
+    uint8_t *l_dig = l_zero + 32;
+    const int dig_t_stride = slab_sub * SUB_BYTES;
+    float *l_xs = reinterpret_cast<float *>(l_dig + TT * dig_t_stride);
     float *l_part = l_xs + TT * slab_sub;
     float *l_red = l_part + a.units_cap * TT * 16;
-    float *l_scale = l_red + MAX_WAVES;   // [TT] 2^p
-    float *l_inv = l_scale + TT;           // [TT] 2^-p
-    float *l_rms = l_inv + TT;             // [TT] 1/rms
+    float *l_scale = l_red + 16;  // [TT] 2^p (times 1/rms for RMSNorm input)
+    float *l_inv = l_scale + TT;  // [TT] 2^-p
 
-    if (threadIdx.x < 8) reinterpret_cast<uint32_t *>(smem + zero_off)[threadIdx.x] = 0u;
+    // ---- stream geometry (wave-uniform) ----
+    const int cps_full = a.slab_blocks / PBS; // chunks per full slab
+    auto slab_chunks = [&](int slab) {
+        const int blocks = min(a.slab_blocks, a.nb - slab * a.slab_blocks);
+        return (blocks + PBS - 1) / PBS;
+    };
+    auto normalize = [&](Cursor &c) {
+        for (;;) {
+            if (c.slab >= a.n_slabs) { c.valid = false; return; }
+            if (c.u >= n_units) { ++c.slab; c.u = wave; c.c = c.u % a.ksplit; continue; }
+            if (c.c >= slab_chunks(c.slab)) { c.u += GEMV_WAVES; c.c = c.u % a.ksplit; continue; }
+            c.valid = true;
+            return;
+        }
+    };
+    auto advance = [&](Cursor &c) { c.c += a.ksplit; normalize(c); };
+    (void)cps_full;
+
+    // per-lane slot decomposition of the NI load instructions of a stage: slot = i*64 + lane -> (row r, chunk c)
+    int slot_r[NI], slot_c[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int slot = i * 64 + lane;
+        const int r = slot / RS;
+        slot_r[i] = r < 16 ? r : 15;
+        slot_c[i] = slot - r * RS; // RS-1 is the padding slot
+    }
+    const int64_t pitch16 = static_cast<int64_t>(a.nb) * 9; // row pitch in 16-byte units
+
+    // request the stage at cursor c into ring stage st: exactly NI load instructions, always
+    auto issue = [&](const Cursor &c, int st) {
+        const int tile = tl0 + c.u / a.ksplit;
+        int sg = 0;
+        while (sg + 1 < a.nseg && tile >= a.seg_tile0[sg + 1]) ++sg;
+        const int64_t row0 = static_cast<int64_t>(tile - a.seg_tile0[sg]) * 16;
+        const int rows_valid = static_cast<int>(min<int64_t>(16, a.seg[sg].n_rows - row0));
+        const int blk0 = c.slab * a.slab_blocks + c.c * PBS;
+        const int ncol = 9 * min(PBS, a.nb - blk0); // valid 16-byte chunks per row in this stage
+        const uint4 *base = reinterpret_cast<const uint4 *>(a.seg[sg].W) + row0 * pitch16 + static_cast<int64_t>(blk0) * 9;
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_address(l_ring + st * STAGE_BYTES));
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads of the stage being overwritten have returned
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            // rows past the end of the matrix and chunks past the end of the row re-read valid data
+            const int r = min(slot_r[i], rows_valid - 1);
+            const int cc = min(slot_c[i], ncol - 1);
+            const uint4 *src = base + r * pitch16 + cc;
+            if (i * 64 + 63 < STAGE_SLOTS || lane < STAGE_SLOTS - i * 64)
+                dma16(src, dst + i * 1024);
+        }
+    };
+
+    // ---- start the weight stream before touching the activations ----
+    Cursor lc;
+    lc.slab = 0; lc.u = wave; lc.c = lc.u % a.ksplit; lc.valid = false;
+    normalize(lc);
+    int issued = 0;
+    for (int s = 0; s < NST - 1 && lc.valid; ++s) {
+        issue(lc, s);
+        advance(lc);
+        ++issued;
+    }
+
+    // zero the partial sums and the zero operand
+    if (threadIdx.x < 8) reinterpret_cast<uint32_t *>(l_zero)[threadIdx.x] = 0u;
+    for (int i = threadIdx.x; i < n_units * TT * 16; i += GEMV_THREADS) l_part[i] = 0.f;
 
     // ---- statistics of the activations: 1/rms (RMSNorm input) and the power-of-two scale ----
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
-        float inv_rms = 1.f;
-        if (a.xmode == X_RMSNORM) {
-            float ss = 0.f;
-            for (int gi = threadIdx.x; gi < K / 8; gi += GEMV_THREADS) {
+        float ss = 0.f, amax = 0.f;
+        for (int gi = threadIdx.x; gi < K / 8; gi += GEMV_THREADS) {
+            float f[8];
+            if (a.xmode == X_RMSNORM) {
                 const float *xp = a.x + t * a.ldx + gi * 8;
                 const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
                 ss += ((v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w)) + ((v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w));
             }
-            ss = wg_reduce<GEMV_WAVES>(ss, l_red, false);
-            inv_rms = 1.0f / sqrtf(ss / static_cast<float>(K) + a.eps);
-        }
-        float amax = 0.f;
-        for (int gi = threadIdx.x; gi < K / 8; gi += GEMV_THREADS) {
-            float f[8];
-            load_act8(a, t, gi * 8, inv_rms, f);
+            load_act8(a, t, gi * 8, f);
 #pragma unroll
             for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
         }
-        amax = wg_reduce<GEMV_WAVES>(amax, l_red, true);
+        float inv_rms = 1.f;
+        if (a.xmode == X_RMSNORM) {
+            ss = wg_reduce(ss, l_red, false);
+            inv_rms = 1.0f / sqrtf(ss / static_cast<float>(K) + a.eps);
+        }
+        amax = wg_reduce(amax, l_red, true) * inv_rms; // max |x*gain| / rms
         int ex = 0;
-        if (amax > 0.f) frexpf(amax, &ex); // amax = m * 2^ex, m in [0.5, 1)  ->  |x| * 2^(30-ex) < 2^30
-        int p = 30 - ex;
+        if (amax > 0.f) frexpf(amax, &ex); // amax = m * 2^ex, m in [0.5, 1)
+        // |v| * 2^(29-ex) < 2^29 leaves room for the rounding of (x*gain)*(inv_rms*2^p) against x*gain*inv_rms
+        int p = 29 - ex;
         p = p > 120 ? 120 : p;
         if (threadIdx.x == 0) {
-            l_scale[t] = ldexpf(1.0f, p);
+            l_scale[t] = ldexpf(inv_rms, p);
             l_inv[t] = ldexpf(1.0f, -p);
-            l_rms[t] = inv_rms;
         }
     }
     __syncthreads();
 
-    // lanes whose output slots hold this lane's k-group carry digits; all others feed zeros
+    // lanes whose output slots hold this lane's k-group carry digits; all others feed zeros.
+    // Digit r of sub-block S sits at byte ((r + S) & 3) * 32 of its 128 bytes (S = s0 + g with s0 % 4 == 0),
+    // so the 16 reading lanes (4 k-groups x 4 digits) fall into different banks.
     const bool active = (j >> 2) == g;
-    const int a_base = active ? g * SUB_LDS + (j & 3) * 32 : zero_off;
-    const int a_step = active ? SUB_LDS : 0;
-    const int a_tstep = active ? dig_t_stride : 0;
+    const int a_lane = active ? 32 + g * SUB_BYTES + (((j & 3) + g) & 3) * 32 : 0; // byte offset from l_zero
+    const int a_mul = active ? 1 : 0;                                              // inactive lanes stay on the zeros
     const int fsh = 6 * g;
-    const int64_t pitch16 = static_cast<int64_t>(a.nb) * 9; // row pitch in 16-byte units
+
+    Cursor cc;
+    cc.slab = 0; cc.u = wave; cc.c = cc.u % a.ksplit; cc.valid = false;
+    normalize(cc);
+    int step = 0, st = 0;
+
+    float yacc[TT], macc[TT];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) { yacc[t] = 0.f; macc[t] = 0.f; }
 
     for (int slab = 0; slab < a.n_slabs; ++slab) {
-        const int p0 = slab * a.pps;                       // first piece of the slab
-        const int p1 = min(p0 + a.pps, a.ppt);
-        const int sb0 = p0 * a.pb;                         // first super-block of the slab
-        const int sb1 = min(p1 * a.pb, a.nb);
-        if (slab > 0) __syncthreads();                     // previous slab's digits no longer in use
+        const int sb0 = slab * a.slab_blocks;
+        const int sb1 = min(sb0 + a.slab_blocks, a.nb);
+        if (slab > 0) __syncthreads(); // previous slab's digits no longer in use
 
         // ---- transform + quantise this slab's activations into LDS ----
         // digits [S][4][32 bytes]; byte order inside a digit row: for each group a of 8 values,
         // values 8a + {0,2,4,6,1,3,5,7}, the order in which the nibble split delivers the weights.
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
-            const float S = l_scale[t], inv_rms = l_rms[t];
+            const float S = l_scale[t];
             for (int gi = sb0 * 32 + threadIdx.x; gi < sb1 * 32; gi += GEMV_THREADS) {
                 float f[8];
-                load_act8(a, t, gi * 8, inv_rms, f);
+                load_act8(a, t, gi * 8, f);
                 if (a.x_tap && blockIdx.x == 0) {
+                    const float unq = S * l_inv[t]; // 1/rms for RMSNorm input, 1 otherwise
                     float *tp = a.x_tap + static_cast<int64_t>(t) * K + gi * 8;
-                    *reinterpret_cast<float4 *>(tp) = make_float4(f[0], f[1], f[2], f[3]);
-                    *reinterpret_cast<float4 *>(tp + 4) = make_float4(f[4], f[5], f[6], f[7]);
+                    *reinterpret_cast<float4 *>(tp) = make_float4(f[0] * unq, f[1] * unq, f[2] * unq, f[3] * unq);
+                    *reinterpret_cast<float4 *>(tp + 4) = make_float4(f[4] * unq, f[5] * unq, f[6] * unq, f[7] * unq);
                 }
                 int r[8];
                 long long sum = 0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    r[e] = static_cast<int>(rintf(f[e] * S)); // power-of-two scaling is exact; one rounding to integer
+                    r[e] = static_cast<int>(rintf(f[e] * S)); // one rounding to integer
                     sum += r[e];
                 }
-                const int s_loc = (gi >> 2) - sb0 * 8, grp = gi & 3;
-                uint8_t *dp = l_dig + t * dig_t_stride + s_loc * SUB_LDS + grp * 8;
+                const int s_glob = gi >> 2, s_loc = s_glob - sb0 * 8, grp = gi & 3;
+                uint8_t *dp = l_dig + t * dig_t_stride + s_loc * SUB_BYTES + grp * 8;
 #pragma unroll
                 for (int dg = 0; dg < 4; ++dg) {
                     uint32_t by[8];
@@ -225,7 +317,7 @@ __global__ void __launch_bounds__(threads_for(TT)) gemv_q4k_persistent_kernel(PG
                     uint2 o;
                     o.x = by[0] | (by[2] << 8) | (by[4] << 16) | (by[6] << 24);
                     o.y = by[1] | (by[3] << 8) | (by[5] << 16) | (by[7] << 24);
-                    *reinterpret_cast<uint2 *>(dp + dg * 32) = o;
+                    *reinterpret_cast<uint2 *>(dp + ((dg + s_glob) & 3) * 32) = o;
                 }
                 sum += __shfl_xor(sum, 1, 64);
                 sum += __shfl_xor(sum, 2, 64);
@@ -234,55 +326,43 @@ __global__ void __launch_bounds__(threads_for(TT)) gemv_q4k_persistent_kernel(PG
         }
         __syncthreads();
 
-        // ---- stream the (tile, piece) units of this slab ----
-        const int pps_here = p1 - p0;
-        const int n_units = ntl * pps_here;
+        // ---- consume this wave's stages of the slab ----
+        while (cc.valid && cc.slab == slab) {
+            if (lc.valid) {
+                issue(lc, (st + NST - 1) % NST);
+                advance(lc);
+                ++issued;
+            }
+            const int newer = issued - (step + 1); // stages requested after the one consumed now
+            if (newer >= 2) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+            else if (newer == 1) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            static_assert(NI == 5 && NST == 3, "the vmcnt immediates above assume 5 loads per stage, 3 stages");
 
-        struct Cursor {
-            int k, b, b_end, tile_local, piece;
-            const uint4 *rowp;
-        };
-        auto seek = [&](Cursor &c) { // position on unit c.k (must be < n_units)
-            c.tile_local = c.k / pps_here;
-            c.piece = p0 + (c.k - c.tile_local * pps_here);
-            c.b = c.piece * a.pb;
-            c.b_end = min(c.b + a.pb, sb1);
-            const int tile = tl0 + c.tile_local;
-            int sg = 0;
-            while (sg + 1 < a.nseg && tile >= a.seg_tile0[sg + 1]) ++sg;
-            const int64_t row = static_cast<int64_t>(tile - a.seg_tile0[sg]) * 16 + j;
-            const int64_t row_ld = row < a.seg[sg].n_rows ? row : a.seg[sg].n_rows - 1; // rows past the end re-read the last row
-            c.rowp = reinterpret_cast<const uint4 *>(a.seg[sg].W) + row_ld * pitch16;
-        };
-        auto advance = [&](Cursor &c) { // next super-block of this wave's stream; sticks on the last one
-            if (c.b + 1 < c.b_end) { ++c.b; return; }
-            if (c.k + GEMV_WAVES < n_units) { c.k += GEMV_WAVES; seek(c); }
-        };
-
-        if (wave < n_units) {
-            float yacc[TT], macc[TT];
+            const int blk0 = sb0 + cc.c * PBS;
+            const int nblk = min(PBS, a.nb - blk0);
+            const uint4 *stage = reinterpret_cast<const uint4 *>(l_ring + st * STAGE_BYTES) + j * RS;
 #pragma unroll
-            for (int t = 0; t < TT; ++t) { yacc[t] = 0.f; macc[t] = 0.f; }
-
-            // one super-block against all tokens: 8 MFMAs per token + integer sub-scales + fp32 recombination
-            auto compute = [&](const BlockRegs &c, int b) {
-                const uint32_t w[8] = {c.qa.x, c.qa.y, c.qa.z, c.qa.w, c.qb.x, c.qb.y, c.qb.z, c.qb.w};
+            for (int b = 0; b < PBS; ++b) {
+                if (b >= nblk) break;
+                const uint4 hdr = stage[b * 9], qa = stage[b * 9 + 1 + g], qb = stage[b * 9 + 5 + g];
+                const uint32_t w[8] = {qa.x, qa.y, qa.z, qa.w, qb.x, qb.y, qb.z, qb.w};
                 long B[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) B[i] = pack64(w[i] & 0x0f0f0f0fu, (w[i] >> 4) & 0x0f0f0f0fu); // weights 8i+{0,2,4,6 | 1,3,5,7}
-                const int sc0 = static_cast<int>(__builtin_amdgcn_ubfe(c.hdr.y, fsh, 6));
-                const int sc1 = static_cast<int>(__builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(c.hdr.z, c.hdr.y, 24), fsh, 6));
-                const float m0 = static_cast<float>(__builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(c.hdr.w, c.hdr.z, 16), fsh, 6));
-                const float m1 = static_cast<float>(__builtin_amdgcn_ubfe(c.hdr.w, 8 + fsh, 6));
-                const float d = hdr_d(c.hdr), dmin = hdr_dmin(c.hdr);
-                const int s_loc = (b - sb0) * 8;
+                const int sc0 = static_cast<int>(__builtin_amdgcn_ubfe(hdr.y, fsh, 6));
+                const int sc1 = static_cast<int>(__builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(hdr.z, hdr.y, 24), fsh, 6));
+                const float m0 = static_cast<float>(__builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(hdr.w, hdr.z, 16), fsh, 6));
+                const float m1 = static_cast<float>(__builtin_amdgcn_ubfe(hdr.w, 8 + fsh, 6));
+                const float d = hdr_d(hdr), dmin = hdr_dmin(hdr);
+                const int s_loc = (blk0 + b - sb0) * 8;
 #pragma unroll
                 for (int t = 0; t < TT; ++t) {
-                    const uint8_t *ap = l_dig + a_base + t * a_tstep + s_loc * a_step;
+                    const uint8_t *ap = l_zero + a_lane + (t * dig_t_stride + s_loc * SUB_BYTES) * a_mul;
                     const uint4 x0 = *reinterpret_cast<const uint4 *>(ap);
                     const uint4 x1 = *reinterpret_cast<const uint4 *>(ap + 16);
-                    const uint4 x2 = *reinterpret_cast<const uint4 *>(ap + 4 * a_step);
-                    const uint4 x3 = *reinterpret_cast<const uint4 *>(ap + 4 * a_step + 16);
+                    const uint4 x2 = *reinterpret_cast<const uint4 *>(ap + 4 * SUB_BYTES * a_mul);
+                    const uint4 x3 = *reinterpret_cast<const uint4 *>(ap + 4 * SUB_BYTES * a_mul + 16);
                     v4i d0 = {0, 0, 0, 0}, d1 = {0, 0, 0, 0};
                     d0 = __builtin_amdgcn_mfma_i32_16x16x32_i8(pack64(x0.x, x0.y), B[0], d0, 0, 0, 0);
                     d1 = __builtin_amdgcn_mfma_i32_16x16x32_i8(pack64(x2.x, x2.y), B[4], d1, 0, 0, 0);
@@ -304,64 +384,36 @@ __global__ void __launch_bounds__(threads_for(TT)) gemv_q4k_persistent_kernel(PG
                     const float *xs = l_xs + t * slab_sub + s_loc;
                     macc[t] = fmaf(dmin, fmaf(m0, xs[g], m1 * xs[4 + g]), macc[t]);
                 }
-            };
-            // leave the unit's sums in its LDS slot: [unit][t][row]
-            auto flush = [&](const Cursor &c) {
-                float *slot = l_part + (c.tile_local * a.ppt + c.piece) * (TT * 16);
+            }
+
+            // next stage of this wave; leave the unit's sums in its slot when the unit (or the slab) ends
+            const int u_done = cc.u;
+            advance(cc);
+            if (!cc.valid || cc.u != u_done || cc.slab != slab) {
+                float *slot = l_part + u_done * (TT * 16);
 #pragma unroll
                 for (int t = 0; t < TT; ++t) {
                     float v = yacc[t] - macc[t];
                     v += __shfl_xor(v, 16, 64);
                     v += __shfl_xor(v, 32, 64);
-                    if (g == 0) slot[t * 16 + j] = v;
+                    if (g == 0) slot[t * 16 + j] += v;
                     yacc[t] = 0.f;
                     macc[t] = 0.f;
                 }
-            };
-
-            Cursor cc, lc; // compute cursor and load cursor (two super-blocks ahead)
-            cc.k = wave;
-            seek(cc);
-            lc = cc;
-            BlockRegs r0, r1, r2;
-            load_block(r0, lc.rowp + lc.b * 9, g);
-            advance(lc);
-            load_block(r1, lc.rowp + lc.b * 9, g);
-            advance(lc);
-            // blocks this wave computes in the slab
-            int remaining = 0;
-            for (int k = wave; k < n_units; k += GEMV_WAVES) {
-                const int piece = p0 + k % pps_here;
-                remaining += min(piece * a.pb + a.pb, sb1) - piece * a.pb;
             }
-            auto step = [&](BlockRegs &use, BlockRegs &refill) {
-                load_block(refill, lc.rowp + lc.b * 9, g);
-                advance(lc);
-                compute(use, cc.b);
-                if (cc.b + 1 == cc.b_end) {
-                    flush(cc);
-                    if (cc.k + GEMV_WAVES < n_units) { cc.k += GEMV_WAVES; seek(cc); }
-                } else {
-                    ++cc.b;
-                }
-                --remaining;
-            };
-            while (remaining > 0) {
-                step(r0, r2);
-                if (remaining > 0) step(r1, r0);
-                if (remaining > 0) step(r2, r1);
-            }
+            st = (st + 1) % NST;
+            ++step;
         }
     }
     __syncthreads();
 
-    // ---- epilogue: add the pieces of every (tile, row, token) in piece order, scale, residual, store ----
+    // ---- epilogue: add the parts of every (tile, row, token) in part order, scale, residual, store ----
     for (int idx = threadIdx.x; idx < ntl * 16 * TT; idx += GEMV_THREADS) {
         const int tile_local = idx / (16 * TT);
         const int rem = idx - tile_local * (16 * TT);
         const int t = rem >> 4, jj = rem & 15;
         float v = 0.f;
-        for (int p = 0; p < a.ppt; ++p) v += l_part[(tile_local * a.ppt + p) * (TT * 16) + t * 16 + jj];
+        for (int p = 0; p < a.ksplit; ++p) v += l_part[(tile_local * a.ksplit + p) * (TT * 16) + t * 16 + jj];
         const int tile = tl0 + tile_local;
         int sg = 0;
         while (sg + 1 < a.nseg && tile >= a.seg_tile0[sg + 1]) ++sg;
@@ -376,7 +428,7 @@ __global__ void __launch_bounds__(threads_for(TT)) gemv_q4k_persistent_kernel(PG
 
 // ------------------------------------------------------------------------------------------
 struct PPlan {
-    int n_tiles, nb, n_wg, pb, ppt, pps, n_slabs, units_cap;
+    int n_tiles, nb, n_wg, ksplit, slab_blocks, n_slabs, units_cap;
     size_t lds_bytes;
     bool ok;
 };
@@ -393,10 +445,9 @@ static int device_cu_count()
     return cus;
 }
 
-static size_t plan_lds(int T, int slab_blocks, int units_cap)
+static size_t fixed_lds(int T, int units_cap)
 {
-    return static_cast<size_t>(T) * slab_blocks * 8 * SUB_LDS + 32 + static_cast<size_t>(T) * slab_blocks * 8 * 4 +
-           static_cast<size_t>(units_cap) * T * 16 * 4 + (MAX_WAVES + 3 * T) * 4 + 64;
+    return RING_BYTES + 32 + static_cast<size_t>(units_cap) * T * 16 * 4 + (16 + 2 * T) * 4 + 64;
 }
 
 static PPlan plan_persistent(const GemvArgs &ga, int T)
@@ -408,20 +459,30 @@ static PPlan plan_persistent(const GemvArgs &ga, int T)
     p.n_wg = device_cu_count();
     if (p.n_wg > p.n_tiles) p.n_wg = p.n_tiles;
     const int tiles_wg = (p.n_tiles + p.n_wg - 1) / p.n_wg;
-    // super-blocks per unit: spread a workgroup's super-blocks over its 16 waves, 2..16 per unit
-    int pb = tiles_wg * p.nb / (threads_for(T) / 64);
-    pb = pb < 2 ? 2 : (pb > 16 ? 16 : pb);
-    if (pb > p.nb) pb = p.nb;
-    p.ppt = (p.nb + pb - 1) / pb;
-    p.pb = (p.nb + p.ppt - 1) / p.ppt;
-    p.ppt = (p.nb + p.pb - 1) / p.pb;
-    p.units_cap = tiles_wg * p.ppt;
-    // pieces per slab: as many as fit in LDS
-    p.pps = p.ppt;
-    while (p.pps > 1 && plan_lds(T, p.pps * p.pb, p.units_cap) > LDS_BUDGET) --p.pps;
-    p.n_slabs = (p.ppt + p.pps - 1) / p.pps;
-    p.lds_bytes = plan_lds(T, p.pps * p.pb, p.units_cap);
-    p.ok = p.lds_bytes <= LDS_BUDGET;
+    const int chunks = (p.nb + PBS - 1) / PBS;
+    // waves per tile: the smallest of 1, 2, 4, 8 that gives every wave a unit and spreads the units evenly
+    int best = 1;
+    double best_eff = 0.0;
+    for (int ks = 1; ks <= GEMV_WAVES; ks *= 2) {
+        if (ks > chunks) break;
+        const int units = tiles_wg * ks;
+        const int rounds = (units + GEMV_WAVES - 1) / GEMV_WAVES;
+        const double eff = static_cast<double>(units) / (rounds * GEMV_WAVES);
+        if (eff > best_eff + 1e-9) { best_eff = eff; best = ks; }
+    }
+    p.ksplit = best;
+    p.units_cap = tiles_wg * p.ksplit;
+    // activations staged per slab: as many super-blocks (even) as the LDS left by rings and partial sums holds
+    const size_t fixed = fixed_lds(T, p.units_cap);
+    const size_t per_block = static_cast<size_t>(T) * 8 * (SUB_BYTES + 4);
+    int cap = fixed < LDS_BUDGET ? static_cast<int>((LDS_BUDGET - fixed) / per_block) : 0;
+    cap &= ~1;
+    p.ok = cap >= 2;
+    if (!p.ok) return p;
+    p.n_slabs = (p.nb + cap - 1) / cap;
+    p.slab_blocks = ((p.nb + p.n_slabs - 1) / p.n_slabs + 1) & ~1;
+    p.n_slabs = (p.nb + p.slab_blocks - 1) / p.slab_blocks;
+    p.lds_bytes = fixed + per_block * p.slab_blocks;
     return p;
 }
 
@@ -435,17 +496,15 @@ static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemv_q4k_persistent_kernel<TT>, dim3(p.n_wg), dim3(threads_for(TT)), p.lds_bytes, st, a);
+    hipLaunchKernelGGL(gemv_q4k_persistent_kernel<TT>, dim3(p.n_wg), dim3(GEMV_THREADS), p.lds_bytes, st, a);
     return hipGetLastError();
 }
 
-size_t gemv_mfma_ws_bytes(int64_t, int64_t, int) { return 256; }
-
 prima_status launch_gemv_mfma(const GemvArgs &ga, hipStream_t st)
 {
-    // up to 8 tokens per pass over the weights
-    for (int t0 = 0; t0 < ga.T; t0 += 8) {
-        const int T = ga.T - t0 < 8 ? ga.T - t0 : 8;
+    // up to MAX_T_PASS tokens per pass over the weights
+    for (int t0 = 0; t0 < ga.T; t0 += MAX_T_PASS) {
+        const int T = ga.T - t0 < MAX_T_PASS ? ga.T - t0 : MAX_T_PASS;
         const PPlan p = plan_persistent(ga, T);
         if (!p.ok) return PRIMA_E_SHAPE;
         PGemvArgs a{};
@@ -468,9 +527,8 @@ prima_status launch_gemv_mfma(const GemvArgs &ga, hipStream_t st)
         a.ldx = ga.ldx;
         a.eps = ga.eps;
         a.x_tap = ga.x_tap ? ga.x_tap + static_cast<int64_t>(t0) * ga.n_cols : nullptr;
-        a.pb = p.pb;
-        a.ppt = p.ppt;
-        a.pps = p.pps;
+        a.ksplit = p.ksplit;
+        a.slab_blocks = p.slab_blocks;
         a.n_slabs = p.n_slabs;
         a.units_cap = p.units_cap;
         a.n_wg = p.n_wg;
