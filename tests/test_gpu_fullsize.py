@@ -1,0 +1,80 @@
+"""GPU parity at the benchmark configurations' full shapes, in the launch configuration bench.py
+times (same Window object, same kv_cap = n_past + T), against the CPU oracle on the same seeded
+tensors.  Windows are cut to their first layers so that the CPU side stays within seconds; the
+full 20-layer window of config 3 is compared inside bench.py itself (max_rel_err_vs_oracle)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from metrics import rel_err
+from workloads import synth
+from workloads.configs import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+HID_TOL = 2e-3
+ATT_TOL = 1e-3
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.mark.parametrize("name,n_layers", [("c0", 1), ("c1", 2), ("c2", 2), ("c3", 2), ("c4k8", 1), ("c4k1", 1)])
+def test_window_full_shape(gpu_lib, name, n_layers):
+    cfg = CONFIGS[name].with_(n_layers=n_layers)
+    d = cfg.dims
+    cap = cfg.n_past + cfg.T
+    x = synth.window_input(cfg)
+    dev_layers, h = [], x.astype(np.float64)
+    gaps = []
+    first = None
+    for l in range(n_layers):
+        t = synth.layer_tensors(cfg, l, kv_cap=cap)
+        dev_layers.append({k: _dev(v) for k, v in t.items()})
+        h, taps = oracle.layer(d, t, h, cfg.n_past, taps=True)
+        gaps.append(taps["min_gap"])
+        if l == 0:
+            first = taps
+        del t
+    win = gpu_lib.Window(d, dev_layers, cap, T_max=cfg.T)
+    xd = _dev(x)
+    # intermediates of the first layer (attention output to 1e-3), on a copy of its caches
+    k0, v0 = dev_layers[0]["k_cache"].clone(), dev_layers[0]["v_cache"].clone()
+    _, gt = win.decode_layer_taps(0, xd, cfg.n_past)
+    dev_layers[0]["k_cache"].copy_(k0)
+    dev_layers[0]["v_cache"].copy_(v0)
+    print(name, "oracle min top-2 logit gaps per layer:", ["%.3g" % g for g in gaps])
+    assert rel_err(gt["o"].cpu().numpy(), first["o"]) < ATT_TOL
+    assert rel_err(gt["q"].cpu().numpy(), first["q"]) < HID_TOL
+    assert rel_err(gt["a"].cpu().numpy(), first["a"]) < HID_TOL
+    y = win.decode(xd, cfg.n_past)
+    err = rel_err(y.cpu().numpy(), h)
+    print(name, "hidden-state max rel err", err)
+    assert err < HID_TOL
+
+
+def test_lm_head_full_vocab(gpu_lib):
+    """Output layer of config 4 (128256 x 8192 Q4_K) for 8 tokens; every logit compared."""
+    cfg = CONFIGS["c4k8"]
+    out = synth.output_layer_tensors(cfg)
+    x = (synth.window_input(cfg).astype(np.float64) * 1e3).astype(np.float32)   # hidden states are large after a window
+    ref = oracle.lm_head(cfg.dims, out["g_final"], out["w_lm"], x.astype(np.float64))
+    got = gpu_lib.lm_head(cfg.dims, _dev(out["g_final"]), _dev(out["w_lm"]), _dev(x)).cpu().numpy()
+    assert rel_err(got, ref) < HID_TOL
+
+
+def test_gemv_sampled_rows_at_full_size(gpu_lib):
+    """Down projection of config 3 (8192 x 28672) at T = 1: rows sampled across tiles and the ragged end
+    are recomputed one by one by a brute-force fp64 product on the dequantised rows."""
+    cfg = CONFIGS["c3"]
+    d = cfg.dims
+    W = synth.q4k_tensor(cfg.config_id, 0, "wdown", d.e, d.ffn)
+    x = (synth.normal_f32(cfg.config_id, 0, "q", (1, d.ffn)).astype(np.float64) * 1e4 + 3e4).astype(np.float32)
+    got = gpu_lib.q4k_gemv(_dev(W), _dev(x)).cpu().numpy()[0]
+    rows = [0, 1, 15, 16, 17, 255, 256, 4095, 4096, 8176, 8190, 8191]
+    dense = oracle.dequant(W[rows]).astype(np.float64)
+    ref = dense @ x[0].astype(np.float64)
+    scale = np.sqrt((ref ** 2).mean())
+    assert np.abs(got[rows] - ref).max() / scale < 1e-5
