@@ -85,7 +85,8 @@ def main():
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
     bytes_step = cfg.bytes_per_step()
 
-    # --- dominant kernel (gate/up projections): HIP events around every launch, on the same stream ---
+    # --- per kind of launch: each replayed on its own, once per layer, between two HIP events on the
+    #     same stream (the dominant kernel is the gate/up projection) ---
     n_prof = 5
     acc = {}
     for _ in range(n_prof):
@@ -94,7 +95,7 @@ def main():
             a = acc.setdefault(k, [0.0, 0])
             a[0] += ms
             a[1] += n
-    per_launch_us = {k: (v[0] / v[1] * 1e3 if v[1] else 0.0) for k, v in acc.items()}
+    per_launch_us = {k: (v[0] / v[1] * 1e3) for k, v in acc.items() if v[1]}
     gate_up_bytes = 2 * d.ffn * (d.e // 256) * 144      # algorithmic bytes of one gate/up launch
     gu_us = per_launch_us["gate_up"]
     achieved = gate_up_bytes / (gu_us * 1e-6) / 1e9
@@ -126,7 +127,7 @@ def main():
         "per_launch_us": {k: round(v, 2) for k, v in per_launch_us.items()},
         "roofline": {
             "bound": "hbm",
-            "kernel": "gemv_q4k_persistent_kernel<T> (gate/up projections, fused RMSNorm)",
+            "kernel": f"gemv_q4k_persistent_kernel<{cfg.T}, 1, 2> (gate/up projections, fused RMSNorm)",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",

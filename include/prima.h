@@ -120,11 +120,12 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
                                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Measurement hook: the same launches as prima_layer_window_decode, with a HIP event recorded on
- * `hip_stream` after every launch.  SYNCHRONISES the stream before returning and creates/destroys
- * events (host-side allocation), so it is not for the serving path.  ms_by_kind and
- * launches_by_kind are HOST arrays of PRIMA_N_KINDS entries: per kind of launch, the summed time
- * from the previous launch's completion to this one's (milliseconds) and the number of launches.
+ * Measurement hook.  Runs one ordinary window step, then replays each kind of launch on its own,
+ * once per layer (L different weight sets), bracketed by two HIP events on `hip_stream`, and
+ * returns per kind the elapsed time of its L back-to-back launches.  SYNCHRONISES the stream before
+ * returning and creates/destroys events (host-side allocation), so it is not for the serving
+ * path.  x_out receives the ordinary step's result.  ms_by_kind and launches_by_kind are HOST
+ * arrays of PRIMA_N_KINDS entries (milliseconds for all launches of the kind; number of launches).
  */
 enum {
     PRIMA_K_QKV = 0,     /* Q/K/V projections with fused RMSNorm */

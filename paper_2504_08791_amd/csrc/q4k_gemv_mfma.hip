@@ -106,17 +106,18 @@ __device__ __forceinline__ float wg_reduce(float v, float *red, bool is_max)
 
 // eight consecutive activations of token t starting at column c0, before the RMSNorm scale:
 // X_PLAIN x, X_RMSNORM x*gain (the 1/rms factor is applied by the caller), X_SWIGLU silu(x)*x2
+template <int XMODE>
 __device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, float *f)
 {
     const float *xp = a.x + t * a.ldx + c0;
     const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
     f[0] = v0.x; f[1] = v0.y; f[2] = v0.z; f[3] = v0.w; f[4] = v1.x; f[5] = v1.y; f[6] = v1.z; f[7] = v1.w;
-    if (a.xmode == X_RMSNORM) {
+    if (XMODE == X_RMSNORM) {
         const float4 g0 = *reinterpret_cast<const float4 *>(a.gain + c0), g1 = *reinterpret_cast<const float4 *>(a.gain + c0 + 4);
         const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
         for (int e = 0; e < 8; ++e) f[e] *= gg[e];
-    } else if (a.xmode == X_SWIGLU) {
+    } else if (XMODE == X_SWIGLU) {
         const float *up = a.x2 + t * a.ldx + c0;
         const float4 u0 = *reinterpret_cast<const float4 *>(up), u1 = *reinterpret_cast<const float4 *>(up + 4);
         const float uu[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
@@ -131,7 +132,9 @@ struct Cursor {
     bool valid;
 };
 
-template <int TT>
+// TT tokens; XMODE how the activations are obtained; NSEG matrices sharing the activations (compile-time
+// so that the projections of a layer appear as separate kernels in a profile)
+template <int TT, int XMODE, int NSEG>
 __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemvArgs a)
 {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -192,7 +195,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     auto issue = [&](const Cursor &c, int st) {
         const int tile = tl0 + c.u / a.ksplit;
         int sg = 0;
-        while (sg + 1 < a.nseg && tile >= a.seg_tile0[sg + 1]) ++sg;
+        while (sg + 1 < NSEG && tile >= a.seg_tile0[sg + 1]) ++sg;
         const int64_t row0 = static_cast<int64_t>(tile - a.seg_tile0[sg]) * 16;
         const int rows_valid = static_cast<int>(min<int64_t>(16, a.seg[sg].n_rows - row0));
         const int blk0 = c.slab * a.slab_blocks + c.c * PBS;
@@ -232,17 +235,17 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         float ss = 0.f, amax = 0.f;
         for (int gi = threadIdx.x; gi < K / 8; gi += GEMV_THREADS) {
             float f[8];
-            if (a.xmode == X_RMSNORM) {
+            if (XMODE == X_RMSNORM) {
                 const float *xp = a.x + t * a.ldx + gi * 8;
                 const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
                 ss += ((v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w)) + ((v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w));
             }
-            load_act8(a, t, gi * 8, f);
+            load_act8<XMODE>(a, t, gi * 8, f);
 #pragma unroll
             for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
         }
         float inv_rms = 1.f;
-        if (a.xmode == X_RMSNORM) {
+        if (XMODE == X_RMSNORM) {
             ss = wg_reduce(ss, l_red, false);
             inv_rms = 1.0f / sqrtf(ss / static_cast<float>(K) + a.eps);
         }
@@ -289,7 +292,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
             const float S = l_scale[t];
             for (int gi = sb0 * 32 + threadIdx.x; gi < sb1 * 32; gi += GEMV_THREADS) {
                 float f[8];
-                load_act8(a, t, gi * 8, f);
+                load_act8<XMODE>(a, t, gi * 8, f);
                 if (a.x_tap && blockIdx.x == 0) {
                     const float unq = S * l_inv[t]; // 1/rms for RMSNorm input, 1 otherwise
                     float *tp = a.x_tap + static_cast<int64_t>(t) * K + gi * 8;
@@ -416,7 +419,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         for (int p = 0; p < a.ksplit; ++p) v += l_part[(tile_local * a.ksplit + p) * (TT * 16) + t * 16 + jj];
         const int tile = tl0 + tile_local;
         int sg = 0;
-        while (sg + 1 < a.nseg && tile >= a.seg_tile0[sg + 1]) ++sg;
+        while (sg + 1 < NSEG && tile >= a.seg_tile0[sg + 1]) ++sg;
         const int64_t row = static_cast<int64_t>(tile - a.seg_tile0[sg]) * 16 + jj;
         if (row < a.seg[sg].n_rows) {
             v *= l_inv[t];
@@ -486,18 +489,30 @@ static PPlan plan_persistent(const GemvArgs &ga, int T)
     return p;
 }
 
-template <int TT>
-static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
+template <int TT, int XMODE, int NSEG>
+static hipError_t launch_inst(const PGemvArgs &a, const PPlan &p, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_q4k_persistent_kernel<TT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_q4k_persistent_kernel<TT, XMODE, NSEG>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(LDS_BUDGET));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(gemv_q4k_persistent_kernel<TT>, dim3(p.n_wg), dim3(GEMV_THREADS), p.lds_bytes, st, a);
+    hipLaunchKernelGGL((gemv_q4k_persistent_kernel<TT, XMODE, NSEG>), dim3(p.n_wg), dim3(GEMV_THREADS), p.lds_bytes, st, a);
     return hipGetLastError();
+}
+
+// the combinations a decoder layer and the output layer use
+template <int TT>
+static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
+{
+    if (a.xmode == X_RMSNORM && a.nseg == 3) return launch_inst<TT, X_RMSNORM, 3>(a, p, st); // Q/K/V
+    if (a.xmode == X_RMSNORM && a.nseg == 2) return launch_inst<TT, X_RMSNORM, 2>(a, p, st); // gate/up
+    if (a.xmode == X_RMSNORM && a.nseg == 1) return launch_inst<TT, X_RMSNORM, 1>(a, p, st); // output layer
+    if (a.xmode == X_SWIGLU && a.nseg == 1) return launch_inst<TT, X_SWIGLU, 1>(a, p, st);   // down
+    if (a.xmode == X_PLAIN && a.nseg == 1) return launch_inst<TT, X_PLAIN, 1>(a, p, st);     // attention output, plain mat-vec
+    return hipErrorInvalidValue;
 }
 
 prima_status launch_gemv_mfma(const GemvArgs &ga, hipStream_t st)

@@ -1,8 +1,6 @@
 // C-ABI entry points: argument validation on the host, workspace carving and the per-layer
 // launch sequence of a layer window (arXiv 2504.08791, Sec. 3.1: a device advances its window
 // of consecutive layers and hands e FP32 values per token to its successor).
-#include <vector>
-
 #include "common.h"
 
 using namespace prima;
@@ -68,68 +66,48 @@ GemvArgs gemv_args(int nseg, int64_t n_cols, const float *x, int64_t ldx, int T,
     return ga;
 }
 
-// optional per-launch timing: an event is recorded on the stream after every launch
-struct LaunchTimer {
-    hipStream_t st;
-    std::vector<hipEvent_t> ev;
-    std::vector<int> kind;
-    bool mark(int k)
-    {
-        hipEvent_t e;
-        if (hipEventCreate(&e) != hipSuccess) return false;
-        if (hipEventRecord(e, st) != hipSuccess) { (void)hipEventDestroy(e); return false; }
-        ev.push_back(e);
-        kind.push_back(k);
-        return true;
-    }
-};
-
 // one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Six launches: Q/K/V projections
 // (RMSNorm fused), attention partial (RoPE + KV append fused) and merge, output projection
 // (+ residual), gate/up projections (RMSNorm fused), down projection (SwiGLU fused, + residual).
 prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
                        const float *x, float *y, void *ws, const WindowWs &w, hipStream_t st,
-                       float *tap_q, float *tap_o, float *tap_h, float *tap_a, LaunchTimer *tm = nullptr)
+                       float *tap_q, float *tap_o, float *tap_h, float *tap_a, int only = -1)
 {
     const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
     float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
     float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *g = at<float>(ws, w.g), *u = at<float>(ws, w.u);
     prima_status s;
 #define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
-#define PRIMA_MARK(k) do { if (tm && !tm->mark(k)) return PRIMA_E_DEVICE; } while (0)
-    {
+#define PRIMA_WANT(k) (only < 0 || only == (k))
+    if (PRIMA_WANT(PRIMA_K_QKV)) {
         GemvArgs ga = gemv_args(3, e, x, e, T, X_RMSNORM, nullptr, L.g_attn, d.rms_eps);
         ga.seg[0] = seg(L.wq, q, qd, qd);
         ga.seg[1] = seg(L.wk, k, kvd, kvd);
         ga.seg[2] = seg(L.wv, v, kvd, kvd);
         PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
-    PRIMA_MARK(PRIMA_K_QKV);
-    PRIMA_TRY(launch_attn(d, q, tap_q, k, v, at<float>(ws, w.rope), static_cast<__half *>(L.k_cache),
-                          static_cast<__half *>(L.v_cache), kv_cap, n_past, T, o, at<char>(ws, w.attn), st));
-    PRIMA_MARK(PRIMA_K_ATTN);
+    if (PRIMA_WANT(PRIMA_K_ATTN))
+        PRIMA_TRY(launch_attn(d, q, tap_q, k, v, at<float>(ws, w.rope), static_cast<__half *>(L.k_cache),
+                              static_cast<__half *>(L.v_cache), kv_cap, n_past, T, o, at<char>(ws, w.attn), st));
     if (tap_o && hipMemcpyAsync(tap_o, o, T * qd * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
-    {
+    if (PRIMA_WANT(PRIMA_K_WO)) {
         GemvArgs ga = gemv_args(1, qd, o, qd, T);
         ga.seg[0] = seg(L.wo, h, e, e, x, e);
         PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
-    PRIMA_MARK(PRIMA_K_WO);
     if (tap_h && hipMemcpyAsync(tap_h, h, T * e * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
-    {
+    if (PRIMA_WANT(PRIMA_K_GATE_UP)) {
         GemvArgs ga = gemv_args(2, e, h, e, T, X_RMSNORM, nullptr, L.g_ffn, d.rms_eps);
         ga.seg[0] = seg(L.wgate, g, F, F);
         ga.seg[1] = seg(L.wup, u, F, F);
         PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
-    PRIMA_MARK(PRIMA_K_GATE_UP);
-    {
+    if (PRIMA_WANT(PRIMA_K_DOWN)) {
         GemvArgs ga = gemv_args(1, F, g, F, T, X_SWIGLU, u, nullptr, 0.f, tap_a);
         ga.seg[0] = seg(L.wdown, y, e, e, h, e);
         PRIMA_TRY(launch_gemv_mfma(ga, st));
     }
-    PRIMA_MARK(PRIMA_K_DOWN);
-#undef PRIMA_MARK
+#undef PRIMA_WANT
 #undef PRIMA_TRY
     return PRIMA_OK;
 }
@@ -259,25 +237,41 @@ prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima
         if ((s = check_layer(layers[i])) != PRIMA_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const WindowWs w = carve(*d, kv_cap, T);
-    LaunchTimer tm;
-    tm.st = st;
+    // one ordinary step first: every intermediate buffer then holds this step's values
     s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
-    if (s == PRIMA_OK && !tm.mark(-1)) s = PRIMA_E_DEVICE;
     const float *cur = x_in;
     for (int i = 0; i < L && s == PRIMA_OK; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
-        s = run_layer(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr, &tm);
+        s = run_layer(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr);
         cur = dst;
     }
+    // then each kind of launch on its own, once per layer (L different weight sets, so nothing is
+    // served from a cache that the real step would not have), between two events
+    hipEvent_t ev[PRIMA_N_KINDS + 1];
+    int n_ev = 0;
+    const int kinds[] = {PRIMA_K_QKV, PRIMA_K_ATTN, PRIMA_K_WO, PRIMA_K_GATE_UP, PRIMA_K_DOWN};
+    const int n_kinds = static_cast<int>(sizeof(kinds) / sizeof(kinds[0]));
     for (int k = 0; k < PRIMA_N_KINDS; ++k) { ms_by_kind[k] = 0.f; launches_by_kind[k] = 0; }
-    if (s == PRIMA_OK && hipStreamSynchronize(st) != hipSuccess) s = PRIMA_E_DEVICE;
-    for (size_t i = 1; i < tm.ev.size() && s == PRIMA_OK; ++i) {
-        float ms = 0.f;
-        if (hipEventElapsedTime(&ms, tm.ev[i - 1], tm.ev[i]) != hipSuccess) { s = PRIMA_E_DEVICE; break; }
-        ms_by_kind[tm.kind[i]] += ms;
-        launches_by_kind[tm.kind[i]] += 1;
+    auto mark = [&]() {
+        if (hipEventCreate(&ev[n_ev]) != hipSuccess) return false;
+        ++n_ev;
+        return hipEventRecord(ev[n_ev - 1], st) == hipSuccess;
+    };
+    if (s == PRIMA_OK && !mark()) s = PRIMA_E_DEVICE;
+    float *scratch_out = at<float>(workspace, w.xb0); // the isolated down projections write here, not to x_out
+    for (int ki = 0; ki < n_kinds && s == PRIMA_OK; ++ki) {
+        for (int i = 0; i < L && s == PRIMA_OK; ++i)
+            s = run_layer(*d, layers[i], kv_cap, n_past, T, x_in, scratch_out, workspace, w, st, nullptr, nullptr, nullptr, nullptr, kinds[ki]);
+        if (s == PRIMA_OK && !mark()) s = PRIMA_E_DEVICE;
     }
-    for (hipEvent_t e : tm.ev) (void)hipEventDestroy(e);
+    if (s == PRIMA_OK && hipStreamSynchronize(st) != hipSuccess) s = PRIMA_E_DEVICE;
+    for (int ki = 0; ki < n_kinds && s == PRIMA_OK; ++ki) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev[ki], ev[ki + 1]) != hipSuccess) { s = PRIMA_E_DEVICE; break; }
+        ms_by_kind[kinds[ki]] = ms;
+        launches_by_kind[kinds[ki]] = L;
+    }
+    for (int i = 0; i < n_ev; ++i) (void)hipEventDestroy(ev[i]);
     return s;
 }
 
