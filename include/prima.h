@@ -156,13 +156,15 @@ prima_status prima_layer_decode_taps(const prima_dims *d, const prima_layer *lay
 /*
  * Output layer (App. A.3: b_o bytes): logits[t][v] = W_lm . rmsnorm(x[t]; g_final).
  * w_lm: Q4_K [vocab][e].  x: fp32 [T][e].  logits: fp32 [T][vocab].
- * workspace >= prima_workspace_bytes(d, 0, T).
+ * workspace >= prima_lm_head_workspace_bytes(d, vocab, T), 256-byte aligned.
  */
 prima_status prima_lm_head(const prima_dims *d, const float *g_final, const void *w_lm, int64_t vocab,
                            const float *x, int32_t T, float *logits,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* Bytes of scratch the window / output-layer calls need for up to T tokens and kv_cap cache rows. */
+size_t prima_lm_head_workspace_bytes(const prima_dims *d, int64_t vocab, int32_t T);
+
+/* Bytes of scratch the window calls need for up to T tokens and kv_cap cache rows. */
 size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
 
 const char *prima_status_str(prima_status s);

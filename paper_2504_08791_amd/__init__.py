@@ -172,7 +172,8 @@ def lm_head(dims, g_final, w_lm, x, logits=None, workspace=None):
     if logits is None:
         logits = torch.empty((T, vocab), dtype=torch.float32, device=x.device)
     if workspace is None:
-        workspace = torch.empty(max(256, workspace_bytes(d, 0, T)), dtype=torch.uint8, device=x.device)
+        need = _ffi.lib().prima_lm_head_workspace_bytes(C.byref(d), vocab, T)
+        workspace = torch.empty(max(256, need), dtype=torch.uint8, device=x.device)
     _ffi.check(_ffi.lib().prima_lm_head(C.byref(d), _ptr(g_final), _ptr(w_lm), vocab, _ptr(x), T, _ptr(logits),
                                         _ptr(workspace), workspace.numel(), _stream()), "prima_lm_head")
     return logits

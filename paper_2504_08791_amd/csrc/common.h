@@ -74,7 +74,13 @@ struct GemvArgs {
 };
 
 prima_status launch_dequant(const uint8_t *W, int64_t n_rows, int64_t n_cols, float *out, hipStream_t st);
-prima_status launch_gemv_mfma(const GemvArgs &a, hipStream_t st);
+// ws: scratch; its first arrivals_region bytes (>= gemv_arrivals_bytes(rows)) are counters that must be
+// zero before the first launch (launch_zero_arrivals) and are left zero by every launch; the partial
+// sums follow (gemv_ws_bytes() covers both for a region of gemv_arrivals_bytes(rows))
+prima_status launch_gemv_mfma(const GemvArgs &a, void *ws, size_t ws_bytes, size_t arrivals_region, hipStream_t st);
+size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T);
+size_t gemv_arrivals_bytes(int64_t n_rows_total);
+prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
 
 prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
 int attn_num_splits(const prima_dims &d, int n_total, int T);

@@ -20,14 +20,17 @@
 //    For T tokens the unpacked weights are reused against each token's digits.
 //
 // Data movement.  One 512-thread workgroup per compute unit, persistent; it owns a contiguous range
-// of 16-row tiles with all of K, so no sum crosses workgroups and every sum has a fixed order.
+// of 16-row tiles (with all of K whenever the activations fit in LDS); every sum has a fixed order.
 // Each wave streams its share of the weights through a private three-stage LDS ring filled by
 // 128-bit global->LDS loads (no VGPR staging): a stage is 16 rows x 2 super-blocks, requested as
 // runs of 288 contiguous bytes per row, laid out with an odd row stride so that the MFMA-order
 // reads (lane (j, g) reads row j) are free of bank conflicts.  Two stages are always in flight
 // per wave while the third is consumed; only s_waitcnt orders them, no barrier.  The activations
 // are transformed (RMSNorm or SwiGLU when asked), quantised and laid out in LDS by every
-// workgroup for itself, slab by slab when K is too long for the LDS left over by the rings.
+// workgroup for itself.  When the digits of all of K do not fit in the LDS left over by the rings, K
+// is cut into slabs and a workgroup handles one slab of a (larger) range of tiles; the slabs'
+// partial sums meet in global memory, where the workgroup that arrives last at a tile adds them in
+// slab order (release/acquire fences and one atomic counter per tile, reset for the next launch).
 #include "common.h"
 
 namespace prima {
@@ -59,10 +62,12 @@ struct PGemvArgs {
     float *x_tap; // optional [T][K]: transformed fp32 activations (written by workgroup 0)
     // decomposition
     int ksplit;      // waves sharing a tile: unit = (tile, part), part p takes chunks p, p+ksplit, ...
-    int slab_blocks; // super-blocks of activations staged in LDS at a time (even)
+    int slab_blocks; // super-blocks of K per slab (even); workgroup w handles slab w % n_slabs
     int n_slabs;
-    int units_cap;   // partial-sum slots per workgroup
+    int units_cap;   // floats reserved for the partial sums (and the per-tile flags of the slab reduction)
     int n_wg;
+    float *part;        // n_slabs > 1: partial sums [n_slabs][n_tiles*16][T]
+    unsigned *arrivals; // n_slabs > 1: per-tile arrival counters, zero between launches
 };
 
 // 16 bytes per lane from global memory straight into LDS: lane l writes bytes [16 l, 16 l + 16) of the
@@ -78,6 +83,13 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory");
 }
 
+// workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
+// load (vmcnt(0)), which would stall the weight stream at each barrier of the prologue.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ uint32_t lds_address(const void *p)
 {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)); // low half of a flat LDS pointer is the LDS byte address
@@ -86,22 +98,6 @@ __device__ __forceinline__ uint32_t lds_address(const void *p)
 __device__ __forceinline__ long pack64(uint32_t lo, uint32_t hi)
 {
     return static_cast<long>(static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32));
-}
-
-__device__ __forceinline__ float wg_reduce(float v, float *red, bool is_max)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        const float o = __shfl_xor(v, off, 64);
-        v = is_max ? fmaxf(v, o) : v + o;
-    }
-    __syncthreads(); // red may still be read from the previous use
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float r = red[0];
-#pragma unroll
-    for (int i = 1; i < GEMV_WAVES; ++i) r = is_max ? fmaxf(r, red[i]) : r + red[i]; // fixed order
-    return r;
 }
 
 // eight consecutive activations of token t starting at column c0, before the RMSNorm scale:
@@ -126,9 +122,9 @@ __device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, flo
     }
 }
 
-// position of a wave in its stream of stages: slab -> unit (tile, part) -> chunk of PBS super-blocks
+// position of a wave in its stream of stages: unit (tile, part) -> chunk of PBS super-blocks
 struct Cursor {
-    int slab, u, c;
+    int u, c;
     bool valid;
 };
 
@@ -143,14 +139,19 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     const int j = lane & 15, g = lane >> 4;
     const int K = a.nb * QK;
 
-    // tiles of this workgroup
-    const int tl0 = static_cast<int>(static_cast<int64_t>(a.n_tiles) * blockIdx.x / a.n_wg);
-    const int tl1 = static_cast<int>(static_cast<int64_t>(a.n_tiles) * (blockIdx.x + 1) / a.n_wg);
+    // slab and tiles of this workgroup
+    const int slab = blockIdx.x % a.n_slabs, rank = blockIdx.x / a.n_slabs;
+    const int nwg_slab = (a.n_wg - slab + a.n_slabs - 1) / a.n_slabs; // workgroups that share this slab
+    const int tl0 = static_cast<int>(static_cast<int64_t>(a.n_tiles) * rank / nwg_slab);
+    const int tl1 = static_cast<int>(static_cast<int64_t>(a.n_tiles) * (rank + 1) / nwg_slab);
     const int ntl = tl1 - tl0;
     if (ntl == 0) return;
     const int n_units = ntl * a.ksplit;
+    const int sb0 = slab * a.slab_blocks;            // super-blocks [sb0, sb1) of every row
+    const int sb1 = min(sb0 + a.slab_blocks, a.nb);
+    const int n_chunks = (sb1 - sb0 + PBS - 1) / PBS;
 
-    // LDS carve: rings | 32 zero bytes | digits [TT][slab_sub][128] | xsum [TT][slab_sub] | partial [units_cap][TT][16] | red[16] | stats [3 TT]
+    // LDS carve: rings | 32 zero bytes | digits [TT][slab_sub][128] | xsum [TT][slab_sub] | partial [units_cap][TT][16] | red[TT][16] | stats [2 TT]
     const int slab_sub = a.slab_blocks * 8;
     uint8_t *l_ring = smem + wave * (NST * STAGE_BYTES);
     uint8_t *l_zero = smem + RING_BYTES;      // 32 zero bytes: the A operand of lanes that carry no digits
@@ -158,27 +159,20 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     const int dig_t_stride = slab_sub * SUB_BYTES;
     float *l_xs = reinterpret_cast<float *>(l_dig + TT * dig_t_stride);
     float *l_part = l_xs + TT * slab_sub;
-    float *l_red = l_part + a.units_cap * TT * 16;
-    float *l_scale = l_red + 16;  // [TT] 2^p (times 1/rms for RMSNorm input)
+    float *l_red = l_part + a.units_cap;
+    float *l_scale = l_red + 16 * TT;  // [TT] 2^p (times 1/rms for RMSNorm input)
     float *l_inv = l_scale + TT;  // [TT] 2^-p
 
     // ---- stream geometry (wave-uniform) ----
-    const int cps_full = a.slab_blocks / PBS; // chunks per full slab
-    auto slab_chunks = [&](int slab) {
-        const int blocks = min(a.slab_blocks, a.nb - slab * a.slab_blocks);
-        return (blocks + PBS - 1) / PBS;
-    };
     auto normalize = [&](Cursor &c) {
         for (;;) {
-            if (c.slab >= a.n_slabs) { c.valid = false; return; }
-            if (c.u >= n_units) { ++c.slab; c.u = wave; c.c = c.u % a.ksplit; continue; }
-            if (c.c >= slab_chunks(c.slab)) { c.u += GEMV_WAVES; c.c = c.u % a.ksplit; continue; }
+            if (c.u >= n_units) { c.valid = false; return; }
+            if (c.c >= n_chunks) { c.u += GEMV_WAVES; c.c = c.u % a.ksplit; continue; }
             c.valid = true;
             return;
         }
     };
     auto advance = [&](Cursor &c) { c.c += a.ksplit; normalize(c); };
-    (void)cps_full;
 
     // per-lane slot decomposition of the NI load instructions of a stage: slot = i*64 + lane -> (row r, chunk c)
     int slot_r[NI], slot_c[NI];
@@ -189,34 +183,102 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         slot_r[i] = r < 16 ? r : 15;
         slot_c[i] = slot - r * RS; // RS-1 is the padding slot
     }
-    const int64_t pitch16 = static_cast<int64_t>(a.nb) * 9; // row pitch in 16-byte units
+    const int64_t pitch16 = static_cast<int64_t>(a.nb) * 9; // row pitch in 16-byte units (< 2^27: n_cols < 2^32)
+
+    // request the stage at cursor c into ring stage st: exactly NI load instructions, always
+    // segment of a tile, from statically indexed kernel arguments only (scalar selects, no memory access)
+    auto seg_of = [&](int tile, const uint4 *&W16, int64_t &n_rows, int &tile0) {
+        W16 = reinterpret_cast<const uint4 *>(a.seg[0].W); n_rows = a.seg[0].n_rows; tile0 = 0;
+        if (NSEG > 1 && tile >= a.seg_tile0[1]) { W16 = reinterpret_cast<const uint4 *>(a.seg[1].W); n_rows = a.seg[1].n_rows; tile0 = a.seg_tile0[1]; }
+        if (NSEG > 2 && tile >= a.seg_tile0[2]) { W16 = reinterpret_cast<const uint4 *>(a.seg[2].W); n_rows = a.seg[2].n_rows; tile0 = a.seg_tile0[2]; }
+    };
+    // offsets (16-byte units) of this lane's slots from the first chunk of a full stage
+    int off_full[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) off_full[i] = slot_r[i] * static_cast<int>(pitch16) + min(slot_c[i], 9 * PBS - 1);
 
     // request the stage at cursor c into ring stage st: exactly NI load instructions, always
     auto issue = [&](const Cursor &c, int st) {
         const int tile = tl0 + c.u / a.ksplit;
-        int sg = 0;
-        while (sg + 1 < NSEG && tile >= a.seg_tile0[sg + 1]) ++sg;
-        const int64_t row0 = static_cast<int64_t>(tile - a.seg_tile0[sg]) * 16;
-        const int rows_valid = static_cast<int>(min<int64_t>(16, a.seg[sg].n_rows - row0));
-        const int blk0 = c.slab * a.slab_blocks + c.c * PBS;
-        const int ncol = 9 * min(PBS, a.nb - blk0); // valid 16-byte chunks per row in this stage
-        const uint4 *base = reinterpret_cast<const uint4 *>(a.seg[sg].W) + row0 * pitch16 + static_cast<int64_t>(blk0) * 9;
+        const uint4 *W16;
+        int64_t n_rows;
+        int tile0;
+        seg_of(tile, W16, n_rows, tile0);
+        const int64_t row0 = static_cast<int64_t>(tile - tile0) * 16;
+        const int rows_valid = static_cast<int>(min<int64_t>(16, n_rows - row0));
+        const int blk0 = sb0 + c.c * PBS;
+        const int nblk = min(PBS, sb1 - blk0);
+        const uint4 *base = W16 + row0 * pitch16 + static_cast<int64_t>(blk0) * 9;
         const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_address(l_ring + st * STAGE_BYTES));
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads of the stage being overwritten have returned
+        if (rows_valid == 16 && nblk == PBS) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
+            for (int i = 0; i < NI; ++i)
+                if (i * 64 + 63 < STAGE_SLOTS || lane < STAGE_SLOTS - i * 64) dma16(base + off_full[i], dst + i * 1024);
+        } else {
             // rows past the end of the matrix and chunks past the end of the row re-read valid data
-            const int r = min(slot_r[i], rows_valid - 1);
-            const int cc = min(slot_c[i], ncol - 1);
-            const uint4 *src = base + r * pitch16 + cc;
-            if (i * 64 + 63 < STAGE_SLOTS || lane < STAGE_SLOTS - i * 64)
-                dma16(src, dst + i * 1024);
+            const int ncol = 9 * nblk;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const int r = min(slot_r[i], rows_valid - 1);
+                const int cc = min(slot_c[i], ncol - 1);
+                if (i * 64 + 63 < STAGE_SLOTS || lane < STAGE_SLOTS - i * 64) dma16(base + r * pitch16 + cc, dst + i * 1024);
+            }
         }
     };
 
-    // ---- start the weight stream before touching the activations ----
+    // ---- statistics of the activations: 1/rms (RMSNorm input) and the power-of-two scale ----
+    // One token: every thread keeps its groups of 8 activations in registers from here to the
+    // quantisation (no second trip to memory).  Several tokens: they are read again.
+    constexpr int MAXG = 8;                                  // register-resident groups per thread
+    const bool resident = TT == 1 && K / 8 <= MAXG * GEMV_THREADS;
+    float xr[TT == 1 ? MAXG : 1][8];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+        float ss = 0.f, amax = 0.f;
+        if (TT == 1 && resident) {
+#pragma unroll
+            for (int i = 0; i < MAXG; ++i) {
+                const int gi = threadIdx.x + i * GEMV_THREADS;
+                if (gi < K / 8) {
+                    if (XMODE == X_RMSNORM) {
+                        const float *xp = a.x + gi * 8;
+                        const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
+                        ss += ((v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w)) + ((v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w));
+                    }
+                    load_act8<XMODE>(a, 0, gi * 8, xr[TT == 1 ? i : 0]);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xr[TT == 1 ? i : 0][e]));
+                }
+            }
+        } else {
+            for (int gi = threadIdx.x; gi < K / 8; gi += GEMV_THREADS) {
+                float f[8];
+                if (XMODE == X_RMSNORM) {
+                    const float *xp = a.x + t * a.ldx + gi * 8;
+                    const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
+                    ss += ((v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w)) + ((v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w));
+                }
+                load_act8<XMODE>(a, t, gi * 8, f);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
+            }
+        }
+        // both reductions in one round: wave shuffles here, one barrier and fixed-order sums below
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            ss += __shfl_xor(ss, off, 64);
+            amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        }
+        float *red = l_red + t * 16;
+        if (lane == 0) { red[wave] = ss; red[8 + wave] = amax; }
+    }
+
+    // ---- start the weight stream: the activation loads above have returned (loads complete in order, so
+    // issuing them after the stream would make them wait for the first stages), the rest of the prologue
+    // overlaps with the first stages' flight ----
     Cursor lc;
-    lc.slab = 0; lc.u = wave; lc.c = lc.u % a.ksplit; lc.valid = false;
+    lc.u = wave; lc.c = lc.u % a.ksplit; lc.valid = false;
     normalize(lc);
     int issued = 0;
     for (int s = 0; s < NST - 1 && lc.valid; ++s) {
@@ -227,29 +289,18 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
 
     // zero the partial sums and the zero operand
     if (threadIdx.x < 8) reinterpret_cast<uint32_t *>(l_zero)[threadIdx.x] = 0u;
-    for (int i = threadIdx.x; i < n_units * TT * 16; i += GEMV_THREADS) l_part[i] = 0.f;
+    if (a.ksplit > 1)
+        for (int i = threadIdx.x; i < n_units * TT * 16; i += GEMV_THREADS) l_part[i] = 0.f;
 
-    // ---- statistics of the activations: 1/rms (RMSNorm input) and the power-of-two scale ----
+    lds_barrier();
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
-        float ss = 0.f, amax = 0.f;
-        for (int gi = threadIdx.x; gi < K / 8; gi += GEMV_THREADS) {
-            float f[8];
-            if (XMODE == X_RMSNORM) {
-                const float *xp = a.x + t * a.ldx + gi * 8;
-                const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
-                ss += ((v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w)) + ((v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w));
-            }
-            load_act8<XMODE>(a, t, gi * 8, f);
+        const float *red = l_red + t * 16;
+        float ss = red[0], amax = red[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
-        }
-        float inv_rms = 1.f;
-        if (XMODE == X_RMSNORM) {
-            ss = wg_reduce(ss, l_red, false);
-            inv_rms = 1.0f / sqrtf(ss / static_cast<float>(K) + a.eps);
-        }
-        amax = wg_reduce(amax, l_red, true) * inv_rms; // max |x*gain| / rms
+        for (int i = 1; i < GEMV_WAVES; ++i) { ss += red[i]; amax = fmaxf(amax, red[8 + i]); } // fixed order
+        const float inv_rms = XMODE == X_RMSNORM ? 1.0f / sqrtf(ss / static_cast<float>(K) + a.eps) : 1.f;
+        amax *= inv_rms; // max |x*gain| / rms
         int ex = 0;
         if (amax > 0.f) frexpf(amax, &ex); // amax = m * 2^ex, m in [0.5, 1)
         // |v| * 2^(29-ex) < 2^29 leaves room for the rounding of (x*gain)*(inv_rms*2^p) against x*gain*inv_rms
@@ -260,7 +311,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
             l_inv[t] = ldexpf(1.0f, -p);
         }
     }
-    __syncthreads();
+    lds_barrier();
 
     // lanes whose output slots hold this lane's k-group carry digits; all others feed zeros.
     // Digit r of sub-block S sits at byte ((r + S) & 3) * 32 of its 128 bytes (S = s0 + g with s0 % 4 == 0),
@@ -270,8 +321,23 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     const int a_mul = active ? 1 : 0;                                              // inactive lanes stay on the zeros
     const int fsh = 6 * g;
 
+    // scale, residual, store of one finished output
+    auto finish = [&](int tile, int jj, int t, float v) {
+        int sg = 0;
+        if (NSEG > 1 && tile >= a.seg_tile0[1]) sg = 1;
+        if (NSEG > 2 && tile >= a.seg_tile0[2]) sg = 2;
+        const GemvSeg &sgm = a.seg[sg];
+        const int64_t row = static_cast<int64_t>(tile - a.seg_tile0[sg]) * 16 + jj;
+        if (row < sgm.n_rows) {
+            v *= l_inv[t];
+            if (sgm.resid) v += sgm.resid[t * sgm.ldr + row];
+            sgm.y[t * sgm.ldy + row] = v;
+        }
+    };
+    const int64_t slab_stride = static_cast<int64_t>(a.n_tiles) * 16 * TT; // elements per slab in the global partial sums
+
     Cursor cc;
-    cc.slab = 0; cc.u = wave; cc.c = cc.u % a.ksplit; cc.valid = false;
+    cc.u = wave; cc.c = cc.u % a.ksplit; cc.valid = false;
     normalize(cc);
     int step = 0, st = 0;
 
@@ -279,58 +345,67 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
 #pragma unroll
     for (int t = 0; t < TT; ++t) { yacc[t] = 0.f; macc[t] = 0.f; }
 
-    for (int slab = 0; slab < a.n_slabs; ++slab) {
-        const int sb0 = slab * a.slab_blocks;
-        const int sb1 = min(sb0 + a.slab_blocks, a.nb);
-        if (slab > 0) __syncthreads(); // previous slab's digits no longer in use
-
+    {
         // ---- transform + quantise this slab's activations into LDS ----
         // digits [S][4][32 bytes]; byte order inside a digit row: for each group a of 8 values,
         // values 8a + {0,2,4,6,1,3,5,7}, the order in which the nibble split delivers the weights.
+        auto quantise8 = [&](int t, int gi, const float *f, float S) {
+            if (a.x_tap && rank == 0) { // one workgroup per slab records its share
+                const float unq = S * l_inv[t]; // 1/rms for RMSNorm input, 1 otherwise
+                float *tp = a.x_tap + static_cast<int64_t>(t) * K + gi * 8;
+                *reinterpret_cast<float4 *>(tp) = make_float4(f[0] * unq, f[1] * unq, f[2] * unq, f[3] * unq);
+                *reinterpret_cast<float4 *>(tp + 4) = make_float4(f[4] * unq, f[5] * unq, f[6] * unq, f[7] * unq);
+            }
+            // xfix = rint(f*S) (one rounding to integer).  Its four signed base-256 digits are the bytes of
+            // (xfix + 0x80808080) ^ 0x80808080: adding 128 to every digit makes them the unsigned bytes of
+            // the biased number, and flipping bit 7 of a byte subtracts the 128 again in two's complement.
+            uint32_t d4[8];
+            float sum = 0.f;
 #pragma unroll
-        for (int t = 0; t < TT; ++t) {
-            const float S = l_scale[t];
-            for (int gi = sb0 * 32 + threadIdx.x; gi < sb1 * 32; gi += GEMV_THREADS) {
-                float f[8];
-                load_act8<XMODE>(a, t, gi * 8, f);
-                if (a.x_tap && blockIdx.x == 0) {
-                    const float unq = S * l_inv[t]; // 1/rms for RMSNorm input, 1 otherwise
-                    float *tp = a.x_tap + static_cast<int64_t>(t) * K + gi * 8;
-                    *reinterpret_cast<float4 *>(tp) = make_float4(f[0] * unq, f[1] * unq, f[2] * unq, f[3] * unq);
-                    *reinterpret_cast<float4 *>(tp + 4) = make_float4(f[4] * unq, f[5] * unq, f[6] * unq, f[7] * unq);
+            for (int e = 0; e < 8; ++e) {
+                const float rf = rintf(f[e] * S);
+                sum += rf; // per-sub-block sum of xfix, to fp32 accuracy
+                d4[e] = (static_cast<uint32_t>(static_cast<int>(rf)) + 0x80808080u) ^ 0x80808080u;
+            }
+            const int s_glob = gi >> 2, s_loc = s_glob - sb0 * 8, grp = gi & 3;
+            uint8_t *dp = l_dig + t * dig_t_stride + s_loc * SUB_BYTES + grp * 8;
+#pragma unroll
+            for (int dg = 0; dg < 4; ++dg) {
+                // byte dg of values 0,2,4,6 and of values 1,3,5,7 (v_perm_b32 picks bytes of a register pair)
+                const uint32_t sel = 0x0c0c0400u + 0x0101u * dg; // {byte dg of src1, byte dg of src0, 0, 0}
+                const uint32_t e02 = __builtin_amdgcn_perm(d4[2], d4[0], sel), e46 = __builtin_amdgcn_perm(d4[6], d4[4], sel);
+                const uint32_t e13 = __builtin_amdgcn_perm(d4[3], d4[1], sel), e57 = __builtin_amdgcn_perm(d4[7], d4[5], sel);
+                uint2 o;
+                o.x = e02 | (e46 << 16);
+                o.y = e13 | (e57 << 16);
+                *reinterpret_cast<uint2 *>(dp + ((dg + s_glob) & 3) * 32) = o;
+            }
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            if (grp == 0) l_xs[t * slab_sub + s_loc] = sum;
+        };
+        if (TT == 1 && resident) {
+            const float S = l_scale[0];
+#pragma unroll
+            for (int i = 0; i < MAXG; ++i) {
+                const int gi = threadIdx.x + i * GEMV_THREADS;
+                if (gi >= sb0 * 32 && gi < sb1 * 32) quantise8(0, gi, xr[TT == 1 ? i : 0], S);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < TT; ++t) {
+                const float S = l_scale[t];
+                for (int gi = sb0 * 32 + threadIdx.x; gi < sb1 * 32; gi += GEMV_THREADS) {
+                    float f[8];
+                    load_act8<XMODE>(a, t, gi * 8, f);
+                    quantise8(t, gi, f, S);
                 }
-                int r[8];
-                long long sum = 0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    r[e] = static_cast<int>(rintf(f[e] * S)); // one rounding to integer
-                    sum += r[e];
-                }
-                const int s_glob = gi >> 2, s_loc = s_glob - sb0 * 8, grp = gi & 3;
-                uint8_t *dp = l_dig + t * dig_t_stride + s_loc * SUB_BYTES + grp * 8;
-#pragma unroll
-                for (int dg = 0; dg < 4; ++dg) {
-                    uint32_t by[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int lowb = static_cast<int>(static_cast<int8_t>(r[e] & 255)); // signed low byte
-                        by[e] = static_cast<uint32_t>(lowb) & 255u;
-                        r[e] = (r[e] - lowb) >> 8;
-                    }
-                    uint2 o;
-                    o.x = by[0] | (by[2] << 8) | (by[4] << 16) | (by[6] << 24);
-                    o.y = by[1] | (by[3] << 8) | (by[5] << 16) | (by[7] << 24);
-                    *reinterpret_cast<uint2 *>(dp + ((dg + s_glob) & 3) * 32) = o;
-                }
-                sum += __shfl_xor(sum, 1, 64);
-                sum += __shfl_xor(sum, 2, 64);
-                if (grp == 0) l_xs[t * slab_sub + s_loc] = static_cast<float>(sum);
             }
         }
-        __syncthreads();
+        lds_barrier();
 
         // ---- consume this wave's stages of the slab ----
-        while (cc.valid && cc.slab == slab) {
+        while (cc.valid) {
             if (lc.valid) {
                 issue(lc, (st + NST - 1) % NST);
                 advance(lc);
@@ -343,7 +418,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
             static_assert(NI == 5 && NST == 3, "the vmcnt immediates above assume 5 loads per stage, 3 stages");
 
             const int blk0 = sb0 + cc.c * PBS;
-            const int nblk = min(PBS, a.nb - blk0);
+            const int nblk = min(PBS, sb1 - blk0);
             const uint4 *stage = reinterpret_cast<const uint4 *>(l_ring + st * STAGE_BYTES) + j * RS;
 #pragma unroll
             for (int b = 0; b < PBS; ++b) {
@@ -389,17 +464,23 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
                 }
             }
 
-            // next stage of this wave; leave the unit's sums in its slot when the unit (or the slab) ends
+            // next stage of this wave; leave the unit's sums in its slot when the unit ends
             const int u_done = cc.u;
             advance(cc);
-            if (!cc.valid || cc.u != u_done || cc.slab != slab) {
+            if (!cc.valid || cc.u != u_done) {
                 float *slot = l_part + u_done * (TT * 16);
+                const int tile_done = tl0 + u_done / a.ksplit;
 #pragma unroll
                 for (int t = 0; t < TT; ++t) {
                     float v = yacc[t] - macc[t];
                     v += __shfl_xor(v, 16, 64);
                     v += __shfl_xor(v, 32, 64);
-                    if (g == 0) slot[t * 16 + j] += v;
+                    if (g == 0) {
+                        if (a.ksplit > 1) slot[t * 16 + j] = v;                    // parts of the tile meet in LDS
+                        else if (a.n_slabs == 1) finish(tile_done, j, t, v);       // the wave owned the whole row: done
+                        else __hip_atomic_store(a.part + slab * slab_stride + static_cast<int64_t>(tile_done) * 16 * TT + t * 16 + j, v,
+                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                     yacc[t] = 0.f;
                     macc[t] = 0.f;
                 }
@@ -408,24 +489,54 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
             ++step;
         }
     }
-    __syncthreads();
+    lds_barrier();
 
-    // ---- epilogue: add the parts of every (tile, row, token) in part order, scale, residual, store ----
+    // ---- epilogue: add the parts of every (tile, row, token) in part order ----
+    if (a.n_slabs == 1) {
+        if (a.ksplit > 1)
+        for (int idx = threadIdx.x; idx < ntl * 16 * TT; idx += GEMV_THREADS) {
+            const int tile_local = idx / (16 * TT);
+            const int rem = idx - tile_local * (16 * TT);
+            const int t = rem >> 4, jj = rem & 15;
+            float v = 0.f;
+            for (int p = 0; p < a.ksplit; ++p) v += l_part[(tile_local * a.ksplit + p) * (TT * 16) + t * 16 + jj];
+            finish(tl0 + tile_local, jj, t, v);
+        }
+        return;
+    }
+
+    // several slabs: this slab's sums go to global memory; whoever arrives last at a tile adds the slabs
+    if (a.ksplit > 1)
     for (int idx = threadIdx.x; idx < ntl * 16 * TT; idx += GEMV_THREADS) {
         const int tile_local = idx / (16 * TT);
         const int rem = idx - tile_local * (16 * TT);
+        float v = 0.f;
+        for (int p = 0; p < a.ksplit; ++p) v += l_part[(tile_local * a.ksplit + p) * (TT * 16) + rem];
+        __hip_atomic_store(a.part + slab * slab_stride + static_cast<int64_t>(tl0 + tile_local) * 16 * TT + rem, v,
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // The partial sums are written with device-scope (write-through) stores and read back with
+    // device-scope loads, so they never sit in one XCD's L2 only; what is left to order is "all of this
+    // workgroup's stores have completed" before its arrival is counted: vmcnt(0) + barrier.  (A release
+    // fence would do the same but writes back and invalidates the whole L2 per workgroup.)
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    for (int tile_local = threadIdx.x; tile_local < ntl; tile_local += GEMV_THREADS) {
+        const unsigned prev = __hip_atomic_fetch_add(a.arrivals + tl0 + tile_local, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = prev + 1 == static_cast<unsigned>(a.n_slabs);
+        if (last) __hip_atomic_store(a.arrivals + tl0 + tile_local, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); // ready for the next launch
+        l_part[tile_local] = last ? 1.f : 0.f; // l_part is free again after the barrier above
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    for (int idx = threadIdx.x; idx < ntl * 16 * TT; idx += GEMV_THREADS) {
+        const int tile_local = idx / (16 * TT);
+        if (l_part[tile_local] == 0.f) continue;
+        const int rem = idx - tile_local * (16 * TT);
         const int t = rem >> 4, jj = rem & 15;
         float v = 0.f;
-        for (int p = 0; p < a.ksplit; ++p) v += l_part[(tile_local * a.ksplit + p) * (TT * 16) + t * 16 + jj];
-        const int tile = tl0 + tile_local;
-        int sg = 0;
-        while (sg + 1 < NSEG && tile >= a.seg_tile0[sg + 1]) ++sg;
-        const int64_t row = static_cast<int64_t>(tile - a.seg_tile0[sg]) * 16 + jj;
-        if (row < a.seg[sg].n_rows) {
-            v *= l_inv[t];
-            if (a.seg[sg].resid) v += a.seg[sg].resid[t * a.seg[sg].ldr + row];
-            a.seg[sg].y[t * a.seg[sg].ldy + row] = v;
-        }
+        for (int sl = 0; sl < a.n_slabs; ++sl) // fixed order
+            v += __hip_atomic_load(a.part + sl * slab_stride + static_cast<int64_t>(tl0 + tile_local) * 16 * TT + rem,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        finish(tl0 + tile_local, jj, t, v);
     }
 }
 
@@ -448,46 +559,87 @@ static int device_cu_count()
     return cus;
 }
 
-static size_t fixed_lds(int T, int units_cap)
+static size_t fixed_lds(int T, int part_floats)
 {
-    return RING_BYTES + 32 + static_cast<size_t>(units_cap) * T * 16 * 4 + (16 + 2 * T) * 4 + 64;
+    return RING_BYTES + 32 + static_cast<size_t>(part_floats) * 4 + (16 * T + 2 * T) * 4 + 64;
 }
 
-static PPlan plan_persistent(const GemvArgs &ga, int T)
+// Decomposition of a launch: slabs of K (as few as the LDS allows), and waves per tile.  Candidates are
+// ranked by the longest wave's share of the ideal time; more slabs cost partial-sum traffic.
+static PPlan plan_for(int n_tiles, int nb, int T)
 {
-    PPlan p{};
-    p.nb = static_cast<int>(ga.n_cols / QK);
-    p.n_tiles = 0;
-    for (int i = 0; i < ga.nseg; ++i) p.n_tiles += static_cast<int>((ga.seg[i].n_rows + 15) / 16);
-    p.n_wg = device_cu_count();
-    if (p.n_wg > p.n_tiles) p.n_wg = p.n_tiles;
-    const int tiles_wg = (p.n_tiles + p.n_wg - 1) / p.n_wg;
-    const int chunks = (p.nb + PBS - 1) / PBS;
-    // waves per tile: the smallest of 1, 2, 4, 8 that gives every wave a unit and spreads the units evenly
-    int best = 1;
-    double best_eff = 0.0;
-    for (int ks = 1; ks <= GEMV_WAVES; ks *= 2) {
-        if (ks > chunks) break;
-        const int units = tiles_wg * ks;
-        const int rounds = (units + GEMV_WAVES - 1) / GEMV_WAVES;
-        const double eff = static_cast<double>(units) / (rounds * GEMV_WAVES);
-        if (eff > best_eff + 1e-9) { best_eff = eff; best = ks; }
-    }
-    p.ksplit = best;
-    p.units_cap = tiles_wg * p.ksplit;
-    // activations staged per slab: as many super-blocks (even) as the LDS left by rings and partial sums holds
-    const size_t fixed = fixed_lds(T, p.units_cap);
+    PPlan best{};
+    best.ok = false;
+    double best_score = 0.0;
+    const int cus = device_cu_count();
     const size_t per_block = static_cast<size_t>(T) * 8 * (SUB_BYTES + 4);
-    int cap = fixed < LDS_BUDGET ? static_cast<int>((LDS_BUDGET - fixed) / per_block) : 0;
-    cap &= ~1;
-    p.ok = cap >= 2;
-    if (!p.ok) return p;
-    p.n_slabs = (p.nb + cap - 1) / cap;
-    p.slab_blocks = ((p.nb + p.n_slabs - 1) / p.n_slabs + 1) & ~1;
-    p.n_slabs = (p.nb + p.slab_blocks - 1) / p.slab_blocks;
-    p.lds_bytes = fixed + per_block * p.slab_blocks;
-    return p;
+    const double ideal = static_cast<double>(n_tiles) * ((nb + PBS - 1) / PBS) / (static_cast<double>(cus) * GEMV_WAVES);
+    int n_min = 0; // the fewest slabs that fit; more (up to twice as many) only if they balance the waves better
+    for (int n_slabs = 1; n_slabs <= 64 && (n_min == 0 || n_slabs <= 2 * n_min); ++n_slabs) {
+        PPlan p{};
+        p.nb = nb;
+        p.n_tiles = n_tiles;
+        p.n_slabs = n_slabs;
+        p.n_wg = cus;
+        if (p.n_wg > n_tiles * n_slabs) p.n_wg = n_tiles * n_slabs;
+        if (p.n_wg < n_slabs) continue;
+        const int wg_per_slab = p.n_wg / n_slabs;                     // the slabs with most tiles per workgroup
+        const int tiles_wg = (n_tiles + wg_per_slab - 1) / wg_per_slab;
+        p.slab_blocks = ((nb + n_slabs - 1) / n_slabs + 1) & ~1;
+        if ((nb + p.slab_blocks - 1) / p.slab_blocks != n_slabs) continue; // rounding to even merged two slabs
+        const int chunks = (p.slab_blocks + PBS - 1) / PBS;
+        for (int ks = 1; ks <= GEMV_WAVES && ks <= chunks; ks *= 2) {
+            // ks == 1: a wave owns its tiles and stores their sums itself; otherwise the parts meet in LDS
+            const int part_floats = ks == 1 ? tiles_wg : tiles_wg * ks * T * 16;
+            const size_t lds = fixed_lds(T, part_floats) + per_block * p.slab_blocks;
+            if (lds > LDS_BUDGET || part_floats * 4 > 24 * 1024) continue;
+            if (n_min == 0) n_min = n_slabs;
+            if (n_min == 1 && n_slabs > 1) continue; // all of K fits: never pay for the reduction across workgroups
+            const int units = tiles_wg * ks;
+            const int rounds = (units + GEMV_WAVES - 1) / GEMV_WAVES;
+            const double longest = static_cast<double>(rounds) * ((chunks + ks - 1) / ks);
+            const double score = ideal / longest * (1.0 - 0.03 * (n_slabs - n_min));
+            if (score > best_score + 1e-9) {
+                best_score = score;
+                best = p;
+                best.ksplit = ks;
+                best.units_cap = part_floats;
+                best.lds_bytes = lds;
+                best.ok = true;
+            }
+        }
+    }
+    return best;
 }
+
+static int tiles_of(const GemvArgs &ga)
+{
+    int n = 0;
+    for (int i = 0; i < ga.nseg; ++i) n += static_cast<int>((ga.seg[i].n_rows + 15) / 16);
+    return n;
+}
+
+// scratch in global memory: partial sums of the slabs and the per-tile arrival counters (which must be
+// zero before the first launch and are left zero by every launch)
+static size_t part_bytes(const PPlan &p, int T) { return round_up(static_cast<size_t>(p.n_slabs) * p.n_tiles * 16 * T * sizeof(float), 256); }
+static size_t arrivals_bytes(int n_tiles) { return round_up(static_cast<size_t>(n_tiles) * sizeof(unsigned), 256); }
+
+size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T)
+{
+    // any segmentation of the rows into up to three matrices adds at most two tiles
+    const int n_tiles = static_cast<int>((n_rows_total + 15) / 16) + 2;
+    size_t worst = 0;
+    for (int t0 = 0; t0 < T; t0 += MAX_T_PASS) {
+        const int Tp = T - t0 < MAX_T_PASS ? T - t0 : MAX_T_PASS;
+        PPlan p = plan_for(n_tiles, static_cast<int>(n_cols / QK), Tp);
+        p.n_slabs += 1; // a slightly different tile count may need one more slab
+        const size_t b = part_bytes(p, Tp);
+        worst = b > worst ? b : worst;
+    }
+    return arrivals_bytes(n_tiles) + worst;
+}
+
+size_t gemv_arrivals_bytes(int64_t n_rows_total) { return arrivals_bytes(static_cast<int>((n_rows_total + 15) / 16) + 2); }
 
 template <int TT, int XMODE, int NSEG>
 static hipError_t launch_inst(const PGemvArgs &a, const PPlan &p, hipStream_t st)
@@ -515,12 +667,13 @@ static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
     return hipErrorInvalidValue;
 }
 
-prima_status launch_gemv_mfma(const GemvArgs &ga, hipStream_t st)
+prima_status launch_gemv_mfma(const GemvArgs &ga, void *ws, size_t ws_bytes, size_t arrivals_region, hipStream_t st)
 {
+    const int n_tiles = tiles_of(ga);
     // up to MAX_T_PASS tokens per pass over the weights
     for (int t0 = 0; t0 < ga.T; t0 += MAX_T_PASS) {
         const int T = ga.T - t0 < MAX_T_PASS ? ga.T - t0 : MAX_T_PASS;
-        const PPlan p = plan_persistent(ga, T);
+        const PPlan p = plan_for(n_tiles, static_cast<int>(ga.n_cols / QK), T);
         if (!p.ok) return PRIMA_E_SHAPE;
         PGemvArgs a{};
         int tile0 = 0;
@@ -547,6 +700,14 @@ prima_status launch_gemv_mfma(const GemvArgs &ga, hipStream_t st)
         a.n_slabs = p.n_slabs;
         a.units_cap = p.units_cap;
         a.n_wg = p.n_wg;
+        if (p.n_slabs > 1) {
+            // the counters sit in a region of fixed size at the start of the scratch, so that launches of
+            // different shapes that share the scratch never write partial sums over each other's counters
+            if (arrivals_region < arrivals_bytes(n_tiles)) return PRIMA_E_WORKSPACE;
+            if (!ws || ws_bytes < arrivals_region + part_bytes(p, T)) return PRIMA_E_WORKSPACE;
+            a.arrivals = static_cast<unsigned *>(ws);
+            a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + arrivals_region);
+        }
         hipError_t e;
         switch (T) {
         case 1: e = launch_tt<1>(a, p, st); break;
@@ -561,6 +722,21 @@ prima_status launch_gemv_mfma(const GemvArgs &ga, hipStream_t st)
         if (e != hipSuccess) return PRIMA_E_DEVICE;
     }
     return PRIMA_OK;
+}
+
+__global__ void zero_u32_kernel(unsigned *p, size_t n)
+{
+    const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// the arrival counters at the start of a mat-vec workspace must be zero before its first use
+prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st)
+{
+    const size_t n = bytes / sizeof(unsigned);
+    if (n == 0) return PRIMA_OK;
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st, static_cast<unsigned *>(ws), n);
+    return last_launch_status();
 }
 
 } // namespace prima

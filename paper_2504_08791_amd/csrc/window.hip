@@ -1,6 +1,8 @@
 // C-ABI entry points: argument validation on the host, workspace carving and the per-layer
 // launch sequence of a layer window (arXiv 2504.08791, Sec. 3.1: a device advances its window
 // of consecutive layers and hands e FP32 values per token to its successor).
+#include <algorithm>
+
 #include "common.h"
 
 using namespace prima;
@@ -8,7 +10,7 @@ using namespace prima;
 namespace {
 
 struct WindowWs {
-    size_t q, k, v, o, h, g, u, xb0, xb1, rope, attn, total;
+    size_t q, k, v, o, h, g, u, xb0, xb1, rope, attn, gemv, gemv_bytes, arrivals_bytes, total;
 };
 
 bool dims_ok(const prima_dims *d)
@@ -36,6 +38,14 @@ WindowWs carve(const prima_dims &d, int kv_cap, int T)
     w.xb1 = take(T * static_cast<size_t>(d.e) * f);
     w.rope = take(T * static_cast<size_t>(d.head_dim) * f);
     w.attn = take(attn_ws_bytes(d, kv_cap, T));
+    // mat-vec scratch: sized for the largest of the layer's (and the output layer's) launches
+    const int64_t rows_max = std::max<int64_t>(2 * static_cast<int64_t>(d.ffn), static_cast<int64_t>(qd + 2 * kvd));
+    const int64_t shapes[4][2] = {{static_cast<int64_t>(qd + 2 * kvd), d.e}, {d.e, static_cast<int64_t>(qd)}, {2 * static_cast<int64_t>(d.ffn), d.e}, {d.e, d.ffn}};
+    w.gemv_bytes = 0;
+    w.arrivals_bytes = gemv_arrivals_bytes(rows_max);
+    for (const auto &sh : shapes) w.gemv_bytes = std::max(w.gemv_bytes, gemv_ws_bytes(sh[0], sh[1], T)); // counters + partial sums
+    w.gemv_bytes += w.arrivals_bytes; // the counter region is sized for the tallest matrix
+    w.gemv = take(w.gemv_bytes);
     w.total = off;
     return w;
 }
@@ -84,7 +94,7 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
         ga.seg[0] = seg(L.wq, q, qd, qd);
         ga.seg[1] = seg(L.wk, k, kvd, kvd);
         ga.seg[2] = seg(L.wv, v, kvd, kvd);
-        PRIMA_TRY(launch_gemv_mfma(ga, st));
+        PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
     }
     if (PRIMA_WANT(PRIMA_K_ATTN))
         PRIMA_TRY(launch_attn(d, q, tap_q, k, v, at<float>(ws, w.rope), static_cast<__half *>(L.k_cache),
@@ -93,19 +103,19 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
     if (PRIMA_WANT(PRIMA_K_WO)) {
         GemvArgs ga = gemv_args(1, qd, o, qd, T);
         ga.seg[0] = seg(L.wo, h, e, e, x, e);
-        PRIMA_TRY(launch_gemv_mfma(ga, st));
+        PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
     }
     if (tap_h && hipMemcpyAsync(tap_h, h, T * e * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     if (PRIMA_WANT(PRIMA_K_GATE_UP)) {
         GemvArgs ga = gemv_args(2, e, h, e, T, X_RMSNORM, nullptr, L.g_ffn, d.rms_eps);
         ga.seg[0] = seg(L.wgate, g, F, F);
         ga.seg[1] = seg(L.wup, u, F, F);
-        PRIMA_TRY(launch_gemv_mfma(ga, st));
+        PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
     }
     if (PRIMA_WANT(PRIMA_K_DOWN)) {
         GemvArgs ga = gemv_args(1, F, g, F, T, X_SWIGLU, u, nullptr, 0.f, tap_a);
         ga.seg[0] = seg(L.wdown, y, e, e, h, e);
-        PRIMA_TRY(launch_gemv_mfma(ga, st));
+        PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
     }
 #undef PRIMA_WANT
 #undef PRIMA_TRY
@@ -155,7 +165,8 @@ prima_status prima_q4k_dequant(const void *W, int64_t n_rows, int64_t n_cols, fl
 size_t prima_gemv_workspace_bytes(int64_t n_rows, int64_t n_cols, int32_t T)
 {
     if (n_rows < 0 || n_cols < 0 || T < 1) return 0;
-    return 256; // the mat-vec keeps its intermediates in LDS; the argument is reserved
+    const size_t b = gemv_ws_bytes(n_rows, n_cols, T);
+    return b < 256 ? 256 : b;
 }
 
 prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int32_t T,
@@ -165,11 +176,14 @@ prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols, const
     if (n_rows < 0 || n_cols <= 0 || n_cols % QK || ldx < n_cols || ldy < n_rows) return PRIMA_E_SHAPE;
     if (T < 1 || T > PRIMA_MAX_TOK) return PRIMA_E_RANGE;
     if (!aligned(W, 16) || !aligned(x, 16) || !aligned(y, 4) || ldx % 4 || !aligned(workspace, 256)) return PRIMA_E_ALIGN;
-    if (workspace_bytes < 256) return PRIMA_E_WORKSPACE;
+    if (workspace_bytes < std::max<size_t>(256, gemv_ws_bytes(n_rows, n_cols, T))) return PRIMA_E_WORKSPACE;
     if (n_rows == 0) return PRIMA_OK;
     GemvArgs ga = gemv_args(1, n_cols, x, ldx, T);
     ga.seg[0] = seg(W, y, n_rows, ldy);
-    return launch_gemv_mfma(ga, static_cast<hipStream_t>(hip_stream));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    prima_status s = launch_zero_arrivals(workspace, gemv_arrivals_bytes(n_rows), st);
+    if (s != PRIMA_OK) return s;
+    return launch_gemv_mfma(ga, workspace, workspace_bytes, gemv_arrivals_bytes(n_rows), st);
 }
 
 size_t prima_attn_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
@@ -212,6 +226,7 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const WindowWs w = carve(*d, kv_cap, T);
     s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
     if (s != PRIMA_OK) return s;
     const float *cur = x_in;
     for (int i = 0; i < L; ++i) {
@@ -239,6 +254,7 @@ prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima
     const WindowWs w = carve(*d, kv_cap, T);
     // one ordinary step first: every intermediate buffer then holds this step's values
     s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
     const float *cur = x_in;
     for (int i = 0; i < L && s == PRIMA_OK; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
@@ -288,8 +304,15 @@ prima_status prima_layer_decode_taps(const prima_dims *d, const prima_layer *lay
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const WindowWs w = carve(*d, kv_cap, T);
     s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
     if (s != PRIMA_OK) return s;
     return run_layer(*d, *layer, kv_cap, n_past, T, x_in, x_out, workspace, w, st, tap_q, tap_o, tap_h, tap_a);
+}
+
+size_t prima_lm_head_workspace_bytes(const prima_dims *d, int64_t vocab, int32_t T)
+{
+    if (!d || !dims_ok(d) || vocab < 1 || T < 1 || T > PRIMA_MAX_TOK) return 0;
+    return std::max<size_t>(256, gemv_ws_bytes(vocab, d->e, T));
 }
 
 prima_status prima_lm_head(const prima_dims *d, const float *g_final, const void *w_lm, int64_t vocab,
@@ -300,12 +323,13 @@ prima_status prima_lm_head(const prima_dims *d, const float *g_final, const void
     if (!dims_ok(d) || vocab < 1) return PRIMA_E_SHAPE;
     if (T < 1 || T > PRIMA_MAX_TOK) return PRIMA_E_RANGE;
     if (!aligned(g_final, 16) || !aligned(w_lm, 16) || !aligned(x, 16) || !aligned(logits, 4) || !aligned(workspace, 256)) return PRIMA_E_ALIGN;
-    const WindowWs w = carve(*d, 0, T);
-    if (workspace_bytes < w.total) return PRIMA_E_WORKSPACE;
+    if (workspace_bytes < prima_lm_head_workspace_bytes(d, vocab, T)) return PRIMA_E_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    prima_status s = launch_zero_arrivals(workspace, gemv_arrivals_bytes(vocab), st);
+    if (s != PRIMA_OK) return s;
     GemvArgs ga = gemv_args(1, d->e, x, d->e, T, X_RMSNORM, nullptr, g_final, d->rms_eps);
     ga.seg[0] = seg(w_lm, logits, vocab, vocab);
-    return launch_gemv_mfma(ga, st);
+    return launch_gemv_mfma(ga, workspace, workspace_bytes, gemv_arrivals_bytes(vocab), st);
 }
 
 } // extern "C"

@@ -39,6 +39,7 @@ def test_window_full_shape(gpu_lib, name, n_layers):
             first = taps
         del t
     win = gpu_lib.Window(d, dev_layers, cap, T_max=cfg.T)
+    win.workspace.fill_(0xFF)      # NaN patterns: nothing may be read from the scratch before it is written
     xd = _dev(x)
     # intermediates of the first layer (attention output to 1e-3), on a copy of its caches
     k0, v0 = dev_layers[0]["k_cache"].clone(), dev_layers[0]["v_cache"].clone()

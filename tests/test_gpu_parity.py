@@ -158,7 +158,9 @@ def test_attention_peaked_logits(gpu_lib):
 
 def _window(gpu_lib, cfg, cap, layers_host):
     dev_layers = [{k: _dev(v) for k, v in t.items()} for t in layers_host]
-    return gpu_lib.Window(cfg.dims, dev_layers, cap, T_max=16), dev_layers
+    win = gpu_lib.Window(cfg.dims, dev_layers, cap, T_max=16)
+    win.workspace.fill_(0xFF)      # NaN patterns: nothing may be read from the scratch before it is written
+    return win, dev_layers
 
 
 @pytest.mark.parametrize("name", ["t0", "t1", "t2"])
