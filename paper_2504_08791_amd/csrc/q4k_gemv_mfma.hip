@@ -122,11 +122,13 @@ __device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, flo
     }
 }
 
-// position of a wave in its stream of stages: unit (tile, part) -> chunk of PBS super-blocks
+// position of a wave in its stream of stages: k-th unit (tile, part) the wave took -> chunk of PBS super-blocks
 struct Cursor {
-    int u, c;
+    int k, u, c;
     bool valid;
 };
+constexpr int STATIC_UNITS = 2; // units per wave assigned by position; the rest go to whichever wave asks first
+constexpr int FIFO = 8;         // units a wave may have requested and not yet consumed (a power of two > NST)
 
 // TT tokens; XMODE how the activations are obtained; NSEG matrices sharing the activations (compile-time
 // so that the projections of a layer appear as separate kernels in a profile)
@@ -162,17 +164,37 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     float *l_red = l_part + a.units_cap;
     float *l_scale = l_red + 16 * TT;  // [TT] 2^p (times 1/rms for RMSNorm input)
     float *l_inv = l_scale + TT;  // [TT] 2^-p
+    int *l_next = reinterpret_cast<int *>(l_inv + TT); // next unit nobody has taken
+    int *l_fifo = l_next + 1 + wave * FIFO;            // units this wave has taken, by k % FIFO
 
     // ---- stream geometry (wave-uniform) ----
-    auto normalize = [&](Cursor &c) {
+    // Units are handed out in order, so the parts of a tile are in flight together; the first STATIC_UNITS of
+    // a wave are fixed (they are requested before the counter exists), the others come from the counter.
+    // The requesting cursor runs ahead and records what it took; the consuming cursor replays the record.
+    auto unit_k = [&](int k, bool requesting) -> int {
+        if (k < STATIC_UNITS) return wave + GEMV_WAVES * k;
+        int u = 0;
+        if (requesting) {
+            if (lane == 0) {
+                u = __hip_atomic_fetch_add(l_next, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                l_fifo[k % FIFO] = u;
+            }
+        } else {
+            u = l_fifo[k % FIFO];
+        }
+        return __builtin_amdgcn_readfirstlane(u);
+    };
+    auto start = [&](Cursor &c) { c.k = 0; c.u = wave; c.c = c.u % a.ksplit; c.valid = false; };
+    // make the cursor point at a chunk that exists (or find that the units have run out); a cursor that
+    // has run out stays so and asks for nothing more
+    auto normalize = [&](Cursor &c, bool requesting) {
         for (;;) {
             if (c.u >= n_units) { c.valid = false; return; }
-            if (c.c >= n_chunks) { c.u += GEMV_WAVES; c.c = c.u % a.ksplit; continue; }
+            if (c.c >= n_chunks) { ++c.k; c.u = unit_k(c.k, requesting); c.c = c.u % a.ksplit; continue; }
             c.valid = true;
             return;
         }
     };
-    auto advance = [&](Cursor &c) { c.c += a.ksplit; normalize(c); };
 
     // per-lane slot decomposition of the NI load instructions of a stage: slot = i*64 + lane -> (row r, chunk c)
     int slot_r[NI], slot_c[NI];
@@ -278,16 +300,18 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     // issuing them after the stream would make them wait for the first stages), the rest of the prologue
     // overlaps with the first stages' flight ----
     Cursor lc;
-    lc.u = wave; lc.c = lc.u % a.ksplit; lc.valid = false;
-    normalize(lc);
+    start(lc);
     int issued = 0;
-    for (int s = 0; s < NST - 1 && lc.valid; ++s) {
+    for (int s = 0; s < NST - 1; ++s) { // touches units k = 0, 1 only
+        normalize(lc, true);
+        if (!lc.valid) break;
         issue(lc, s);
-        advance(lc);
+        lc.c += a.ksplit;
         ++issued;
     }
 
     // zero the partial sums and the zero operand
+    if (threadIdx.x == 0) *l_next = STATIC_UNITS * GEMV_WAVES;
     if (threadIdx.x < 8) reinterpret_cast<uint32_t *>(l_zero)[threadIdx.x] = 0u;
     if (a.ksplit > 1)
         for (int i = threadIdx.x; i < n_units * TT * 16; i += GEMV_THREADS) l_part[i] = 0.f;
@@ -337,8 +361,8 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     const int64_t slab_stride = static_cast<int64_t>(a.n_tiles) * 16 * TT; // elements per slab in the global partial sums
 
     Cursor cc;
-    cc.u = wave; cc.c = cc.u % a.ksplit; cc.valid = false;
-    normalize(cc);
+    start(cc);
+    normalize(cc, false);
     int step = 0, st = 0;
 
     float yacc[TT], macc[TT];
@@ -402,15 +426,19 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
                 }
             }
         }
+        // the third stage goes out once this wave's digits are written; from here on a stage is refilled
+        // as soon as it has been consumed
+        normalize(lc, true);
+        if (lc.valid) {
+            issue(lc, NST - 1);
+            lc.c += a.ksplit;
+            ++issued;
+        }
         lds_barrier();
 
         // ---- consume this wave's stages of the slab ----
+
         while (cc.valid) {
-            if (lc.valid) {
-                issue(lc, (st + NST - 1) % NST);
-                advance(lc);
-                ++issued;
-            }
             const int newer = issued - (step + 1); // stages requested after the one consumed now
             if (newer >= 2) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
             else if (newer == 1) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
@@ -466,7 +494,8 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
 
             // next stage of this wave; leave the unit's sums in its slot when the unit ends
             const int u_done = cc.u;
-            advance(cc);
+            cc.c += a.ksplit;
+            normalize(cc, false);
             if (!cc.valid || cc.u != u_done) {
                 float *slot = l_part + u_done * (TT * 16);
                 const int tile_done = tl0 + u_done / a.ksplit;
@@ -484,6 +513,12 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
                     yacc[t] = 0.f;
                     macc[t] = 0.f;
                 }
+            }
+            normalize(lc, true);
+            if (lc.valid) {
+                issue(lc, st);
+                lc.c += a.ksplit;
+                ++issued;
             }
             st = (st + 1) % NST;
             ++step;
@@ -561,7 +596,7 @@ static int device_cu_count()
 
 static size_t fixed_lds(int T, int part_floats)
 {
-    return RING_BYTES + 32 + static_cast<size_t>(part_floats) * 4 + (16 * T + 2 * T) * 4 + 64;
+    return RING_BYTES + 32 + static_cast<size_t>(part_floats) * 4 + (16 * T + 2 * T) * 4 + (1 + GEMV_WAVES * FIFO) * 4 + 64;
 }
 
 // Decomposition of a launch: slabs of K (as few as the LDS allows), and waves per tile.  Candidates are
@@ -588,7 +623,7 @@ static PPlan plan_for(int n_tiles, int nb, int T)
         p.slab_blocks = ((nb + n_slabs - 1) / n_slabs + 1) & ~1;
         if ((nb + p.slab_blocks - 1) / p.slab_blocks != n_slabs) continue; // rounding to even merged two slabs
         const int chunks = (p.slab_blocks + PBS - 1) / PBS;
-        for (int ks = 1; ks <= GEMV_WAVES && ks <= chunks; ks *= 2) {
+        for (int ks = 1; ks <= 4 * GEMV_WAVES && ks <= chunks; ks *= 2) {
             // ks == 1: a wave owns its tiles and stores their sums itself; otherwise the parts meet in LDS
             const int part_floats = ks == 1 ? tiles_wg : tiles_wg * ks * T * 16;
             const size_t lds = fixed_lds(T, part_floats) + per_block * p.slab_blocks;
@@ -598,7 +633,8 @@ static PPlan plan_for(int n_tiles, int nb, int T)
             const int units = tiles_wg * ks;
             const int rounds = (units + GEMV_WAVES - 1) / GEMV_WAVES;
             const double longest = static_cast<double>(rounds) * ((chunks + ks - 1) / ks);
-            const double score = ideal / longest * (1.0 - 0.03 * (n_slabs - n_min));
+            // waves take units as they finish: finer parts even out what the memory system does not
+            const double score = ideal / longest * (1.0 - 0.03 * (n_slabs - n_min)) * (1.0 + 0.001 * ks);
             if (score > best_score + 1e-9) {
                 best_score = score;
                 best = p;
