@@ -127,7 +127,7 @@ def main():
         "per_launch_us": {k: round(v, 2) for k, v in per_launch_us.items()},
         "roofline": {
             "bound": "hbm",
-            "kernel": f"gemv_q4k_persistent_kernel<{cfg.T}, 1, 2> (gate/up projections, fused RMSNorm)",
+            "kernel": f"gemv_q4k_persistent_kernel<{cfg.T}> as launched for the gate/up projections (RMSNorm in front, SwiGLU behind)",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",

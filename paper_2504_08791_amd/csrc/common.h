@@ -53,9 +53,14 @@ struct GemvSeg {
 
 // how the mat-vec obtains its activation vector
 enum XMode {
-    X_PLAIN = 0,   // x as given
-    X_RMSNORM = 1, // x * gain / sqrt(mean(x^2) + eps)
-    X_SWIGLU = 2   // silu(x) * x2
+    X_PLAIN = 0,  // x as given
+    X_RMSNORM = 1 // x * gain / sqrt(mean(x^2) + eps)
+};
+
+// what a launch stores
+enum Epilogue {
+    EPI_ROWS = 0,  // every segment's rows (+ residual) to its own y
+    EPI_SWIGLU = 1 // two segments of equal shape (gate, up): silu(gate_r) * up_r to seg[0].y, nothing else
 };
 
 // up to three matrices with the same n_cols multiplied with the same activations in one launch
@@ -67,10 +72,9 @@ struct GemvArgs {
     int64_t ldx;
     int T;
     int xmode;         // XMode
-    const float *x2;   // X_SWIGLU: second operand [T][ldx]
+    int epi;           // Epilogue
     const float *gain; // X_RMSNORM: fp32 [n_cols]
     float eps;         // X_RMSNORM
-    float *x_tap;      // optional fp32 [T][n_cols]: the transformed activations (test hook)
 };
 
 prima_status launch_dequant(const uint8_t *W, int64_t n_rows, int64_t n_cols, float *out, hipStream_t st);

@@ -55,16 +55,16 @@ struct PGemvArgs {
     int seg_tile0[3]; // first 16-row tile of each segment
     int nseg, n_tiles, nb, T;
     // activations
-    int xmode;
-    const float *x, *x2, *gain;
+    int xmode, epi;
+    const float *x, *gain;
     int64_t ldx;
     float eps;
-    float *x_tap; // optional [T][K]: transformed fp32 activations (written by workgroup 0)
     // decomposition
     int ksplit;      // waves sharing a tile: unit = (tile, part), part p takes chunks p, p+ksplit, ...
     int slab_blocks; // super-blocks of K per slab (even); workgroup w handles slab w % n_slabs
     int n_slabs;
     int units_cap;   // floats reserved for the partial sums (and the per-tile flags of the slab reduction)
+    int direct;      // a wave owns whole rows of the slab (ksplit == 1) and stores their sums itself
     int n_wg;
     float *part;        // n_slabs > 1: partial sums [n_slabs][n_tiles*16][T]
     unsigned *arrivals; // n_slabs > 1: per-tile arrival counters, zero between launches
@@ -101,24 +101,17 @@ __device__ __forceinline__ long pack64(uint32_t lo, uint32_t hi)
 }
 
 // eight consecutive activations of token t starting at column c0, before the RMSNorm scale:
-// X_PLAIN x, X_RMSNORM x*gain (the 1/rms factor is applied by the caller), X_SWIGLU silu(x)*x2
-template <int XMODE>
+// X_PLAIN x, X_RMSNORM x*gain (the 1/rms factor is applied by the caller)
 __device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, float *f)
 {
     const float *xp = a.x + t * a.ldx + c0;
     const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
     f[0] = v0.x; f[1] = v0.y; f[2] = v0.z; f[3] = v0.w; f[4] = v1.x; f[5] = v1.y; f[6] = v1.z; f[7] = v1.w;
-    if (XMODE == X_RMSNORM) {
+    if (a.xmode == X_RMSNORM) {
         const float4 g0 = *reinterpret_cast<const float4 *>(a.gain + c0), g1 = *reinterpret_cast<const float4 *>(a.gain + c0 + 4);
         const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
         for (int e = 0; e < 8; ++e) f[e] *= gg[e];
-    } else if (XMODE == X_SWIGLU) {
-        const float *up = a.x2 + t * a.ldx + c0;
-        const float4 u0 = *reinterpret_cast<const float4 *>(up), u1 = *reinterpret_cast<const float4 *>(up + 4);
-        const float uu[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] = f[e] / (1.0f + expf(-f[e])) * uu[e];
     }
 }
 
@@ -130,9 +123,11 @@ struct Cursor {
 constexpr int STATIC_UNITS = 2; // units per wave assigned by position; the rest go to whichever wave asks first
 constexpr int FIFO = 8;         // units a wave may have requested and not yet consumed (a power of two > NST)
 
-// TT tokens; XMODE how the activations are obtained; NSEG matrices sharing the activations (compile-time
-// so that the projections of a layer appear as separate kernels in a profile)
-template <int TT, int XMODE, int NSEG>
+// TT tokens per pass.  The kind of activations, the number of matrices and the epilogue are run-time
+// arguments: the projections of a layer then share one piece of code, which stays in the instruction
+// caches from launch to launch (with one kernel per projection every launch started on cold caches and
+// took 3-4 us longer).
+template <int TT>
 __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemvArgs a)
 {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -140,12 +135,16 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15, g = lane >> 4;
     const int K = a.nb * QK;
+    const bool rmsnorm = a.xmode == X_RMSNORM;
+    const bool pairs = a.epi == EPI_SWIGLU;
+    const int gran = pairs ? 2 : 1; // tiles that are finished together: a (gate, up) pair sits on tiles 2p, 2p+1
 
     // slab and tiles of this workgroup
     const int slab = blockIdx.x % a.n_slabs, rank = blockIdx.x / a.n_slabs;
     const int nwg_slab = (a.n_wg - slab + a.n_slabs - 1) / a.n_slabs; // workgroups that share this slab
-    const int tl0 = static_cast<int>(static_cast<int64_t>(a.n_tiles) * rank / nwg_slab);
-    const int tl1 = static_cast<int>(static_cast<int64_t>(a.n_tiles) * (rank + 1) / nwg_slab);
+    const int n_groups = a.n_tiles / gran;
+    const int tl0 = gran * static_cast<int>(static_cast<int64_t>(n_groups) * rank / nwg_slab);
+    const int tl1 = gran * static_cast<int>(static_cast<int64_t>(n_groups) * (rank + 1) / nwg_slab);
     const int ntl = tl1 - tl0;
     if (ntl == 0) return;
     const int n_units = ntl * a.ksplit;
@@ -207,12 +206,13 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     }
     const int64_t pitch16 = static_cast<int64_t>(a.nb) * 9; // row pitch in 16-byte units (< 2^27: n_cols < 2^32)
 
-    // request the stage at cursor c into ring stage st: exactly NI load instructions, always
-    // segment of a tile, from statically indexed kernel arguments only (scalar selects, no memory access)
-    auto seg_of = [&](int tile, const uint4 *&W16, int64_t &n_rows, int &tile0) {
-        W16 = reinterpret_cast<const uint4 *>(a.seg[0].W); n_rows = a.seg[0].n_rows; tile0 = 0;
-        if (NSEG > 1 && tile >= a.seg_tile0[1]) { W16 = reinterpret_cast<const uint4 *>(a.seg[1].W); n_rows = a.seg[1].n_rows; tile0 = a.seg_tile0[1]; }
-        if (NSEG > 2 && tile >= a.seg_tile0[2]) { W16 = reinterpret_cast<const uint4 *>(a.seg[2].W); n_rows = a.seg[2].n_rows; tile0 = a.seg_tile0[2]; }
+    // matrix and position of a tile, from statically indexed kernel arguments only (scalar selects, no
+    // memory access): sg segment, tis tile inside the segment
+    auto seg_of = [&](int tile, int &sg, int &tis) {
+        if (pairs) { sg = tile & 1; tis = tile >> 1; return; }
+        sg = 0; tis = tile;
+        if (a.nseg > 1 && tile >= a.seg_tile0[1]) { sg = 1; tis = tile - a.seg_tile0[1]; }
+        if (a.nseg > 2 && tile >= a.seg_tile0[2]) { sg = 2; tis = tile - a.seg_tile0[2]; }
     };
     // offsets (16-byte units) of this lane's slots from the first chunk of a full stage
     int off_full[NI];
@@ -222,11 +222,11 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     // request the stage at cursor c into ring stage st: exactly NI load instructions, always
     auto issue = [&](const Cursor &c, int st) {
         const int tile = tl0 + c.u / a.ksplit;
-        const uint4 *W16;
-        int64_t n_rows;
-        int tile0;
-        seg_of(tile, W16, n_rows, tile0);
-        const int64_t row0 = static_cast<int64_t>(tile - tile0) * 16;
+        int sg, tis;
+        seg_of(tile, sg, tis);
+        const uint4 *W16 = reinterpret_cast<const uint4 *>(sg == 0 ? a.seg[0].W : (sg == 1 ? a.seg[1].W : a.seg[2].W));
+        const int64_t n_rows = sg == 0 ? a.seg[0].n_rows : (sg == 1 ? a.seg[1].n_rows : a.seg[2].n_rows);
+        const int64_t row0 = static_cast<int64_t>(tis) * 16;
         const int rows_valid = static_cast<int>(min<int64_t>(16, n_rows - row0));
         const int blk0 = sb0 + c.c * PBS;
         const int nblk = min(PBS, sb1 - blk0);
@@ -249,11 +249,13 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         }
     };
 
-    // ---- statistics of the activations: 1/rms (RMSNorm input) and the power-of-two scale ----
+    // ---- statistics of the activations: 1/rms over the whole row (RMSNorm input) and the power-of-two
+    // scale of this slab's part (each slab has its own, its sums are scaled back before they meet) ----
     // One token: every thread keeps its groups of 8 activations in registers from here to the
     // quantisation (no second trip to memory).  Several tokens: they are read again.
     constexpr int MAXG = 8;                                  // register-resident groups per thread
-    const bool resident = TT == 1 && K / 8 <= MAXG * GEMV_THREADS;
+    const int g_lo = rmsnorm ? 0 : sb0 * 32, g_hi = rmsnorm ? K / 8 : sb1 * 32; // groups of 8 columns to look at
+    const bool resident = TT == 1 && g_hi - g_lo <= MAXG * GEMV_THREADS;
     float xr[TT == 1 ? MAXG : 1][8];
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
@@ -261,29 +263,33 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         if (TT == 1 && resident) {
 #pragma unroll
             for (int i = 0; i < MAXG; ++i) {
-                const int gi = threadIdx.x + i * GEMV_THREADS;
-                if (gi < K / 8) {
-                    if (XMODE == X_RMSNORM) {
+                const int gi = g_lo + threadIdx.x + i * GEMV_THREADS;
+                if (gi < g_hi) {
+                    if (rmsnorm) {
                         const float *xp = a.x + gi * 8;
                         const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
                         ss += ((v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w)) + ((v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w));
                     }
-                    load_act8<XMODE>(a, 0, gi * 8, xr[TT == 1 ? i : 0]);
+                    if (gi >= sb0 * 32 && gi < sb1 * 32) {
+                        load_act8(a, 0, gi * 8, xr[TT == 1 ? i : 0]);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xr[TT == 1 ? i : 0][e]));
+                        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xr[TT == 1 ? i : 0][e]));
+                    }
                 }
             }
         } else {
-            for (int gi = threadIdx.x; gi < K / 8; gi += GEMV_THREADS) {
+            for (int gi = g_lo + threadIdx.x; gi < g_hi; gi += GEMV_THREADS) {
                 float f[8];
-                if (XMODE == X_RMSNORM) {
+                if (rmsnorm) {
                     const float *xp = a.x + t * a.ldx + gi * 8;
                     const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
                     ss += ((v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w)) + ((v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w));
                 }
-                load_act8<XMODE>(a, t, gi * 8, f);
+                if (gi >= sb0 * 32 && gi < sb1 * 32) {
+                    load_act8(a, t, gi * 8, f);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
+                    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
+                }
             }
         }
         // both reductions in one round: wave shuffles here, one barrier and fixed-order sums below
@@ -313,7 +319,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     // zero the partial sums and the zero operand
     if (threadIdx.x == 0) *l_next = STATIC_UNITS * GEMV_WAVES;
     if (threadIdx.x < 8) reinterpret_cast<uint32_t *>(l_zero)[threadIdx.x] = 0u;
-    if (a.ksplit > 1)
+    if (!a.direct)
         for (int i = threadIdx.x; i < n_units * TT * 16; i += GEMV_THREADS) l_part[i] = 0.f;
 
     lds_barrier();
@@ -323,7 +329,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         float ss = red[0], amax = red[8];
 #pragma unroll
         for (int i = 1; i < GEMV_WAVES; ++i) { ss += red[i]; amax = fmaxf(amax, red[8 + i]); } // fixed order
-        const float inv_rms = XMODE == X_RMSNORM ? 1.0f / sqrtf(ss / static_cast<float>(K) + a.eps) : 1.f;
+        const float inv_rms = rmsnorm ? 1.0f / sqrtf(ss / static_cast<float>(K) + a.eps) : 1.f;
         amax *= inv_rms; // max |x*gain| / rms
         int ex = 0;
         if (amax > 0.f) frexpf(amax, &ex); // amax = m * 2^ex, m in [0.5, 1)
@@ -345,18 +351,25 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     const int a_mul = active ? 1 : 0;                                              // inactive lanes stay on the zeros
     const int fsh = 6 * g;
 
-    // scale, residual, store of one finished output
-    auto finish = [&](int tile, int jj, int t, float v) {
-        int sg = 0;
-        if (NSEG > 1 && tile >= a.seg_tile0[1]) sg = 1;
-        if (NSEG > 2 && tile >= a.seg_tile0[2]) sg = 2;
-        const GemvSeg &sgm = a.seg[sg];
-        const int64_t row = static_cast<int64_t>(tile - a.seg_tile0[sg]) * 16 + jj;
-        if (row < sgm.n_rows) {
-            v *= l_inv[t];
-            if (sgm.resid) v += sgm.resid[t * sgm.ldr + row];
-            sgm.y[t * sgm.ldy + row] = v;
+    // residual and store of one finished output of an EPI_ROWS launch (v already scaled back)
+    auto out_row = [&](int tile, int jj, int t, float v) {
+        int sg, tis;
+        seg_of(tile, sg, tis);
+        const int64_t n_rows = sg == 0 ? a.seg[0].n_rows : (sg == 1 ? a.seg[1].n_rows : a.seg[2].n_rows);
+        const int64_t row = static_cast<int64_t>(tis) * 16 + jj;
+        if (row < n_rows) {
+            const float *resid = sg == 0 ? a.seg[0].resid : (sg == 1 ? a.seg[1].resid : a.seg[2].resid);
+            float *y = sg == 0 ? a.seg[0].y : (sg == 1 ? a.seg[1].y : a.seg[2].y);
+            const int64_t ldy = sg == 0 ? a.seg[0].ldy : (sg == 1 ? a.seg[1].ldy : a.seg[2].ldy);
+            const int64_t ldr = sg == 0 ? a.seg[0].ldr : (sg == 1 ? a.seg[1].ldr : a.seg[2].ldr);
+            if (resid) v += resid[t * ldr + row];
+            y[t * ldy + row] = v;
         }
+    };
+    // EPI_SWIGLU: gate and up sums of row (pair, jj) -> silu(gate) * up
+    auto out_pair = [&](int tile_even, int jj, int t, float gt, float up) {
+        const int64_t row = static_cast<int64_t>(tile_even >> 1) * 16 + jj;
+        if (row < a.seg[0].n_rows) a.seg[0].y[t * a.seg[0].ldy + row] = gt / (1.0f + expf(-gt)) * up;
     };
     const int64_t slab_stride = static_cast<int64_t>(a.n_tiles) * 16 * TT; // elements per slab in the global partial sums
 
@@ -374,12 +387,6 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         // digits [S][4][32 bytes]; byte order inside a digit row: for each group a of 8 values,
         // values 8a + {0,2,4,6,1,3,5,7}, the order in which the nibble split delivers the weights.
         auto quantise8 = [&](int t, int gi, const float *f, float S) {
-            if (a.x_tap && rank == 0) { // one workgroup per slab records its share
-                const float unq = S * l_inv[t]; // 1/rms for RMSNorm input, 1 otherwise
-                float *tp = a.x_tap + static_cast<int64_t>(t) * K + gi * 8;
-                *reinterpret_cast<float4 *>(tp) = make_float4(f[0] * unq, f[1] * unq, f[2] * unq, f[3] * unq);
-                *reinterpret_cast<float4 *>(tp + 4) = make_float4(f[4] * unq, f[5] * unq, f[6] * unq, f[7] * unq);
-            }
             // xfix = rint(f*S) (one rounding to integer).  Its four signed base-256 digits are the bytes of
             // (xfix + 0x80808080) ^ 0x80808080: adding 128 to every digit makes them the unsigned bytes of
             // the biased number, and flipping bit 7 of a byte subtracts the 128 again in two's complement.
@@ -412,7 +419,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
             const float S = l_scale[0];
 #pragma unroll
             for (int i = 0; i < MAXG; ++i) {
-                const int gi = threadIdx.x + i * GEMV_THREADS;
+                const int gi = g_lo + threadIdx.x + i * GEMV_THREADS;
                 if (gi >= sb0 * 32 && gi < sb1 * 32) quantise8(0, gi, xr[TT == 1 ? i : 0], S);
             }
         } else {
@@ -421,7 +428,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
                 const float S = l_scale[t];
                 for (int gi = sb0 * 32 + threadIdx.x; gi < sb1 * 32; gi += GEMV_THREADS) {
                     float f[8];
-                    load_act8<XMODE>(a, t, gi * 8, f);
+                    load_act8(a, t, gi * 8, f);
                     quantise8(t, gi, f, S);
                 }
             }
@@ -437,7 +444,6 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         lds_barrier();
 
         // ---- consume this wave's stages of the slab ----
-
         while (cc.valid) {
             const int newer = issued - (step + 1); // stages requested after the one consumed now
             if (newer >= 2) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
@@ -505,9 +511,9 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
                     v += __shfl_xor(v, 16, 64);
                     v += __shfl_xor(v, 32, 64);
                     if (g == 0) {
-                        if (a.ksplit > 1) slot[t * 16 + j] = v;                    // parts of the tile meet in LDS
-                        else if (a.n_slabs == 1) finish(tile_done, j, t, v);       // the wave owned the whole row: done
-                        else __hip_atomic_store(a.part + slab * slab_stride + static_cast<int64_t>(tile_done) * 16 * TT + t * 16 + j, v,
+                        if (!a.direct) slot[t * 16 + j] = v;                                  // the parts of a tile meet in LDS
+                        else if (a.n_slabs == 1) out_row(tile_done, j, t, v * l_inv[t]);     // the wave owned the whole row: done
+                        else __hip_atomic_store(a.part + slab * slab_stride + static_cast<int64_t>(tile_done) * 16 * TT + t * 16 + j, v * l_inv[t],
                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                     yacc[t] = 0.f;
@@ -526,58 +532,66 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     }
     lds_barrier();
 
-    // ---- epilogue: add the parts of every (tile, row, token) in part order ----
+    // ---- epilogue ----
+    // this slab's sum of (local tile, element) over the parts in part order, scaled back to real units
+    auto slab_sum = [&](int tile_local, int rem) {
+        float v = 0.f;
+        for (int p = 0; p < a.ksplit; ++p) v += l_part[(tile_local * a.ksplit + p) * (TT * 16) + rem];
+        return v * l_inv[rem >> 4];
+    };
+    const int ngl = ntl / gran; // output groups (tiles, or gate/up pairs) of this workgroup
     if (a.n_slabs == 1) {
-        if (a.ksplit > 1)
-        for (int idx = threadIdx.x; idx < ntl * 16 * TT; idx += GEMV_THREADS) {
-            const int tile_local = idx / (16 * TT);
-            const int rem = idx - tile_local * (16 * TT);
+        if (a.direct) return;
+        for (int idx = threadIdx.x; idx < ngl * 16 * TT; idx += GEMV_THREADS) {
+            const int gl = idx / (16 * TT);
+            const int rem = idx - gl * (16 * TT);
             const int t = rem >> 4, jj = rem & 15;
-            float v = 0.f;
-            for (int p = 0; p < a.ksplit; ++p) v += l_part[(tile_local * a.ksplit + p) * (TT * 16) + t * 16 + jj];
-            finish(tl0 + tile_local, jj, t, v);
+            if (pairs) out_pair(tl0 + 2 * gl, jj, t, slab_sum(2 * gl, rem), slab_sum(2 * gl + 1, rem));
+            else out_row(tl0 + gl, jj, t, slab_sum(gl, rem));
         }
         return;
     }
 
-    // several slabs: this slab's sums go to global memory; whoever arrives last at a tile adds the slabs
-    if (a.ksplit > 1)
-    for (int idx = threadIdx.x; idx < ntl * 16 * TT; idx += GEMV_THREADS) {
-        const int tile_local = idx / (16 * TT);
-        const int rem = idx - tile_local * (16 * TT);
-        float v = 0.f;
-        for (int p = 0; p < a.ksplit; ++p) v += l_part[(tile_local * a.ksplit + p) * (TT * 16) + rem];
-        __hip_atomic_store(a.part + slab * slab_stride + static_cast<int64_t>(tl0 + tile_local) * 16 * TT + rem, v,
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    // several slabs: this slab's sums go to global memory; whoever arrives last at a tile (or pair) adds the slabs
+    if (!a.direct)
+        for (int idx = threadIdx.x; idx < ntl * 16 * TT; idx += GEMV_THREADS) {
+            const int tile_local = idx / (16 * TT);
+            const int rem = idx - tile_local * (16 * TT);
+            __hip_atomic_store(a.part + slab * slab_stride + static_cast<int64_t>(tl0 + tile_local) * 16 * TT + rem, slab_sum(tile_local, rem),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     // The partial sums are written with device-scope (write-through) stores and read back with
     // device-scope loads, so they never sit in one XCD's L2 only; what is left to order is "all of this
     // workgroup's stores have completed" before its arrival is counted: vmcnt(0) + barrier.  (A release
     // fence would do the same but writes back and invalidates the whole L2 per workgroup.)
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    for (int tile_local = threadIdx.x; tile_local < ntl; tile_local += GEMV_THREADS) {
-        const unsigned prev = __hip_atomic_fetch_add(a.arrivals + tl0 + tile_local, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int grp0 = tl0 / gran;
+    for (int gl = threadIdx.x; gl < ngl; gl += GEMV_THREADS) {
+        const unsigned prev = __hip_atomic_fetch_add(a.arrivals + grp0 + gl, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const bool last = prev + 1 == static_cast<unsigned>(a.n_slabs);
-        if (last) __hip_atomic_store(a.arrivals + tl0 + tile_local, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); // ready for the next launch
-        l_part[tile_local] = last ? 1.f : 0.f; // l_part is free again after the barrier above
+        if (last) __hip_atomic_store(a.arrivals + grp0 + gl, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); // ready for the next launch
+        l_part[gl] = last ? 1.f : 0.f; // l_part is free again after the barrier above
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    for (int idx = threadIdx.x; idx < ntl * 16 * TT; idx += GEMV_THREADS) {
-        const int tile_local = idx / (16 * TT);
-        if (l_part[tile_local] == 0.f) continue;
-        const int rem = idx - tile_local * (16 * TT);
-        const int t = rem >> 4, jj = rem & 15;
+    auto all_slabs = [&](int tile, int rem) {
         float v = 0.f;
         for (int sl = 0; sl < a.n_slabs; ++sl) // fixed order
-            v += __hip_atomic_load(a.part + sl * slab_stride + static_cast<int64_t>(tl0 + tile_local) * 16 * TT + rem,
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        finish(tl0 + tile_local, jj, t, v);
+            v += __hip_atomic_load(a.part + sl * slab_stride + static_cast<int64_t>(tile) * 16 * TT + rem, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return v;
+    };
+    for (int idx = threadIdx.x; idx < ngl * 16 * TT; idx += GEMV_THREADS) {
+        const int gl = idx / (16 * TT);
+        if (l_part[gl] == 0.f) continue;
+        const int rem = idx - gl * (16 * TT);
+        const int t = rem >> 4, jj = rem & 15;
+        if (pairs) out_pair(tl0 + 2 * gl, jj, t, all_slabs(tl0 + 2 * gl, rem), all_slabs(tl0 + 2 * gl + 1, rem));
+        else out_row(tl0 + gl, jj, t, all_slabs(tl0 + gl, rem));
     }
 }
 
 // ------------------------------------------------------------------------------------------
 struct PPlan {
-    int n_tiles, nb, n_wg, ksplit, slab_blocks, n_slabs, units_cap;
+    int n_tiles, nb, n_wg, ksplit, slab_blocks, n_slabs, units_cap, direct;
     size_t lds_bytes;
     bool ok;
 };
@@ -601,8 +615,10 @@ static size_t fixed_lds(int T, int part_floats)
 
 // Decomposition of a launch: slabs of K (as few as the LDS allows), and waves per tile.  Candidates are
 // ranked by the longest wave's share of the ideal time; more slabs cost partial-sum traffic.
-static PPlan plan_for(int n_tiles, int nb, int T)
+static PPlan plan_for(int n_tiles, int nb, int T, int epi)
 {
+    const int gran = epi == EPI_SWIGLU ? 2 : 1; // tiles that stay together on a workgroup
+    const int n_groups = n_tiles / gran;
     PPlan best{};
     best.ok = false;
     double best_score = 0.0;
@@ -616,16 +632,18 @@ static PPlan plan_for(int n_tiles, int nb, int T)
         p.n_tiles = n_tiles;
         p.n_slabs = n_slabs;
         p.n_wg = cus;
-        if (p.n_wg > n_tiles * n_slabs) p.n_wg = n_tiles * n_slabs;
+        if (p.n_wg > n_groups * n_slabs) p.n_wg = n_groups * n_slabs;
         if (p.n_wg < n_slabs) continue;
         const int wg_per_slab = p.n_wg / n_slabs;                     // the slabs with most tiles per workgroup
-        const int tiles_wg = (n_tiles + wg_per_slab - 1) / wg_per_slab;
+        const int tiles_wg = gran * ((n_groups + wg_per_slab - 1) / wg_per_slab);
         p.slab_blocks = ((nb + n_slabs - 1) / n_slabs + 1) & ~1;
         if ((nb + p.slab_blocks - 1) / p.slab_blocks != n_slabs) continue; // rounding to even merged two slabs
         const int chunks = (p.slab_blocks + PBS - 1) / PBS;
         for (int ks = 1; ks <= 4 * GEMV_WAVES && ks <= chunks; ks *= 2) {
-            // ks == 1: a wave owns its tiles and stores their sums itself; otherwise the parts meet in LDS
-            const int part_floats = ks == 1 ? tiles_wg : tiles_wg * ks * T * 16;
+            // ks == 1: a wave owns its tiles and stores their sums itself (a pair's two sums can only meet in
+            // global memory, i.e. with several slabs); otherwise the parts meet in LDS
+            const bool direct = ks == 1 && (gran == 1 || n_slabs > 1);
+            const int part_floats = direct ? tiles_wg : tiles_wg * ks * T * 16;
             const size_t lds = fixed_lds(T, part_floats) + per_block * p.slab_blocks;
             if (lds > LDS_BUDGET || part_floats * 4 > 24 * 1024) continue;
             if (n_min == 0) n_min = n_slabs;
@@ -639,6 +657,7 @@ static PPlan plan_for(int n_tiles, int nb, int T)
                 best_score = score;
                 best = p;
                 best.ksplit = ks;
+                best.direct = direct ? 1 : 0;
                 best.units_cap = part_floats;
                 best.lds_bytes = lds;
                 best.ok = true;
@@ -667,49 +686,43 @@ size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T)
     size_t worst = 0;
     for (int t0 = 0; t0 < T; t0 += MAX_T_PASS) {
         const int Tp = T - t0 < MAX_T_PASS ? T - t0 : MAX_T_PASS;
-        PPlan p = plan_for(n_tiles, static_cast<int>(n_cols / QK), Tp);
-        p.n_slabs += 1; // a slightly different tile count may need one more slab
-        const size_t b = part_bytes(p, Tp);
-        worst = b > worst ? b : worst;
+        for (int epi : {EPI_ROWS, EPI_SWIGLU}) {
+            PPlan p = plan_for(n_tiles & ~1, static_cast<int>(n_cols / QK), Tp, epi);
+            p.n_tiles = n_tiles;
+            p.n_slabs += 1; // a slightly different tile count may need one more slab
+            const size_t b = part_bytes(p, Tp);
+            worst = b > worst ? b : worst;
+        }
     }
     return arrivals_bytes(n_tiles) + worst;
 }
 
 size_t gemv_arrivals_bytes(int64_t n_rows_total) { return arrivals_bytes(static_cast<int>((n_rows_total + 15) / 16) + 2); }
 
-template <int TT, int XMODE, int NSEG>
-static hipError_t launch_inst(const PGemvArgs &a, const PPlan &p, hipStream_t st)
+template <int TT>
+static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
 {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_q4k_persistent_kernel<TT, XMODE, NSEG>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_q4k_persistent_kernel<TT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(LDS_BUDGET));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemv_q4k_persistent_kernel<TT, XMODE, NSEG>), dim3(p.n_wg), dim3(GEMV_THREADS), p.lds_bytes, st, a);
+    hipLaunchKernelGGL((gemv_q4k_persistent_kernel<TT>), dim3(p.n_wg), dim3(GEMV_THREADS), p.lds_bytes, st, a);
     return hipGetLastError();
-}
-
-// the combinations a decoder layer and the output layer use
-template <int TT>
-static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
-{
-    if (a.xmode == X_RMSNORM && a.nseg == 3) return launch_inst<TT, X_RMSNORM, 3>(a, p, st); // Q/K/V
-    if (a.xmode == X_RMSNORM && a.nseg == 2) return launch_inst<TT, X_RMSNORM, 2>(a, p, st); // gate/up
-    if (a.xmode == X_RMSNORM && a.nseg == 1) return launch_inst<TT, X_RMSNORM, 1>(a, p, st); // output layer
-    if (a.xmode == X_SWIGLU && a.nseg == 1) return launch_inst<TT, X_SWIGLU, 1>(a, p, st);   // down
-    if (a.xmode == X_PLAIN && a.nseg == 1) return launch_inst<TT, X_PLAIN, 1>(a, p, st);     // attention output, plain mat-vec
-    return hipErrorInvalidValue;
 }
 
 prima_status launch_gemv_mfma(const GemvArgs &ga, void *ws, size_t ws_bytes, size_t arrivals_region, hipStream_t st)
 {
+    if (ga.xmode != X_PLAIN && ga.xmode != X_RMSNORM) return PRIMA_E_SHAPE;
+    if (ga.epi == EPI_SWIGLU && (ga.nseg != 2 || ga.seg[0].n_rows != ga.seg[1].n_rows)) return PRIMA_E_SHAPE;
+    if (ga.epi != EPI_SWIGLU && ga.epi != EPI_ROWS) return PRIMA_E_SHAPE;
     const int n_tiles = tiles_of(ga);
     // up to MAX_T_PASS tokens per pass over the weights
     for (int t0 = 0; t0 < ga.T; t0 += MAX_T_PASS) {
         const int T = ga.T - t0 < MAX_T_PASS ? ga.T - t0 : MAX_T_PASS;
-        const PPlan p = plan_for(n_tiles, static_cast<int>(ga.n_cols / QK), T);
+        const PPlan p = plan_for(n_tiles, static_cast<int>(ga.n_cols / QK), T, ga.epi);
         if (!p.ok) return PRIMA_E_SHAPE;
         PGemvArgs a{};
         int tile0 = 0;
@@ -725,16 +738,16 @@ prima_status launch_gemv_mfma(const GemvArgs &ga, void *ws, size_t ws_bytes, siz
         a.nb = p.nb;
         a.T = T;
         a.xmode = ga.xmode;
+        a.epi = ga.epi;
         a.x = ga.x + t0 * ga.ldx;
-        a.x2 = ga.x2 ? ga.x2 + t0 * ga.ldx : nullptr;
         a.gain = ga.gain;
         a.ldx = ga.ldx;
         a.eps = ga.eps;
-        a.x_tap = ga.x_tap ? ga.x_tap + static_cast<int64_t>(t0) * ga.n_cols : nullptr;
         a.ksplit = p.ksplit;
         a.slab_blocks = p.slab_blocks;
         a.n_slabs = p.n_slabs;
         a.units_cap = p.units_cap;
+        a.direct = p.direct;
         a.n_wg = p.n_wg;
         if (p.n_slabs > 1) {
             // the counters sit in a region of fixed size at the start of the scratch, so that launches of

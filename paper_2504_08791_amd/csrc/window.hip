@@ -10,7 +10,7 @@ using namespace prima;
 namespace {
 
 struct WindowWs {
-    size_t q, k, v, o, h, g, u, xb0, xb1, rope, attn, gemv, gemv_bytes, arrivals_bytes, total;
+    size_t q, k, v, o, h, a, xb0, xb1, rope, attn, gemv, gemv_bytes, arrivals_bytes, total;
 };
 
 bool dims_ok(const prima_dims *d)
@@ -32,8 +32,7 @@ WindowWs carve(const prima_dims &d, int kv_cap, int T)
     w.v = take(T * kvd * f);
     w.o = take(T * qd * f);
     w.h = take(T * static_cast<size_t>(d.e) * f);
-    w.g = take(T * static_cast<size_t>(d.ffn) * f);
-    w.u = take(T * static_cast<size_t>(d.ffn) * f);
+    w.a = take(T * static_cast<size_t>(d.ffn) * f);
     w.xb0 = take(T * static_cast<size_t>(d.e) * f);
     w.xb1 = take(T * static_cast<size_t>(d.e) * f);
     w.rope = take(T * static_cast<size_t>(d.head_dim) * f);
@@ -68,29 +67,29 @@ prima_status check_layer(const prima_layer &l)
 }
 
 GemvArgs gemv_args(int nseg, int64_t n_cols, const float *x, int64_t ldx, int T, int xmode = X_PLAIN,
-                   const float *x2 = nullptr, const float *gain = nullptr, float eps = 0.f, float *x_tap = nullptr)
+                   const float *gain = nullptr, float eps = 0.f, int epi = EPI_ROWS)
 {
     GemvArgs ga{};
     ga.nseg = nseg; ga.n_cols = n_cols; ga.x = x; ga.ldx = ldx; ga.T = T;
-    ga.xmode = xmode; ga.x2 = x2; ga.gain = gain; ga.eps = eps; ga.x_tap = x_tap;
+    ga.xmode = xmode; ga.epi = epi; ga.gain = gain; ga.eps = eps;
     return ga;
 }
 
 // one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Six launches: Q/K/V projections
 // (RMSNorm fused), attention partial (RoPE + KV append fused) and merge, output projection
-// (+ residual), gate/up projections (RMSNorm fused), down projection (SwiGLU fused, + residual).
+// (+ residual), gate/up projections (RMSNorm fused in front, SwiGLU behind), down projection (+ residual).
 prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
                        const float *x, float *y, void *ws, const WindowWs &w, hipStream_t st,
                        float *tap_q, float *tap_o, float *tap_h, float *tap_a, int only = -1)
 {
     const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
     float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
-    float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *g = at<float>(ws, w.g), *u = at<float>(ws, w.u);
+    float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *act = at<float>(ws, w.a);
     prima_status s;
 #define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
 #define PRIMA_WANT(k) (only < 0 || only == (k))
     if (PRIMA_WANT(PRIMA_K_QKV)) {
-        GemvArgs ga = gemv_args(3, e, x, e, T, X_RMSNORM, nullptr, L.g_attn, d.rms_eps);
+        GemvArgs ga = gemv_args(3, e, x, e, T, X_RMSNORM, L.g_attn, d.rms_eps);
         ga.seg[0] = seg(L.wq, q, qd, qd);
         ga.seg[1] = seg(L.wk, k, kvd, kvd);
         ga.seg[2] = seg(L.wv, v, kvd, kvd);
@@ -107,13 +106,14 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
     }
     if (tap_h && hipMemcpyAsync(tap_h, h, T * e * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     if (PRIMA_WANT(PRIMA_K_GATE_UP)) {
-        GemvArgs ga = gemv_args(2, e, h, e, T, X_RMSNORM, nullptr, L.g_ffn, d.rms_eps);
-        ga.seg[0] = seg(L.wgate, g, F, F);
-        ga.seg[1] = seg(L.wup, u, F, F);
+        GemvArgs ga = gemv_args(2, e, h, e, T, X_RMSNORM, L.g_ffn, d.rms_eps, EPI_SWIGLU);
+        ga.seg[0] = seg(L.wgate, act, F, F); // silu(gate) * up lands here
+        ga.seg[1] = seg(L.wup, nullptr, F, F);
         PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
     }
+    if (tap_a && hipMemcpyAsync(tap_a, act, T * F * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     if (PRIMA_WANT(PRIMA_K_DOWN)) {
-        GemvArgs ga = gemv_args(1, F, g, F, T, X_SWIGLU, u, nullptr, 0.f, tap_a);
+        GemvArgs ga = gemv_args(1, F, act, F, T);
         ga.seg[0] = seg(L.wdown, y, e, e, h, e);
         PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
     }
@@ -327,7 +327,7 @@ prima_status prima_lm_head(const prima_dims *d, const float *g_final, const void
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     prima_status s = launch_zero_arrivals(workspace, gemv_arrivals_bytes(vocab), st);
     if (s != PRIMA_OK) return s;
-    GemvArgs ga = gemv_args(1, d->e, x, d->e, T, X_RMSNORM, nullptr, g_final, d->rms_eps);
+    GemvArgs ga = gemv_args(1, d->e, x, d->e, T, X_RMSNORM, g_final, d->rms_eps);
     ga.seg[0] = seg(w_lm, logits, vocab, vocab);
     return launch_gemv_mfma(ga, workspace, workspace_bytes, gemv_arrivals_bytes(vocab), st);
 }
