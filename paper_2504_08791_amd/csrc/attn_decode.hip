@@ -2,17 +2,26 @@
 // log-sum-exp.  Per layer and step it reads 2(h_k e_k + h_v e_v) n_kv bytes (arXiv 2504.08791,
 // App. A.3, device-loading term) and appends 2(h_k e_k + h_v e_v) bytes per token.
 //
-// One workgroup handles (key range, KV head, group of up to 8 queries that share the head).
+// The work per launch is small (tens of KB per compute unit), so the kernel is built as one short
+// dependency chain: everything a wave needs is requested from memory in its first instructions, and
+// nothing is staged through LDS before the matrix multiply.
+// One workgroup handles (key range, KV head, group of up to 8 queries that share the head); each of
+// its waves takes 16-key tiles of the range.
 //  * Q.K^T runs on the matrix cores: the fp16 cache rows are MFMA operands as they lie in memory
-//    (lane (n, c) loads 16 bytes of key n), the queries are pre-scaled by a power of two and split
-//    into fp16 high and low parts that occupy rows 0-7 and 8-15 of the A operand, so the logits
-//    carry the queries' full fp32 precision with fp32 accumulation.
-//  * softmax statistics are kept online per 16-key tile in fp32.
-//  * P.V runs on the vector ALUs in fp32: lane (dg, ks) owns 8 output columns for the keys
-//    congruent to ks mod 4 (one 128-bit load of V per key), combined across lanes at the end.
-//  * when asked, the kernel also does the layer's RoPE and KV append: queries are rotated as they
-//    are loaded, and the workgroup whose key range holds the new rows rotates k, rounds k and v to
-//    fp16 (nearest even) and stores them before reading them back like any other row.
+//    (lane (n, c) loads 16 bytes of key n), the queries are loaded by every wave straight into the
+//    A-operand layout, rotated there (RoPE partners sit in the same lane), pre-scaled by a power of two
+//    and split into fp16 high and low parts that occupy rows 0-7 and 8-15 of the A operand, so the
+//    logits carry the queries' full fp32 precision with fp32 accumulation.
+//  * softmax statistics are kept online per 16-key tile in fp32; reductions over the 16 keys of a
+//    tile are row rotations inside the vector ALU (DPP), not LDS permutes.
+//  * P.V runs on the vector ALUs in fp32: a lane owns two output columns for all keys of the tile
+//    (one 32-bit load per key), so no reduction across lanes is needed; the probabilities reach the
+//    lanes as LDS broadcasts.
+//  * fused RoPE + KV append: a workgroup whose key range holds new rows builds them from the projection
+//    output (rotate k, round k and v to fp16, nearest even), keeps them in LDS for its own tiles and
+//    stores them to the cache on the side, so the appended rows cost no store-to-load round trip.
+//  * the workgroup that arrives last at a (KV head, query group) merges the key ranges; partial
+//    records travel through device-scope stores and loads, ordered by one counter per group.
 #include "common.h"
 
 namespace prima {
@@ -21,33 +30,99 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int QG = 8;        // queries per workgroup
-constexpr int ATT_WAVES = 4; // waves per workgroup
+constexpr int ATT_WAVES = 8; // waves per workgroup
+constexpr int ATT_THREADS = ATT_WAVES * 64;
 constexpr int MAX_SPLITS = 64;
 
 struct AttnArgs {
     const float *q;       // [T][Hq][D]; rotated already unless rope_tab is set
-    float *q_rot_out;     // optional: rotated queries written back (split 0 only)
+    float *q_rot_out;     // optional: rotated queries written back (first key range only)
     const float *k_new;   // fused append: un-rotated k [T][Hkv][D], else null
     const float *v_new;   // fused append: v [T][Hkv][D]
     const float2 *rope_tab; // [T][D/2] (cos, sin) or null
     __half *K, *V;        // caches [Hkv][kv_cap][D]
     float *part;          // [T*Hq][nsplit][2 + D]
-    int Hq, Hkv, kv_cap, n_past, T, nsplit, keys_per_split, rope_mode;
+    unsigned *arrivals;   // [Hkv * query groups], zero between launches
+    float *o;             // [T][Hq][D]
+    int Hq, Hkv, kv_cap, n_past, T, nsplit, keys_per_split;
 };
 
-__device__ __forceinline__ void rope_pair_index(int i, int half, int mode, int &ia, int &ib)
+// value of lane (i + n) % 16 of the same 16-lane row
+template <int N>
+__device__ __forceinline__ float row_ror(float v)
 {
-    ia = mode ? 2 * i : i;
-    ib = mode ? 2 * i + 1 : i + half;
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row_max16(float v)
+{
+    v = fmaxf(v, row_ror<8>(v));
+    v = fmaxf(v, row_ror<4>(v));
+    v = fmaxf(v, row_ror<2>(v));
+    return fmaxf(v, row_ror<1>(v));
+}
+__device__ __forceinline__ float row_sum16(float v)
+{
+    v += row_ror<8>(v);
+    v += row_ror<4>(v);
+    v += row_ror<2>(v);
+    return v + row_ror<1>(v);
+}
+
+// Rotate the D/8-element slices a lane holds of one head vector: v[x][e] = element 32x + 8c + e.
+// mode 0 pairs element i with i + D/2 (the partner is v[x + NA/2][e] of the same lane), mode 1 pairs
+// 2i with 2i + 1.  tab = this token's D/2 (cos, sin) pairs.
+template <int D, int MODE>
+__device__ __forceinline__ void rope_in_lane(float (&v)[D / 32][8], const float2 *tab, int c)
+{
+    constexpr int NA = D / 32;
+    if (MODE == 0) {
+#pragma unroll
+        for (int x = 0; x < NA / 2; ++x) {
+            const float4 *tp = reinterpret_cast<const float4 *>(tab + 32 * x + 8 * c);
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                const float4 cs = tp[h]; // (cos, sin) of pairs 2h, 2h + 1 of this slice
+                const float a0 = v[x][2 * h], b0 = v[x + NA / 2][2 * h], a1 = v[x][2 * h + 1], b1 = v[x + NA / 2][2 * h + 1];
+                v[x][2 * h] = a0 * cs.x - b0 * cs.y;
+                v[x + NA / 2][2 * h] = a0 * cs.y + b0 * cs.x;
+                v[x][2 * h + 1] = a1 * cs.z - b1 * cs.w;
+                v[x + NA / 2][2 * h + 1] = a1 * cs.w + b1 * cs.z;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int x = 0; x < NA; ++x) {
+            const float4 *tp = reinterpret_cast<const float4 *>(tab + 16 * x + 4 * c);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float4 cs = tp[h];
+                const float a0 = v[x][4 * h], b0 = v[x][4 * h + 1], a1 = v[x][4 * h + 2], b1 = v[x][4 * h + 3];
+                v[x][4 * h] = a0 * cs.x - b0 * cs.y;
+                v[x][4 * h + 1] = a0 * cs.y + b0 * cs.x;
+                v[x][4 * h + 2] = a1 * cs.z - b1 * cs.w;
+                v[x][4 * h + 3] = a1 * cs.w + b1 * cs.z;
+            }
+        }
+    }
 }
 
 template <int D>
-__global__ void __launch_bounds__(ATT_WAVES * 64, 2) attn_partial_kernel(AttnArgs a)
+__device__ __forceinline__ void load_slices(const float *p, int c, float (&v)[D / 32][8])
+{
+#pragma unroll
+    for (int x = 0; x < D / 32; ++x) {
+        const float4 a = *reinterpret_cast<const float4 *>(p + 32 * x + 8 * c), b = *reinterpret_cast<const float4 *>(p + 32 * x + 8 * c + 4);
+        v[x][0] = a.x; v[x][1] = a.y; v[x][2] = a.z; v[x][3] = a.w; v[x][4] = b.x; v[x][5] = b.y; v[x][6] = b.z; v[x][7] = b.w;
+    }
+}
+
+template <int D, int MODE> // head size, RoPE pairing (0: i with i + D/2, 1: 2i with 2i + 1)
+__global__ void __launch_bounds__(ATT_THREADS) attn_decode_kernel(AttnArgs a)
 {
     constexpr int NA = D / 32;   // MFMAs (k-steps of 32) per 16-key tile
-    constexpr int DG = D / 8;    // lanes per V row (8 columns each)
-    constexpr int KS = 64 / DG;  // V rows per wave instruction
-    constexpr int VPT = 16 / KS; // V loads per lane per 16-key tile
+    constexpr int DL = D / 2;    // lanes per V row (2 columns each)
+    constexpr int KSV = 64 / DL; // V rows per wave instruction (1 or 2)
+    constexpr int VPT = 16 / KSV; // V loads per lane per 16-key tile
     const int split = blockIdx.x, kvh = blockIdx.y, qgrp = blockIdx.z;
     const int G = a.Hq / a.Hkv, NQ = G * a.T; // queries on this KV head, index = t*G + hg
     const int q0 = qgrp * QG;
@@ -56,152 +131,186 @@ __global__ void __launch_bounds__(ATT_WAVES * 64, 2) attn_partial_kernel(AttnArg
     const int n_total = a.n_past + a.T;
     const int p_begin = split * a.keys_per_split;
     const int p_end = min(p_begin + a.keys_per_split, n_total);
+    const bool fused = a.k_new != nullptr;
 
-    __shared__ __align__(16) _Float16 s_q[16][D + 8];     // rows 0-7 high parts, 8-15 low parts (+8: bank skew)
-    __shared__ float s_fq[QG];                            // per-query logit factor 2^e / sqrt(D)
-    __shared__ int s_limit[QG];                           // last visible cache row per query
     __shared__ __align__(16) float s_p[ATT_WAVES][16][QG]; // probabilities of the current tile [key][query]
-    __shared__ float s_corr[ATT_WAVES][QG];
+    __shared__ __align__(16) float s_corr[ATT_WAVES][QG];
     __shared__ float s_m[ATT_WAVES][QG], s_l[ATT_WAVES][QG];
     __shared__ __align__(16) float s_o[ATT_WAVES][QG][D];
+    __shared__ int s_last;
+    __shared__ __align__(16) __half s_knew[PRIMA_MAX_TOK][D], s_vnew[PRIMA_MAX_TOK][D]; // the step's new rows (fused append)
 
     __half *Kh = a.K + static_cast<int64_t>(kvh) * a.kv_cap * D;
     __half *Vh = a.V + static_cast<int64_t>(kvh) * a.kv_cap * D;
 
-    // ---- fused KV append: a workgroup whose range contains new rows writes them first (when several
-    // query groups share the range each writes the same values) ----
-    if (a.k_new && p_end > a.n_past && p_begin < n_total) {
-        for (int idx = threadIdx.x; idx < a.T * (D / 2); idx += blockDim.x) {
-            const int t = idx / (D / 2), i = idx - t * (D / 2);
-            const int row = a.n_past + t;
-            if (row < p_begin || row >= p_end) continue;
-            int ia, ib;
-            rope_pair_index(i, D / 2, a.rope_mode, ia, ib);
-            const float2 cs = a.rope_tab[t * (D / 2) + i];
-            const float *kp = a.k_new + (static_cast<int64_t>(t) * a.Hkv + kvh) * D;
-            const float ka = kp[ia], kb = kp[ib];
-            Kh[static_cast<int64_t>(row) * D + ia] = __float2half_rn(ka * cs.x - kb * cs.y);
-            Kh[static_cast<int64_t>(row) * D + ib] = __float2half_rn(ka * cs.y + kb * cs.x);
-            const float *vp = a.v_new + (static_cast<int64_t>(t) * a.Hkv + kvh) * D;
-            Vh[static_cast<int64_t>(row) * D + 2 * i] = __float2half_rn(vp[2 * i]);
-            Vh[static_cast<int64_t>(row) * D + 2 * i + 1] = __float2half_rn(vp[2 * i + 1]);
-        }
-        __threadfence_block();
-    }
-
-    // ---- queries: rotate (if asked), scale by a power of two, split into fp16 high + low ----
-    for (int i = threadIdx.x; i < 16 * (D + 8); i += blockDim.x) (&s_q[0][0])[i] = static_cast<_Float16>(0.f);
-    __syncthreads();
-    // appended rows are visible from here on: request the first tile before staging the queries
     const int mrow = lane & 15, kc = lane >> 4;
-    // softmax bookkeeping for the 4 queries this lane sees in the MFMA result: m = 4*(kc&1) + r
-    const int mq0 = 4 * (kc & 1);
-    // P.V ownership: lane (dg, ks): columns 8dg..8dg+7, keys = tile key 4i + ks (D = 128) or 8i + ks (D = 64)
-    const int dg = lane % DG, ks = lane / DG;
-    float o[QG][8];
-#pragma unroll
-    for (int i = 0; i < QG; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[i][e] = 0.f;
-
+    const int dl = lane % DL, ksl = lane / DL; // P.V: columns 2 dl, 2 dl + 1 of keys ksl, ksl + KSV, ...
     const int last_row = n_total - 1;
+
+    // B operand: lane (n, c) holds elements 32x + 8c .. + 8 of key n.  New rows are not read from the
+    // cache but from LDS, where the workgroup has put them (below).
+    const bool has_new = fused && p_end > a.n_past;
     auto load_k = [&](int k0, half8 *kbuf) {
         const int krow = min(k0 + mrow, last_row);
         const __half *kp = Kh + static_cast<int64_t>(krow) * D + 8 * kc;
 #pragma unroll
         for (int x = 0; x < NA; ++x) kbuf[x] = *reinterpret_cast<const half8 *>(kp + 32 * x);
     };
-    auto load_v = [&](int k0, uint4 *vbuf) {
+    auto patch_k = [&](int k0, half8 *kbuf) {
+        const int krow = min(k0 + mrow, last_row);
+        if (has_new && krow >= a.n_past) {
+#pragma unroll
+            for (int x = 0; x < NA; ++x) kbuf[x] = *reinterpret_cast<const half8 *>(&s_knew[krow - a.n_past][32 * x + 8 * kc]);
+        }
+    };
+    auto load_v = [&](int k0, uint32_t *vbuf) {
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-            const int vrow = min(k0 + KS * i + ks, last_row);
-            vbuf[i] = *reinterpret_cast<const uint4 *>(Vh + static_cast<int64_t>(vrow) * D + 8 * dg);
+            const int vrow = min(k0 + KSV * i + ksl, last_row);
+            vbuf[i] = *reinterpret_cast<const uint32_t *>(Vh + static_cast<int64_t>(vrow) * D + 2 * dl);
+        }
+    };
+    auto patch_v = [&](int k0, uint32_t *vbuf) {
+        if (has_new && k0 + 16 > a.n_past) {
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) {
+                const int vrow = min(k0 + KSV * i + ksl, last_row);
+                if (vrow >= a.n_past) vbuf[i] = *reinterpret_cast<const uint32_t *>(&s_vnew[vrow - a.n_past][2 * dl]);
+            }
         }
     };
 
-    // one K and one V buffer per lane: the next tile's K is requested as soon as the MFMAs have
-    // consumed the current one, the next V as soon as P.V is done
     half8 kb[NA];
-    uint4 vb[VPT];
+    uint32_t vb[VPT];
     const int tile_stride = ATT_WAVES * 16;
     int key0 = p_begin + wave * 16;
-    if (key0 < p_end) {
-        load_k(key0, kb);
-        load_v(key0, vb);
-    }
-    if (wave < 2) {
-        // wave w handles queries 4w..4w+3, 16 lanes per query
-        const int qi_l = wave * 4 + (lane >> 4), sub = lane & 15;
-        if (qi_l < nq) {
+
+    // ---- queries: A operand row m holds query m % 8, high part for m < 8, low part otherwise ----
+    const int qi_l = mrow & 7;
+    const bool q_valid = qi_l < nq;
+    // fused RoPE + KV append: a workgroup whose key range holds new rows builds them once (rotate k, round
+    // k and v to fp16, nearest even), keeps them in LDS for its own tiles and stores them to the cache on
+    // the side; its cache reads of those rows are replaced, never waited for.  When several query groups
+    // share the range each writes the same values.  The inputs are requested here, behind the tile.
+    constexpr int NPT = (PRIMA_MAX_TOK * (D / 2) + ATT_THREADS - 1) / ATT_THREADS; // new (k pair, v pair)s per thread
+    float2 n_cs[NPT], n_k[NPT], n_v[NPT];
+    half8 qa[NA];
+    float fq_own = 0.f; // logit factor 2^-p / sqrt(D) of query qi_l
+    {
+        float qv[NA][8];
+#pragma unroll
+        for (int x = 0; x < NA; ++x)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qv[x][e] = 0.f;
+        if (q_valid) {
             const int qi = q0 + qi_l, t = qi / G, hg = qi - t * G;
             const int64_t qoff = (static_cast<int64_t>(t) * a.Hq + kvh * G + hg) * D;
-            float v[D / 16];
-            float amax = 0.f;
+            load_slices<D>(a.q + qoff, kc, qv);
+        }
+        // the queries (cache hits) are requested first, the tile right behind them: loads return in order,
+        // so the query preparation below runs while the tile is still on its way from HBM
+        if (key0 < p_end) {
+            load_k(key0, kb);
+            load_v(key0, vb);
+        }
+        if (has_new) {
 #pragma unroll
-            for (int c = 0; c < D / 32; ++c) {
-                // pair index i = sub + 16c  (i < D/2)
-                const int i = sub + 16 * c;
-                int ia, ib;
-                rope_pair_index(i, D / 2, a.rope_mode, ia, ib);
-                float xa = a.q[qoff + ia], xb = a.q[qoff + ib];
-                if (a.rope_tab) {
-                    const float2 cs = a.rope_tab[t * (D / 2) + i];
-                    const float ra = xa * cs.x - xb * cs.y, rb = xa * cs.y + xb * cs.x;
-                    xa = ra;
-                    xb = rb;
-                    if (a.q_rot_out && split == 0) {
-                        a.q_rot_out[qoff + ia] = xa;
-                        a.q_rot_out[qoff + ib] = xb;
+            for (int k = 0; k < NPT; ++k) {
+                const int idx = threadIdx.x + k * ATT_THREADS;
+                if (idx < a.T * (D / 2)) {
+                    const int t = idx / (D / 2), i = idx - t * (D / 2);
+                    const int ia = MODE ? 2 * i : i, ib = MODE ? 2 * i + 1 : i + D / 2;
+                    const float *kp = a.k_new + (static_cast<int64_t>(t) * a.Hkv + kvh) * D;
+                    n_cs[k] = a.rope_tab[t * (D / 2) + i];
+                    n_k[k] = make_float2(kp[ia], kp[ib]);
+                    n_v[k] = *reinterpret_cast<const float2 *>(a.v_new + (static_cast<int64_t>(t) * a.Hkv + kvh) * D + 2 * i);
+                }
+            }
+        }
+        if (q_valid) {
+            const int qi = q0 + qi_l, t = qi / G, hg = qi - t * G;
+            const int64_t qoff = (static_cast<int64_t>(t) * a.Hq + kvh * G + hg) * D;
+            if (a.rope_tab) {
+                rope_in_lane<D, MODE>(qv, a.rope_tab + t * (D / 2), kc);
+                if (a.q_rot_out && split == 0 && wave == 0 && mrow < 8) {
+#pragma unroll
+                    for (int x = 0; x < NA; ++x) {
+                        float *dst = a.q_rot_out + qoff + 32 * x + 8 * kc;
+                        *reinterpret_cast<float4 *>(dst) = make_float4(qv[x][0], qv[x][1], qv[x][2], qv[x][3]);
+                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(qv[x][4], qv[x][5], qv[x][6], qv[x][7]);
                     }
                 }
-                v[2 * c] = xa;
-                v[2 * c + 1] = xb;
-                amax = fmaxf(amax, fmaxf(fabsf(xa), fabsf(xb)));
             }
+        }
+        float amax = 0.f;
 #pragma unroll
-            for (int off = 8; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
-            int ex = 0;
-            if (amax > 0.f) frexpf(amax, &ex);  // amax < 2^ex
-            int p = 12 - ex;                    // scaled |q| < 2^12
-            p = p > 100 ? 100 : (p < -100 ? -100 : p);
-            const float S = ldexpf(1.0f, p);
+        for (int x = 0; x < NA; ++x)
 #pragma unroll
-            for (int c = 0; c < D / 32; ++c) {
-                const int i = sub + 16 * c;
-                int ia, ib;
-                rope_pair_index(i, D / 2, a.rope_mode, ia, ib);
-                const float sa = v[2 * c] * S, sb = v[2 * c + 1] * S;
-                const _Float16 ha = static_cast<_Float16>(sa), hb = static_cast<_Float16>(sb);
-                s_q[qi_l][ia] = ha;
-                s_q[qi_l][ib] = hb;
-                s_q[8 + qi_l][ia] = static_cast<_Float16>(sa - static_cast<float>(ha));
-                s_q[8 + qi_l][ib] = static_cast<_Float16>(sb - static_cast<float>(hb));
+            for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(qv[x][e]));
+        amax = fmaxf(amax, __shfl_xor(amax, 16, 64)); // the four slices c of the row
+        amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+        int ex = 0;
+        if (amax > 0.f) frexpf(amax, &ex); // amax < 2^ex
+        int p = 12 - ex;                   // scaled |q| < 2^12
+        p = p > 100 ? 100 : (p < -100 ? -100 : p);
+        const float S = ldexpf(1.0f, p);
+        const bool low = mrow >= 8;
+#pragma unroll
+        for (int x = 0; x < NA; ++x) {
+            half8 h;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float sv = qv[x][e] * S;
+                const _Float16 hi = static_cast<_Float16>(sv);
+                h[e] = low ? static_cast<_Float16>(sv - static_cast<float>(hi)) : hi;
             }
-            if (sub == 0) {
-                s_fq[qi_l] = ldexpf(1.0f, -p) * rsqrtf(static_cast<float>(D));
-                s_limit[qi_l] = a.n_past + t;
+            qa[x] = h;
+        }
+        fq_own = q_valid ? ldexpf(1.0f, -p) * rsqrtf(static_cast<float>(D)) : 0.f;
+    }
+    if (has_new) {
+#pragma unroll
+        for (int k = 0; k < NPT; ++k) {
+            const int idx = threadIdx.x + k * ATT_THREADS;
+            if (idx < a.T * (D / 2)) {
+                const int t = idx / (D / 2), i = idx - t * (D / 2);
+                const int row = a.n_past + t;
+                const int ia = MODE ? 2 * i : i, ib = MODE ? 2 * i + 1 : i + D / 2;
+                const __half ra = __float2half_rn(n_k[k].x * n_cs[k].x - n_k[k].y * n_cs[k].y);
+                const __half rb = __float2half_rn(n_k[k].x * n_cs[k].y + n_k[k].y * n_cs[k].x);
+                const __half2 hv = __floats2half2_rn(n_v[k].x, n_v[k].y);
+                s_knew[t][ia] = ra;
+                s_knew[t][ib] = rb;
+                *reinterpret_cast<__half2 *>(&s_vnew[t][2 * i]) = hv;
+                if (row >= p_begin && row < p_end) { // the range that owns the row stores it
+                    Kh[static_cast<int64_t>(row) * D + ia] = ra;
+                    Kh[static_cast<int64_t>(row) * D + ib] = rb;
+                    *reinterpret_cast<__half2 *>(Vh + static_cast<int64_t>(row) * D + 2 * i) = hv;
+                }
             }
-        } else if (sub == 0 && qi_l < QG) {
-            s_fq[qi_l] = 0.f;
-            s_limit[qi_l] = -1;
+        }
+        __syncthreads(); // the new rows are in LDS
+        if (key0 < p_end) {
+            patch_k(key0, kb);
+            patch_v(key0, vb);
         }
     }
-    __syncthreads();
 
-
-    // A operands: lane (m = lane%16, c = lane/16) holds s_q[m][32a + 8c .. +8] for a = 0..NA-1
-    half8 qa[NA];
-#pragma unroll
-    for (int x = 0; x < NA; ++x) qa[x] = *reinterpret_cast<const half8 *>(&s_q[mrow][32 * x + 8 * kc]);
+    // softmax bookkeeping for the 4 queries this lane sees in the MFMA result: m = 4*(kc&1) + r
+    const int mq0 = 4 * (kc & 1);
     float fq[4], m_run[4], l_run[4];
     int lim[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        fq[r] = s_fq[mq0 + r];
-        lim[r] = s_limit[mq0 + r];
+        fq[r] = __shfl(fq_own, mq0 + r, 64); // lane mq0 + r holds query mq0 + r
+        const int qi = q0 + mq0 + r;
+        lim[r] = (mq0 + r < nq) ? a.n_past + qi / G : -1; // last visible cache row
         m_run[r] = -INFINITY;
         l_run[r] = 0.f;
     }
+    float o[QG][2];
+#pragma unroll
+    for (int i = 0; i < QG; ++i) { o[i][0] = 0.f; o[i][1] = 0.f; }
 
     while (key0 < p_end) {
         const int next = key0 + tile_stride;
@@ -216,73 +325,66 @@ __global__ void __launch_bounds__(ATT_WAVES * 64, 2) attn_partial_kernel(AttnArg
         for (int r = 0; r < 4; ++r) {
             float sv = (acc[r] + __shfl_xor(acc[r], 32, 64)) * fq[r];
             if (key >= p_end || key > lim[r]) sv = -INFINITY;
-            float mx = sv;
-#pragma unroll
-            for (int off = 8; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-            const float mn = fmaxf(m_run[r], mx);
+            const float mn = fmaxf(m_run[r], row_max16(sv));
             corr[r] = (mn == -INFINITY) ? 1.f : __expf(m_run[r] - mn); // exp(-inf) = 0 on the first visible key
             pr[r] = (sv == -INFINITY) ? 0.f : __expf(sv - mn);
-            float ps = pr[r];
-#pragma unroll
-            for (int off = 8; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
-            l_run[r] = l_run[r] * corr[r] + ps;
+            l_run[r] = l_run[r] * corr[r] + row_sum16(pr[r]);
             m_run[r] = mn;
         }
-        if (next < p_end) load_k(next, kb);
+        if (next < p_end) {
+            load_k(next, kb);
+            patch_k(next, kb);
+        }
         if (kc < 2) {
             *reinterpret_cast<float4 *>(&s_p[wave][mrow][mq0]) = make_float4(pr[0], pr[1], pr[2], pr[3]);
             if (mrow == 0) *reinterpret_cast<float4 *>(&s_corr[wave][mq0]) = make_float4(corr[0], corr[1], corr[2], corr[3]);
         }
         __builtin_amdgcn_wave_barrier();
         // P.V
+        {
+            const float4 c0 = *reinterpret_cast<const float4 *>(&s_corr[wave][0]), c1 = *reinterpret_cast<const float4 *>(&s_corr[wave][4]);
+            const float cw[QG] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
-        for (int q = 0; q < QG; q += 4) {
-            const float4 c4 = *reinterpret_cast<const float4 *>(&s_corr[wave][q]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                o[q][e] *= c4.x; o[q + 1][e] *= c4.y; o[q + 2][e] *= c4.z; o[q + 3][e] *= c4.w;
-            }
+            for (int q = 0; q < QG; ++q) { o[q][0] *= cw[q]; o[q][1] *= cw[q]; }
         }
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-            const int kt = KS * i + ks;
+            const int kt = KSV * i + ksl;
             const float4 p0 = *reinterpret_cast<const float4 *>(&s_p[wave][kt][0]);
             const float4 p1 = *reinterpret_cast<const float4 *>(&s_p[wave][kt][4]);
             const float pw[QG] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-            const __half2 *h = reinterpret_cast<const __half2 *>(&vb[i]);
-            float vf[8];
+            const float2 vf = __half22float2(*reinterpret_cast<const __half2 *>(&vb[i]));
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float2 f2 = __half22float2(h[e]);
-                vf[2 * e] = f2.x;
-                vf[2 * e + 1] = f2.y;
+            for (int q = 0; q < QG; ++q) {
+                o[q][0] = fmaf(pw[q], vf.x, o[q][0]);
+                o[q][1] = fmaf(pw[q], vf.y, o[q][1]);
             }
-#pragma unroll
-            for (int q = 0; q < QG; ++q)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[q][e] = fmaf(pw[q], vf[e], o[q][e]);
+            // finish these keys before the next ones' probabilities are read (otherwise all 16 keys' 128
+            // values are fetched up front and the kernel spills)
+            if ((i & 3) == 3)
+                asm volatile("" : "+v"(o[0][0]), "+v"(o[0][1]), "+v"(o[1][0]), "+v"(o[1][1]), "+v"(o[2][0]), "+v"(o[2][1]), "+v"(o[3][0]), "+v"(o[3][1]),
+                                  "+v"(o[4][0]), "+v"(o[4][1]), "+v"(o[5][0]), "+v"(o[5][1]), "+v"(o[6][0]), "+v"(o[6][1]), "+v"(o[7][0]), "+v"(o[7][1])
+                             :: "memory");
         }
         __builtin_amdgcn_wave_barrier();
-        if (next < p_end) load_v(next, vb);
+        if (next < p_end) {
+            load_v(next, vb);
+            patch_v(next, vb);
+        }
         key0 = next;
     }
 
-    // ---- merge the KS lane groups of the wave, then the waves ----
-#pragma unroll
-    for (int q = 0; q < QG; ++q)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float v = o[q][e];
-#pragma unroll
-            for (int off = DG; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
-            o[q][e] = v;
-        }
-    if (ks == 0) {
+    // ---- the waves' results meet in LDS ----
+    if (KSV > 1) {
 #pragma unroll
         for (int q = 0; q < QG; ++q) {
-            *reinterpret_cast<float4 *>(&s_o[wave][q][8 * dg]) = make_float4(o[q][0], o[q][1], o[q][2], o[q][3]);
-            *reinterpret_cast<float4 *>(&s_o[wave][q][8 * dg + 4]) = make_float4(o[q][4], o[q][5], o[q][6], o[q][7]);
+            o[q][0] += __shfl_xor(o[q][0], 32, 64);
+            o[q][1] += __shfl_xor(o[q][1], 32, 64);
         }
+    }
+    if (ksl == 0) {
+#pragma unroll
+        for (int q = 0; q < QG; ++q) *reinterpret_cast<float2 *>(&s_o[wave][q][2 * dl]) = make_float2(o[q][0], o[q][1]);
     }
     if (mrow == 0 && kc < 2) {
 #pragma unroll
@@ -292,7 +394,8 @@ __global__ void __launch_bounds__(ATT_WAVES * 64, 2) attn_partial_kernel(AttnArg
         }
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < nq * D; idx += blockDim.x) {
+    const int nqg = gridDim.z;
+    for (int idx = threadIdx.x; idx < nq * D; idx += ATT_THREADS) {
         const int i = idx / D, e = idx - i * D;
         float mm = -INFINITY;
 #pragma unroll
@@ -305,68 +408,110 @@ __global__ void __launch_bounds__(ATT_WAVES * 64, 2) attn_partial_kernel(AttnArg
             accv += s_o[w][i][e] * f;
         }
         const int qi = q0 + i, t = qi / G, hg = qi - t * G;
-        float *rec = a.part + ((static_cast<int64_t>(t) * a.Hq + kvh * G + hg) * a.nsplit + split) * (2 + D);
-        if (e == 0) { rec[0] = mm; rec[1] = ll; }
-        rec[2 + e] = accv;
+        const int64_t head = static_cast<int64_t>(t) * a.Hq + kvh * G + hg;
+        if (a.nsplit == 1) { // nothing to merge
+            a.o[head * D + e] = accv / ll;
+            continue;
+        }
+        float *rec = a.part + (head * a.nsplit + split) * (2 + D);
+        if (e == 0) {
+            __hip_atomic_store(rec, mm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(rec + 1, ll, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __hip_atomic_store(rec + 2 + e, accv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (a.nsplit == 1) return;
+
+    // ---- the last workgroup of this (KV head, query group) merges the key ranges ----
+    // o[t][h][:] = sum_i part_i.o * exp(m_i - M) / sum_i part_i.l * exp(m_i - M); a key range that held no
+    // visible key has (max, sum) = (-inf, 0) and drops out.  The records were written with device-scope
+    // stores; vmcnt(0) + barrier makes them complete before the arrival is counted.
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (threadIdx.x == 0) {
+        unsigned *ctr = a.arrivals + kvh * nqg + qgrp;
+        const unsigned prev = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = prev + 1 == static_cast<unsigned>(a.nsplit);
+        if (last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); // ready for the next launch
+        s_last = last ? 1 : 0;
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (!s_last) return;
+    // One wave per query, one round trip: lane s requests (max, sum) of key range s, every lane requests
+    // its columns of all ranges right behind; the weights come out of wave reductions and reach the
+    // lanes as scalar broadcasts.
+    static_assert(QG <= ATT_WAVES, "one wave per query of the group");
+    if (wave >= nq) return;
+    {
+        const int qi = q0 + wave, t = qi / G, hg = qi - t * G;
+        const int64_t head = static_cast<int64_t>(t) * a.Hq + kvh * G + hg;
+        const float *rec0 = a.part + head * a.nsplit * (2 + D);
+        // 2 + D is even and the records start 8-byte aligned: (max, sum) is one 64-bit load
+        const uint64_t ml = __hip_atomic_load(reinterpret_cast<const uint64_t *>(rec0 + min(lane, a.nsplit - 1) * (2 + D)),
+                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        constexpr int CPL = D / 64; // columns per lane
+        float acc[CPL];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) acc[c] = 0.f;
+        const float ms = lane < a.nsplit ? __uint_as_float(static_cast<uint32_t>(ml)) : -INFINITY;
+        const float ls = lane < a.nsplit ? __uint_as_float(static_cast<uint32_t>(ml >> 32)) : 0.f;
+        float wgt = 0.f;
+        for (int s0 = 0; s0 < a.nsplit; s0 += 32) {
+            float v[32][CPL];
+#pragma unroll
+            for (int jj = 0; jj < 32; ++jj)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+                    v[jj][c] = __hip_atomic_load(rec0 + min(s0 + jj, a.nsplit - 1) * (2 + D) + 2 + lane + 64 * c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (s0 == 0) {
+                float mm = ms;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) mm = fmaxf(mm, __shfl_xor(mm, off, 64));
+                const float w = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
+                float ll = ls * w;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) ll += __shfl_xor(ll, off, 64);
+                wgt = w / ll;
+            }
+#pragma unroll
+            for (int jj = 0; jj < 32; ++jj) {
+                // lanes past the last range carry weight 0 (and the clamped loads above are then unused)
+                const float wj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wgt), jj)); // s0 == 0
+                const float wk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wgt), 32 + jj));
+                const float wsel = s0 == 0 ? wj : wk;
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) acc[c] = fmaf(v[jj][c], wsel, acc[c]);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) a.o[head * D + lane + 64 * c] = acc[c];
     }
 }
 
-// o[t][h][:] = sum_i part_i.o * exp(m_i - M) / sum_i part_i.l * exp(m_i - M); a key range that
-// held no visible key has (max, sum) = (-inf, 0) and drops out.  One workgroup per (token, head).
-template <int D>
-__global__ void __launch_bounds__(256) attn_merge_kernel(const float *__restrict__ part, float *__restrict__ o, int nsplit)
+static int query_groups(const prima_dims &d, int T)
 {
-    __shared__ float s_w[MAX_SPLITS];
-    __shared__ float s_red[4][D];
-    __shared__ float s_L;
-    const int64_t qh = blockIdx.x;
-    const float *rec = part + qh * nsplit * (2 + D);
-    if (threadIdx.x < 64) {
-        const int s = threadIdx.x;
-        const float ms = s < nsplit ? rec[s * (2 + D)] : -INFINITY;
-        const float ls = s < nsplit ? rec[s * (2 + D) + 1] : 0.f;
-        float mm = ms;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) mm = fmaxf(mm, __shfl_xor(mm, off, 64));
-        const float w = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
-        float ll = ls * w;
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) ll += __shfl_xor(ll, off, 64);
-        s_w[s] = w;
-        if (s == 0) s_L = ll;
-    }
-    __syncthreads();
-    // 256 threads: 256/D groups of splits, D columns
-    constexpr int NG = 256 / D;
-    const int e = threadIdx.x % D, grp = threadIdx.x / D;
-    float acc = 0.f;
-#pragma unroll 8
-    for (int s = grp; s < nsplit; s += NG) acc = fmaf(rec[s * (2 + D) + 2 + e], s_w[s], acc);
-    s_red[grp][e] = acc;
-    __syncthreads();
-    if (grp == 0) {
-        float v = s_red[0][e];
-#pragma unroll
-        for (int g2 = 1; g2 < NG; ++g2) v += s_red[g2][e];
-        o[qh * D + e] = v / s_L;
-    }
+    const int G = d.n_q_heads / d.n_kv_heads;
+    return (G * T + QG - 1) / QG;
 }
 
 int attn_num_splits(const prima_dims &d, int n_total, int T)
 {
-    const int G = d.n_q_heads / d.n_kv_heads;
-    const int nqg = (G * T + QG - 1) / QG;
-    const int by_len = (n_total + 63) / 64;                                     // at least one 16-key tile per wave
-    const int by_grid = (512 + d.n_kv_heads * nqg - 1) / (d.n_kv_heads * nqg);  // about 2 workgroups per CU
+    const int wgs = d.n_kv_heads * query_groups(d, T);
+    const int by_len = (n_total + 16 * ATT_WAVES - 1) / (16 * ATT_WAVES); // at least one 16-key tile per wave
+    const int by_grid = (256 + wgs - 1) / wgs;                            // about one workgroup per compute unit
     int ns = by_len < by_grid ? by_len : by_grid;
     if (ns < 1) ns = 1;
     if (ns > MAX_SPLITS) ns = MAX_SPLITS;
     return ns;
 }
 
+size_t attn_counter_bytes(const prima_dims &d, int T)
+{
+    return round_up(static_cast<size_t>(d.n_kv_heads) * query_groups(d, T) * sizeof(unsigned), 256);
+}
+
 size_t attn_ws_bytes(const prima_dims &d, int, int T)
 {
-    return round_up(static_cast<size_t>(T) * d.n_q_heads * MAX_SPLITS * (2 + d.head_dim) * sizeof(float), 256);
+    return attn_counter_bytes(d, T) + round_up(static_cast<size_t>(T) * d.n_q_heads * MAX_SPLITS * (2 + d.head_dim) * sizeof(float), 256);
 }
 
 prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
@@ -377,24 +522,21 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
     AttnArgs a{};
     a.q = q; a.q_rot_out = q_rot_out; a.k_new = k_new; a.v_new = v_new;
     a.rope_tab = reinterpret_cast<const float2 *>(rope_tab);
-    a.K = K; a.V = V; a.part = static_cast<float *>(ws);
+    a.K = K; a.V = V;
+    a.arrivals = static_cast<unsigned *>(ws);
+    a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + attn_counter_bytes(d, T));
+    a.o = o;
     a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.kv_cap = kv_cap; a.n_past = n_past; a.T = T;
-    a.nsplit = attn_num_splits(d, n_total, T);
-    // key ranges are multiples of 16 so that tiles never straddle two workgroups
-    a.keys_per_split = ((n_total + a.nsplit - 1) / a.nsplit + 15) / 16 * 16;
-    a.rope_mode = d.rope_mode;
-    const int G = d.n_q_heads / d.n_kv_heads;
-    const int nqg = (G * T + QG - 1) / QG;
-    const dim3 grid(a.nsplit, d.n_kv_heads, nqg), block(ATT_WAVES * 64);
-    if (d.head_dim == 128) {
-        hipLaunchKernelGGL(attn_partial_kernel<128>, grid, block, 0, st, a);
-        hipLaunchKernelGGL(attn_merge_kernel<128>, dim3(T * d.n_q_heads), dim3(256), 0, st, a.part, o, a.nsplit);
-    } else if (d.head_dim == 64) {
-        hipLaunchKernelGGL(attn_partial_kernel<64>, grid, block, 0, st, a);
-        hipLaunchKernelGGL(attn_merge_kernel<64>, dim3(T * d.n_q_heads), dim3(256), 0, st, a.part, o, a.nsplit);
-    } else {
-        return PRIMA_E_SHAPE;
-    }
+    // key ranges are multiples of 16 so that tiles never straddle two workgroups, and none is empty
+    const int want = attn_num_splits(d, n_total, T);
+    a.keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
+    a.nsplit = (n_total + a.keys_per_split - 1) / a.keys_per_split;
+    const dim3 grid(a.nsplit, d.n_kv_heads, query_groups(d, T)), block(ATT_THREADS);
+    if (d.head_dim == 128 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<128, 0>), grid, block, 0, st, a);
+    else if (d.head_dim == 128 && d.rope_mode == 1) hipLaunchKernelGGL((attn_decode_kernel<128, 1>), grid, block, 0, st, a);
+    else if (d.head_dim == 64 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<64, 0>), grid, block, 0, st, a);
+    else if (d.head_dim == 64 && d.rope_mode == 1) hipLaunchKernelGGL((attn_decode_kernel<64, 1>), grid, block, 0, st, a);
+    else return PRIMA_E_SHAPE;
     return last_launch_status();
 }
 

@@ -89,6 +89,9 @@ prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
 prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
 int attn_num_splits(const prima_dims &d, int n_total, int T);
 size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);
+// the first attn_counter_bytes() of the attention scratch are arrival counters: zero before the first
+// launch (launch_zero_arrivals), left zero by every launch
+size_t attn_counter_bytes(const prima_dims &d, int T);
 // q: [T][Hq][D].  With rope_tab set, q and k_new are un-rotated and the kernel rotates them and
 // appends k_new / v_new to the caches; otherwise q is used as is and the caches are complete.
 prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,

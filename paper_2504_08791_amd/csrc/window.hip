@@ -75,8 +75,8 @@ GemvArgs gemv_args(int nseg, int64_t n_cols, const float *x, int64_t ldx, int T,
     return ga;
 }
 
-// one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Six launches: Q/K/V projections
-// (RMSNorm fused), attention partial (RoPE + KV append fused) and merge, output projection
+// one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Five launches: Q/K/V projections
+// (RMSNorm fused), attention (RoPE + KV append fused, key ranges merged by the last arriver), output projection
 // (+ residual), gate/up projections (RMSNorm fused in front, SwiGLU behind), down projection (+ residual).
 prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
                        const float *x, float *y, void *ws, const WindowWs &w, hipStream_t st,
@@ -201,6 +201,8 @@ prima_status prima_attn_decode(const prima_dims *d, const float *q, const void *
     if (T < 1 || T > PRIMA_MAX_TOK || n_past < 0 || kv_cap < 1 || static_cast<int64_t>(n_past) + T > kv_cap) return PRIMA_E_RANGE;
     if (!aligned(q, 16) || !aligned(o, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(workspace, 256)) return PRIMA_E_ALIGN;
     if (workspace_bytes < attn_ws_bytes(*d, kv_cap, T)) return PRIMA_E_WORKSPACE;
+    const prima_status s = launch_zero_arrivals(workspace, attn_counter_bytes(*d, T), static_cast<hipStream_t>(hip_stream));
+    if (s != PRIMA_OK) return s;
     return launch_attn(*d, q, nullptr, nullptr, nullptr, nullptr,
                        static_cast<__half *>(const_cast<void *>(k_cache)), static_cast<__half *>(const_cast<void *>(v_cache)),
                        kv_cap, n_past, T, o, workspace, static_cast<hipStream_t>(hip_stream));
@@ -227,6 +229,7 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
     const WindowWs w = carve(*d, kv_cap, T);
     s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
     if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, T), st);
     if (s != PRIMA_OK) return s;
     const float *cur = x_in;
     for (int i = 0; i < L; ++i) {
@@ -255,6 +258,7 @@ prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima
     // one ordinary step first: every intermediate buffer then holds this step's values
     s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
     if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, T), st);
     const float *cur = x_in;
     for (int i = 0; i < L && s == PRIMA_OK; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
@@ -305,6 +309,7 @@ prima_status prima_layer_decode_taps(const prima_dims *d, const prima_layer *lay
     const WindowWs w = carve(*d, kv_cap, T);
     s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
     if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, T), st);
     if (s != PRIMA_OK) return s;
     return run_layer(*d, *layer, kv_cap, n_past, T, x_in, x_out, workspace, w, st, tap_q, tap_o, tap_h, tap_a);
 }
