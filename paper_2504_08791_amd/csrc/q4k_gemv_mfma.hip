@@ -36,6 +36,7 @@
 namespace prima {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int GEMV_THREADS = 512;
 constexpr int GEMV_WAVES = GEMV_THREADS / 64;
@@ -81,6 +82,17 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
     // one wait state is required between the SALU write of M0 and the load that reads it; M0 is a reserved
     // register that nothing else in this file uses
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory");
+}
+
+// 16 bytes per lane into registers, requested now and waited for by hand: the compiler does not know
+// that the result arrives later, which is the point: it cannot put a wait for *all* outstanding loads
+// (the ring stages behind them included) in front of the first use.  Until the hand-written wait, which
+// names these registers as operands, nothing may touch them.
+__device__ __forceinline__ v4f load16_early(const void *gptr)
+{
+    v4f v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(v) : "v"(gptr) : "memory");
+    return v;
 }
 
 // workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
@@ -249,6 +261,43 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         }
     };
 
+    // ---- start the weight stream.  Loads return in order per wave and the global->LDS loads of a compute
+    // unit go out at only about 1 KiB per 25 ns, so the order is: request the activations (ordinary loads,
+    // quick to issue), request the first two ring stages right behind them, and wait for the activations
+    // only.  One token and at most two groups of 8 activations per thread: that is done with hand-waited
+    // loads.  Otherwise the activations are read (and waited for) first. ----
+    Cursor lc;
+    start(lc);
+    int issued = 0;
+    auto first_stages = [&]() {
+        for (int s = 0; s < NST - 1; ++s) { // touches units k = 0, 1 only
+            normalize(lc, true);
+            if (!lc.valid) break;
+            issue(lc, s);
+            lc.c += a.ksplit;
+            ++issued;
+        }
+    };
+    const bool early = TT == 1 && (sb1 - sb0) * 32 <= 2 * GEMV_THREADS && (!rmsnorm || a.n_slabs == 1);
+    v4f ex[2][2], eg[2][2]; // early: activations and gains of this thread's two groups
+    if (early) {
+        const float *gp = rmsnorm ? a.gain : a.x; // without gains the second set of loads is a dummy
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int gi = min(sb0 * 32 + static_cast<int>(threadIdx.x) + i * GEMV_THREADS, sb1 * 32 - 1); // clamped: always a valid address
+            ex[i][0] = load16_early(a.x + gi * 8);
+            ex[i][1] = load16_early(a.x + gi * 8 + 4);
+            eg[i][0] = load16_early(gp + gi * 8);
+            eg[i][1] = load16_early(gp + gi * 8 + 4);
+        }
+        first_stages();
+        // the eight loads above are older than the ring stages: with both stages requested, 10 loads may
+        // still be out (a wave with fewer stages to request simply waits for everything).  One wait
+        // statement names all eight registers, so that every use of them comes after it.
+        if (issued < 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(10)" : "+v"(ex[0][0]), "+v"(ex[0][1]), "+v"(ex[1][0]), "+v"(ex[1][1]), "+v"(eg[0][0]), "+v"(eg[0][1]), "+v"(eg[1][0]), "+v"(eg[1][1]) :: "memory");
+    }
+
     // ---- statistics of the activations: 1/rms over the whole row (RMSNorm input) and the power-of-two
     // scale of this slab's part (each slab has its own, its sums are scaled back before they meet) ----
     // One token: every thread keeps its groups of 8 activations in registers from here to the
@@ -260,7 +309,24 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
         float ss = 0.f, amax = 0.f;
-        if (TT == 1 && resident) {
+        if (TT == 1 && early) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int gi = sb0 * 32 + threadIdx.x + i * GEMV_THREADS;
+                if (gi < sb1 * 32) {
+                    const v4f v0 = ex[i][0], v1 = ex[i][1];
+                    float *f = xr[TT == 1 ? i : 0];
+                    f[0] = v0.x; f[1] = v0.y; f[2] = v0.z; f[3] = v0.w; f[4] = v1.x; f[5] = v1.y; f[6] = v1.z; f[7] = v1.w;
+                    if (rmsnorm) {
+                        ss += ((v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w)) + ((v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w));
+                        const v4f g0 = eg[i][0], g1 = eg[i][1];
+                        f[0] *= g0.x; f[1] *= g0.y; f[2] *= g0.z; f[3] *= g0.w; f[4] *= g1.x; f[5] *= g1.y; f[6] *= g1.z; f[7] *= g1.w;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
+                }
+            }
+        } else if (TT == 1 && resident) {
 #pragma unroll
             for (int i = 0; i < MAXG; ++i) {
                 const int gi = g_lo + threadIdx.x + i * GEMV_THREADS;
@@ -301,20 +367,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         float *red = l_red + t * 16;
         if (lane == 0) { red[wave] = ss; red[8 + wave] = amax; }
     }
-
-    // ---- start the weight stream: the activation loads above have returned (loads complete in order, so
-    // issuing them after the stream would make them wait for the first stages), the rest of the prologue
-    // overlaps with the first stages' flight ----
-    Cursor lc;
-    start(lc);
-    int issued = 0;
-    for (int s = 0; s < NST - 1; ++s) { // touches units k = 0, 1 only
-        normalize(lc, true);
-        if (!lc.valid) break;
-        issue(lc, s);
-        lc.c += a.ksplit;
-        ++issued;
-    }
+    if (!early) first_stages();
 
     // zero the partial sums and the zero operand
     if (threadIdx.x == 0) *l_next = STATIC_UNITS * GEMV_WAVES;
@@ -415,7 +468,14 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
             sum += __shfl_xor(sum, 2, 64);
             if (grp == 0) l_xs[t * slab_sub + s_loc] = sum;
         };
-        if (TT == 1 && resident) {
+        if (TT == 1 && early) {
+            const float S = l_scale[0];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int gi = sb0 * 32 + threadIdx.x + i * GEMV_THREADS;
+                if (gi < sb1 * 32) quantise8(0, gi, xr[TT == 1 ? i : 0], S);
+            }
+        } else if (TT == 1 && resident) {
             const float S = l_scale[0];
 #pragma unroll
             for (int i = 0; i < MAXG; ++i) {
