@@ -269,8 +269,8 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     Cursor lc;
     start(lc);
     int issued = 0;
-    auto first_stages = [&]() {
-        for (int s = 0; s < NST - 1; ++s) { // touches units k = 0, 1 only
+    auto first_stages = [&](int n) {
+        for (int s = issued; s < n; ++s) { // touches units k = 0, 1 only
             normalize(lc, true);
             if (!lc.valid) break;
             issue(lc, s);
@@ -290,12 +290,12 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
             eg[i][0] = load16_early(gp + gi * 8);
             eg[i][1] = load16_early(gp + gi * 8 + 4);
         }
-        first_stages();
+        first_stages(1);
         // the eight loads above are older than the ring stages: with both stages requested, 10 loads may
         // still be out (a wave with fewer stages to request simply waits for everything).  One wait
         // statement names all eight registers, so that every use of them comes after it.
-        if (issued < 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        asm volatile("s_waitcnt vmcnt(10)" : "+v"(ex[0][0]), "+v"(ex[0][1]), "+v"(ex[1][0]), "+v"(ex[1][1]), "+v"(eg[0][0]), "+v"(eg[0][1]), "+v"(eg[1][0]), "+v"(eg[1][1]) :: "memory");
+        if (issued < 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(5)" : "+v"(ex[0][0]), "+v"(ex[0][1]), "+v"(ex[1][0]), "+v"(ex[1][1]), "+v"(eg[0][0]), "+v"(eg[0][1]), "+v"(eg[1][0]), "+v"(eg[1][1]) :: "memory");
     }
 
     // ---- statistics of the activations: 1/rms over the whole row (RMSNorm input) and the power-of-two
@@ -367,7 +367,7 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
         float *red = l_red + t * 16;
         if (lane == 0) { red[wave] = ss; red[8 + wave] = amax; }
     }
-    if (!early) first_stages();
+    first_stages(NST - 1);
 
     // zero the partial sums and the zero operand
     if (threadIdx.x == 0) *l_next = STATIC_UNITS * GEMV_WAVES;
