@@ -5,7 +5,7 @@ A step = one pass of the whole hot path (every layer of the window: Q4_K project
 RMSNorm / SwiGLU / residuals, RoPE + fp16 KV append, GQA attention) over one batch of T tokens
 of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--no-cpu-baseline] [--copy-calibration]
 """
 import argparse
 import json
@@ -19,6 +19,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 
+# HBM bytes of one gate/up launch of config 3 from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs (scaled by
+# what the same counters read for a plain 256 MiB copy): see profiles/gemv_q4k_persistent_c3_hbm_traffic.txt
+GATE_UP_TRAFFIC_BYTES = 265_170_000
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -27,6 +32,8 @@ def main():
     ap.add_argument("--config", default="c3")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run three plain 256 MiB device copies first (reference kernel of known traffic for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -70,6 +77,13 @@ def main():
     y = torch.empty_like(x)
     stream = torch.cuda.current_stream()
 
+    if args.copy_calibration:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         win.decode(x, cfg.n_past, x_out=y)
     torch.cuda.synchronize()
@@ -134,7 +148,7 @@ def main():
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "bytes_per_launch": gate_up_bytes,
             "avg_launch_us": round(gu_us, 2),
-            "traffic": None,
+            "traffic": GATE_UP_TRAFFIC_BYTES if (cfg.name == "c3" and cfg.T == 1) else None,
         },
     }
     if want_cpu:
