@@ -1,0 +1,129 @@
+// Declarations shared by the stand-alone attention kernel and the fused window kernel (the design is
+// described in attn_decode.hip); the body itself is attn_body.inc.
+#pragma once
+#include "common.h"
+
+namespace prima {
+
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int QG = 8;        // queries per workgroup
+constexpr int ATT_WAVES = 8; // waves per workgroup
+constexpr int ATT_THREADS = ATT_WAVES * 64;
+constexpr int MAX_SPLITS = 64;
+
+struct AttnArgs {
+    const float *q;       // [T][Hq][D]; rotated already unless rope_tab is set
+    float *q_rot_out;     // optional: rotated queries written back (first key range only)
+    const float *k_new;   // fused append: un-rotated k [T][Hkv][D], else null
+    const float *v_new;   // fused append: v [T][Hkv][D]
+    const float2 *rope_tab; // [T][D/2] (cos, sin) or null
+    __half *K, *V;        // caches [Hkv][kv_cap][D]
+    float *part;          // [T*Hq][nsplit][2 + D]
+    unsigned *arrivals;   // [Hkv * query groups], zero between launches
+    float *o;             // [T][Hq][D]
+    int Hq, Hkv, kv_cap, n_past, T, nsplit, keys_per_split;
+};
+
+// value of lane (i + n) % 16 of the same 16-lane row
+template <int N>
+__device__ __forceinline__ float row_ror(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row_max16(float v)
+{
+    v = fmaxf(v, row_ror<8>(v));
+    v = fmaxf(v, row_ror<4>(v));
+    v = fmaxf(v, row_ror<2>(v));
+    return fmaxf(v, row_ror<1>(v));
+}
+__device__ __forceinline__ float row_sum16(float v)
+{
+    v += row_ror<8>(v);
+    v += row_ror<4>(v);
+    v += row_ror<2>(v);
+    return v + row_ror<1>(v);
+}
+
+// Rotate the D/8-element slices a lane holds of one head vector: v[x][e] = element 32x + 8c + e.
+// mode 0 pairs element i with i + D/2 (the partner is v[x + NA/2][e] of the same lane), mode 1 pairs
+// 2i with 2i + 1.  tab = this token's D/2 (cos, sin) pairs.
+template <int D, int MODE>
+__device__ __forceinline__ void rope_in_lane(float (&v)[D / 32][8], const float2 *tab, int c)
+{
+    constexpr int NA = D / 32;
+    if (MODE == 0) {
+#pragma unroll
+        for (int x = 0; x < NA / 2; ++x) {
+            const float4 *tp = reinterpret_cast<const float4 *>(tab + 32 * x + 8 * c);
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                const float4 cs = tp[h]; // (cos, sin) of pairs 2h, 2h + 1 of this slice
+                const float a0 = v[x][2 * h], b0 = v[x + NA / 2][2 * h], a1 = v[x][2 * h + 1], b1 = v[x + NA / 2][2 * h + 1];
+                v[x][2 * h] = a0 * cs.x - b0 * cs.y;
+                v[x + NA / 2][2 * h] = a0 * cs.y + b0 * cs.x;
+                v[x][2 * h + 1] = a1 * cs.z - b1 * cs.w;
+                v[x + NA / 2][2 * h + 1] = a1 * cs.w + b1 * cs.z;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int x = 0; x < NA; ++x) {
+            const float4 *tp = reinterpret_cast<const float4 *>(tab + 16 * x + 4 * c);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float4 cs = tp[h];
+                const float a0 = v[x][4 * h], b0 = v[x][4 * h + 1], a1 = v[x][4 * h + 2], b1 = v[x][4 * h + 3];
+                v[x][4 * h] = a0 * cs.x - b0 * cs.y;
+                v[x][4 * h + 1] = a0 * cs.y + b0 * cs.x;
+                v[x][4 * h + 2] = a1 * cs.z - b1 * cs.w;
+                v[x][4 * h + 3] = a1 * cs.w + b1 * cs.z;
+            }
+        }
+    }
+}
+
+// COH: the vector was written by other workgroups of the same launch: device-scope loads, waited for here
+template <int D, bool COH>
+__device__ __forceinline__ void load_slices(const float *p, int c, float (&v)[D / 32][8])
+{
+    if (!COH) {
+#pragma unroll
+        for (int x = 0; x < D / 32; ++x) {
+            const float4 a = *reinterpret_cast<const float4 *>(p + 32 * x + 8 * c), b = *reinterpret_cast<const float4 *>(p + 32 * x + 8 * c + 4);
+            v[x][0] = a.x; v[x][1] = a.y; v[x][2] = a.z; v[x][3] = a.w; v[x][4] = b.x; v[x][5] = b.y; v[x][6] = b.z; v[x][7] = b.w;
+        }
+    } else {
+        static_assert(D / 32 <= 4, "eight registers named in the wait below");
+        v4f r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int x = 0; x < D / 32; ++x) {
+            asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(r[2 * x]) : "v"(p + 32 * x + 8 * c) : "memory");
+            asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(r[2 * x + 1]) : "v"(p + 32 * x + 8 * c + 4) : "memory");
+        }
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]) :: "memory");
+#pragma unroll
+        for (int x = 0; x < D / 32; ++x) {
+            v[x][0] = r[2 * x][0]; v[x][1] = r[2 * x][1]; v[x][2] = r[2 * x][2]; v[x][3] = r[2 * x][3];
+            v[x][4] = r[2 * x + 1][0]; v[x][5] = r[2 * x + 1][1]; v[x][6] = r[2 * x + 1][2]; v[x][7] = r[2 * x + 1][3];
+        }
+    }
+}
+
+// dynamic LDS of the attention body
+template <int D>
+struct AttnLds {
+    float p[ATT_WAVES][16][QG]; // probabilities of the current tile [key][query]
+    float corr[ATT_WAVES][QG];
+    float m[ATT_WAVES][QG], l[ATT_WAVES][QG];
+    float o[ATT_WAVES][QG][D];
+    __half knew[PRIMA_MAX_TOK][D], vnew[PRIMA_MAX_TOK][D]; // the step's new rows (fused append)
+    int last;
+};
+
+} // namespace prima

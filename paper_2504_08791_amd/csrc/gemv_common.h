@@ -1,0 +1,195 @@
+// Declarations shared by the stand-alone Q4_K mat-vec kernel and the fused window kernel (the design is
+// described in q4k_gemv_mfma.hip); the body of the mat-vec itself is gemv_body.inc.
+#pragma once
+#include "common.h"
+
+namespace prima {
+
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int GEMV_THREADS = 512;
+constexpr int GEMV_WAVES = GEMV_THREADS / 64;
+constexpr int NST = 3;                       // ring stages per wave
+constexpr int PBS = 2;                       // super-blocks per stage
+constexpr int RS = 9 * PBS + 1;              // row stride of a stage in 16-byte slots (odd)
+constexpr int STAGE_SLOTS = 16 * RS;         // 304
+constexpr int NI = (STAGE_SLOTS + 63) / 64;  // load instructions per stage (5; the last one uses 48 lanes)
+constexpr int STAGE_BYTES = STAGE_SLOTS * 16;
+constexpr int RING_BYTES = GEMV_WAVES * NST * STAGE_BYTES;
+constexpr int SUB_BYTES = 128;               // digits of one sub-block: 4 digits x 32 values
+constexpr size_t LDS_BUDGET = 160 * 1024;
+constexpr int MAX_T_PASS = 8;                // tokens per pass over the weights
+
+struct PGemvArgs {
+    GemvSeg seg[3];
+    int seg_tile0[3]; // first 16-row tile of each segment
+    int nseg, n_tiles, nb, T;
+    // activations
+    int xmode, epi;
+    const float *x, *gain;
+    int64_t ldx;
+    float eps;
+    // decomposition
+    int ksplit;      // waves sharing a tile: unit = (tile, part), part p takes chunks p, p+ksplit, ...
+    int slab_blocks; // super-blocks of K per slab (even); workgroup w handles slab w % n_slabs
+    int n_slabs;
+    int units_cap;   // floats reserved for the partial sums (and the per-tile flags of the slab reduction)
+    int direct;      // a wave owns whole rows of the slab (ksplit == 1) and stores their sums itself
+    int n_wg;
+    float *part;        // n_slabs > 1: partial sums [n_slabs][n_tiles*16][T]
+    unsigned *arrivals; // n_slabs > 1: per-tile arrival counters, zero between launches
+};
+
+// 16 bytes per lane from global memory straight into LDS: lane l writes bytes [16 l, 16 l + 16) of the
+// 1 KiB at LDS byte address lds_addr (wave-uniform, goes through M0).  Written as inline assembly on
+// purpose: the compiler then does not know these loads write LDS and leaves the ordering against the
+// later LDS reads to the explicit s_waitcnt vmcnt(N) below, which lets newer stages stay in flight
+// (with the builtin it waits for *all* outstanding loads before any LDS read).  Loads complete in
+// order, so loads the compiler does not know about can only make its own waits stricter.
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
+{
+    // one wait state is required between the SALU write of M0 and the load that reads it; M0 is a reserved
+    // register that nothing else in this file uses
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory");
+}
+
+// 16 bytes per lane into registers, requested now and waited for by hand: the compiler does not know
+// that the result arrives later, which is the point: it cannot put a wait for *all* outstanding loads
+// (the ring stages behind them included) in front of the first use.  Until the hand-written wait, which
+// names these registers as operands, nothing may touch them.
+template <bool COH> // COH: device scope (data written by other workgroups of the same launch)
+__device__ __forceinline__ v4f load16_early(const void *gptr)
+{
+    v4f v;
+    if (COH) asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(v) : "v"(gptr) : "memory");
+    else asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(v) : "v"(gptr) : "memory");
+    return v;
+}
+
+// workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
+// load (vmcnt(0)), which would stall the weight stream at each barrier of the prologue.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)); // low half of a flat LDS pointer is the LDS byte address
+}
+
+__device__ __forceinline__ long pack64(uint32_t lo, uint32_t hi)
+{
+    return static_cast<long>(static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32));
+}
+
+// eight consecutive activations of token t starting at column c0, before the RMSNorm scale:
+// X_PLAIN x, X_RMSNORM x*gain (the 1/rms factor is applied by the caller)
+__device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, float *f)
+{
+    const float *xp = a.x + t * a.ldx + c0;
+    const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
+    f[0] = v0.x; f[1] = v0.y; f[2] = v0.z; f[3] = v0.w; f[4] = v1.x; f[5] = v1.y; f[6] = v1.z; f[7] = v1.w;
+    if (a.xmode == X_RMSNORM) {
+        const float4 g0 = *reinterpret_cast<const float4 *>(a.gain + c0), g1 = *reinterpret_cast<const float4 *>(a.gain + c0 + 4);
+        const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] *= gg[e];
+    }
+}
+
+// position of a wave in its stream of stages: k-th unit (tile, part) the wave took -> chunk of PBS super-blocks
+struct Cursor {
+    int k, u, c;
+    bool valid;
+};
+constexpr int STATIC_UNITS = 2; // units per wave assigned by position; the rest go to whichever wave asks first
+constexpr int FIFO = 8;         // units a wave may have requested and not yet consumed (a power of two > NST)
+
+// ------------------------------------------------------------------------------------------
+struct PPlan {
+    int n_tiles, nb, n_wg, ksplit, slab_blocks, n_slabs, units_cap, direct;
+    size_t lds_bytes;
+    bool ok;
+};
+
+inline int device_cu_count()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
+    }
+    return cus;
+}
+
+inline size_t fixed_lds(int T, int part_floats)
+{
+    return RING_BYTES + 32 + static_cast<size_t>(part_floats) * 4 + (16 * T + 2 * T) * 4 + (1 + GEMV_WAVES * FIFO) * 4 + 64;
+}
+
+// Decomposition of a launch: slabs of K (as few as the LDS allows), and waves per tile.  Candidates are
+// ranked by the longest wave's share of the ideal time; more slabs cost partial-sum traffic.
+inline PPlan plan_for(int n_tiles, int nb, int T, int epi)
+{
+    const int gran = epi == EPI_SWIGLU ? 2 : 1; // tiles that stay together on a workgroup
+    const int n_groups = n_tiles / gran;
+    PPlan best{};
+    best.ok = false;
+    double best_score = 0.0;
+    const int cus = device_cu_count();
+    const size_t per_block = static_cast<size_t>(T) * 8 * (SUB_BYTES + 4);
+    const double ideal = static_cast<double>(n_tiles) * ((nb + PBS - 1) / PBS) / (static_cast<double>(cus) * GEMV_WAVES);
+    int n_min = 0; // the fewest slabs that fit; more (up to twice as many) only if they balance the waves better
+    for (int n_slabs = 1; n_slabs <= 64 && (n_min == 0 || n_slabs <= 2 * n_min); ++n_slabs) {
+        PPlan p{};
+        p.nb = nb;
+        p.n_tiles = n_tiles;
+        p.n_slabs = n_slabs;
+        p.n_wg = cus;
+        if (p.n_wg > n_groups * n_slabs) p.n_wg = n_groups * n_slabs;
+        if (p.n_wg < n_slabs) continue;
+        const int wg_per_slab = p.n_wg / n_slabs;                     // the slabs with most tiles per workgroup
+        const int tiles_wg = gran * ((n_groups + wg_per_slab - 1) / wg_per_slab);
+        p.slab_blocks = ((nb + n_slabs - 1) / n_slabs + 1) & ~1;
+        if ((nb + p.slab_blocks - 1) / p.slab_blocks != n_slabs) continue; // rounding to even merged two slabs
+        const int chunks = (p.slab_blocks + PBS - 1) / PBS;
+        for (int ks = 1; ks <= 4 * GEMV_WAVES && ks <= chunks; ks *= 2) {
+            // ks == 1: a wave owns its tiles and stores their sums itself (a pair's two sums can only meet in
+            // global memory, i.e. with several slabs); otherwise the parts meet in LDS
+            const bool direct = ks == 1 && (gran == 1 || n_slabs > 1);
+            const int part_floats = direct ? tiles_wg : tiles_wg * ks * T * 16;
+            const size_t lds = fixed_lds(T, part_floats) + per_block * p.slab_blocks;
+            if (lds > LDS_BUDGET || part_floats * 4 > 24 * 1024) continue;
+            if (n_min == 0) n_min = n_slabs;
+            if (n_min == 1 && n_slabs > 1) continue; // all of K fits: never pay for the reduction across workgroups
+            const int units = tiles_wg * ks;
+            const int rounds = (units + GEMV_WAVES - 1) / GEMV_WAVES;
+            const double longest = static_cast<double>(rounds) * ((chunks + ks - 1) / ks);
+            // waves take units as they finish: finer parts even out what the memory system does not
+            const double score = ideal / longest * (1.0 - 0.03 * (n_slabs - n_min)) * (1.0 + 0.001 * ks);
+            if (score > best_score + 1e-9) {
+                best_score = score;
+                best = p;
+                best.ksplit = ks;
+                best.direct = direct ? 1 : 0;
+                best.units_cap = part_floats;
+                best.lds_bytes = lds;
+                best.ok = true;
+            }
+        }
+    }
+    return best;
+}
+
+
+// the stand-alone kernel has nothing to wait for
+struct NoSync {
+    __device__ __forceinline__ void wait() {}
+};
+
+} // namespace prima
