@@ -120,6 +120,19 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
                                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Optional single-launch path for one token (T = 1): the layers' kernels run back to back on one persistent
+ * grid (one launch per 24 layers), separated by grid barriers; same arithmetic, same bits.  It is OFF by
+ * default (measured slower than one launch per projection); prima_set_fused_window(1) switches it on for the
+ * process.  Shapes that do not fill the device evenly, and T > 1, always run one kernel per projection.
+ * The barriers poll with a bound; prima_window_check() waits for `hip_stream` (it SYNCHRONISES) and returns
+ * PRIMA_E_DEVICE if a barrier of the last call on this workspace gave up, in which case x_out of that call
+ * is not valid.
+ */
+void prima_set_fused_window(int32_t enabled);
+prima_status prima_window_check(const prima_dims *d, int32_t kv_cap, int32_t T,
+                                const void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Measurement hook.  Runs one ordinary window step, then replays each kind of launch on its own,
  * once per layer (L different weight sets), bracketed by two HIP events on `hip_stream`, and
  * returns per kind the elapsed time of its L back-to-back launches.  SYNCHRONISES the stream before

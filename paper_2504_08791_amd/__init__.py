@@ -92,6 +92,11 @@ def workspace_bytes(dims, kv_cap, T):
     return _ffi.lib().prima_workspace_bytes(C.byref(d), kv_cap, T)
 
 
+def set_fused_window(enabled):
+    """Single-launch window steps for one token on or off (default), process-wide."""
+    _ffi.lib().prima_set_fused_window(1 if enabled else 0)
+
+
 class Window:
     """A window of decoder layers resident in HBM: keeps the tensors alive, the descriptor array
     and a workspace, so that a step is a single C call."""
@@ -127,6 +132,11 @@ class Window:
                                                         n_past, T, _ptr(x_in), _ptr(x_out), _ptr(self.workspace),
                                                         self.workspace.numel(), _stream()), "prima_layer_window_decode")
         return x_out
+
+    def check(self, T=1):
+        """Waits for the stream; raises if a grid barrier of the last single-launch step gave up."""
+        _ffi.check(_ffi.lib().prima_window_check(C.byref(self.dims), self.kv_cap, T, _ptr(self.workspace),
+                                                 self.workspace.numel(), _stream()), "prima_window_check")
 
     def decode_profiled(self, x_in, n_past, x_out=None):
         """Measurement hook: one step with an event after every launch; synchronises.

@@ -12,7 +12,8 @@ STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIG
 
 EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", "prima_attn_decode",
            "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_window_decode_profiled", "prima_layer_decode_taps",
-           "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version"]
+           "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
+           "prima_set_fused_window", "prima_window_check"]
 
 
 class Dims(C.Structure):
@@ -59,13 +60,16 @@ def lib():
         L.prima_lm_head_workspace_bytes.restype = sz
         L.prima_workspace_bytes.argtypes = [dp, i32, i32]
         L.prima_workspace_bytes.restype = sz
+        L.prima_set_fused_window.argtypes = [i32]
+        L.prima_window_check.argtypes = [dp, i32, i32, vp, sz, vp]
         L.prima_status_str.argtypes = [C.c_int]
         L.prima_status_str.restype = C.c_char_p
         L.prima_abi_version.restype = C.c_int
         for name in ("prima_q4k_gemv", "prima_q4k_dequant", "prima_attn_decode", "prima_layer_window_decode",
                      "prima_layer_window_decode_profiled",
-                     "prima_layer_decode_taps", "prima_lm_head"):
+                     "prima_layer_decode_taps", "prima_lm_head", "prima_window_check"):
             getattr(L, name).restype = C.c_int
+        L.prima_set_fused_window.restype = None
         _lib = L
     return _lib
 

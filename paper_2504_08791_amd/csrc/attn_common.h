@@ -126,4 +126,30 @@ struct AttnLds {
     int last;
 };
 
+inline int query_groups(const prima_dims &d, int T)
+{
+    const int G = d.n_q_heads / d.n_kv_heads;
+    return (G * T + QG - 1) / QG;
+}
+
+
+inline AttnArgs build_attn_args(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
+                                const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o, void *ws)
+{
+    const int n_total = n_past + T;
+    AttnArgs a{};
+    a.q = q; a.q_rot_out = q_rot_out; a.k_new = k_new; a.v_new = v_new;
+    a.rope_tab = reinterpret_cast<const float2 *>(rope_tab);
+    a.K = K; a.V = V;
+    a.arrivals = static_cast<unsigned *>(ws);
+    a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + attn_counter_bytes(d, T));
+    a.o = o;
+    a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.kv_cap = kv_cap; a.n_past = n_past; a.T = T;
+    // key ranges are multiples of 16 so that tiles never straddle two workgroups, and none is empty
+    const int want = attn_num_splits(d, n_total, T);
+    a.keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
+    a.nsplit = (n_total + a.keys_per_split - 1) / a.keys_per_split;
+    return a;
+}
+
 } // namespace prima

@@ -37,13 +37,8 @@ __global__ void __launch_bounds__(ATT_THREADS) attn_decode_kernel(AttnArgs a)
     constexpr bool COH = false;
     const int split = blockIdx.x, kvh = blockIdx.y, qgrp = blockIdx.z, nqg = gridDim.z;
     AttnNoSync sync;
+    __half *const arg_K = a.K, *const arg_V = a.V;
 #include "attn_body.inc"
-}
-
-static int query_groups(const prima_dims &d, int T)
-{
-    const int G = d.n_q_heads / d.n_kv_heads;
-    return (G * T + QG - 1) / QG;
 }
 
 int attn_num_splits(const prima_dims &d, int n_total, int T)
@@ -71,19 +66,7 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
                          const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
                          void *ws, hipStream_t st)
 {
-    const int n_total = n_past + T;
-    AttnArgs a{};
-    a.q = q; a.q_rot_out = q_rot_out; a.k_new = k_new; a.v_new = v_new;
-    a.rope_tab = reinterpret_cast<const float2 *>(rope_tab);
-    a.K = K; a.V = V;
-    a.arrivals = static_cast<unsigned *>(ws);
-    a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + attn_counter_bytes(d, T));
-    a.o = o;
-    a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.kv_cap = kv_cap; a.n_past = n_past; a.T = T;
-    // key ranges are multiples of 16 so that tiles never straddle two workgroups, and none is empty
-    const int want = attn_num_splits(d, n_total, T);
-    a.keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
-    a.nsplit = (n_total + a.keys_per_split - 1) / a.keys_per_split;
+    const AttnArgs a = build_attn_args(d, q, q_rot_out, k_new, v_new, rope_tab, K, V, kv_cap, n_past, T, o, ws);
     const dim3 grid(a.nsplit, d.n_kv_heads, query_groups(d, T)), block(ATT_THREADS);
     if (d.head_dim == 128 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<128, 0>), grid, block, sizeof(AttnLds<128>), st, a);
     else if (d.head_dim == 128 && d.rope_mode == 1) hipLaunchKernelGGL((attn_decode_kernel<128, 1>), grid, block, sizeof(AttnLds<128>), st, a);

@@ -98,4 +98,13 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
                          const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
                          void *ws, hipStream_t st);
 
+// one token through a whole window in one launch per FUSED_MAX_LAYERS layers (fused_window.hip); PRIMA_E_SHAPE
+// with nothing launched when the shapes do not qualify
+size_t fused_sync_bytes();
+prima_status launch_fused_window(const prima_dims &d, const prima_layer *layers, int L, const GemvArgs ga[4],
+                                 void *gemv_ws, size_t gemv_ws_bytes, size_t arrivals_region,
+                                 const float *q, const float *k_new, const float *v_new, const float *rope_tab,
+                                 int kv_cap, int n_past, float *o, void *attn_ws,
+                                 const float *x_in, float *x_out, float *xb0, float *xb1, void *sync, hipStream_t st);
+
 } // namespace prima

@@ -75,6 +75,15 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Tells the compiler that a pointer obtained as a plain value (e.g. read from the kernel-argument segment by
+// hand) points to global memory: generic loads count on both memory counters and every wait would then
+// drain the weight stream.
+template <class T>
+__device__ __forceinline__ T *as_global(T *p)
+{
+    return (T *)(__attribute__((address_space(1))) T *)p;
+}
+
 __device__ __forceinline__ uint32_t lds_address(const void *p)
 {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)); // low half of a flat LDS pointer is the LDS byte address
@@ -87,17 +96,27 @@ __device__ __forceinline__ long pack64(uint32_t lo, uint32_t hi)
 
 // eight consecutive activations of token t starting at column c0, before the RMSNorm scale:
 // X_PLAIN x, X_RMSNORM x*gain (the 1/rms factor is applied by the caller)
-__device__ __forceinline__ void load_act8(const PGemvArgs &a, int t, int c0, float *f)
+__device__ __forceinline__ void load_act8(const float *x, const float *gain, int64_t ldx, bool rmsnorm, int t, int c0, float *f)
 {
-    const float *xp = a.x + t * a.ldx + c0;
+    const float *xp = x + t * ldx + c0;
     const float4 v0 = *reinterpret_cast<const float4 *>(xp), v1 = *reinterpret_cast<const float4 *>(xp + 4);
     f[0] = v0.x; f[1] = v0.y; f[2] = v0.z; f[3] = v0.w; f[4] = v1.x; f[5] = v1.y; f[6] = v1.z; f[7] = v1.w;
-    if (a.xmode == X_RMSNORM) {
-        const float4 g0 = *reinterpret_cast<const float4 *>(a.gain + c0), g1 = *reinterpret_cast<const float4 *>(a.gain + c0 + 4);
+    if (rmsnorm) {
+        const float4 g0 = *reinterpret_cast<const float4 *>(gain + c0), g1 = *reinterpret_cast<const float4 *>(gain + c0 + 4);
         const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
 #pragma unroll
         for (int e = 0; e < 8; ++e) f[e] *= gg[e];
     }
+}
+
+// segment sg and tile-in-segment tis of a tile: (gate, up) pairs sit on tiles 2p, 2p + 1; otherwise the
+// segments follow each other, t1 and t2 being the first tiles of segments 1 and 2
+__device__ __forceinline__ void tile_segment(bool pairs, int nseg, int t1, int t2, int tile, int &sg, int &tis)
+{
+    if (pairs) { sg = tile & 1; tis = tile >> 1; return; }
+    sg = 0; tis = tile;
+    if (nseg > 1 && tile >= t1) { sg = 1; tis = tile - t1; }
+    if (nseg > 2 && tile >= t2) { sg = 2; tis = tile - t2; }
 }
 
 // position of a wave in its stream of stages: k-th unit (tile, part) the wave took -> chunk of PBS super-blocks
@@ -105,7 +124,8 @@ struct Cursor {
     int k, u, c;
     bool valid;
 };
-constexpr int STATIC_UNITS = 2; // units per wave assigned by position; the rest go to whichever wave asks first
+constexpr int STATIC_UNITS = NST; // units per wave assigned by position (up to one per ring stage may be
+                                  // requested before the counter exists); the rest go to whichever wave asks first
 constexpr int FIFO = 8;         // units a wave may have requested and not yet consumed (a power of two > NST)
 
 // ------------------------------------------------------------------------------------------
@@ -186,6 +206,66 @@ inline PPlan plan_for(int n_tiles, int nb, int T, int epi)
     return best;
 }
 
+
+inline int tiles_of(const GemvArgs &ga)
+{
+    int n = 0;
+    for (int i = 0; i < ga.nseg; ++i) n += static_cast<int>((ga.seg[i].n_rows + 15) / 16);
+    return n;
+}
+
+// scratch in global memory: partial sums of the slabs and the per-tile arrival counters (which must be
+// zero before the first launch and are left zero by every launch)
+inline size_t part_bytes(const PPlan &p, int T) { return round_up(static_cast<size_t>(p.n_slabs) * p.n_tiles * 16 * T * sizeof(float), 256); }
+inline size_t arrivals_bytes(int n_tiles) { return round_up(static_cast<size_t>(n_tiles) * sizeof(unsigned), 256); }
+
+
+// Arguments and plan of one pass (tokens t0 .. t0+T-1, T <= MAX_T_PASS) of a mat-vec.  ws: scratch whose
+// first arrivals_region bytes are the (zero) arrival counters, the slabs' partial sums follow.
+inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size_t ws_bytes, size_t arrivals_region,
+                               PGemvArgs &a, PPlan &p)
+{
+    if (ga.xmode != X_PLAIN && ga.xmode != X_RMSNORM) return PRIMA_E_SHAPE;
+    if (ga.epi == EPI_SWIGLU && (ga.nseg != 2 || ga.seg[0].n_rows != ga.seg[1].n_rows)) return PRIMA_E_SHAPE;
+    if (ga.epi != EPI_SWIGLU && ga.epi != EPI_ROWS) return PRIMA_E_SHAPE;
+    const int n_tiles = tiles_of(ga);
+    p = plan_for(n_tiles, static_cast<int>(ga.n_cols / QK), T, ga.epi);
+    if (!p.ok) return PRIMA_E_SHAPE;
+    a = PGemvArgs{};
+    int tile0 = 0;
+    for (int i = 0; i < ga.nseg; ++i) {
+        a.seg[i] = ga.seg[i];
+        if (a.seg[i].y) a.seg[i].y += t0 * ga.seg[i].ldy;
+        if (a.seg[i].resid) a.seg[i].resid += t0 * ga.seg[i].ldr;
+        a.seg_tile0[i] = tile0;
+        tile0 += static_cast<int>((ga.seg[i].n_rows + 15) / 16);
+    }
+    a.nseg = ga.nseg;
+    a.n_tiles = p.n_tiles;
+    a.nb = p.nb;
+    a.T = T;
+    a.xmode = ga.xmode;
+    a.epi = ga.epi;
+    a.x = ga.x + t0 * ga.ldx;
+    a.gain = ga.gain;
+    a.ldx = ga.ldx;
+    a.eps = ga.eps;
+    a.ksplit = p.ksplit;
+    a.slab_blocks = p.slab_blocks;
+    a.n_slabs = p.n_slabs;
+    a.units_cap = p.units_cap;
+    a.direct = p.direct;
+    a.n_wg = p.n_wg;
+    if (p.n_slabs > 1) {
+        // the counters sit in a region of fixed size at the start of the scratch, so that launches of
+        // different shapes that share the scratch never write partial sums over each other's counters
+        if (arrivals_region < arrivals_bytes(n_tiles)) return PRIMA_E_WORKSPACE;
+        if (!ws || ws_bytes < arrivals_region + part_bytes(p, T)) return PRIMA_E_WORKSPACE;
+        a.arrivals = static_cast<unsigned *>(ws);
+        a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + arrivals_region);
+    }
+    return PRIMA_OK;
+}
 
 // the stand-alone kernel has nothing to wait for
 struct NoSync {

@@ -46,20 +46,12 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
     constexpr bool COH = false;
     const int wg_index = blockIdx.x;
     NoSync sync;
+    const float *const arg_x = a.x, *const arg_gain = a.gain;
+    const uint8_t *const arg_W0 = a.seg[0].W, *const arg_W1 = a.seg[1].W, *const arg_W2 = a.seg[2].W;
+    float *const arg_y0 = a.seg[0].y, *const arg_y1 = a.seg[1].y, *const arg_y2 = a.seg[2].y;
+    const float *const arg_r0 = a.seg[0].resid, *const arg_r1 = a.seg[1].resid, *const arg_r2 = a.seg[2].resid;
 #include "gemv_body.inc"
 }
-
-static int tiles_of(const GemvArgs &ga)
-{
-    int n = 0;
-    for (int i = 0; i < ga.nseg; ++i) n += static_cast<int>((ga.seg[i].n_rows + 15) / 16);
-    return n;
-}
-
-// scratch in global memory: partial sums of the slabs and the per-tile arrival counters (which must be
-// zero before the first launch and are left zero by every launch)
-static size_t part_bytes(const PPlan &p, int T) { return round_up(static_cast<size_t>(p.n_slabs) * p.n_tiles * 16 * T * sizeof(float), 256); }
-static size_t arrivals_bytes(int n_tiles) { return round_up(static_cast<size_t>(n_tiles) * sizeof(unsigned), 256); }
 
 size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T)
 {
@@ -97,48 +89,13 @@ static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
 
 prima_status launch_gemv_mfma(const GemvArgs &ga, void *ws, size_t ws_bytes, size_t arrivals_region, hipStream_t st)
 {
-    if (ga.xmode != X_PLAIN && ga.xmode != X_RMSNORM) return PRIMA_E_SHAPE;
-    if (ga.epi == EPI_SWIGLU && (ga.nseg != 2 || ga.seg[0].n_rows != ga.seg[1].n_rows)) return PRIMA_E_SHAPE;
-    if (ga.epi != EPI_SWIGLU && ga.epi != EPI_ROWS) return PRIMA_E_SHAPE;
-    const int n_tiles = tiles_of(ga);
     // up to MAX_T_PASS tokens per pass over the weights
     for (int t0 = 0; t0 < ga.T; t0 += MAX_T_PASS) {
         const int T = ga.T - t0 < MAX_T_PASS ? ga.T - t0 : MAX_T_PASS;
-        const PPlan p = plan_for(n_tiles, static_cast<int>(ga.n_cols / QK), T, ga.epi);
-        if (!p.ok) return PRIMA_E_SHAPE;
-        PGemvArgs a{};
-        int tile0 = 0;
-        for (int i = 0; i < ga.nseg; ++i) {
-            a.seg[i] = ga.seg[i];
-            a.seg[i].y += t0 * ga.seg[i].ldy;
-            if (a.seg[i].resid) a.seg[i].resid += t0 * ga.seg[i].ldr;
-            a.seg_tile0[i] = tile0;
-            tile0 += static_cast<int>((ga.seg[i].n_rows + 15) / 16);
-        }
-        a.nseg = ga.nseg;
-        a.n_tiles = p.n_tiles;
-        a.nb = p.nb;
-        a.T = T;
-        a.xmode = ga.xmode;
-        a.epi = ga.epi;
-        a.x = ga.x + t0 * ga.ldx;
-        a.gain = ga.gain;
-        a.ldx = ga.ldx;
-        a.eps = ga.eps;
-        a.ksplit = p.ksplit;
-        a.slab_blocks = p.slab_blocks;
-        a.n_slabs = p.n_slabs;
-        a.units_cap = p.units_cap;
-        a.direct = p.direct;
-        a.n_wg = p.n_wg;
-        if (p.n_slabs > 1) {
-            // the counters sit in a region of fixed size at the start of the scratch, so that launches of
-            // different shapes that share the scratch never write partial sums over each other's counters
-            if (arrivals_region < arrivals_bytes(n_tiles)) return PRIMA_E_WORKSPACE;
-            if (!ws || ws_bytes < arrivals_region + part_bytes(p, T)) return PRIMA_E_WORKSPACE;
-            a.arrivals = static_cast<unsigned *>(ws);
-            a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + arrivals_region);
-        }
+        PPlan p;
+        PGemvArgs a;
+        const prima_status bs = build_pass(ga, t0, T, ws, ws_bytes, arrivals_region, a, p);
+        if (bs != PRIMA_OK) return bs;
         hipError_t e;
         switch (T) {
         case 1: e = launch_tt<1>(a, p, st); break;

@@ -10,7 +10,7 @@ using namespace prima;
 namespace {
 
 struct WindowWs {
-    size_t q, k, v, o, h, a, xb0, xb1, rope, attn, gemv, gemv_bytes, arrivals_bytes, total;
+    size_t q, k, v, o, h, a, xb0, xb1, rope, attn, gemv, gemv_bytes, arrivals_bytes, sync, total;
 };
 
 bool dims_ok(const prima_dims *d)
@@ -45,6 +45,7 @@ WindowWs carve(const prima_dims &d, int kv_cap, int T)
     for (const auto &sh : shapes) w.gemv_bytes = std::max(w.gemv_bytes, gemv_ws_bytes(sh[0], sh[1], T)); // counters + partial sums
     w.gemv_bytes += w.arrivals_bytes; // the counter region is sized for the tallest matrix
     w.gemv = take(w.gemv_bytes);
+    w.sync = take(fused_sync_bytes());
     w.total = off;
     return w;
 }
@@ -74,6 +75,31 @@ GemvArgs gemv_args(int nseg, int64_t n_cols, const float *x, int64_t ldx, int T,
     ga.xmode = xmode; ga.epi = epi; ga.gain = gain; ga.eps = eps;
     return ga;
 }
+
+// the four projections of a layer as mat-vec arguments, in launch order (Q/K/V, output, gate/up, down)
+void layer_gemv_args(const prima_dims &d, const prima_layer &L, int T, const float *x, float *y, void *ws, const WindowWs &w, GemvArgs ga[4])
+{
+    const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
+    float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
+    float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *act = at<float>(ws, w.a);
+    ga[0] = gemv_args(3, e, x, e, T, X_RMSNORM, L.g_attn, d.rms_eps);
+    ga[0].seg[0] = seg(L.wq, q, qd, qd);
+    ga[0].seg[1] = seg(L.wk, k, kvd, kvd);
+    ga[0].seg[2] = seg(L.wv, v, kvd, kvd);
+    ga[1] = gemv_args(1, qd, o, qd, T);
+    ga[1].seg[0] = seg(L.wo, h, e, e, x, e);
+    ga[2] = gemv_args(2, e, h, e, T, X_RMSNORM, L.g_ffn, d.rms_eps, EPI_SWIGLU);
+    ga[2].seg[0] = seg(L.wgate, act, F, F); // silu(gate) * up lands here
+    ga[2].seg[1] = seg(L.wup, nullptr, F, F);
+    ga[3] = gemv_args(1, F, act, F, T);
+    ga[3].seg[0] = seg(L.wdown, y, e, e, h, e);
+}
+
+// whether windows of one token try the single-launch path first.  Off unless asked for: it gives the same
+// bits, but measured slower than one launch per projection (config 3: 186 vs 129 us per layer): a grid barrier
+// costs ~3 us, the activations then take a device-scope round trip (~2.5 us) and the workgroups wait 6-11 us
+// per barrier for the slowest one, which the three prefetched ring stages (~5 us of traffic) do not cover.
+bool g_fused_enabled = false;
 
 // one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Five launches: Q/K/V projections
 // (RMSNorm fused), attention (RoPE + KV append fused, key ranges merged by the last arriver), output projection
@@ -231,6 +257,17 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
     if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
     if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, T), st);
     if (s != PRIMA_OK) return s;
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.sync), fused_sync_bytes(), st);
+    if (s != PRIMA_OK) return s;
+    if (T == 1 && g_fused_enabled) {
+        GemvArgs ga[4];
+        layer_gemv_args(*d, layers[0], T, x_in, x_out, workspace, w, ga);
+        s = launch_fused_window(*d, layers, L, ga, at<char>(workspace, w.gemv), w.gemv_bytes, w.arrivals_bytes,
+                                at<float>(workspace, w.q), at<float>(workspace, w.k), at<float>(workspace, w.v), at<float>(workspace, w.rope),
+                                kv_cap, n_past, at<float>(workspace, w.o), at<char>(workspace, w.attn),
+                                x_in, x_out, at<float>(workspace, w.xb0), at<float>(workspace, w.xb1), at<char>(workspace, w.sync), st);
+        if (s != PRIMA_E_SHAPE) return s; // ran (or failed for good); E_SHAPE: not eligible, nothing was launched
+    }
     const float *cur = x_in;
     for (int i = 0; i < L; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
@@ -239,6 +276,20 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
         cur = dst;
     }
     return PRIMA_OK;
+}
+
+void prima_set_fused_window(int32_t enabled) { g_fused_enabled = enabled != 0; }
+
+prima_status prima_window_check(const prima_dims *d, int32_t kv_cap, int32_t T, const void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!d || !workspace) return PRIMA_E_NULL;
+    if (!dims_ok(d) || T < 1 || T > PRIMA_MAX_TOK || kv_cap < 1) return PRIMA_E_SHAPE;
+    const WindowWs w = carve(*d, kv_cap, T);
+    if (workspace_bytes < w.total) return PRIMA_E_WORKSPACE;
+    if (hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) return PRIMA_E_DEVICE;
+    int flag = 0;
+    if (hipMemcpy(&flag, static_cast<const char *>(workspace) + w.sync + 128, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) return PRIMA_E_DEVICE;
+    return flag == 0 ? PRIMA_OK : PRIMA_E_DEVICE;
 }
 
 prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima_layer *layers, int32_t L,

@@ -79,3 +79,39 @@ def test_gemv_sampled_rows_at_full_size(gpu_lib):
     ref = dense @ x[0].astype(np.float64)
     scale = np.sqrt((ref ** 2).mean())
     assert np.abs(got[rows] - ref).max() / scale < 1e-5
+
+
+def test_single_launch_window_matches(gpu_lib):
+    """The optional single-launch path (config 3's shape, 3 layers): same bits as one launch per
+    projection, the oracle's hidden state within tolerance, the same appended K/V rows, and no
+    barrier time-out."""
+    cfg = CONFIGS["c3"].with_(n_layers=3)
+    d = cfg.dims
+    cap = cfg.n_past + cfg.T
+    x = synth.window_input(cfg)
+    dev_layers, h = [], x.astype(np.float64)
+    for l in range(cfg.n_layers):
+        t = synth.layer_tensors(cfg, l, kv_cap=cap)
+        dev_layers.append({k: _dev(v) for k, v in t.items()})
+        h = oracle.layer(d, t, h, cfg.n_past)
+        del t
+    win = gpu_lib.Window(d, dev_layers, cap, T_max=cfg.T)
+    win.workspace.fill_(0xFF)
+    xd = _dev(x)
+    try:
+        gpu_lib.set_fused_window(False)
+        y0 = win.decode(xd, cfg.n_past).clone()
+        rows0 = [(l["k_cache"][:, cfg.n_past].clone(), l["v_cache"][:, cfg.n_past].clone()) for l in dev_layers]
+        for l in dev_layers:     # wipe the appended rows so that the second path has to write them itself
+            l["k_cache"][:, cfg.n_past].zero_()
+            l["v_cache"][:, cfg.n_past].zero_()
+        gpu_lib.set_fused_window(True)
+        y1 = win.decode(xd, cfg.n_past)
+        win.check()              # waits; raises if a grid barrier gave up
+    finally:
+        gpu_lib.set_fused_window(False)
+    assert torch.equal(y0, y1)
+    for l, (k0, v0) in zip(dev_layers, rows0):
+        assert torch.equal(l["k_cache"][:, cfg.n_past], k0)
+        assert torch.equal(l["v_cache"][:, cfg.n_past], v0)
+    assert rel_err(y1.cpu().numpy(), h) < HID_TOL
