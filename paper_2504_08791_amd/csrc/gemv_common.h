@@ -162,7 +162,8 @@ inline PPlan plan_for(int n_tiles, int nb, int T, int epi)
     best.ok = false;
     double best_score = 0.0;
     const int cus = device_cu_count();
-    const size_t per_block = static_cast<size_t>(T) * 8 * (SUB_BYTES + 4);
+    const int Tq = T == 1 ? 1 : (T + 3) / 4 * 4; // token slots laid out in LDS (several tokens: groups of four)
+    const size_t per_block = static_cast<size_t>(Tq) * 8 * (SUB_BYTES + 4);
     const double ideal = static_cast<double>(n_tiles) * ((nb + PBS - 1) / PBS) / (static_cast<double>(cus) * GEMV_WAVES);
     int n_min = 0; // the fewest slabs that fit; more (up to twice as many) only if they balance the waves better
     for (int n_slabs = 1; n_slabs <= 64 && (n_min == 0 || n_slabs <= 2 * n_min); ++n_slabs) {
