@@ -37,6 +37,7 @@ struct PGemvArgs {
     int n_slabs;
     int units_cap;   // floats reserved for the partial sums (and the per-tile flags of the slab reduction)
     int direct;      // a wave owns whole rows of the slab (ksplit == 1) and stores their sums itself
+    int defer;       // n_slabs > 1: the slabs are added by a second kernel instead of the workgroup that arrives last
     int n_wg;
     float *part;        // n_slabs > 1: partial sums [n_slabs][n_tiles*16][T]
     unsigned *arrivals; // n_slabs > 1: per-tile arrival counters, zero between launches
@@ -256,6 +257,10 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
     a.n_slabs = p.n_slabs;
     a.units_cap = p.units_cap;
     a.direct = p.direct;
+    // Several tokens: a workgroup has many tiles and the slabs finish together, so "whoever arrives last" is
+    // one workgroup for nearly all of them (measured: the slowest one adds for 50-70 us while the rest idle);
+    // a second small launch does the additions in parallel instead.
+    a.defer = (p.n_slabs > 1 && T > 1) ? 1 : 0;
     a.n_wg = p.n_wg;
     if (p.n_slabs > 1) {
         // the counters sit in a region of fixed size at the start of the scratch, so that launches of

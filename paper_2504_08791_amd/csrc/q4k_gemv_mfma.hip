@@ -53,6 +53,44 @@ __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemv
 #include "gemv_body.inc"
 }
 
+// Second kernel of a launch with deferred slab addition: one thread per (tile or gate/up pair, token, row) adds
+// the slabs' partial sums in slab order and applies the epilogue (residual, or SwiGLU on a pair).
+template <int TT>
+__global__ void __launch_bounds__(256) gemv_slab_reduce_kernel(PGemvArgs a)
+{
+    const bool pairs = a.epi == EPI_SWIGLU;
+    const int gran = pairs ? 2 : 1;
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t n_out = static_cast<int64_t>(a.n_tiles / gran) * 16 * TT;
+    if (idx >= n_out) return;
+    const int gl = static_cast<int>(idx / (16 * TT));
+    const int rem = static_cast<int>(idx - static_cast<int64_t>(gl) * (16 * TT));
+    const int t = rem >> 4, jj = rem & 15;
+    const int64_t slab_stride = static_cast<int64_t>(a.n_tiles) * 16 * TT;
+    auto all_slabs = [&](int tile) {
+        float v = 0.f;
+        for (int sl = 0; sl < a.n_slabs; ++sl) v += a.part[sl * slab_stride + static_cast<int64_t>(tile) * 16 * TT + rem]; // fixed order
+        return v;
+    };
+    if (pairs) {
+        const int64_t row = static_cast<int64_t>(gl) * 16 + jj;
+        if (row < a.seg[0].n_rows) {
+            const float gt = all_slabs(2 * gl), up = all_slabs(2 * gl + 1);
+            a.seg[0].y[t * a.seg[0].ldy + row] = gt / (1.0f + expf(-gt)) * up;
+        }
+    } else {
+        int sg, tis;
+        tile_segment(false, a.nseg, a.seg_tile0[1], a.seg_tile0[2], gl, sg, tis);
+        const GemvSeg &sgm = a.seg[sg];
+        const int64_t row = static_cast<int64_t>(tis) * 16 + jj;
+        if (row < sgm.n_rows) {
+            float v = all_slabs(gl);
+            if (sgm.resid) v += sgm.resid[t * sgm.ldr + row];
+            sgm.y[t * sgm.ldy + row] = v;
+        }
+    }
+}
+
 size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T)
 {
     // any segmentation of the rows into up to three matrices adds at most two tiles
@@ -84,6 +122,10 @@ static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
         attr_set = true;
     }
     hipLaunchKernelGGL((gemv_q4k_persistent_kernel<TT>), dim3(p.n_wg), dim3(GEMV_THREADS), p.lds_bytes, st, a);
+    if (a.defer) {
+        const int64_t n_out = static_cast<int64_t>(a.n_tiles / (a.epi == EPI_SWIGLU ? 2 : 1)) * 16 * TT;
+        hipLaunchKernelGGL((gemv_slab_reduce_kernel<TT>), dim3(static_cast<unsigned>((n_out + 255) / 256)), dim3(256), 0, st, a);
+    }
     return hipGetLastError();
 }
 
