@@ -17,7 +17,11 @@
 //  * the 6-bit sub-scale multiplies these integers (still exact), the four digits are recombined
 //    in fp32, and d (fp16) scales the super-block.  The min term uses per-sub-block sums of xfix:
 //        y = 2^-p * sum_blocks [ d * sum_s sc_s * (q . xfix)_s  -  dmin * sum_s m_s * Xsum_s ].
-//    For T tokens the unpacked weights are reused against each token's digits.
+//  * several tokens (speculative verification, App. A.12) use the rows of the A operand for
+//    (token, digit) pairs instead: 4 tokens x 4 digits, one MFMA per sub-block for all four tokens,
+//    lane (j, g) receives the digit sums of token g with row j.  Each weight byte is unpacked once
+//    and nothing is multiplied by zeros; at 8 tokens the loop is bound by the vector ALU
+//    (4 multiply-adds per sub-block and token group for the sub-scales), at ~3.9 TB/s of weights.
 //
 // Data movement.  One 512-thread workgroup per compute unit, persistent; it owns a contiguous range
 // of 16-row tiles (with all of K whenever the activations fit in LDS); every sum has a fixed order.
@@ -25,12 +29,16 @@
 // 128-bit global->LDS loads (no VGPR staging): a stage is 16 rows x 2 super-blocks, requested as
 // runs of 288 contiguous bytes per row, laid out with an odd row stride so that the MFMA-order
 // reads (lane (j, g) reads row j) are free of bank conflicts.  Two stages are always in flight
-// per wave while the third is consumed; only s_waitcnt orders them, no barrier.  The activations
-// are transformed (RMSNorm or SwiGLU when asked), quantised and laid out in LDS by every
-// workgroup for itself.  When the digits of all of K do not fit in the LDS left over by the rings, K
-// is cut into slabs and a workgroup handles one slab of a (larger) range of tiles; the slabs'
-// partial sums meet in global memory, where the workgroup that arrives last at a tile adds them in
-// slab order (release/acquire fences and one atomic counter per tile, reset for the next launch).
+// per wave while the third is consumed; only s_waitcnt orders them, no barrier.  Waves take
+// (tile, part) units from an LDS counter.  The activations are transformed (RMSNorm when asked),
+// quantised and laid out in LDS by every workgroup for itself.  When the digits of all of K do not
+// fit in the LDS left over by the rings, K is cut into slabs and a workgroup handles one slab of a
+// (larger) range of tiles, with its own fixed-point scale; the slabs' partial sums meet in global
+// memory.  One token: the workgroup that arrives last at a tile adds them in slab order (device-scope
+// stores and loads, one relaxed atomic counter per tile, reset for the next launch; no fences).
+// Several tokens: a second small kernel adds them (the last arriver would be one workgroup for
+// nearly all tiles).  The epilogue adds the residual, or applies SwiGLU to a (gate, up) pair of tiles.
+// The body is gemv_body.inc (shared with the single-launch window kernel).
 #include "gemv_common.h"
 
 namespace prima {
