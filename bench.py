@@ -99,6 +99,21 @@ def main():
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
     bytes_step = cfg.bytes_per_step()
 
+    # --- what a plain linear read reaches on this device (4 GiB, far beyond the last-level cache) ---
+    probe = torch.empty(4 * 1024 ** 3, dtype=torch.uint8, device=dev)
+    probe.zero_()
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    for _ in range(2):
+        prima.stream_read_probe(probe, sink)
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record(stream)
+    for _ in range(5):
+        prima.stream_read_probe(probe, sink)
+    p1.record(stream)
+    torch.cuda.synchronize()
+    stream_read_gbps = probe.numel() * 5 / (p0.elapsed_time(p1) * 1e-3) / 1e9
+    del probe
+
     # --- per kind of launch: each replayed on its own, once per layer, between two HIP events on the
     #     same stream (the dominant kernel is the gate/up projection) ---
     n_prof = 5
@@ -139,6 +154,7 @@ def main():
         "window_hbm_frac": round(bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "wall_ms_per_step": round(wall_ms / args.steps, 4),
         "per_launch_us": {k: round(v, 2) for k, v in per_launch_us.items()},
+        "plain_read_gbps": round(stream_read_gbps, 1),  # linear 128-bit read of 4 GiB: the practical ceiling
         "roofline": {
             "bound": "hbm",
             "kernel": f"gemv_q4k_persistent_kernel<{cfg.T}> as launched for the gate/up projections (RMSNorm in front, SwiGLU behind)",

@@ -81,6 +81,15 @@ prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols,
 size_t prima_gemv_workspace_bytes(int64_t n_rows, int64_t n_cols, int32_t T);
 
 /*
+ * Measurement hook: reads `bytes` (rounded down to 16) of device memory at `src` once, linearly, with
+ * 128-bit loads from about 8 workgroups per compute unit, and discards them; `sink` is 4 bytes of device
+ * memory that is (practically never) written.  Timed by the caller it states what a plain read of HBM
+ * reaches on this device, the practical ceiling beside the nominal peak (App. A.3's device-loading
+ * throughput).  src 16-byte aligned.
+ */
+prima_status prima_stream_read_probe(const void *src, size_t bytes, void *sink, void *hip_stream);
+
+/*
  * Test hook: out[r*n_cols + c] = fp32 value of weight (r, c).  The value is the fp32 number
  * nearest to the exact d*sc*q - dmin*m (both products are exact in fp32); results are
  * bit-exact by contract.

@@ -92,6 +92,12 @@ def workspace_bytes(dims, kv_cap, T):
     return _ffi.lib().prima_workspace_bytes(C.byref(d), kv_cap, T)
 
 
+def stream_read_probe(buf, sink):
+    """Measurement hook: one linear read of the uint8 tensor `buf` (discarded); `sink` any 4-byte device tensor."""
+    _ffi.check(_ffi.lib().prima_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()),
+               "prima_stream_read_probe")
+
+
 def set_fused_window(enabled):
     """Single-launch window steps for one token on or off (default), process-wide."""
     _ffi.lib().prima_set_fused_window(1 if enabled else 0)

@@ -13,7 +13,7 @@ STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIG
 EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", "prima_attn_decode",
            "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_window_decode_profiled", "prima_layer_decode_taps",
            "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
-           "prima_set_fused_window", "prima_window_check"]
+           "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe"]
 
 
 class Dims(C.Structure):
@@ -60,6 +60,7 @@ def lib():
         L.prima_lm_head_workspace_bytes.restype = sz
         L.prima_workspace_bytes.argtypes = [dp, i32, i32]
         L.prima_workspace_bytes.restype = sz
+        L.prima_stream_read_probe.argtypes = [vp, sz, vp, vp]
         L.prima_set_fused_window.argtypes = [i32]
         L.prima_window_check.argtypes = [dp, i32, i32, vp, sz, vp]
         L.prima_status_str.argtypes = [C.c_int]
@@ -67,7 +68,7 @@ def lib():
         L.prima_abi_version.restype = C.c_int
         for name in ("prima_q4k_gemv", "prima_q4k_dequant", "prima_attn_decode", "prima_layer_window_decode",
                      "prima_layer_window_decode_profiled",
-                     "prima_layer_decode_taps", "prima_lm_head", "prima_window_check"):
+                     "prima_layer_decode_taps", "prima_lm_head", "prima_window_check", "prima_stream_read_probe"):
             getattr(L, name).restype = C.c_int
         L.prima_set_fused_window.restype = None
         _lib = L

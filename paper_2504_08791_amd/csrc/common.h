@@ -86,6 +86,7 @@ size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T);
 size_t gemv_arrivals_bytes(int64_t n_rows_total);
 prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
 
+prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
 prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
 int attn_num_splits(const prima_dims &d, int n_total, int T);
 size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);

@@ -23,4 +23,28 @@ prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta
     return last_launch_status();
 }
 
+// Read-only streaming probe: every thread reads 16 bytes per step with a grid-wide stride and folds them
+// into one word, so that the loads cannot be dropped.  States what this device delivers for a plain
+// linear read, next to the nominal HBM peak.
+__global__ void __launch_bounds__(256) stream_read_kernel(const uint4 *__restrict__ src, size_t n16, uint32_t *sink)
+{
+    uint32_t acc = 0;
+    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride) {
+        const uint4 v = src[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc; // practically never: keeps the loop alive without a store per thread
+}
+
+prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st)
+{
+    int dev = 0, cus = 256;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0) cus = prop.multiProcessorCount;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4 *>(src), bytes / 16,
+                       static_cast<uint32_t *>(sink));
+    return last_launch_status();
+}
+
 } // namespace prima

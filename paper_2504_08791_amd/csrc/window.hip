@@ -188,6 +188,14 @@ prima_status prima_q4k_dequant(const void *W, int64_t n_rows, int64_t n_cols, fl
     return launch_dequant(static_cast<const uint8_t *>(W), n_rows, n_cols, out, static_cast<hipStream_t>(hip_stream));
 }
 
+prima_status prima_stream_read_probe(const void *src, size_t bytes, void *sink, void *hip_stream)
+{
+    if (!src || !sink) return PRIMA_E_NULL;
+    if (!aligned(src, 16) || !aligned(sink, 4)) return PRIMA_E_ALIGN;
+    if (bytes < 16) return PRIMA_OK;
+    return launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream));
+}
+
 size_t prima_gemv_workspace_bytes(int64_t n_rows, int64_t n_cols, int32_t T)
 {
     if (n_rows < 0 || n_cols < 0 || T < 1) return 0;
