@@ -36,7 +36,7 @@ def main():
                     help="run three plain 256 MiB device copies first (reference kernel of known traffic for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+        sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
 
     import numpy as np
     import torch
