@@ -6,6 +6,7 @@ RMSNorm / SwiGLU / residuals, RoPE + fp16 KV append, GQA attention) over one bat
 of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--no-cpu-baseline] [--copy-calibration]
+  python bench.py --batch B ...   a side measurement: B independent sequences, one token each per step
 """
 import argparse
 import json
@@ -32,6 +33,8 @@ def main():
     ap.add_argument("--config", default="c3")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="side measurement: B sequences of the config's context length, one token each per step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 256 MiB device copies first (reference kernel of known traffic for counter runs)")
     args = ap.parse_args()
@@ -47,6 +50,8 @@ def main():
     cfg = CONFIGS[args.config]
     if args.layers:
         cfg = cfg.with_(n_layers=args.layers)
+    if args.batch:
+        return bench_batch(args, cfg)
     d = cfg.dims
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -180,6 +185,65 @@ def main():
             "sample": f"the whole {cfg.n_layers}-layer window, {cfg.T} token(s), once ({cpu_seconds:.1f} s of CPU time; "
                       "tensor generation excluded)",
         }
+    print(json.dumps(out), flush=True)
+
+
+def bench_batch(args, cfg):
+    """B independent sequences (each with the config's context in its own caches) advance by one token per step."""
+    import numpy as np
+    import torch
+    import paper_2504_08791_amd as prima
+    from workloads import synth
+
+    d, B = cfg.dims, args.batch
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cap = cfg.n_past + 1
+    n_past = [cfg.n_past] * B
+    want_cpu = not args.no_cpu_baseline
+    host_layers, dev_layers = [], []
+    for l in range(cfg.n_layers):
+        t = synth.layer_tensors(cfg.with_(n_past=0), l, kv_cap=1)   # weights and gains; the window's own caches stay unused
+        dev_layers.append({k: torch.from_numpy(v).to(dev) for k, v in t.items()})
+        dev_layers[-1]["k_cache"] = torch.zeros((d.n_kv_heads, cap, d.head_dim), dtype=torch.float16, device=dev)
+        dev_layers[-1]["v_cache"] = dev_layers[-1]["k_cache"]
+        if want_cpu:
+            host_layers.append(t)
+    caches = synth.batch_caches(cfg, cfg.n_layers, n_past, cap)
+    dev_caches = [[(torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)) for k, v in per_layer] for per_layer in caches]
+    win = prima.Window(d, dev_layers, cap, T_max=B)
+    x_host = synth.batch_input(cfg, B)
+    x = torch.from_numpy(x_host).to(dev)
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        win.decode_batch(x, n_past, dev_caches, x_out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        win.decode_batch(x, n_past, dev_caches, x_out=y)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    out = {
+        "metric": "decode tokens/s per layer window, batch of independent sequences",
+        "value": round(B / (ms_per_step * 1e-3), 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} shape: {cfg.n_layers}-layer window, {B} sequences x 1 token, n_kv={cfg.n_past} each, "
+                               "Q4_K weights, fp16 KV", "tokens_per_step": B, "layers": cfg.n_layers, "kv_context": cfg.n_past},
+    }
+    if want_cpu:
+        import oracle
+        t0 = time.perf_counter()
+        ref = oracle.window_batch(d, host_layers, caches, x_host.astype(np.float64), n_past)
+        cpu_seconds = time.perf_counter() - t0
+        got = y.cpu().numpy().astype(np.float64)
+        rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+        out["max_rel_err_vs_oracle"] = float((np.abs(got - ref) / np.maximum(np.abs(ref), np.maximum(rms, 1e-30))).max())
+        out["cpu_baseline"] = {"value": round(B / cpu_seconds, 4), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"the whole step once ({cpu_seconds:.1f} s of CPU time)"}
     print(json.dumps(out), flush=True)
 
 

@@ -129,6 +129,24 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
                                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * One step of a batch of B independent sequences through the window: sequence b contributes one token
+ * (x_in[b], fp32 [B][e]) that continues its own cached context of n_past[b] rows (continuous batching of
+ * requests on a layer window, App. A.12).  The mat-vecs stream the weights once for up to 8 tokens, as for T
+ * tokens of one sequence; attention, RoPE (position n_past[b]) and the KV append run per sequence.
+ *   n_past    HOST array of B lengths, 0 <= n_past[b] < kv_cap; they may differ.
+ *   k_caches  HOST array of L*B DEVICE pointers: entry [l*B + b] is the fp16 K cache [n_kv_heads][kv_cap][head_dim]
+ *   v_caches  of layer l for sequence b (same layout as prima_layer.k_cache / v_cache, which this call ignores;
+ *             they may be null).  Row n_past[b] of every cache of sequence b is written.
+ *   B         1 <= B <= PRIMA_MAX_TOK; workspace as for prima_workspace_bytes(d, kv_cap, B).
+ * The pointer arrays and n_past are read before the call returns.  Errors as for prima_layer_window_decode.
+ */
+prima_status prima_layer_window_decode_batch(const prima_dims *d, const prima_layer *layers, int32_t L,
+                                             int32_t kv_cap, int32_t B, const int32_t *n_past,
+                                             void *const *k_caches, void *const *v_caches,
+                                             const float *x_in, float *x_out,
+                                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Optional single-launch path for one token (T = 1): the layers' kernels run back to back on one persistent
  * grid (one launch per 24 layers), separated by grid barriers; same arithmetic, same bits.  It is OFF by
  * default (measured slower than one launch per projection); prima_set_fused_window(1) switches it on for the

@@ -139,6 +139,31 @@ class Window:
                                                         self.workspace.numel(), _stream()), "prima_layer_window_decode")
         return x_out
 
+    def decode_batch(self, x_in, n_past, caches, x_out=None):
+        """One token for each of B = x_in.shape[0] independent sequences: n_past[b] cached rows of sequence b,
+        caches[l][b] = (k_cache, v_cache) of layer l for sequence b (float16 [Hkv, kv_cap, D]); the window's own
+        caches are not touched.  Returns x_out float32 [B, e]."""
+        _need(x_in, torch.float32, "x_in")
+        B, L = x_in.shape[0], len(self.layers)
+        if len(n_past) != B or len(caches) != L or any(len(c) != B for c in caches):
+            raise ValueError("n_past needs B entries and caches L x B pairs")
+        for per_layer in caches:
+            for k, v in per_layer:
+                _need(k, torch.float16, "k_cache")
+                _need(v, torch.float16, "v_cache")
+                if k.shape[1] != self.kv_cap or v.shape[1] != self.kv_cap:
+                    raise ValueError("kv_cap does not match the cache tensors")
+        if x_out is None:
+            x_out = torch.empty_like(x_in)
+        np_arr = (C.c_int32 * B)(*[int(n) for n in n_past])
+        k_arr = (C.c_void_p * (L * B))(*[caches[l][b][0].data_ptr() for l in range(L) for b in range(B)])
+        v_arr = (C.c_void_p * (L * B))(*[caches[l][b][1].data_ptr() for l in range(L) for b in range(B)])
+        _ffi.check(_ffi.lib().prima_layer_window_decode_batch(C.byref(self.dims), self._arr, L, self.kv_cap, B, np_arr,
+                                                              k_arr, v_arr, _ptr(x_in), _ptr(x_out), _ptr(self.workspace),
+                                                              self.workspace.numel(), _stream()),
+                   "prima_layer_window_decode_batch")
+        return x_out
+
     def check(self, T=1):
         """Waits for the stream; raises if a grid barrier of the last single-launch step gave up."""
         _ffi.check(_ffi.lib().prima_window_check(C.byref(self.dims), self.kv_cap, T, _ptr(self.workspace),

@@ -13,7 +13,7 @@ STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIG
 EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", "prima_attn_decode",
            "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_window_decode_profiled", "prima_layer_decode_taps",
            "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
-           "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe"]
+           "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch"]
 
 
 class Dims(C.Structure):
@@ -54,6 +54,9 @@ def lib():
         L.prima_layer_window_decode.argtypes = [dp, lp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
         L.prima_layer_window_decode_profiled.argtypes = [dp, lp, i32, i32, i32, i32, vp, vp, vp, sz, vp,
                                                          C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.prima_layer_window_decode_batch.argtypes = [dp, lp, i32, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_void_p),
+                                                      C.POINTER(C.c_void_p), vp, vp, vp, sz, vp]
+        L.prima_layer_window_decode_batch.restype = C.c_int
         L.prima_layer_decode_taps.argtypes = [dp, lp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.prima_lm_head.argtypes = [dp, vp, vp, i64, vp, i32, vp, vp, sz, vp]
         L.prima_lm_head_workspace_bytes.argtypes = [dp, i64, i32]

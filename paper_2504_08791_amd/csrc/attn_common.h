@@ -25,6 +25,12 @@ struct AttnArgs {
     unsigned *arrivals;   // [Hkv * query groups], zero between launches
     float *o;             // [T][Hq][D]
     int Hq, Hkv, kv_cap, n_past, T, nsplit, keys_per_split;
+    // Batch of sequences (continuous batching, App. A.12: one token each): token b is the next token of a
+    // sequence of its own, with its own caches and length.  Query group z of the grid then belongs to sequence
+    // z / ceil(G / QG), and a workgroup works like a one-token call for that sequence.
+    int batch;                       // 0: the T tokens continue one sequence (K, V, n_past above)
+    int seq_n_past[PRIMA_MAX_TOK];   // batch: cached rows of sequence b
+    __half *seq_K[PRIMA_MAX_TOK], *seq_V[PRIMA_MAX_TOK]; // batch: its caches [Hkv][kv_cap][D]
 };
 
 // value of lane (i + n) % 16 of the same 16-lane row
@@ -131,13 +137,36 @@ inline int query_groups(const prima_dims &d, int T)
     const int G = d.n_q_heads / d.n_kv_heads;
     return (G * T + QG - 1) / QG;
 }
+// a batch of T sequences: the groups of one sequence's queries on a KV head, times T
+inline int query_groups_batch(const prima_dims &d, int T)
+{
+    const int G = d.n_q_heads / d.n_kv_heads;
+    return (G + QG - 1) / QG * T;
+}
 
+
+// seq (batch): per token its sequence's caches and length (then K, V and n_past are not used)
+struct AttnSeqs {
+    const int *n_past;
+    __half *const *K, *const *V;
+};
 
 inline AttnArgs build_attn_args(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
-                                const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o, void *ws)
+                                const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o, void *ws,
+                                const AttnSeqs *seq = nullptr)
 {
-    const int n_total = n_past + T;
+    int n_total = n_past + T;
     AttnArgs a{};
+    if (seq) {
+        a.batch = 1;
+        n_total = 0; // the longest sequence sets the key ranges
+        for (int b = 0; b < T; ++b) {
+            a.seq_n_past[b] = seq->n_past[b];
+            a.seq_K[b] = seq->K[b];
+            a.seq_V[b] = seq->V[b];
+            n_total = seq->n_past[b] + 1 > n_total ? seq->n_past[b] + 1 : n_total;
+        }
+    }
     a.q = q; a.q_rot_out = q_rot_out; a.k_new = k_new; a.v_new = v_new;
     a.rope_tab = reinterpret_cast<const float2 *>(rope_tab);
     a.K = K; a.V = V;
@@ -146,7 +175,7 @@ inline AttnArgs build_attn_args(const prima_dims &d, const float *q, float *q_ro
     a.o = o;
     a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.kv_cap = kv_cap; a.n_past = n_past; a.T = T;
     // key ranges are multiples of 16 so that tiles never straddle two workgroups, and none is empty
-    const int want = attn_num_splits(d, n_total, T);
+    const int want = attn_num_splits(d, n_total, T, seq != nullptr);
     a.keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
     a.nsplit = (n_total + a.keys_per_split - 1) / a.keys_per_split;
     return a;

@@ -35,15 +35,31 @@ __global__ void __launch_bounds__(ATT_THREADS) attn_decode_kernel(AttnArgs a)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr bool COH = false;
-    const int split = blockIdx.x, kvh = blockIdx.y, qgrp = blockIdx.z, nqg = gridDim.z;
+    const int split = blockIdx.x, kvh = blockIdx.y;
     AttnNoSync sync;
-    __half *const arg_K = a.K, *const arg_V = a.V;
+    // the view of this workgroup: all T tokens of one sequence, or (batch) the one token of sequence tok0
+    const bool batch = a.batch != 0;
+    const int gps = (a.Hq / a.Hkv + QG - 1) / QG; // query groups of one token
+    const int tok0 = batch ? blockIdx.z / gps : 0;
+    const int qgrp = batch ? blockIdx.z - tok0 * gps : blockIdx.z, nqg = batch ? gps : gridDim.z;
+    const int arg_T = batch ? 1 : a.T;
+    __half *arg_K = a.K, *arg_V = a.V;
+    int arg_n_past = a.n_past;
+    if (batch) {
+        // read by hand from the argument segment: indexing the by-value argument with a run-time index would
+        // make the compiler copy all of it to scratch memory
+        typedef const __attribute__((address_space(4))) AttnArgs ConstAttnArgs;
+        ConstAttnArgs &ka = *(ConstAttnArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+        arg_K = ka.seq_K[tok0];
+        arg_V = ka.seq_V[tok0];
+        arg_n_past = ka.seq_n_past[tok0];
+    }
 #include "attn_body.inc"
 }
 
-int attn_num_splits(const prima_dims &d, int n_total, int T)
+int attn_num_splits(const prima_dims &d, int n_total, int T, bool batch)
 {
-    const int wgs = d.n_kv_heads * query_groups(d, T);
+    const int wgs = d.n_kv_heads * (batch ? query_groups_batch(d, T) : query_groups(d, T));
     const int by_len = (n_total + 16 * ATT_WAVES - 1) / (16 * ATT_WAVES); // at least one 16-key tile per wave
     const int by_grid = (256 + wgs - 1) / wgs;                            // about one workgroup per compute unit
     int ns = by_len < by_grid ? by_len : by_grid;
@@ -54,7 +70,7 @@ int attn_num_splits(const prima_dims &d, int n_total, int T)
 
 size_t attn_counter_bytes(const prima_dims &d, int T)
 {
-    return round_up(static_cast<size_t>(d.n_kv_heads) * query_groups(d, T) * sizeof(unsigned), 256);
+    return round_up(static_cast<size_t>(d.n_kv_heads) * query_groups_batch(d, T) * sizeof(unsigned), 256); // >= query_groups(d, T)
 }
 
 size_t attn_ws_bytes(const prima_dims &d, int, int T)
@@ -64,10 +80,10 @@ size_t attn_ws_bytes(const prima_dims &d, int, int T)
 
 prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
                          const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
-                         void *ws, hipStream_t st)
+                         void *ws, hipStream_t st, const AttnSeqs *seq)
 {
-    const AttnArgs a = build_attn_args(d, q, q_rot_out, k_new, v_new, rope_tab, K, V, kv_cap, n_past, T, o, ws);
-    const dim3 grid(a.nsplit, d.n_kv_heads, query_groups(d, T)), block(ATT_THREADS);
+    const AttnArgs a = build_attn_args(d, q, q_rot_out, k_new, v_new, rope_tab, K, V, kv_cap, n_past, T, o, ws, seq);
+    const dim3 grid(a.nsplit, d.n_kv_heads, seq ? query_groups_batch(d, T) : query_groups(d, T)), block(ATT_THREADS);
     if (d.head_dim == 128 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<128, 0>), grid, block, sizeof(AttnLds<128>), st, a);
     else if (d.head_dim == 128 && d.rope_mode == 1) hipLaunchKernelGGL((attn_decode_kernel<128, 1>), grid, block, sizeof(AttnLds<128>), st, a);
     else if (d.head_dim == 64 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<64, 0>), grid, block, sizeof(AttnLds<64>), st, a);

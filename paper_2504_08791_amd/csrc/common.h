@@ -87,17 +87,21 @@ size_t gemv_arrivals_bytes(int64_t n_rows_total);
 prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
 
 prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
-prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
-int attn_num_splits(const prima_dims &d, int n_total, int T);
+// positions: null (token t sits at n_past + t) or T positions, one per token (a batch of sequences)
+prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st, const int *positions = nullptr);
+int attn_num_splits(const prima_dims &d, int n_total, int T, bool batch = false);
 size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);
 // the first attn_counter_bytes() of the attention scratch are arrival counters: zero before the first
 // launch (launch_zero_arrivals), left zero by every launch
 size_t attn_counter_bytes(const prima_dims &d, int T);
 // q: [T][Hq][D].  With rope_tab set, q and k_new are un-rotated and the kernel rotates them and
 // appends k_new / v_new to the caches; otherwise q is used as is and the caches are complete.
+// seq: null, or (a batch of T sequences, one token each) per token its sequence's caches and length; K, V and
+// n_past are then not used.
+struct AttnSeqs;
 prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
                          const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
-                         void *ws, hipStream_t st);
+                         void *ws, hipStream_t st, const AttnSeqs *seq = nullptr);
 
 // one token through a whole window in one launch per FUSED_MAX_LAYERS layers (fused_window.hip); PRIMA_E_SHAPE
 // with nothing launched when the shapes do not qualify

@@ -6,20 +6,28 @@ namespace prima {
 
 // tab[t][i] = (cos, sin) of (n_past + t) * theta^(-2i/D), evaluated in fp64: at positions of
 // several thousand an fp32 angle would already be off by ~1e-4 rad.
-__global__ void rope_table_kernel(float2 *tab, int T, int half, int n_past, double theta)
+struct RopePositions {
+    int pos[PRIMA_MAX_TOK];
+};
+__global__ void rope_table_kernel(float2 *tab, int T, int half, RopePositions p, double theta)
 {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= T * half) return;
     const int t = idx / half, i = idx - t * half;
-    const double ang = static_cast<double>(n_past + t) * pow(theta, -static_cast<double>(i) / static_cast<double>(half));
+    int pos = 0;
+#pragma unroll
+    for (int k = 0; k < PRIMA_MAX_TOK; ++k) pos = (k == t) ? p.pos[k] : pos; // no run-time index into the arguments
+    const double ang = static_cast<double>(pos) * pow(theta, -static_cast<double>(i) / static_cast<double>(half));
     tab[idx] = make_float2(static_cast<float>(cos(ang)), static_cast<float>(sin(ang)));
 }
 
-prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st)
+prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st, const int *positions)
 {
     const int n = T * (D / 2);
+    RopePositions p{};
+    for (int t = 0; t < T && t < PRIMA_MAX_TOK; ++t) p.pos[t] = positions ? positions[t] : n_past + t;
     hipLaunchKernelGGL(rope_table_kernel, dim3((n + 127) / 128), dim3(128), 0, st,
-                       reinterpret_cast<float2 *>(tab), T, D / 2, n_past, static_cast<double>(theta));
+                       reinterpret_cast<float2 *>(tab), T, D / 2, p, static_cast<double>(theta));
     return last_launch_status();
 }
 

@@ -120,6 +120,8 @@ __global__ void __launch_bounds__(GEMV_THREADS) window_fused_kernel(FusedArgs fa
                     const int kvh = (wg_index / a.nsplit) % a.Hkv;
                     const int qgrp = wg_index / (a.nsplit * a.Hkv);
                     const int nqg = fa.nqg;
+                    constexpr int tok0 = 0; // one sequence
+                    const int arg_T = a.T, arg_n_past = a.n_past;
 #include "attn_body.inc"
                 }
             } else {

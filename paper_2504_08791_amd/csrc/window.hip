@@ -3,7 +3,7 @@
 // of consecutive layers and hands e FP32 values per token to its successor).
 #include <algorithm>
 
-#include "common.h"
+#include "attn_common.h"
 
 using namespace prima;
 
@@ -57,9 +57,10 @@ GemvSeg seg(const void *W, float *y, int64_t rows, int64_t ldy, const float *res
     return GemvSeg{static_cast<const uint8_t *>(W), y, resid, rows, ldy, ldr};
 }
 
-prima_status check_layer(const prima_layer &l)
+prima_status check_layer(const prima_layer &l, bool with_caches = true)
 {
-    const void *ptrs[] = {l.wq, l.wk, l.wv, l.wo, l.wgate, l.wup, l.wdown, l.g_attn, l.g_ffn, l.k_cache, l.v_cache};
+    const void *ptrs[] = {l.wq, l.wk, l.wv, l.wo, l.wgate, l.wup, l.wdown, l.g_attn, l.g_ffn,
+                          with_caches ? l.k_cache : l.wq, with_caches ? l.v_cache : l.wq};
     for (const void *p : ptrs) {
         if (!p) return PRIMA_E_NULL;
         if (!aligned(p, 16)) return PRIMA_E_ALIGN;
@@ -106,7 +107,7 @@ bool g_fused_enabled = false;
 // (+ residual), gate/up projections (RMSNorm fused in front, SwiGLU behind), down projection (+ residual).
 prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
                        const float *x, float *y, void *ws, const WindowWs &w, hipStream_t st,
-                       float *tap_q, float *tap_o, float *tap_h, float *tap_a, int only = -1)
+                       float *tap_q, float *tap_o, float *tap_h, float *tap_a, int only = -1, const AttnSeqs *seq = nullptr)
 {
     const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
     float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
@@ -123,7 +124,7 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
     }
     if (PRIMA_WANT(PRIMA_K_ATTN))
         PRIMA_TRY(launch_attn(d, q, tap_q, k, v, at<float>(ws, w.rope), static_cast<__half *>(L.k_cache),
-                              static_cast<__half *>(L.v_cache), kv_cap, n_past, T, o, at<char>(ws, w.attn), st));
+                              static_cast<__half *>(L.v_cache), kv_cap, n_past, T, o, at<char>(ws, w.attn), st, seq));
     if (tap_o && hipMemcpyAsync(tap_o, o, T * qd * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     if (PRIMA_WANT(PRIMA_K_WO)) {
         GemvArgs ga = gemv_args(1, qd, o, qd, T);
@@ -280,6 +281,48 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
     for (int i = 0; i < L; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
         s = run_layer(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr);
+        if (s != PRIMA_OK) return s;
+        cur = dst;
+    }
+    return PRIMA_OK;
+}
+
+prima_status prima_layer_window_decode_batch(const prima_dims *d, const prima_layer *layers, int32_t L,
+                                             int32_t kv_cap, int32_t B, const int32_t *n_past,
+                                             void *const *k_caches, void *const *v_caches,
+                                             const float *x_in, float *x_out,
+                                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!layers || !n_past || !k_caches || !v_caches) return PRIMA_E_NULL;
+    prima_status s = check_window_args(d, kv_cap, 0, B, x_in, x_out, workspace, workspace_bytes);
+    if (s != PRIMA_OK) return s;
+    if (L < 1) return PRIMA_E_RANGE;
+    for (int b = 0; b < B; ++b)
+        if (n_past[b] < 0 || static_cast<int64_t>(n_past[b]) + 1 > kv_cap) return PRIMA_E_RANGE;
+    for (int i = 0; i < L; ++i) {
+        if ((s = check_layer(layers[i], false)) != PRIMA_OK) return s;
+        for (int b = 0; b < B; ++b) {
+            const void *kc = k_caches[static_cast<size_t>(i) * B + b], *vc = v_caches[static_cast<size_t>(i) * B + b];
+            if (!kc || !vc) return PRIMA_E_NULL;
+            if (!aligned(kc, 16) || !aligned(vc, 16)) return PRIMA_E_ALIGN;
+        }
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const WindowWs w = carve(*d, kv_cap, B);
+    s = launch_rope_table(at<float>(workspace, w.rope), B, d->head_dim, 0, d->rope_theta, st, n_past);
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
+    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, B), st);
+    if (s != PRIMA_OK) return s;
+    const float *cur = x_in;
+    for (int i = 0; i < L; ++i) {
+        float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
+        __half *kc[PRIMA_MAX_TOK], *vc[PRIMA_MAX_TOK];
+        for (int b = 0; b < B; ++b) {
+            kc[b] = static_cast<__half *>(k_caches[static_cast<size_t>(i) * B + b]);
+            vc[b] = static_cast<__half *>(v_caches[static_cast<size_t>(i) * B + b]);
+        }
+        const AttnSeqs seq{n_past, kc, vc};
+        s = run_layer(*d, layers[i], kv_cap, 0, B, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr, -1, &seq);
         if (s != PRIMA_OK) return s;
         cur = dst;
     }

@@ -115,3 +115,31 @@ def test_single_launch_window_matches(gpu_lib):
         assert torch.equal(l["k_cache"][:, cfg.n_past], k0)
         assert torch.equal(l["v_cache"][:, cfg.n_past], v0)
     assert rel_err(y1.cpu().numpy(), h) < HID_TOL
+
+
+def test_batch_of_sequences_full_shape(gpu_lib):
+    """Config 3's layer shape, 2 layers, 8 sequences of different lengths (one token each) in one step."""
+    cfg = CONFIGS["c3"].with_(n_layers=2)
+    cap = 4096
+    n_past = [4095, 1000, 0, 17, 2048, 4000, 333, 4094]
+    B = len(n_past)
+    host = [synth.layer_tensors(cfg.with_(n_past=0), l, kv_cap=16) for l in range(cfg.n_layers)]   # the layers' own caches are not used
+    dev_layers = [{k: _dev(v) for k, v in t.items()} for t in host]
+    for t in dev_layers:   # the window wants caches of the right capacity, although this call ignores them
+        t["k_cache"] = torch.zeros((cfg.dims.n_kv_heads, cap, cfg.dims.head_dim), dtype=torch.float16, device="cuda")
+        t["v_cache"] = torch.zeros_like(t["k_cache"])
+    win = gpu_lib.Window(cfg.dims, dev_layers, cap, T_max=B)
+    win.workspace.fill_(0xFF)
+    x = synth.batch_input(cfg, B)
+    caches = synth.batch_caches(cfg, cfg.n_layers, n_past, cap)
+    dev_caches = [[(_dev(k), _dev(v)) for k, v in per_layer] for per_layer in caches]
+    ref = oracle.window_batch(cfg.dims, host, caches, x.astype(np.float64), n_past)
+    y = win.decode_batch(_dev(x), n_past, dev_caches)
+    err = rel_err(y.cpu().numpy(), ref)
+    print("batch of 8 sequences, hidden-state max rel err", err)
+    assert err < HID_TOL
+    for l in range(cfg.n_layers):
+        for b in range(B):
+            for got_d, want in zip(dev_caches[l][b], caches[l][b]):
+                got = got_d[:, n_past[b]].cpu().numpy().astype(np.float64).reshape(1, -1)
+                assert rel_err(got, want[:, n_past[b]].astype(np.float64).reshape(1, -1)) < 1e-3

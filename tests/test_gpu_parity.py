@@ -203,6 +203,52 @@ def test_window_vs_oracle(gpu_lib, name):
     assert torch.equal(y2, y)
 
 
+@pytest.mark.parametrize("name", ["t0", "t1", "t2"])
+def test_batch_of_sequences_vs_oracle(gpu_lib, name):
+    """One token for each of B sequences with their own caches and lengths (an empty one, a full one, equal
+    ones): hidden states against the oracle's independent one-token steps, the appended rows, nothing else
+    written, and the same bits on a second run."""
+    cfg = TINY[name]
+    cap = cfg.n_past + 6
+    n_past = [0, cfg.n_past, cap - 1, 17, 17, 1, cfg.n_past + 3]
+    B = len(n_past)
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    win, _ = _window(gpu_lib, cfg, cap, host)
+    x = synth.batch_input(cfg, B)
+    caches = synth.batch_caches(cfg, cfg.n_layers, n_past, cap)
+    before = copy.deepcopy(caches)
+    dev_caches = [[(_dev(k), _dev(v)) for k, v in per_layer] for per_layer in caches]
+    ref = oracle.window_batch(cfg.dims, host, caches, x.astype(np.float64), n_past)
+    y = win.decode_batch(_dev(x), n_past, dev_caches)
+    assert rel_err(y.cpu().numpy(), ref) < HID_TOL
+    for l in range(cfg.n_layers):
+        for b in range(B):
+            for got_d, want, old in zip(dev_caches[l][b], caches[l][b], before[l][b]):
+                got = got_d.cpu().numpy()
+                row = n_past[b]
+                assert rel_err(got[:, row].astype(np.float64).reshape(1, -1), want[:, row].astype(np.float64).reshape(1, -1)) < 1e-3
+                keep = np.ones(cap, dtype=bool)
+                keep[row] = False
+                assert np.array_equal(got[:, keep].view(np.uint16), old[:, keep].view(np.uint16))
+    dev_again = [[(_dev(k), _dev(v)) for k, v in per_layer] for per_layer in before]
+    y2 = win.decode_batch(_dev(x), n_past, dev_again)
+    assert torch.equal(y, y2)
+
+
+def test_batch_of_one_equals_single_sequence_step(gpu_lib):
+    cfg = TINY["t1"]
+    cap = cfg.n_past + 2
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    win, dev_layers = _window(gpu_lib, cfg, cap, host)
+    x = _dev(synth.batch_input(cfg, 1))
+    caches = [[(t["k_cache"].clone(), t["v_cache"].clone())] for t in dev_layers]
+    yb = win.decode_batch(x, [cfg.n_past], caches)
+    ys = win.decode(x, cfg.n_past)
+    assert torch.equal(yb, ys)
+    for t, per_layer in zip(dev_layers, caches):
+        assert torch.equal(t["k_cache"], per_layer[0][0]) and torch.equal(t["v_cache"], per_layer[0][1])
+
+
 def test_joint_equals_sequential_on_gpu(gpu_lib):
     cfg = TINY["t1"]
     cap = cfg.n_past + cfg.T

@@ -98,6 +98,38 @@ def test_joint_equals_sequential():
         assert np.array_equal(a["v_cache"].view(np.uint16), b["v_cache"].view(np.uint16))
 
 
+def test_batch_of_sequences_is_independent_one_token_steps():
+    """A batch step (one token for each of B sequences with their own caches and lengths) is, per sequence, the
+    one-token window step of that sequence alone: same bits, same appended rows, whatever the other sequences
+    are and in whatever order they stand; nothing else in a cache changes."""
+    cfg = TINY["t1"]
+    cap = 40
+    n_past = [0, 7, 39, 21]
+    B = len(n_past)
+    layers = _layers(cfg)
+    x = synth.batch_input(cfg, B).astype(np.float64)
+    caches = synth.batch_caches(cfg, len(layers), n_past, cap)
+    before = copy.deepcopy(caches)
+    y = oracle.window_batch(cfg.dims, layers, caches, x, n_past)
+    perm = [2, 0, 3, 1]
+    caches_p = [[copy.deepcopy(before[l][b]) for b in perm] for l in range(len(layers))]
+    y_p = oracle.window_batch(cfg.dims, layers, caches_p, x[perm], [n_past[b] for b in perm])
+    assert np.array_equal(y_p, y[perm])
+    for b in range(B):
+        alone = [dict(t) for t in layers]
+        for l, t in enumerate(alone):
+            t["k_cache"], t["v_cache"] = copy.deepcopy(before[l][b])
+        y_b = oracle.window(cfg.dims, alone, x[b:b + 1], n_past[b])
+        assert np.array_equal(y_b[0], y[b])
+        for l, t in enumerate(alone):
+            for got, ref, old in zip(caches[l][b], (t["k_cache"], t["v_cache"]), before[l][b]):
+                assert np.array_equal(got.view(np.uint16), ref.view(np.uint16))
+                keep = np.ones(cap, dtype=bool)
+                keep[n_past[b]] = False
+                assert np.array_equal(got[:, keep].view(np.uint16), old[:, keep].view(np.uint16))
+                assert np.any(got[:, n_past[b]] != 0)
+
+
 def test_window_is_composition_of_layers():
     cfg = TINY["t0"]
     x = synth.window_input(cfg).astype(np.float64)

@@ -21,8 +21,9 @@ BLOCK_BYTES = 144
 TENSOR_IDS = {
     "wq": 0, "wk": 1, "wv": 2, "wo": 3, "wgate": 4, "wup": 5, "wdown": 6,
     "g_attn": 7, "g_ffn": 8, "k_cache": 9, "v_cache": 10, "x_in": 11,
-    "g_final": 12, "w_lm": 13, "q": 14,
+    "g_final": 12, "w_lm": 13, "q": 14, "x_in_batch": 15,
 }
+SEQ_CACHE_ID0 = 100  # K, V caches of sequence b of a batch: ids 100 + 2b, 101 + 2b
 
 
 def _rng(config_id, layer, tensor):
@@ -82,6 +83,20 @@ def layer_tensors(cfg, layer, kv_cap=None):
         "k_cache": kv_cache_f16(cid, layer, "k_cache", d.n_kv_heads, cap, d.head_dim, cfg.n_past),
         "v_cache": kv_cache_f16(cid, layer, "v_cache", d.n_kv_heads, cap, d.head_dim, cfg.n_past),
     }
+
+
+def batch_caches(cfg, n_layers, n_past, kv_cap):
+    """KV caches of a batch of independent sequences: [layer][sequence] -> (k_cache, v_cache), sequence b
+    holding n_past[b] rows ~ N(0,1) (fp16 [n_kv_heads, kv_cap, head_dim], the rest zero)."""
+    d = cfg.dims
+    return [[(kv_cache_f16(cfg.config_id, l, SEQ_CACHE_ID0 + 2 * b, d.n_kv_heads, kv_cap, d.head_dim, n),
+              kv_cache_f16(cfg.config_id, l, SEQ_CACHE_ID0 + 2 * b + 1, d.n_kv_heads, kv_cap, d.head_dim, n))
+             for b, n in enumerate(n_past)] for l in range(n_layers)]
+
+
+def batch_input(cfg, B):
+    """x_in fp32 [B, e] ~ N(0,1): one token per sequence."""
+    return normal_f32(cfg.config_id, 0, "x_in_batch", (B, cfg.dims.e))
 
 
 def window_input(cfg):
