@@ -96,6 +96,38 @@ def test_window_argument_errors():
     assert L.prima_workspace_bytes(C.byref(_dims(e=100)), 64, 1) == 0
 
 
+def test_batch_window_argument_errors():
+    L = _ffi.lib()
+    d = _dims()
+    lay = (_ffi.Layer * 2)()
+    for i in range(2):
+        for name, _ in _ffi.Layer._fields_:
+            setattr(lay[i], name, None if name in ("k_cache", "v_cache") else FAKE)   # the layers' own caches may be null
+    B = 3
+    need = L.prima_workspace_bytes(C.byref(d), 64, B)
+    np_ok = (C.c_int32 * B)(0, 10, 63)
+    ptrs = (C.c_void_p * (2 * B))(*([FAKE] * (2 * B)))
+    f = lambda dd=d, layers=lay, Ln=2, cap=64, Bn=B, npast=np_ok, kc=ptrs, vc=ptrs, xi=FAKE, xo=FAKE, ws=FAKE, wsb=need: \
+        L.prima_layer_window_decode_batch(C.byref(dd), layers, Ln, cap, Bn, npast, kc, vc, xi, xo, ws, wsb, None)
+    assert f(npast=None) == 1 and f(kc=None) == 1 and f(vc=None) == 1 and f(xi=None) == 1 and f(layers=None) == 1
+    assert f(dd=_dims(head_dim=96)) == 2
+    assert f(Bn=0) == 4 and f(Bn=17) == 4 and f(Ln=0) == 4
+    assert f(npast=(C.c_int32 * B)(0, 64, 1)) == 4 and f(npast=(C.c_int32 * B)(0, -1, 1)) == 4
+    hole = (C.c_void_p * (2 * B))(*([FAKE] * (2 * B)))
+    hole[4] = None
+    assert f(kc=hole) == 1
+    odd = (C.c_void_p * (2 * B))(*([FAKE] * (2 * B)))
+    odd[1] = FAKE + 2
+    assert f(vc=odd) == 3
+    assert f(wsb=need - 1) == 5
+    bad = (_ffi.Layer * 2)()
+    for i in range(2):
+        for name, _ in _ffi.Layer._fields_:
+            setattr(bad[i], name, FAKE)
+    bad[1].wdown = None
+    assert f(layers=bad) == 1
+
+
 def test_missing_library_is_an_error(monkeypatch, tmp_path):
     monkeypatch.setattr(_ffi, "_lib", None)
     monkeypatch.setattr(_ffi, "LIB_PATH", str(tmp_path / "absent.so"))

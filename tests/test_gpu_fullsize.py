@@ -143,3 +143,19 @@ def test_batch_of_sequences_full_shape(gpu_lib):
             for got_d, want in zip(dev_caches[l][b], caches[l][b]):
                 got = got_d[:, n_past[b]].cpu().numpy().astype(np.float64).reshape(1, -1)
                 assert rel_err(got, want[:, n_past[b]].astype(np.float64).reshape(1, -1)) < 1e-3
+
+
+def test_attention_long_context(gpu_lib):
+    """32768 cached rows (the most key ranges the kernel uses, several tiles per wave and range), config 3's
+    heads, one token and three tokens, against the oracle."""
+    from workloads.configs import ModelDims
+    rng = np.random.default_rng(77)
+    one_kv_head = ModelDims(8 * 128, 8, 1, 128, 256, 1e4)     # one KV head: the cap on the number of key ranges binds
+    for d, n_past, T in ((CONFIGS["c3"].dims, 32767, 1), (CONFIGS["c3"].dims, 32700, 3), (one_kv_head, 20000, 1)):
+        cap = n_past + T
+        K = (0.5 * rng.standard_normal((d.n_kv_heads, cap, d.head_dim), dtype=np.float32)).astype(np.float16)
+        V = rng.standard_normal((d.n_kv_heads, cap, d.head_dim), dtype=np.float32).astype(np.float16)
+        q = rng.standard_normal((T, d.n_q_heads, d.head_dim), dtype=np.float32)
+        ref = oracle.attn_decode(d, q.astype(np.float64), K, V, n_past, T)
+        got = gpu_lib.attn_decode(d, _dev(q), _dev(K), _dev(V), n_past).cpu().numpy()
+        assert rel_err(got.reshape(T, -1), ref.reshape(T, -1)) < ATT_TOL
