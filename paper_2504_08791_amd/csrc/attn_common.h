@@ -56,9 +56,11 @@ __device__ __forceinline__ float row_sum16(float v)
 
 // Rotate the D/8-element slices a lane holds of one head vector: v[x][e] = element 32x + 8c + e.
 // mode 0 pairs element i with i + D/2 (the partner is v[x + NA/2][e] of the same lane), mode 1 pairs
-// 2i with 2i + 1.  tab = this token's D/2 (cos, sin) pairs.
+// 2i with 2i + 1.  tab = this token's D/2 (cos, sin) pairs.  In two steps, so that the table entries can be
+// requested ahead of other loads and used after them: rope_load fetches the lane's D/16 float4 (two (cos, sin)
+// pairs each), rope_apply rotates.
 template <int D, int MODE>
-__device__ __forceinline__ void rope_in_lane(float (&v)[D / 32][8], const float2 *tab, int c)
+__device__ __forceinline__ void rope_load(const float2 *tab, int c, float4 (&rt)[D / 16])
 {
     constexpr int NA = D / 32;
     if (MODE == 0) {
@@ -66,8 +68,27 @@ __device__ __forceinline__ void rope_in_lane(float (&v)[D / 32][8], const float2
         for (int x = 0; x < NA / 2; ++x) {
             const float4 *tp = reinterpret_cast<const float4 *>(tab + 32 * x + 8 * c);
 #pragma unroll
+            for (int h = 0; h < 4; ++h) rt[4 * x + h] = tp[h]; // (cos, sin) of pairs 2h, 2h + 1 of this slice
+        }
+    } else {
+#pragma unroll
+        for (int x = 0; x < NA; ++x) {
+            const float4 *tp = reinterpret_cast<const float4 *>(tab + 16 * x + 4 * c);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) rt[2 * x + h] = tp[h];
+        }
+    }
+}
+template <int D, int MODE>
+__device__ __forceinline__ void rope_apply(float (&v)[D / 32][8], const float4 (&rt)[D / 16])
+{
+    constexpr int NA = D / 32;
+    if (MODE == 0) {
+#pragma unroll
+        for (int x = 0; x < NA / 2; ++x) {
+#pragma unroll
             for (int h = 0; h < 4; ++h) {
-                const float4 cs = tp[h]; // (cos, sin) of pairs 2h, 2h + 1 of this slice
+                const float4 cs = rt[4 * x + h];
                 const float a0 = v[x][2 * h], b0 = v[x + NA / 2][2 * h], a1 = v[x][2 * h + 1], b1 = v[x + NA / 2][2 * h + 1];
                 v[x][2 * h] = a0 * cs.x - b0 * cs.y;
                 v[x + NA / 2][2 * h] = a0 * cs.y + b0 * cs.x;
@@ -78,10 +99,9 @@ __device__ __forceinline__ void rope_in_lane(float (&v)[D / 32][8], const float2
     } else {
 #pragma unroll
         for (int x = 0; x < NA; ++x) {
-            const float4 *tp = reinterpret_cast<const float4 *>(tab + 16 * x + 4 * c);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const float4 cs = tp[h];
+                const float4 cs = rt[2 * x + h];
                 const float a0 = v[x][4 * h], b0 = v[x][4 * h + 1], a1 = v[x][4 * h + 2], b1 = v[x][4 * h + 3];
                 v[x][4 * h] = a0 * cs.x - b0 * cs.y;
                 v[x][4 * h + 1] = a0 * cs.y + b0 * cs.x;
