@@ -87,8 +87,10 @@ size_t gemv_arrivals_bytes(int64_t n_rows_total);
 prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
 
 prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
+// the RoPE table [T][D/2] of (cos, sin) and up to three zeroed regions (null: none) in one launch.
 // positions: null (token t sits at n_past + t) or T positions, one per token (a batch of sequences)
-prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st, const int *positions = nullptr);
+prima_status launch_step_init(float *tab, int T, int D, int n_past, float theta, const int *positions,
+                              void *const zero_ptr[3], const size_t zero_bytes[3], hipStream_t st);
 int attn_num_splits(const prima_dims &d, int n_total, int T, bool batch = false);
 size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);
 // the first attn_counter_bytes() of the attention scratch are arrival counters: zero before the first

@@ -4,15 +4,25 @@
 
 namespace prima {
 
-// tab[t][i] = (cos, sin) of (n_past + t) * theta^(-2i/D), evaluated in fp64: at positions of
-// several thousand an fp32 angle would already be off by ~1e-4 rad.
 struct RopePositions {
     int pos[PRIMA_MAX_TOK];
 };
-__global__ void rope_table_kernel(float2 *tab, int T, int half, RopePositions p, double theta)
+
+// Everything a window step needs before its first layer, in one launch: zeroed counter regions and the RoPE
+// table, tab[t][i] = (cos, sin) of pos_t * theta^(-2i/D) with pos_t = n_past + t (or the token's own position in
+// a batch of sequences), evaluated in fp64: at positions of several thousand an fp32 angle would already be off
+// by ~1e-4 rad.
+struct ZeroRegions {
+    unsigned *p[3];
+    unsigned n[3]; // 32-bit words
+};
+__global__ void step_init_kernel(float2 *tab, int T, int half, RopePositions p, double theta, ZeroRegions z)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= T * half) return;
+    const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < z.n[0]) z.p[0][idx] = 0u;
+    if (idx < z.n[1]) z.p[1][idx] = 0u;
+    if (idx < z.n[2]) z.p[2][idx] = 0u;
+    if (idx >= static_cast<unsigned>(T * half)) return;
     const int t = idx / half, i = idx - t * half;
     int pos = 0;
 #pragma unroll
@@ -21,13 +31,20 @@ __global__ void rope_table_kernel(float2 *tab, int T, int half, RopePositions p,
     tab[idx] = make_float2(static_cast<float>(cos(ang)), static_cast<float>(sin(ang)));
 }
 
-prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st, const int *positions)
+prima_status launch_step_init(float *tab, int T, int D, int n_past, float theta, const int *positions,
+                              void *const zero_ptr[3], const size_t zero_bytes[3], hipStream_t st)
 {
-    const int n = T * (D / 2);
     RopePositions p{};
     for (int t = 0; t < T && t < PRIMA_MAX_TOK; ++t) p.pos[t] = positions ? positions[t] : n_past + t;
-    hipLaunchKernelGGL(rope_table_kernel, dim3((n + 127) / 128), dim3(128), 0, st,
-                       reinterpret_cast<float2 *>(tab), T, D / 2, p, static_cast<double>(theta));
+    ZeroRegions z{};
+    unsigned n = static_cast<unsigned>(T * (D / 2));
+    for (int k = 0; k < 3; ++k) {
+        z.p[k] = static_cast<unsigned *>(zero_ptr[k]);
+        z.n[k] = zero_ptr[k] ? static_cast<unsigned>(zero_bytes[k] / sizeof(unsigned)) : 0u;
+        n = z.n[k] > n ? z.n[k] : n;
+    }
+    hipLaunchKernelGGL(step_init_kernel, dim3((n + 255) / 256), dim3(256), 0, st,
+                       reinterpret_cast<float2 *>(tab), T, D / 2, p, static_cast<double>(theta), z);
     return last_launch_status();
 }
 

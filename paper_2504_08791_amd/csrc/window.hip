@@ -149,6 +149,15 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
     return PRIMA_OK;
 }
 
+// before the first layer of a step: RoPE table, and the counters of the mat-vec, attention (and single-launch)
+// scratch zeroed, in one launch
+prima_status step_init(const prima_dims &d, void *ws, const WindowWs &w, int T, int n_past, const int *positions, bool with_sync, hipStream_t st)
+{
+    void *const zp[3] = {at<char>(ws, w.gemv), at<char>(ws, w.attn), with_sync ? at<char>(ws, w.sync) : nullptr};
+    const size_t zb[3] = {w.arrivals_bytes, attn_counter_bytes(d, T), fused_sync_bytes()};
+    return launch_step_init(at<float>(ws, w.rope), T, d.head_dim, n_past, d.rope_theta, positions, zp, zb, st);
+}
+
 prima_status check_window_args(const prima_dims *d, int32_t kv_cap, int32_t n_past, int32_t T,
                                const float *x_in, float *x_out, void *ws, size_t ws_bytes)
 {
@@ -262,11 +271,7 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
         if ((s = check_layer(layers[i])) != PRIMA_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const WindowWs w = carve(*d, kv_cap, T);
-    s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, T), st);
-    if (s != PRIMA_OK) return s;
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.sync), fused_sync_bytes(), st);
+    s = step_init(*d, workspace, w, T, n_past, nullptr, true, st);
     if (s != PRIMA_OK) return s;
     if (T == 1 && g_fused_enabled) {
         GemvArgs ga[4];
@@ -309,9 +314,7 @@ prima_status prima_layer_window_decode_batch(const prima_dims *d, const prima_la
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const WindowWs w = carve(*d, kv_cap, B);
-    s = launch_rope_table(at<float>(workspace, w.rope), B, d->head_dim, 0, d->rope_theta, st, n_past);
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, B), st);
+    s = step_init(*d, workspace, w, B, 0, n_past, false, st);
     if (s != PRIMA_OK) return s;
     const float *cur = x_in;
     for (int i = 0; i < L; ++i) {
@@ -358,9 +361,7 @@ prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const WindowWs w = carve(*d, kv_cap, T);
     // one ordinary step first: every intermediate buffer then holds this step's values
-    s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, T), st);
+    s = step_init(*d, workspace, w, T, n_past, nullptr, false, st);
     const float *cur = x_in;
     for (int i = 0; i < L && s == PRIMA_OK; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
@@ -409,9 +410,7 @@ prima_status prima_layer_decode_taps(const prima_dims *d, const prima_layer *lay
     if ((s = check_layer(*layer)) != PRIMA_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const WindowWs w = carve(*d, kv_cap, T);
-    s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.gemv), w.arrivals_bytes, st);
-    if (s == PRIMA_OK) s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, T), st);
+    s = step_init(*d, workspace, w, T, n_past, nullptr, false, st);
     if (s != PRIMA_OK) return s;
     return run_layer(*d, *layer, kv_cap, n_past, T, x_in, x_out, workspace, w, st, tap_q, tap_o, tap_h, tap_a);
 }
