@@ -71,6 +71,30 @@ def test_gemv_vs_oracle(gpu_lib, rows, nb, T):
     assert rel_err(got, ref) < 1e-4, rel_err(got, ref)
 
 
+def test_gemv_random_shapes(gpu_lib):
+    """Shapes drawn at random (rows ragged against the 16-row tiles, odd and large numbers of super-blocks, every
+    token count: one and several slabs of K, parts meeting in LDS or not, passes of up to 8 tokens), activations
+    with a different scale per token: each against the oracle, and twice with identical bits."""
+    rng = np.random.default_rng(2024)
+    cases = []
+    for _ in range(100):
+        nb = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 20, 28, 32, 33, 56, 64, 100, 112, 120]))
+        rows = int(rng.integers(1, max(1, min(9000, 6_000_000 // (nb * 256))) + 1))
+        if rng.random() < 0.3:
+            rows = max(1, rows // 16 * 16 + int(rng.choice([0, 1, 15])))
+        cases.append((rows, nb, int(rng.choice([1, 1, 1, 2, 3, 4, 5, 7, 8, 9, 12, 16]))))
+    cases += [(8192, 112, 1), (8192, 112, 8), (4096, 56, 4), (16, 120, 16), (1, 120, 8), (5000, 1, 16), (257, 33, 7)]
+    for rows, nb, T in cases:
+        W = _rand_q4k(rng, rows, nb)
+        x = (rng.standard_normal((T, nb * 256)) * np.exp(3 * rng.standard_normal((T, 1)))).astype(np.float32)
+        ref = oracle.gemv(W, x.astype(np.float64))
+        Wd, xd = _dev(W), _dev(x)
+        got = gpu_lib.q4k_gemv(Wd, xd).cpu().numpy()
+        again = gpu_lib.q4k_gemv(Wd, xd).cpu().numpy()
+        assert rel_err(got, ref) < 1e-4, (rows, nb, T, rel_err(got, ref))
+        assert np.array_equal(got.view(np.uint32), again.view(np.uint32)), (rows, nb, T)
+
+
 def test_gemv_wide_dynamic_range(gpu_lib):
     """Activations like the SwiGLU output of the synthetic models: huge, common-mode, with outliers."""
     rng = np.random.default_rng(5)
@@ -287,6 +311,62 @@ def test_rerun_is_bit_identical(gpu_lib):
     a = win.decode(x, cfg.n_past).clone()
     b = win.decode(x, cfg.n_past)
     assert torch.equal(a, b)
+
+
+def test_attention_random_shapes(gpu_lib):
+    """Head counts (groups of 1 to 16 queries per KV head, not only powers of two), both head sizes, context
+    lengths around the tile and key-range boundaries and token counts drawn at random."""
+    rng = np.random.default_rng(7)
+    n = 0
+    while n < 50:
+        D, Hkv, G = int(rng.choice([64, 128])), int(rng.choice([1, 2, 3, 4, 8])), int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16]))
+        Hq = Hkv * G
+        if (Hq * D) % 256:
+            continue
+        T = int(rng.choice([1, 1, 2, 3, 4, 7, 8, 13, 16]))
+        n_past = int(rng.choice([0, 1, 15, 16, 17, 100, 127, 128, 129, 500, 1023, 3000]))
+        dims = ModelDims(Hq * D, Hq, Hkv, D, 256, 1e4)
+        cap = n_past + T + int(rng.integers(0, 3))
+        K = rng.standard_normal((Hkv, cap, D)).astype(np.float16)
+        V = rng.standard_normal((Hkv, cap, D)).astype(np.float16)
+        K[:, n_past + T:] = np.float16(300.0)
+        V[:, n_past + T:] = np.float16(-300.0)
+        q = (rng.standard_normal((T, Hq, D)) * float(np.exp(rng.standard_normal()))).astype(np.float32)
+        ref = oracle.attn_decode(dims, q.astype(np.float64), K, V, n_past, T)
+        got = gpu_lib.attn_decode(dims, _dev(q), _dev(K), _dev(V), n_past).cpu().numpy()
+        assert rel_err(got.reshape(T, -1), ref.reshape(T, -1)) < ATT_TOL, (Hq, Hkv, D, n_past, T)
+        n += 1
+
+
+def test_window_random_shapes(gpu_lib):
+    """Small windows of random shape (widths, FFN sizes with odd numbers of tiles and super-blocks, head layouts,
+    both RoPE pairings, 1 to 3 layers, every token count), as T tokens of one sequence and as a batch of T
+    sequences of random lengths over the same weights."""
+    from workloads.configs import WindowConfig
+    rng = np.random.default_rng(11)
+    n = 0
+    while n < 30:
+        D, Hkv, G = int(rng.choice([64, 128])), int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 3, 4, 5, 8]))
+        Hq = Hkv * G
+        if (Hq * D) % 256:
+            continue
+        e, ffn = int(rng.choice([256, 512, 768, 1024, 1280, 2048])), int(rng.choice([256, 512, 768, 1280, 1536, 2816, 3584]))
+        T, n_past = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16])), int(rng.choice([0, 1, 17, 63, 130, 400]))
+        dims = ModelDims(e, Hq, Hkv, D, ffn, float(rng.choice([1e4, 5e5, 1e6])), rope_mode=int(rng.integers(0, 2)))
+        cfg = WindowConfig("r%d" % n, 600 + n, dims, int(rng.integers(1, 4)), T, n_past)
+        cap = n_past + T + 2
+        host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+        win, _ = _window(gpu_lib, cfg, cap, host)
+        x = synth.window_input(cfg)
+        ref = oracle.window(dims, host, x.astype(np.float64), n_past)
+        assert rel_err(win.decode(_dev(x), n_past).cpu().numpy(), ref) < HID_TOL, cfg
+        lens = [int(rng.integers(0, cap)) for _ in range(T)]
+        caches = synth.batch_caches(cfg, cfg.n_layers, lens, cap)
+        dev_caches = [[(_dev(k), _dev(v)) for k, v in per_layer] for per_layer in caches]
+        xb = synth.batch_input(cfg, T)
+        refb = oracle.window_batch(dims, host, caches, xb.astype(np.float64), lens)
+        assert rel_err(win.decode_batch(_dev(xb), lens, dev_caches).cpu().numpy(), refb) < HID_TOL, (cfg, lens)
+        n += 1
 
 
 def test_lm_head_vs_oracle(gpu_lib):
