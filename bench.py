@@ -81,6 +81,23 @@ def main():
     x = torch.from_numpy(x_host).to(dev)
     y = torch.empty_like(x)
     stream = torch.cuda.current_stream()
+    # a configuration with an output layer (config 4): final RMSNorm + lm_head follow the window in every step
+    head = None
+    if cfg.vocab:
+        out_t = synth.output_layer_tensors(cfg)
+        head = {k: torch.from_numpy(v).to(dev) for k, v in out_t.items()}
+        logits = torch.empty((cfg.T, cfg.vocab), dtype=torch.float32, device=dev)
+        head_ws = torch.empty(max(256, prima.lm_head_workspace_bytes(d, cfg.vocab, cfg.T)), dtype=torch.uint8, device=dev)
+        if want_cpu:
+            t0 = time.perf_counter()
+            logits_ref = oracle.lm_head(d, out_t["g_final"], out_t["w_lm"], h_ref)
+            cpu_seconds += time.perf_counter() - t0
+        del out_t
+
+    def step():
+        win.decode(x, cfg.n_past, x_out=y)
+        if head is not None:
+            prima.lm_head(d, head["g_final"], head["w_lm"], y, logits, head_ws)
 
     if args.copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
@@ -90,19 +107,19 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
-        win.decode(x, cfg.n_past, x_out=y)
+        step()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record(stream)
     for _ in range(args.steps):
-        win.decode(x, cfg.n_past, x_out=y)
+        step()
     e1.record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = e0.elapsed_time(e1) / args.steps
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
-    bytes_step = cfg.bytes_per_step()
+    bytes_step = cfg.bytes_per_step()   # the output layer's bytes included when there is one
 
     # --- what a plain linear read reaches on this device (4 GiB, far beyond the last-level cache) ---
     probe = torch.empty(4 * 1024 ** 3, dtype=torch.uint8, device=dev)
@@ -177,6 +194,10 @@ def main():
         rms = np.sqrt((h_ref ** 2).mean(axis=1, keepdims=True))
         err = float((np.abs(got - h_ref) / np.maximum(np.abs(h_ref), np.maximum(rms, 1e-30))).max())
         out["max_rel_err_vs_oracle"] = err
+        if head is not None:
+            gl = logits.cpu().numpy().astype(np.float64)
+            rms = np.sqrt((logits_ref ** 2).mean(axis=1, keepdims=True))
+            out["max_rel_err_logits_vs_oracle"] = float((np.abs(gl - logits_ref) / np.maximum(np.abs(logits_ref), np.maximum(rms, 1e-30))).max())
         out["cpu_baseline"] = {
             "value": round(cfg.T / cpu_seconds, 4),
             "unit": "tokens/s",

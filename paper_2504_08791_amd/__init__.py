@@ -203,6 +203,11 @@ class Window:
         return x_out, taps
 
 
+def lm_head_workspace_bytes(dims, vocab, T):
+    d = make_dims(dims)
+    return _ffi.lib().prima_lm_head_workspace_bytes(C.byref(d), vocab, T)
+
+
 def lm_head(dims, g_final, w_lm, x, logits=None, workspace=None):
     """logits[t, v] = W_lm . rmsnorm(x[t]; g_final)."""
     d = make_dims(dims)
@@ -213,8 +218,7 @@ def lm_head(dims, g_final, w_lm, x, logits=None, workspace=None):
     if logits is None:
         logits = torch.empty((T, vocab), dtype=torch.float32, device=x.device)
     if workspace is None:
-        need = _ffi.lib().prima_lm_head_workspace_bytes(C.byref(d), vocab, T)
-        workspace = torch.empty(max(256, need), dtype=torch.uint8, device=x.device)
+        workspace = torch.empty(max(256, lm_head_workspace_bytes(d, vocab, T)), dtype=torch.uint8, device=x.device)
     _ffi.check(_ffi.lib().prima_lm_head(C.byref(d), _ptr(g_final), _ptr(w_lm), vocab, _ptr(x), T, _ptr(logits),
                                         _ptr(workspace), workspace.numel(), _stream()), "prima_lm_head")
     return logits
