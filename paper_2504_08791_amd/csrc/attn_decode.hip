@@ -82,6 +82,8 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
                          const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
                          void *ws, hipStream_t st, const AttnSeqs *seq)
 {
+    // several tokens of one sequence: both products on the matrix cores (attn_decode_mt.hip)
+    if (!seq && T >= 2) return launch_attn_mt(d, q, q_rot_out, k_new, v_new, rope_tab, K, V, kv_cap, n_past, T, o, ws, st);
     const AttnArgs a = build_attn_args(d, q, q_rot_out, k_new, v_new, rope_tab, K, V, kv_cap, n_past, T, o, ws, seq);
     const dim3 grid(a.nsplit, d.n_kv_heads, seq ? query_groups_batch(d, T) : query_groups(d, T)), block(ATT_THREADS);
     if (d.head_dim == 128 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<128, 0>), grid, block, sizeof(AttnLds<128>), st, a);

@@ -105,6 +105,10 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
                          const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
                          void *ws, hipStream_t st, const AttnSeqs *seq = nullptr);
 
+prima_status launch_attn_mt(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
+                            const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
+                            void *ws, hipStream_t st);
+
 // one token through a whole window in one launch per FUSED_MAX_LAYERS layers (fused_window.hip); PRIMA_E_SHAPE
 // with nothing launched when the shapes do not qualify
 size_t fused_sync_bytes();
@@ -113,5 +117,23 @@ prima_status launch_fused_window(const prima_dims &d, const prima_layer *layers,
                                  const float *q, const float *k_new, const float *v_new, const float *rope_tab,
                                  int kv_cap, int n_past, float *o, void *attn_ws,
                                  const float *x_in, float *x_out, float *xb0, float *xb1, void *sync, hipStream_t st);
+
+// 16 bytes per lane from global memory straight into LDS: lane l writes bytes [16 l, 16 l + 16) of the
+// 1 KiB at LDS byte address lds_addr (wave-uniform, goes through M0).  Written as inline assembly on
+// purpose: the compiler then does not know these loads write LDS and leaves the ordering against the
+// later LDS reads to the explicit s_waitcnt vmcnt(N) below, which lets newer stages stay in flight
+// (with the builtin it waits for *all* outstanding loads before any LDS read).  Loads complete in
+// order, so loads the compiler does not know about can only make its own waits stricter.
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
+{
+    // one wait state is required between the SALU write of M0 and the load that reads it; M0 is a reserved
+    // register that nothing else in this file uses
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)); // low half of a flat LDS pointer is the LDS byte address
+}
 
 } // namespace prima

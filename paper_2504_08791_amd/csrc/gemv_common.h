@@ -43,19 +43,6 @@ struct PGemvArgs {
     unsigned *arrivals; // n_slabs > 1: per-tile arrival counters, zero between launches
 };
 
-// 16 bytes per lane from global memory straight into LDS: lane l writes bytes [16 l, 16 l + 16) of the
-// 1 KiB at LDS byte address lds_addr (wave-uniform, goes through M0).  Written as inline assembly on
-// purpose: the compiler then does not know these loads write LDS and leaves the ordering against the
-// later LDS reads to the explicit s_waitcnt vmcnt(N) below, which lets newer stages stay in flight
-// (with the builtin it waits for *all* outstanding loads before any LDS read).  Loads complete in
-// order, so loads the compiler does not know about can only make its own waits stricter.
-__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
-{
-    // one wait state is required between the SALU write of M0 and the load that reads it; M0 is a reserved
-    // register that nothing else in this file uses
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_addr) : "memory");
-}
-
 // 16 bytes per lane into registers, requested now and waited for by hand: the compiler does not know
 // that the result arrives later, which is the point: it cannot put a wait for *all* outstanding loads
 // (the ring stages behind them included) in front of the first use.  Until the hand-written wait, which
@@ -83,11 +70,6 @@ template <class T>
 __device__ __forceinline__ T *as_global(T *p)
 {
     return (T *)(__attribute__((address_space(1))) T *)p;
-}
-
-__device__ __forceinline__ uint32_t lds_address(const void *p)
-{
-    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)); // low half of a flat LDS pointer is the LDS byte address
 }
 
 __device__ __forceinline__ long pack64(uint32_t lo, uint32_t hi)
