@@ -158,10 +158,11 @@ def test_attention_vs_oracle(gpu_lib, Hq, Hkv, D, n_past, T):
     cap = n_past + T + 2
     K = rng.standard_normal((Hkv, cap, D)).astype(np.float16)
     V = rng.standard_normal((Hkv, cap, D)).astype(np.float16)
-    K[:, n_past + T:] = np.float16(300.0)     # rows beyond the step must never be read
-    V[:, n_past + T:] = np.float16(-300.0)
+    K[:, n_past + T:] = np.float16(np.nan)    # rows beyond the step must never reach a result
+    V[:, n_past + T:] = np.float16(np.nan)
     q = rng.standard_normal((T, Hq, D)).astype(np.float32)
     ref = oracle.attn_decode(dims, q.astype(np.float64), K, V, n_past, T)
+    assert np.isfinite(ref).all()
     got = gpu_lib.attn_decode(dims, _dev(q), _dev(K), _dev(V), n_past).cpu().numpy()
     assert rel_err(got.reshape(T, -1), ref.reshape(T, -1)) < ATT_TOL
 
@@ -273,6 +274,39 @@ def test_batch_of_one_equals_single_sequence_step(gpu_lib):
         assert torch.equal(t["k_cache"], per_layer[0][0]) and torch.equal(t["v_cache"], per_layer[0][1])
 
 
+@pytest.mark.parametrize("name", ["t0", "t1", "t2"])
+def test_unwritten_cache_rows_may_hold_anything(gpu_lib, name):
+    """Cache rows at and beyond n_past are not part of the context: filled with NaN patterns before the step, they
+    must neither reach a result (one sequence: T tokens; and a batch of sequences) nor survive where the step
+    appends."""
+    cfg = TINY[name]
+    cap = cfg.n_past + cfg.T + 20
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    x = synth.window_input(cfg)
+    ref = oracle.window(cfg.dims, copy.deepcopy(host), x.astype(np.float64), cfg.n_past)
+    nan16 = np.uint16(0x7E00)
+    for t in host:
+        for key in ("k_cache", "v_cache"):
+            t[key].view(np.uint16)[:, cfg.n_past:] = nan16
+    win, dev_layers = _window(gpu_lib, cfg, cap, host)
+    y = win.decode(_dev(x), cfg.n_past).cpu().numpy()
+    assert np.isfinite(y).all() and rel_err(y, ref) < HID_TOL
+    for t in dev_layers:
+        for key in ("k_cache", "v_cache"):
+            rows = t[key][:, cfg.n_past:cfg.n_past + cfg.T].cpu().numpy()
+            assert np.isfinite(rows.astype(np.float32)).all()
+    lens = [0, cfg.n_past, 5][:max(1, min(3, cfg.T))] if cfg.T > 1 else [cfg.n_past]
+    caches = synth.batch_caches(cfg, cfg.n_layers, lens, cap)
+    refb = oracle.window_batch(cfg.dims, host, copy.deepcopy(caches), synth.batch_input(cfg, len(lens)).astype(np.float64), lens)
+    for per_layer in caches:
+        for b, (k, v) in enumerate(per_layer):
+            k.view(np.uint16)[:, lens[b]:] = nan16
+            v.view(np.uint16)[:, lens[b]:] = nan16
+    dev_caches = [[(_dev(k), _dev(v)) for k, v in per_layer] for per_layer in caches]
+    yb = win.decode_batch(_dev(synth.batch_input(cfg, len(lens))), lens, dev_caches).cpu().numpy()
+    assert np.isfinite(yb).all() and rel_err(yb, refb) < HID_TOL
+
+
 def test_joint_equals_sequential_on_gpu(gpu_lib):
     cfg = TINY["t1"]
     cap = cfg.n_past + cfg.T
@@ -329,8 +363,8 @@ def test_attention_random_shapes(gpu_lib):
         cap = n_past + T + int(rng.integers(0, 3))
         K = rng.standard_normal((Hkv, cap, D)).astype(np.float16)
         V = rng.standard_normal((Hkv, cap, D)).astype(np.float16)
-        K[:, n_past + T:] = np.float16(300.0)
-        V[:, n_past + T:] = np.float16(-300.0)
+        K[:, n_past + T:] = np.float16(np.nan)
+        V[:, n_past + T:] = np.float16(np.nan)
         q = (rng.standard_normal((T, Hq, D)) * float(np.exp(rng.standard_normal()))).astype(np.float32)
         ref = oracle.attn_decode(dims, q.astype(np.float64), K, V, n_past, T)
         got = gpu_lib.attn_decode(dims, _dev(q), _dev(K), _dev(V), n_past).cpu().numpy()
