@@ -148,7 +148,8 @@ prima_status prima_layer_window_decode_batch(const prima_dims *d, const prima_la
 
 /*
  * Optional single-launch path for one token (T = 1): the layers' kernels run back to back on one persistent
- * grid (one launch per 24 layers), separated by grid barriers; same arithmetic, same bits.  It is OFF by
+ * grid (one launch per 24 layers), separated by grid barriers; same mat-vec arithmetic and bits, an attention
+ * phase of its own (same results within rounding).  It is OFF by
  * default (measured slower than one launch per projection); prima_set_fused_window(1) switches it on for the
  * process.  Shapes that do not fill the device evenly, and T > 1, always run one kernel per projection.
  * The barriers poll with a bound; prima_window_check() waits for `hip_stream` (it SYNCHRONISES) and returns

@@ -1,62 +1,30 @@
-// GQA decode attention over an fp16 KV cache, split over the KV length, partials merged by
-// log-sum-exp.  Per layer and step it reads 2(h_k e_k + h_v e_v) n_kv bytes (arXiv 2504.08791,
-// App. A.3, device-loading term) and appends 2(h_k e_k + h_v e_v) bytes per token.
-//
-// The work per launch is small (tens of KB per compute unit), so the kernel is built as one short
-// dependency chain: everything a wave needs is requested from memory in its first instructions, and
-// nothing is staged through LDS before the matrix multiply.
-// One workgroup handles (key range, KV head, group of up to 8 queries that share the head); each of
-// its waves takes 16-key tiles of the range.
-//  * Q.K^T runs on the matrix cores: the fp16 cache rows are MFMA operands as they lie in memory
-//    (lane (n, c) loads 16 bytes of key n), the queries are loaded by every wave straight into the
-//    A-operand layout, rotated there (RoPE partners sit in the same lane), pre-scaled by a power of two
-//    and split into fp16 high and low parts that occupy rows 0-7 and 8-15 of the A operand, so the
-//    logits carry the queries' full fp32 precision with fp32 accumulation.
-//  * softmax statistics are kept online per 16-key tile in fp32; reductions over the 16 keys of a
-//    tile are row rotations inside the vector ALU (DPP), not LDS permutes.
-//  * P.V runs on the vector ALUs in fp32: a lane owns two output columns for all keys of the tile
-//    (one 32-bit load per key), so no reduction across lanes is needed; the probabilities reach the
-//    lanes as LDS broadcasts.
-//  * fused RoPE + KV append: a workgroup whose key range holds new rows builds them from the projection
-//    output (rotate k, round k and v to fp16, nearest even), keeps them in LDS for its own tiles and
-//    stores them to the cache on the side, so the appended rows cost no store-to-load round trip.
-//  * the workgroup that arrives last at a (KV head, query group) merges the key ranges; partial
-//    records travel through device-scope stores and loads, ordered by one counter per group.
+// GQA decode attention over an fp16 KV cache, split over the KV length, partials merged by log-sum-exp.
+// Per layer and step it reads 2(h_k e_k + h_v e_v) n_kv bytes (arXiv 2504.08791, App. A.3, device-loading term)
+// and appends 2(h_k e_k + h_v e_v) bytes per token.  One token, several tokens of one sequence (speculative
+// verification, App. A.12: the G*T queries on a KV head share every key and value they may see, so the work per
+// byte of cache is T-fold) or a batch of sequences with one token each.  Both products run on the matrix cores.
+//  * A workgroup handles (key range, KV head, group of up to 16 queries); each wave takes 16-key tiles.
+//  * Logits transposed, S^T = K Q^T: the cache rows are the A operand as they lie in memory, the queries (RoPE
+//    applied in-lane, pre-scaled by a power of two, split into fp16 high and low parts: two MFMAs into one
+//    accumulator, so the logits carry the queries' fp32 precision) the B operand.  Lane (q, g) then holds the
+//    logits of query q with keys 4g..4g+3, which is exactly the A-operand layout of the second product, so
+//    the probabilities never leave the registers.
+//  * Online softmax per query: four keys in-lane, the other twelve two shuffles away.
+//  * P.V: P (fp16 high + low parts, again two MFMAs into one accumulator: fp32-accurate probabilities) times
+//    the 16 x D tile of V.  The cache keeps V row-major [key][d] while the B operand wants four keys of one
+//    column per lane, so the tile (contiguous 32 D bytes) goes from global memory straight into LDS and the
+//    lanes pick their 2-byte elements from there; tiles are double-buffered per wave.
+//  * RoPE + KV append fused: a workgroup whose key range holds new rows builds them once from the projection
+//    output (rotate k, round k and v to fp16, nearest even), keeps them in LDS (they replace what the tile
+//    loads brought from the cache) and stores them to the cache on the side: no store-to-load round trip.
+//  * Waves meet in LDS, key ranges in global memory; the workgroup that arrives last merges them.
 #include "attn_common.h"
 
 namespace prima {
 
-struct AttnNoSync {
-    __device__ __forceinline__ void wait() {}
-};
+constexpr int QGM = 16; // queries per workgroup
 
-template <int D, int MODE> // head size, RoPE pairing (0: i with i + D/2, 1: 2i with 2i + 1)
-__global__ void __launch_bounds__(ATT_THREADS) attn_decode_kernel(AttnArgs a)
-{
-    extern __shared__ __align__(16) uint8_t smem[];
-    constexpr bool COH = false;
-    const int split = blockIdx.x, kvh = blockIdx.y;
-    AttnNoSync sync;
-    // the view of this workgroup: all T tokens of one sequence, or (batch) the one token of sequence tok0
-    const bool batch = a.batch != 0;
-    const int gps = (a.Hq / a.Hkv + QG - 1) / QG; // query groups of one token
-    const int tok0 = batch ? blockIdx.z / gps : 0;
-    const int qgrp = batch ? blockIdx.z - tok0 * gps : blockIdx.z, nqg = batch ? gps : gridDim.z;
-    const int arg_T = batch ? 1 : a.T;
-    __half *arg_K = a.K, *arg_V = a.V;
-    int arg_n_past = a.n_past;
-    if (batch) {
-        // read by hand from the argument segment: indexing the by-value argument with a run-time index would
-        // make the compiler copy all of it to scratch memory
-        typedef const __attribute__((address_space(4))) AttnArgs ConstAttnArgs;
-        ConstAttnArgs &ka = *(ConstAttnArgs *)__builtin_amdgcn_kernarg_segment_ptr();
-        arg_K = ka.seq_K[tok0];
-        arg_V = ka.seq_V[tok0];
-        arg_n_past = ka.seq_n_past[tok0];
-    }
-#include "attn_body.inc"
-}
-
+// key ranges of the single-launch window kernel's attention phase (groups of 8 queries, attn_body.inc)
 int attn_num_splits(const prima_dims &d, int n_total, int T, bool batch)
 {
     const int wgs = d.n_kv_heads * (batch ? query_groups_batch(d, T) : query_groups(d, T));
@@ -78,18 +46,426 @@ size_t attn_ws_bytes(const prima_dims &d, int, int T)
     return attn_counter_bytes(d, T) + round_up(static_cast<size_t>(T) * d.n_q_heads * MAX_SPLITS * (2 + d.head_dim) * sizeof(float), 256);
 }
 
-prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
-                         const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
-                         void *ws, hipStream_t st, const AttnSeqs *seq)
+
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+struct AttnTileLds {
+    union {
+        __half vt[ATT_WAVES][2][16][D]; // V tiles of the loop
+        float o[ATT_WAVES][QGM][D];     // afterwards: the waves' un-normalised outputs
+    };
+    float corr[ATT_WAVES][QGM];
+    float m[ATT_WAVES][QGM], l[ATT_WAVES][QGM];
+    __half knew[PRIMA_MAX_TOK][D], vnew[PRIMA_MAX_TOK][D]; // the step's new rows (fused append)
+    int last;
+};
+
+template <int D, int MODE> // head size, RoPE pairing (0: i with i + D/2, 1: 2i with 2i + 1)
+__global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a) // 4 waves per SIMD (two workgroups per compute unit): at most 128 VGPRs
 {
-    // several tokens of one sequence: both products on the matrix cores (attn_decode_mt.hip)
-    if (!seq && T >= 2) return launch_attn_mt(d, q, q_rot_out, k_new, v_new, rope_tab, K, V, kv_cap, n_past, T, o, ws, st);
-    const AttnArgs a = build_attn_args(d, q, q_rot_out, k_new, v_new, rope_tab, K, V, kv_cap, n_past, T, o, ws, seq);
-    const dim3 grid(a.nsplit, d.n_kv_heads, seq ? query_groups_batch(d, T) : query_groups(d, T)), block(ATT_THREADS);
-    if (d.head_dim == 128 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<128, 0>), grid, block, sizeof(AttnLds<128>), st, a);
-    else if (d.head_dim == 128 && d.rope_mode == 1) hipLaunchKernelGGL((attn_decode_kernel<128, 1>), grid, block, sizeof(AttnLds<128>), st, a);
-    else if (d.head_dim == 64 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<64, 0>), grid, block, sizeof(AttnLds<64>), st, a);
-    else if (d.head_dim == 64 && d.rope_mode == 1) hipLaunchKernelGGL((attn_decode_kernel<64, 1>), grid, block, sizeof(AttnLds<64>), st, a);
+    extern __shared__ __align__(16) uint8_t smem[];
+    constexpr int NA = D / 32; // MFMAs (k-steps of 32) per tile of logits and query part
+    constexpr int NB = D / 16; // 16-column blocks of the output
+    const int split = blockIdx.x, kvh = blockIdx.y;
+    const int G = a.Hq / a.Hkv;
+    // The view of this workgroup: arg_T tokens that continue one sequence whose caches are arg_K, arg_V with
+    // arg_n_past rows; they are tokens tok0 .. tok0 + arg_T - 1 of the call's q, k_new, v_new, rope_tab and o.
+    // A call for one sequence: all of its tokens.  A batch of sequences: the one token of sequence tok0, whose
+    // caches and length are read by hand from the argument segment (indexing the by-value argument with a
+    // run-time index would make the compiler copy all of it to scratch memory).
+    const bool batch = a.batch != 0;
+    const int gps = (G + QGM - 1) / QGM; // query groups of one token
+    const int tok0 = batch ? blockIdx.z / gps : 0;
+    const int qgrp = batch ? blockIdx.z - tok0 * gps : blockIdx.z, nqg = batch ? gps : gridDim.z;
+    const int arg_T = batch ? 1 : a.T;
+    __half *arg_K = a.K, *arg_V = a.V;
+    int arg_n_past = a.n_past;
+    if (batch) {
+        typedef const __attribute__((address_space(4))) AttnArgs ConstAttnArgs;
+        ConstAttnArgs &ka = *(ConstAttnArgs *)__builtin_amdgcn_kernarg_segment_ptr();
+        arg_K = ka.seq_K[tok0];
+        arg_V = ka.seq_V[tok0];
+        arg_n_past = ka.seq_n_past[tok0];
+    }
+    const int NQ = G * arg_T; // queries on this KV head, index = t*G + hg
+    const int q0 = qgrp * QGM;
+    const int nq = min(QGM, NQ - q0);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n_total = arg_n_past + arg_T;
+    const int p_begin = split * a.keys_per_split;
+    const int p_end = min(p_begin + a.keys_per_split, n_total);
+    const bool fused = a.k_new != nullptr;
+
+    AttnTileLds<D> &lds = *reinterpret_cast<AttnTileLds<D> *>(smem);
+    __half *Kh = arg_K + static_cast<int64_t>(kvh) * a.kv_cap * D;
+    __half *Vh = arg_V + static_cast<int64_t>(kvh) * a.kv_cap * D;
+
+    const int col = lane & 15, g = lane >> 4; // MFMA lane coordinates
+    const int last_row = n_total - 1;
+    const bool has_new = fused && p_end > arg_n_past;
+
+    // A operand of the logits: lane (key, c) holds elements 32x + 8c .. + 8 of the key.  New rows come from LDS.
+    auto load_k = [&](int k0, half8 *kbuf) __attribute__((always_inline)) {
+        const int krow = min(k0 + col, last_row);
+        const __half *kp = Kh + static_cast<int64_t>(krow) * D + 8 * g;
+#pragma unroll
+        for (int x = 0; x < NA; ++x) kbuf[x] = *reinterpret_cast<const half8 *>(kp + 32 * x);
+    };
+    auto patch_k = [&](int k0, half8 *kbuf) __attribute__((always_inline)) {
+        const int krow = min(k0 + col, last_row);
+        if (has_new && krow >= arg_n_past) {
+#pragma unroll
+            for (int x = 0; x < NA; ++x) kbuf[x] = *reinterpret_cast<const half8 *>(&lds.knew[krow - arg_n_past][32 * x + 8 * g]);
+        }
+    };
+    // the 16 x D tile of V into this wave's LDS buffer `buf`: 1 KiB (1024 / 2D rows) per instruction; rows past
+    // the last one re-read it.  Nothing the compiler knows of waits for these loads: s_waitcnt vmcnt(0) below.
+    auto request_v = [&](int k0, int buf) __attribute__((always_inline)) {
+        constexpr int LPR = D / 8;        // lanes per row
+        constexpr int RPI = 64 / LPR;     // rows per instruction
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_address(&lds.vt[wave][buf][0][0]));
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads of the buffer being overwritten have returned
+#pragma unroll
+        for (int i = 0; i < 16 / RPI; ++i) {
+            const int vrow = min(k0 + RPI * i + lane / LPR, last_row);
+            dma16(Vh + static_cast<int64_t>(vrow) * D + (lane % LPR) * 8, dst + i * 1024);
+        }
+    };
+
+    half8 kb[NA];
+    const int tile_stride = ATT_WAVES * 16;
+    int key0 = p_begin + wave * 16;
+
+    // ---- queries: lane (q, c) holds the slices c of query q (B operand of the logits), high and low parts ----
+    const bool q_valid = col < nq;
+    const int qi = q0 + col, q_t = qi / G, q_hg = qi - q_t * G;
+    const int64_t qoff = (static_cast<int64_t>(tok0 + q_t) * a.Hq + kvh * G + q_hg) * D;
+    constexpr int NPT = (PRIMA_MAX_TOK * (D / 2) + ATT_THREADS - 1) / ATT_THREADS; // new (k pair, v pair)s per thread
+    float2 n_cs[NPT], n_k[NPT], n_v[NPT];
+    half8 qh[NA], ql[NA];
+    float fq = 0.f; // logit factor 2^-p / sqrt(D) of this lane's query
+    {
+        float qv[NA][8];
+        float4 q_rt[D / 16];
+#pragma unroll
+        for (int x = 0; x < NA; ++x)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qv[x][e] = 0.f;
+        if (q_valid) {
+            load_slices<D, false>(a.q + qoff, g, qv);
+            if (a.rope_tab) rope_load<D, MODE>(a.rope_tab + (tok0 + q_t) * (D / 2), g, q_rt);
+        }
+        // the first tile right behind the queries: they are prepared while it is on its way
+        if (key0 < p_end) {
+            load_k(key0, kb);
+            request_v(key0, 0);
+        }
+        if (has_new) {
+#pragma unroll
+            for (int k = 0; k < NPT; ++k) {
+                const int idx = threadIdx.x + k * ATT_THREADS;
+                if (idx < arg_T * (D / 2)) {
+                    const int t = idx / (D / 2), i = idx - t * (D / 2);
+                    const int ia = MODE ? 2 * i : i, ib = MODE ? 2 * i + 1 : i + D / 2;
+                    const float *kp = a.k_new + (static_cast<int64_t>(tok0 + t) * a.Hkv + kvh) * D;
+                    n_cs[k] = a.rope_tab[(tok0 + t) * (D / 2) + i];
+                    n_k[k] = make_float2(kp[ia], kp[ib]);
+                    n_v[k] = *reinterpret_cast<const float2 *>(a.v_new + (static_cast<int64_t>(tok0 + t) * a.Hkv + kvh) * D + 2 * i);
+                }
+            }
+        }
+        if (q_valid && a.rope_tab) {
+            rope_apply<D, MODE>(qv, q_rt);
+            if (a.q_rot_out && split == 0 && wave == 0) {
+#pragma unroll
+                for (int x = 0; x < NA; ++x) {
+                    float *dst = a.q_rot_out + qoff + 32 * x + 8 * g;
+                    *reinterpret_cast<float4 *>(dst) = make_float4(qv[x][0], qv[x][1], qv[x][2], qv[x][3]);
+                    *reinterpret_cast<float4 *>(dst + 4) = make_float4(qv[x][4], qv[x][5], qv[x][6], qv[x][7]);
+                }
+            }
+        }
+        float amax = 0.f;
+#pragma unroll
+        for (int x = 0; x < NA; ++x)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(qv[x][e]));
+        amax = fmaxf(amax, __shfl_xor(amax, 16, 64)); // the four slices of the query
+        amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+        int ex = 0;
+        if (amax > 0.f) frexpf(amax, &ex); // amax < 2^ex
+        int p = 12 - ex;                   // scaled |q| < 2^12
+        p = p > 100 ? 100 : (p < -100 ? -100 : p);
+        const float S = ldexpf(1.0f, p);
+#pragma unroll
+        for (int x = 0; x < NA; ++x) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float sv = qv[x][e] * S;
+                const _Float16 hi = static_cast<_Float16>(sv);
+                qh[x][e] = hi;
+                ql[x][e] = static_cast<_Float16>(sv - static_cast<float>(hi));
+            }
+        }
+        fq = q_valid ? ldexpf(1.0f, -p) * rsqrtf(static_cast<float>(D)) : 0.f;
+    }
+    const int lim = q_valid ? arg_n_past + q_t : -1; // last cache row this lane's query may see
+    if (has_new) {
+        // fused RoPE + KV append: rotate k, round k and v to fp16 (nearest even), keep the rows in LDS for this
+        // workgroup's tiles, and the range that owns a row stores it to the cache
+#pragma unroll
+        for (int k = 0; k < NPT; ++k) {
+            const int idx = threadIdx.x + k * ATT_THREADS;
+            if (idx < arg_T * (D / 2)) {
+                const int t = idx / (D / 2), i = idx - t * (D / 2);
+                const int row = arg_n_past + t;
+                const int ia = MODE ? 2 * i : i, ib = MODE ? 2 * i + 1 : i + D / 2;
+                const __half ra = __float2half_rn(n_k[k].x * n_cs[k].x - n_k[k].y * n_cs[k].y);
+                const __half rb = __float2half_rn(n_k[k].x * n_cs[k].y + n_k[k].y * n_cs[k].x);
+                const __half2 hv = __floats2half2_rn(n_v[k].x, n_v[k].y);
+                lds.knew[t][ia] = ra;
+                lds.knew[t][ib] = rb;
+                *reinterpret_cast<__half2 *>(&lds.vnew[t][2 * i]) = hv;
+                if (row >= p_begin && row < p_end) {
+                    Kh[static_cast<int64_t>(row) * D + ia] = ra;
+                    Kh[static_cast<int64_t>(row) * D + ib] = rb;
+                    *reinterpret_cast<__half2 *>(Vh + static_cast<int64_t>(row) * D + 2 * i) = hv;
+                }
+            }
+        }
+        __syncthreads(); // the new rows are in LDS
+        if (key0 < p_end) patch_k(key0, kb);
+    }
+
+    float m_run = -INFINITY, l_run = 0.f; // of this lane's query (the same in its four lanes)
+    v4f oacc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) oacc[nb] = {0.f, 0.f, 0.f, 0.f};
+    int buf = 0;
+
+    while (key0 < p_end) {
+        const int next = key0 + tile_stride;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this tile's V is in LDS (its K is waited for by the compiler)
+        if (has_new && key0 + 16 > arg_n_past) {
+            // rows of this step in the tile, and the rows past the last one (which repeat it): what the cache
+            // held for them is replaced, so that nothing undefined meets a zero probability
+            for (int r = max(0, arg_n_past - key0); r < 16; ++r)
+                if (lane < D / 2)
+                    reinterpret_cast<uint32_t *>(&lds.vt[wave][buf][r][0])[lane] =
+                        reinterpret_cast<const uint32_t *>(&lds.vnew[min(key0 + r, last_row) - arg_n_past][0])[lane];
+            __builtin_amdgcn_wave_barrier();
+        }
+        // logits, transposed: rows = keys 4g..4g+3, column = this lane's query
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int x = 0; x < NA; ++x) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[x], qh[x], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kb[x], ql[x], acc, 0, 0, 0);
+        }
+        float sv[4], tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int key = key0 + 4 * g + r;
+            sv[r] = (key >= p_end || key > lim) ? -INFINITY : acc[r] * fq;
+            tmax = fmaxf(tmax, sv[r]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float mn = fmaxf(m_run, tmax);
+        const float corr = (mn == -INFINITY) ? 1.f : __expf(m_run - mn); // exp(-inf) = 0 on the first visible key
+        float pr[4], ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            pr[r] = (sv[r] == -INFINITY) ? 0.f : __expf(sv[r] - mn);
+            ps += pr[r];
+        }
+        ps += __shfl_xor(ps, 16, 64);
+        ps += __shfl_xor(ps, 32, 64);
+        l_run = l_run * corr + ps;
+        m_run = mn;
+        // the next tile: its K replaces the one just consumed, its V goes to the other buffer
+        if (next < p_end) {
+            load_k(next, kb);
+            patch_k(next, kb);
+            request_v(next, buf ^ 1);
+        }
+        // rescale what has been accumulated (rows of the accumulators are queries 4g..4g+3: their factors come
+        // from the lanes that own those queries, through LDS); skipped when no maximum moved
+        if (__ballot(corr != 1.f) != 0) {
+            if (g == 0) lds.corr[wave][col] = corr;
+            __builtin_amdgcn_wave_barrier();
+            const float4 c4 = *reinterpret_cast<const float4 *>(&lds.corr[wave][4 * g]);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                oacc[nb][0] *= c4.x;
+                oacc[nb][1] *= c4.y;
+                oacc[nb][2] *= c4.z;
+                oacc[nb][3] *= c4.w;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        // P.V: the probabilities are the A operand as they stand (keys 4g..4g+3 of this lane's query)
+        half4 ph, pl;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const _Float16 hi = static_cast<_Float16>(pr[r]);
+            ph[r] = hi;
+            pl[r] = static_cast<_Float16>(pr[r] - static_cast<float>(hi));
+        }
+        const _Float16 *vt = reinterpret_cast<const _Float16 *>(&lds.vt[wave][buf][4 * g][col]);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            half4 vb;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) vb[r] = vt[r * D + 16 * nb]; // V[key 4g + r][16 nb + col]
+            oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(ph, vb, oacc[nb], 0, 0, 0);
+            oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(pl, vb, oacc[nb], 0, 0, 0);
+        }
+        buf ^= 1;
+        key0 = next;
+    }
+
+    // ---- the waves' results meet in LDS (the V tiles are not needed any more) ----
+    __syncthreads();
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) lds.o[wave][4 * g + r][16 * nb + col] = oacc[nb][r];
+    if (g == 0) {
+        lds.m[wave][col] = m_run;
+        lds.l[wave][col] = l_run;
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < nq * D; idx += ATT_THREADS) {
+        const int i = idx / D, e = idx - i * D;
+        float mm = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; ++w) mm = fmaxf(mm, lds.m[w][i]);
+        float ll = 0.f, accv = 0.f;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; ++w) {
+            const float f = (lds.m[w][i] == -INFINITY) ? 0.f : __expf(lds.m[w][i] - mm);
+            ll += lds.l[w][i] * f;
+            accv += lds.o[w][i][e] * f;
+        }
+        const int qj = q0 + i, t = qj / G, hg = qj - t * G;
+        const int64_t head = static_cast<int64_t>(tok0 + t) * a.Hq + kvh * G + hg;
+        if (a.nsplit == 1) { // nothing to merge
+            a.o[head * D + e] = accv / ll;
+            continue;
+        }
+        float *rec = a.part + (head * a.nsplit + split) * (2 + D);
+        if (e == 0) {
+            __hip_atomic_store(rec, mm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(rec + 1, ll, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __hip_atomic_store(rec + 2 + e, accv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (a.nsplit == 1) return;
+
+    // ---- the last workgroup of this (KV head, query group) merges the key ranges ----
+    // o[t][h][:] = sum_i part_i.o * exp(m_i - M) / sum_i part_i.l * exp(m_i - M); a key range that held no
+    // visible key has (max, sum) = (-inf, 0) and drops out.  The records were written with device-scope
+    // stores; vmcnt(0) + barrier makes them complete before the arrival is counted.
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (threadIdx.x == 0) {
+        unsigned *ctr = a.arrivals + (tok0 * a.Hkv + kvh) * nqg + qgrp;
+        const unsigned prev = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = prev + 1 == static_cast<unsigned>(a.nsplit);
+        if (last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); // ready for the next launch
+        lds.last = last ? 1 : 0;
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (!lds.last) return;
+    // one wave per query at a time: lane s takes (max, sum) of key range s, every lane its columns of all ranges
+    for (int qq = wave; qq < nq; qq += ATT_WAVES) {
+        const int qj = q0 + qq, t = qj / G, hg = qj - t * G;
+        const int64_t head = static_cast<int64_t>(tok0 + t) * a.Hq + kvh * G + hg;
+        const float *rec0 = a.part + head * a.nsplit * (2 + D);
+        // 2 + D is even and the records start 8-byte aligned: (max, sum) is one 64-bit load
+        const uint64_t ml = __hip_atomic_load(reinterpret_cast<const uint64_t *>(rec0 + min(lane, a.nsplit - 1) * (2 + D)),
+                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float ms = lane < a.nsplit ? __uint_as_float(static_cast<uint32_t>(ml)) : -INFINITY;
+        const float ls = lane < a.nsplit ? __uint_as_float(static_cast<uint32_t>(ml >> 32)) : 0.f;
+        float mm = ms;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mm = fmaxf(mm, __shfl_xor(mm, off, 64));
+        const float w = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
+        float ll = ls * w;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ll += __shfl_xor(ll, off, 64);
+        const float wgt = w / ll; // lanes past the last range carry weight 0
+        constexpr int CPL = D / 64; // columns per lane
+        float accq[CPL];
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) accq[c] = 0.f;
+        // sixteen ranges at a time: all their loads are out before the first is used
+        for (int s0 = 0; s0 < a.nsplit; s0 += 16) {
+            float v[16][CPL];
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+                    v[jj][c] = __hip_atomic_load(rec0 + min(s0 + jj, a.nsplit - 1) * (2 + D) + 2 + lane + 64 * c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const float ws = (s0 + jj < a.nsplit) ? __shfl(wgt, s0 + jj, 64) : 0.f; // (the clamped loads above are then unused)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) accq[c] = fmaf(v[jj][c], ws, accq[c]);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) a.o[head * D + lane + 64 * c] = accq[c];
+    }
+}
+
+// key ranges for several tokens of one sequence: about one workgroup per compute unit
+static int tile_query_groups(const prima_dims &d, int T, bool batch)
+{
+    const int G = d.n_q_heads / d.n_kv_heads;
+    return batch ? (G + QGM - 1) / QGM * T : (G * T + QGM - 1) / QGM;
+}
+
+static int tile_num_splits(const prima_dims &d, int n_total, int T, bool batch)
+{
+    const int wgs = d.n_kv_heads * tile_query_groups(d, T, batch);
+    const int by_len = (n_total + 16 * ATT_WAVES - 1) / (16 * ATT_WAVES);
+    const int by_grid = (256 + wgs - 1) / wgs; // measured: 128, 192 and 384 workgroups are slower
+    int ns = by_len < by_grid ? by_len : by_grid;
+    if (ns < 1) ns = 1;
+    if (ns > MAX_SPLITS) ns = MAX_SPLITS;
+    return ns;
+}
+
+prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
+                            const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
+                            void *ws, hipStream_t st, const AttnSeqs *seq)
+{
+    AttnArgs a = build_attn_args(d, q, q_rot_out, k_new, v_new, rope_tab, K, V, kv_cap, n_past, T, o, ws, seq);
+    int n_total = n_past + T;
+    if (seq) { // the longest sequence sets the key ranges
+        n_total = 0;
+        for (int b = 0; b < T; ++b) n_total = seq->n_past[b] + 1 > n_total ? seq->n_past[b] + 1 : n_total;
+    }
+    const int want = tile_num_splits(d, n_total, T, seq != nullptr);
+    a.keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
+    a.nsplit = (n_total + a.keys_per_split - 1) / a.keys_per_split;
+    const dim3 grid(a.nsplit, d.n_kv_heads, tile_query_groups(d, T, seq != nullptr)), block(ATT_THREADS);
+    static bool attr_set = false;
+    if (!attr_set) {
+        const void *fns[] = {reinterpret_cast<const void *>(attn_decode_kernel<128, 0>), reinterpret_cast<const void *>(attn_decode_kernel<128, 1>),
+                             reinterpret_cast<const void *>(attn_decode_kernel<64, 0>), reinterpret_cast<const void *>(attn_decode_kernel<64, 1>)};
+        const int sizes[] = {static_cast<int>(sizeof(AttnTileLds<128>)), static_cast<int>(sizeof(AttnTileLds<128>)),
+                             static_cast<int>(sizeof(AttnTileLds<64>)), static_cast<int>(sizeof(AttnTileLds<64>))};
+        for (int i = 0; i < 4; ++i)
+            if (hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, sizes[i]) != hipSuccess) return PRIMA_E_DEVICE;
+        attr_set = true;
+    }
+    if (d.head_dim == 128 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<128, 0>), grid, block, sizeof(AttnTileLds<128>), st, a);
+    else if (d.head_dim == 128 && d.rope_mode == 1) hipLaunchKernelGGL((attn_decode_kernel<128, 1>), grid, block, sizeof(AttnTileLds<128>), st, a);
+    else if (d.head_dim == 64 && d.rope_mode == 0) hipLaunchKernelGGL((attn_decode_kernel<64, 0>), grid, block, sizeof(AttnTileLds<64>), st, a);
+    else if (d.head_dim == 64 && d.rope_mode == 1) hipLaunchKernelGGL((attn_decode_kernel<64, 1>), grid, block, sizeof(AttnTileLds<64>), st, a);
     else return PRIMA_E_SHAPE;
     return last_launch_status();
 }

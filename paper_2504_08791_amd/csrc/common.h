@@ -105,10 +105,6 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
                          const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
                          void *ws, hipStream_t st, const AttnSeqs *seq = nullptr);
 
-prima_status launch_attn_mt(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
-                            const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
-                            void *ws, hipStream_t st);
-
 // one token through a whole window in one launch per FUSED_MAX_LAYERS layers (fused_window.hip); PRIMA_E_SHAPE
 // with nothing launched when the shapes do not qualify
 size_t fused_sync_bytes();
