@@ -430,7 +430,9 @@ static int tile_query_groups(const prima_dims &d, int T, bool batch)
 static int tile_num_splits(const prima_dims &d, int n_total, int T, bool batch)
 {
     const int wgs = d.n_kv_heads * tile_query_groups(d, T, batch);
-    const int by_len = (n_total + 16 * ATT_WAVES - 1) / (16 * ATT_WAVES);
+    // at least two 16-key tiles per wave: every key range costs a record, an arrival and a share of the merge
+    // (4096 rows, one token: 16 ranges 14.8 us, 32 ranges 16.0 us, 8 ranges 16.8 us)
+    const int by_len = (n_total + 32 * ATT_WAVES - 1) / (32 * ATT_WAVES);
     const int by_grid = (256 + wgs - 1) / wgs; // measured: 128, 192 and 384 workgroups are slower
     int ns = by_len < by_grid ? by_len : by_grid;
     if (ns < 1) ns = 1;
