@@ -1,0 +1,48 @@
+"""The one-token mat-vec requests its activations with loads that the compiler does not know to be in flight
+(inline assembly) and waits for them by hand.  Between the requests and the wait nothing may read, copy or
+overwrite the destination registers: this compiles the kernel to assembly and checks exactly that."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2504_08791_amd", "csrc")
+KERNEL = "_ZN5prima26gemv_q4k_persistent_kernelILi1EEEvNS_9PGemvArgsE"
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
+def test_registers_of_early_loads_are_untouched_until_the_wait(tmp_path):
+    out = tmp_path / "k.s"
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-S", "--cuda-device-only", "-o", str(out),
+           os.path.join(CSRC, "q4k_gemv_mfma.hip")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = out.read_text().split("\n")
+    start = next(i for i, l in enumerate(lines) if l.startswith(KERNEL + ":"))
+    end = next(i for i in range(start, len(lines)) if "s_endpgm" in lines[i])
+    body = lines[start:end]
+    loads = []
+    for i, l in enumerate(body):
+        m = re.search(r"global_load_dwordx4 v\[(\d+):(\d+)\], v\[\d+:\d+\], off\s*$", l)
+        if m and i > 0 and "#ASMSTART" in body[i - 1]:
+            loads.append((i, int(m.group(1)), int(m.group(2))))
+    assert len(loads) >= 8, "the hand-waited loads are gone"
+    loads = loads[:8]   # the stand-alone kernel requests them once, first of all
+    wait = next(i for i in range(loads[-1][0], len(body)) if "s_waitcnt vmcnt(5)" in body[i])
+    regs = set()
+    for _, a, b in loads:
+        regs.update(range(a, b + 1))
+    assert len(regs) == 32, "two loads share a destination register"
+    load_lines = {i for i, _, _ in loads}
+    for i in range(loads[0][0] + 1, wait):
+        if i in load_lines:
+            continue
+        code = body[i].split(";")[0]
+        used = {int(m.group(1)) for m in re.finditer(r"\bv(\d+)\b", code)}
+        for m in re.finditer(r"\bv\[(\d+):(\d+)\]", code):
+            used.update(range(int(m.group(1)), int(m.group(2)) + 1))
+        assert not (used & regs), (i, body[i].strip())
