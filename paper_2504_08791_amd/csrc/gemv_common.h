@@ -215,6 +215,7 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
     const int n_tiles = tiles_of(ga);
     p = plan_for(n_tiles, static_cast<int>(ga.n_cols / QK), T, ga.epi);
     if (!p.ok) return PRIMA_E_SHAPE;
+    if (static_cast<int64_t>(n_tiles) * (p.n_wg + 1) >= (int64_t{1} << 31)) return PRIMA_E_SHAPE; // the kernel's 32-bit tile arithmetic
     a = PGemvArgs{};
     int tile0 = 0;
     for (int i = 0; i < ga.nseg; ++i) {
