@@ -33,27 +33,6 @@ struct AttnArgs {
     __half *seq_K[PRIMA_MAX_TOK], *seq_V[PRIMA_MAX_TOK]; // batch: its caches [Hkv][kv_cap][D]
 };
 
-// value of lane (i + n) % 16 of the same 16-lane row
-template <int N>
-__device__ __forceinline__ float row_ror(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf, true));
-}
-__device__ __forceinline__ float row_max16(float v)
-{
-    v = fmaxf(v, row_ror<8>(v));
-    v = fmaxf(v, row_ror<4>(v));
-    v = fmaxf(v, row_ror<2>(v));
-    return fmaxf(v, row_ror<1>(v));
-}
-__device__ __forceinline__ float row_sum16(float v)
-{
-    v += row_ror<8>(v);
-    v += row_ror<4>(v);
-    v += row_ror<2>(v);
-    return v + row_ror<1>(v);
-}
-
 // Rotate the D/8-element slices a lane holds of one head vector: v[x][e] = element 32x + 8c + e.
 // mode 0 pairs element i with i + D/2 (the partner is v[x + NA/2][e] of the same lane), mode 1 pairs
 // 2i with 2i + 1.  tab = this token's D/2 (cos, sin) pairs.  In two steps, so that the table entries can be

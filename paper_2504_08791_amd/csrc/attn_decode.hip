@@ -191,8 +191,7 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
         for (int x = 0; x < NA; ++x)
 #pragma unroll
             for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(qv[x][e]));
-        amax = fmaxf(amax, __shfl_xor(amax, 16, 64)); // the four slices of the query
-        amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+        amax = max_across_32(max_across_16(amax)); // the four slices of the query
         int ex = 0;
         if (amax > 0.f) frexpf(amax, &ex); // amax < 2^ex
         int p = 12 - ex;                   // scaled |q| < 2^12
@@ -270,8 +269,7 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
             sv[r] = (key >= p_end || key > lim) ? -INFINITY : acc[r] * fq;
             tmax = fmaxf(tmax, sv[r]);
         }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        tmax = max_across_32(max_across_16(tmax));
         const float mn = fmaxf(m_run, tmax);
         const float corr = (mn == -INFINITY) ? 1.f : __expf(m_run - mn); // exp(-inf) = 0 on the first visible key
         float pr[4], ps = 0.f;
@@ -280,8 +278,7 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
             pr[r] = (sv[r] == -INFINITY) ? 0.f : __expf(sv[r] - mn);
             ps += pr[r];
         }
-        ps += __shfl_xor(ps, 16, 64);
-        ps += __shfl_xor(ps, 32, 64);
+        ps = add_across_32(add_across_16(ps));
         l_run = l_run * corr + ps;
         m_run = mn;
         // the next tile: its K replaces the one just consumed, its V goes to the other buffer

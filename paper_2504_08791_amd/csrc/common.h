@@ -132,4 +132,69 @@ __device__ __forceinline__ uint32_t lds_address(const void *p)
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(p)); // low half of a flat LDS pointer is the LDS byte address
 }
 
+// value of lane (i + n) % 16 of the same 16-lane row
+template <int N>
+__device__ __forceinline__ float row_ror(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x120 + N, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row_max16(float v)
+{
+    v = fmaxf(v, row_ror<8>(v));
+    v = fmaxf(v, row_ror<4>(v));
+    v = fmaxf(v, row_ror<2>(v));
+    return fmaxf(v, row_ror<1>(v));
+}
+__device__ __forceinline__ float row_sum16(float v)
+{
+    v += row_ror<8>(v);
+    v += row_ror<4>(v);
+    v += row_ror<2>(v);
+    return v + row_ror<1>(v);
+}
+
+// Combining a value across the four 16-lane rows of a wave without LDS permutes: v_permlane16_swap_b32 a, b
+// (gfx950) exchanges the odd rows of a with the even rows of b, v_permlane32_swap_b32 the upper half of a with the
+// lower half of b.  With the value in both registers the results are (rows r0 r0 r2 r2, rows r1 r1 r3 r3) and
+// (lower half twice, upper half twice); combining the two leaves, in every lane, the combination of its own
+// value with the one 16 (32) lanes away.  (ds_bpermute, which __shfl_xor uses for these distances, costs an
+// LDS round trip each.)  Written as inline assembly, with the wait states the instruction needs after a VALU
+// write of its operands and before a VALU read of its results: the compiler's builtin for it was seen to take
+// the two results for the same register (x + y compiled to x + x).
+__device__ __forceinline__ void swap16_rows(unsigned &a, unsigned &b)
+{
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void swap32_halves(unsigned &a, unsigned &b)
+{
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float add_across_16(float v)
+{
+    unsigned a = __builtin_bit_cast(unsigned, v), b = a;
+    swap16_rows(a, b);
+    return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+}
+__device__ __forceinline__ float add_across_32(float v)
+{
+    unsigned a = __builtin_bit_cast(unsigned, v), b = a;
+    swap32_halves(a, b);
+    return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+}
+__device__ __forceinline__ float max_across_16(float v)
+{
+    unsigned a = __builtin_bit_cast(unsigned, v), b = a;
+    swap16_rows(a, b);
+    return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+__device__ __forceinline__ float max_across_32(float v)
+{
+    unsigned a = __builtin_bit_cast(unsigned, v), b = a;
+    swap32_halves(a, b);
+    return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+}
+// over all 64 lanes, the result in every lane: rotations inside the rows, then across them
+__device__ __forceinline__ float wave_sum(float v) { return add_across_32(add_across_16(row_sum16(v))); }
+__device__ __forceinline__ float wave_max(float v) { return max_across_32(max_across_16(row_max16(v))); }
+
 } // namespace prima
