@@ -118,6 +118,32 @@ def test_single_launch_window_matches(gpu_lib):
     assert rel_err(y1.cpu().numpy(), h) < HID_TOL
 
 
+def test_window_equals_its_layers_one_by_one(gpu_lib):
+    """Config 3's shape, 3 layers, one token: the window's output equals the three layers run as three
+    windows of one layer, bit for bit (nothing a layer computes depends on its place in a window, and the
+    scratch carries nothing from layer to layer but the hidden state)."""
+    cfg = CONFIGS["c3"].with_(n_layers=3)
+    d = cfg.dims
+    cap = cfg.n_past + cfg.T
+    xd = _dev(synth.window_input(cfg))
+    dev_layers = [{k: _dev(v) for k, v in synth.layer_tensors(cfg, l, kv_cap=cap).items()} for l in range(cfg.n_layers)]
+    win = gpu_lib.Window(d, dev_layers, cap, T_max=1)
+    win.workspace.fill_(0xFF)
+    y = win.decode(xd, cfg.n_past).clone()
+    rows = [(l["k_cache"][:, cfg.n_past].clone(), l["v_cache"][:, cfg.n_past].clone()) for l in dev_layers]
+    cur = xd
+    for l in dev_layers:
+        l["k_cache"][:, cfg.n_past].zero_()
+        l["v_cache"][:, cfg.n_past].zero_()
+        one = gpu_lib.Window(d, [l], cap, T_max=1)
+        one.workspace.fill_(0xFF)
+        cur = one.decode(cur, cfg.n_past).clone()
+    assert torch.isfinite(y).all()
+    assert torch.equal(y, cur)
+    for l, (k0, v0) in zip(dev_layers, rows):
+        assert torch.equal(l["k_cache"][:, cfg.n_past], k0) and torch.equal(l["v_cache"][:, cfg.n_past], v0)
+
+
 def test_batch_of_sequences_full_shape(gpu_lib):
     """Config 3's layer shape, 2 layers, 8 sequences of different lengths (one token each) in one step."""
     cfg = CONFIGS["c3"].with_(n_layers=2)
