@@ -91,6 +91,55 @@ def gemv(W, x):
     return y
 
 
+FORMATS = {"q4_k": 0, "q5_k": 1, "q6_k": 2, "q8_0": 3, "f16": 4, "f32": 5}
+
+
+def fmt_tensor_bytes(fmt, n_rows, n_cols):
+    lib().orc_fmt_tensor_bytes.restype = C.c_int64
+    return int(lib().orc_fmt_tensor_bytes(C.c_int32(FORMATS[fmt]), C.c_int64(n_rows), C.c_int64(n_cols)))
+
+
+def _wf(fmt, W, n_rows, n_cols):
+    W = np.ascontiguousarray(W, dtype=np.uint8).reshape(-1)
+    assert W.size == fmt_tensor_bytes(fmt, n_rows, n_cols), (fmt, W.size, n_rows, n_cols)
+    return W
+
+
+def fmt_dequant(fmt, W, n_rows, n_cols):
+    """float32 [n_rows, n_cols]: the weights of a tensor (flat uint8) in one of FORMATS."""
+    W = _wf(fmt, W, n_rows, n_cols)
+    out = np.empty((n_rows, n_cols), dtype=np.float32)
+    rc = lib().orc_fmt_dequant(C.c_int32(FORMATS[fmt]), _p(W), C.c_int64(n_rows), C.c_int64(n_cols), _p(out))
+    assert rc == 0
+    return out
+
+
+def fmt_gemv(fmt, W, n_rows, n_cols, x):
+    """y float64 [T, n_rows] = x [T, n_cols] times the transposed weights (fp64 accumulation)."""
+    W = _wf(fmt, W, n_rows, n_cols)
+    x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
+    T = x.shape[0]
+    assert x.shape[1] == n_cols
+    y = np.empty((T, n_rows), dtype=np.float64)
+    rc = lib().orc_fmt_gemv(C.c_int32(FORMATS[fmt]), _p(W), C.c_int64(n_rows), C.c_int64(n_cols), _p(x), C.c_int64(n_cols),
+                            C.c_int32(T), _p(y), C.c_int64(n_rows))
+    assert rc == 0
+    return y
+
+
+def lm_head_fmt(dims, fmt, g_final, w_lm, vocab, x):
+    """logits float64 [T, vocab]: final RMSNorm, then the output matrix in one of FORMATS."""
+    W = _wf(fmt, w_lm, vocab, dims.e)
+    x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
+    T = x.shape[0]
+    g = np.ascontiguousarray(g_final, dtype=np.float32)
+    out = np.empty((T, vocab), dtype=np.float64)
+    dd = _dims(dims)
+    rc = lib().orc_lm_head_fmt(C.byref(dd), C.c_int32(FORMATS[fmt]), _p(g), _p(W), C.c_int64(vocab), _p(x), C.c_int32(T), _p(out))
+    assert rc == 0
+    return out
+
+
 def rmsnorm(x, g, eps):
     x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
     g = np.ascontiguousarray(g, dtype=np.float32)

@@ -19,6 +19,9 @@
  * model families (Llama, Qwen) but writes none of the layer formulas; each
  * function below states the standard definition it evaluates.
  *
+ * The other weight formats the paper lists (Q5_K, Q6_K, Q8_0, FP16, FP32) are
+ * decoded further down; their pins are in tests/test_oracle_formats.py.
+ *
  * Pins (tests/test_oracle_*.py): hand-built super-blocks with values known by
  * mental arithmetic, exact rational evaluation of the dequantisation rule,
  * brute-force dense products, library fp64 matmul / softmax, invariants of
@@ -154,6 +157,120 @@ int orc_q4k_gemv(const uint8_t *W, int64_t n_rows, int64_t n_cols,
             }
         }
         for (int t = 0; t < T; ++t) y[(int64_t)t * ldy + r] = acc[t];
+    }
+    return 0;
+}
+
+/* ---------- the other weight formats of the set Q (Sec. 4 / App. A.3, the profiler's list of formats:
+ * Q4_K, Q5_K, Q6_K, Q8_0, FP16, FP32) ----------
+ * The paper names the formats and gives no layout.  Field sizes and the value rule are those the names
+ * stand for; the placement of the fields is this repository's (version 1): each field of a tensor is a
+ * plane of its own, the planes follow one another without padding, and inside a plane blocks are in
+ * row-major order (row r, block b -> index r * (n_cols / block) + b).  n = number of 256-weight
+ * super-blocks of the tensor.
+ *
+ *   Q5_K (5.5 bits per weight): plane 1, 16 bytes per super-block: d, dmin (binary16) and the sixteen
+ *     6-bit fields exactly as bytes 0..15 of a Q4_K super-block; plane 2 at byte 16 n, 128 bytes per
+ *     super-block: low 4 bits of weight t in byte t/2 (low nibble when t is even); plane 3 at byte
+ *     144 n, 32 bytes per super-block: bit 4 of weight t is bit t%8 of byte t/8.
+ *     w = d * sc_s * q - dmin * m_s, q in 0..31, s = t / 32.
+ *   Q6_K (6.5625 bits): plane 1, 128 bytes per super-block: low 4 bits (as above); plane 2 at 128 n,
+ *     64 bytes: bits 4..5 of weight t are bits 2(t%4), 2(t%4)+1 of byte t/4; plane 3 at 192 n, 16
+ *     signed bytes: sc_s for s = t / 16; plane 4 at 208 n: d (binary16).
+ *     w = d * sc_s * (q - 32), q in 0..63.
+ *   Q8_0 (8.5 bits): plane 1: one signed byte per weight; plane 2 at n_rows * n_cols: d (binary16) per
+ *     32 weights.  w = d * q.
+ *   FP16, FP32: row-major numbers.
+ * Rounding: every product above is exact in fp32 (at most 11 + 7 + 5 significant bits), so w32 is the
+ * fp32 number nearest to the exact value in each format.
+ */
+enum { FMT_Q4_K = 0, FMT_Q5_K = 1, FMT_Q6_K = 2, FMT_Q8_0 = 3, FMT_F16 = 4, FMT_F32 = 5 };
+
+static float half_at(const uint8_t *p) { return (float)half_to_double((uint16_t)(p[0] | (p[1] << 8))); }
+
+int64_t orc_fmt_tensor_bytes(int32_t fmt, int64_t n_rows, int64_t n_cols)
+{
+    if (n_rows < 0 || n_cols < 0 || n_cols % QK) return -1;
+    int64_t n = n_rows * (n_cols / QK);
+    switch (fmt) {
+    case FMT_Q4_K: return n * 144;
+    case FMT_Q5_K: return n * 176;
+    case FMT_Q6_K: return n * 210;
+    case FMT_Q8_0: return n * 272;
+    case FMT_F16: return n * 512;
+    case FMT_F32: return n * 1024;
+    }
+    return -1;
+}
+
+/* the dequantised weights of row r, fp32 */
+static void decode_row(int32_t fmt, const uint8_t *W, int64_t n_rows, int64_t n_cols, int64_t r, float *w)
+{
+    int64_t nb = n_cols / QK, n = n_rows * nb;
+    for (int64_t b = 0; b < nb; ++b) {
+        int64_t blk = r * nb + b;
+        float *o = w + b * QK;
+        if (fmt == FMT_Q4_K) {
+            decode_block(W + blk * BLOCK_BYTES, o);
+        } else if (fmt == FMT_Q5_K) {
+            const uint8_t *hdr = W + blk * 16, *qs = W + 16 * n + blk * 128, *qh = W + 144 * n + blk * 32;
+            float d = half_at(hdr), dmin = half_at(hdr + 2);
+            for (int t = 0; t < QK; ++t) {
+                int s = t / 32;
+                float sc = (float)field6(hdr, s), m = (float)field6(hdr, 8 + s); /* field6 skips the 4 bytes of d, dmin */
+                int lo = (t & 1) ? (qs[t / 2] >> 4) : (qs[t / 2] & 15);
+                int hi = (qh[t / 8] >> (t % 8)) & 1;
+                volatile float p1 = d * sc;
+                volatile float p2 = p1 * (float)(lo | (hi << 4));
+                volatile float p3 = dmin * m;
+                o[t] = p2 - p3;
+            }
+        } else if (fmt == FMT_Q6_K) {
+            const uint8_t *ql = W + blk * 128, *qh = W + 128 * n + blk * 64;
+            const int8_t *sc = (const int8_t *)(W + 192 * n + blk * 16);
+            float d = half_at(W + 208 * n + blk * 2);
+            for (int t = 0; t < QK; ++t) {
+                int lo = (t & 1) ? (ql[t / 2] >> 4) : (ql[t / 2] & 15);
+                int hi = (qh[t / 4] >> (2 * (t % 4))) & 3;
+                volatile float p1 = d * (float)sc[t / 16];
+                o[t] = p1 * (float)((lo | (hi << 4)) - 32);
+            }
+        } else if (fmt == FMT_Q8_0) {
+            const int8_t *q = (const int8_t *)W + blk * QK;
+            const uint8_t *dp = W + n_rows * n_cols + blk * 16; /* 8 scales of 2 bytes per 256 weights */
+            for (int t = 0; t < QK; ++t) o[t] = half_at(dp + 2 * (t / 32)) * (float)q[t];
+        } else if (fmt == FMT_F16) {
+            for (int t = 0; t < QK; ++t) o[t] = half_at(W + (blk * QK + t) * 2);
+        } else {
+            memcpy(o, W + blk * QK * 4, QK * 4);
+        }
+    }
+}
+
+int orc_fmt_dequant(int32_t fmt, const uint8_t *W, int64_t n_rows, int64_t n_cols, float *out)
+{
+    if (orc_fmt_tensor_bytes(fmt, n_rows, n_cols) < 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < n_rows; ++r) decode_row(fmt, W, n_rows, n_cols, r, out + r * n_cols);
+    return 0;
+}
+
+/* y[t][r] = sum_c w32[r][c] * x[t][c], fp64 accumulation, ascending c */
+int orc_fmt_gemv(int32_t fmt, const uint8_t *W, int64_t n_rows, int64_t n_cols,
+                 const double *x, int64_t ldx, int32_t T, double *y, int64_t ldy)
+{
+    if (orc_fmt_tensor_bytes(fmt, n_rows, n_cols) < 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < n_rows; ++r) {
+        float *w = malloc(sizeof(float) * (size_t)(n_cols ? n_cols : 1));
+        decode_row(fmt, W, n_rows, n_cols, r, w);
+        for (int t = 0; t < T; ++t) {
+            const double *xt = x + (int64_t)t * ldx;
+            double a = 0.0;
+            for (int64_t c = 0; c < n_cols; ++c) a += (double)w[c] * xt[c];
+            y[(int64_t)t * ldy + r] = a;
+        }
+        free(w);
     }
     return 0;
 }
@@ -320,6 +437,18 @@ int orc_lm_head(const orc_dims *d, const float *g_final, const uint8_t *w_lm, in
     double *n = malloc(sizeof(double) * T * e);
     for (int j = 0; j < T; ++j) orc_rmsnorm(x + (int64_t)j * e, g_final, e, d->rms_eps, n + (int64_t)j * e);
     int rc = orc_q4k_gemv(w_lm, vocab, e, n, e, T, logits, vocab);
+    free(n);
+    return rc;
+}
+
+/* the same with the output matrix in any format of the set */
+int orc_lm_head_fmt(const orc_dims *d, int32_t fmt, const float *g_final, const uint8_t *w_lm, int64_t vocab,
+                    const double *x, int32_t T, double *logits)
+{
+    int e = d->e;
+    double *n = malloc(sizeof(double) * T * e);
+    for (int j = 0; j < T; ++j) orc_rmsnorm(x + (int64_t)j * e, g_final, e, d->rms_eps, n + (int64_t)j * e);
+    int rc = orc_fmt_gemv(fmt, w_lm, vocab, e, n, e, T, logits, vocab);
     free(n);
     return rc;
 }

@@ -45,6 +45,40 @@ def q4k_tensor(config_id, layer, tensor, n_rows, n_cols):
     return raw.reshape(n_rows, n_cols // QK, BLOCK_BYTES)
 
 
+FORMAT_BITS = {"q4_k": 4.5, "q5_k": 5.5, "q6_k": 6.5625, "q8_0": 8.5, "f16": 16, "f32": 32}
+
+
+def fmt_tensor(config_id, layer, tensor, fmt, n_rows, n_cols):
+    """Flat uint8 tensor in one of the other weight formats (planes one after the other; see the layout
+    text of the format).  As for Q4_K every quant, sub-scale and sub-min field is uniform over its whole
+    range, which uniform random bytes give whatever the bit placement; only the binary16 scales are written
+    as numbers (at their byte positions, uniform in a range that keeps weights of the order of 0.1)."""
+    assert n_cols % QK == 0
+    rng = _rng(config_id, layer, tensor)
+    n = n_rows * (n_cols // QK)
+    if fmt == "q4_k":
+        return q4k_tensor(config_id, layer, tensor, n_rows, n_cols).reshape(-1)
+    if fmt in ("f16", "f32"):
+        w = (0.05 * rng.standard_normal((n_rows, n_cols), dtype=np.float32))
+        return w.astype(np.float16 if fmt == "f16" else np.float32).view(np.uint8).reshape(-1)
+    nbytes = int(n * QK * FORMAT_BITS[fmt] / 8)
+    raw = rng.bit_generator.random_raw((nbytes + 7) // 8).view(np.uint8)[:nbytes].copy()
+
+    def scales(count, lo, hi):
+        u = rng.random(count, dtype=np.float32)
+        return (np.float32(lo) + np.float32(hi - lo) * u).astype(np.float16).view(np.uint8)
+
+    if fmt == "q5_k":     # d, dmin: bytes 0..3 of every 16-byte header (first plane)
+        raw[:16 * n].reshape(n, 16)[:, 0:4] = scales(2 * n, 5e-4, 2e-3).reshape(n, 4)
+    elif fmt == "q6_k":   # d: the last plane, 2 bytes per super-block
+        raw[208 * n:] = scales(n, 2e-5, 8e-5)
+    elif fmt == "q8_0":   # d: the last plane, 2 bytes per 32 weights
+        raw[n_rows * n_cols:] = scales(8 * n, 5e-4, 2e-3)
+    else:
+        raise KeyError(fmt)
+    return raw
+
+
 def normal_f32(config_id, layer, tensor, shape):
     """fp32 N(0,1)."""
     return _rng(config_id, layer, tensor).standard_normal(shape, dtype=np.float64).astype(np.float32)
