@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0,
                     help="side measurement: B sequences of the config's context length, one token each per step")
+    ap.add_argument("--format", default="", choices=["", "q5_k", "q6_k", "q8_0", "f16", "f32"],
+                    help="side measurement: the mat-vec of another weight format at the output layer's and the down projection's shape")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 256 MiB device copies first (reference kernel of known traffic for counter runs)")
     args = ap.parse_args()
@@ -52,6 +54,8 @@ def main():
         cfg = cfg.with_(n_layers=args.layers)
     if args.batch:
         return bench_batch(args, cfg)
+    if args.format:
+        return bench_format(args)
     d = cfg.dims
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -265,6 +269,94 @@ def bench_batch(args, cfg):
         out["max_rel_err_vs_oracle"] = float((np.abs(got - ref) / np.maximum(np.abs(ref), np.maximum(rms, 1e-30))).max())
         out["cpu_baseline"] = {"value": round(B / cpu_seconds, 4), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"the whole step once ({cpu_seconds:.1f} s of CPU time)"}
+    print(json.dumps(out), flush=True)
+
+
+def bench_format(args):
+    """Mat-vec of one of the other weight formats, one token: the output layer of config 4 (128256 x 8192, the tensor a
+    "Q4K" model most often keeps in another format) with the final RMSNorm in front, and the down projection's shape
+    (8192 x 28672).  Each launch reads a copy that the previous launches did not touch (the smaller matrix would
+    otherwise sit in the 256 MB last-level cache)."""
+    import numpy as np
+    import torch
+    import paper_2504_08791_amd as prima
+    from workloads import synth
+    from workloads.configs import CONFIGS
+
+    fmt = args.format
+    cfg = CONFIGS["c4k1"]
+    d = cfg.dims
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+    res = {}
+    g_host = synth.gain_f32(cfg.config_id, 0, "g_final", d.e)
+    g = torch.from_numpy(g_host).to(dev)
+    for name, rows, cols, with_norm in (("output_layer", cfg.vocab, d.e, True), ("down_projection", d.e, d.ffn, False)):
+        nbytes = prima.fmt_tensor_bytes(fmt, rows, cols)
+        W_host = synth.fmt_tensor(cfg.config_id, 0, "w_lm" if with_norm else "wdown", fmt, rows, cols)
+        copies = [torch.from_numpy(W_host).to(dev)]
+        while len(copies) * nbytes < 1_200_000_000:
+            copies.append(copies[0].clone())
+        x_host = synth.normal_f32(cfg.config_id, 0, "x_in", (1, cols))
+        x = torch.from_numpy(x_host).to(dev)
+        y = torch.empty((1, rows), dtype=torch.float32, device=dev)
+
+        def launch(i):
+            if with_norm:
+                prima.lm_head_fmt(d, fmt, g, copies[i % len(copies)], rows, x, logits=y)
+            else:
+                prima.fmt_gemv(fmt, copies[i % len(copies)], rows, cols, x, y=y)
+        for i in range(args.warmup):
+            launch(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(args.steps):
+            launch(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / args.steps
+        res[name] = {"rows": rows, "cols": cols, "bytes_per_launch": nbytes, "avg_launch_us": round(us, 2),
+                     "gbps": round(nbytes / us / 1e3, 1), "frac_of_8000": round(nbytes / us / 1e3 / 8000.0, 4)}
+        if not args.no_cpu_baseline:
+            import oracle
+            launch(0)
+            got = y.cpu().numpy().astype(np.float64)[0]
+            sample = np.unique(np.concatenate([np.arange(0, 2048), np.arange(rows - 2048, rows)]))
+            # the sampled rows as a tensor of their own: plane by plane (the planes of a tensor are row-major)
+            n, nb = rows * cols // 256, cols // 256
+            per_block = {"q5_k": [16, 128, 32], "q6_k": [128, 64, 16, 2], "q8_0": [256, 16], "f16": [512], "f32": [1024]}[fmt]
+            parts, off = [], 0
+            for pb in per_block:
+                plane = W_host[off:off + n * pb].reshape(rows, nb * pb)
+                parts.append(plane[sample].reshape(-1))
+                off += n * pb
+            Ws = np.concatenate(parts)
+            xin = x_host.astype(np.float64)
+            t0 = time.perf_counter()
+            if with_norm:
+                ref = oracle.lm_head_fmt(d, fmt, g_host, Ws, len(sample), xin)[0]
+            else:
+                ref = oracle.fmt_gemv(fmt, Ws, len(sample), cols, xin)[0]
+            cpu_seconds = time.perf_counter() - t0
+            rms = np.sqrt((ref ** 2).mean())
+            res[name]["max_rel_err_vs_oracle_sampled_rows"] = float((np.abs(got[sample] - ref) / np.maximum(np.abs(ref), rms)).max())
+            res[name]["cpu_oracle_rows_per_s"] = round(len(sample) / cpu_seconds, 1)
+            res[name]["cpu_cores"] = oracle.num_threads()
+        del copies
+    o = res["output_layer"]
+    out = {
+        "metric": f"weight streaming of the {fmt} mat-vec (one token), GB/s vs MI355X peak", "value": o["gbps"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(o["avg_launch_us"] / 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"output layer of config 4 ({cfg.vocab} x {d.e}) in {fmt}, final RMSNorm in front, T=1; "
+                               f"also the down projection's shape ({d.e} x {d.ffn})"},
+        "roofline": {"bound": "hbm", "kernel": "fmt_gemv_kernel (output layer launch)", "achieved": o["gbps"], "peak": 8000.0,
+                     "unit": "GB/s", "frac": o["frac_of_8000"], "bytes_per_launch": o["bytes_per_launch"],
+                     "avg_launch_us": o["avg_launch_us"], "traffic": None},
+        "shapes": res,
+    }
     print(json.dumps(out), flush=True)
 
 

@@ -205,6 +205,53 @@ prima_status prima_lm_head(const prima_dims *d, const float *g_final, const void
 
 size_t prima_lm_head_workspace_bytes(const prima_dims *d, int64_t vocab, int32_t T);
 
+/*
+ * The other weight formats of the format set (Sec. 4 / App. A.3, the profiler paragraph: a "Q4K" model
+ * keeps some tensors in Q5_K, Q6_K, Q8_0, FP16 or FP32).  The paper names the formats and gives no layout;
+ * field sizes and value rules are the formats' own, the placement is this library's (version 1): every
+ * field of a tensor is a plane of its own, planes follow one another without padding, blocks inside a
+ * plane are in row-major order (row r, block b -> r * n_cols / block + b).  n = n_rows * n_cols / 256.
+ *   Q5_K  [n][16]: d, dmin (binary16, little endian), then sixteen 6-bit fields sc_0..7, m_0..7 as a
+ *         96-bit little-endian stream (bytes 0..15 of a Q4_K super-block) | [n][128]: bits 0..3 of
+ *         weight t in byte t/2, low nibble when t is even | [n][32]: bit 4 of weight t = bit t%8 of byte
+ *         t/8.   w = d sc_s q - dmin m_s, q in 0..31, s = t/32.
+ *   Q6_K  [n][128]: bits 0..3 (as above) | [n][64]: bits 4..5 of weight t = bits 2(t%4), 2(t%4)+1 of byte
+ *         t/4 | [n][16]: signed bytes sc_s, s = t/16 | [n]: d (binary16).   w = d sc_s (q - 32), q in 0..63.
+ *   Q8_0  [n_rows*n_cols]: one signed byte per weight | [n_rows*n_cols/32]: d (binary16) per 32 weights.
+ *         w = d q.
+ *   F16, F32: row-major numbers.
+ * Every product above is exact in fp32, so a dequantised weight is the fp32 number nearest to the exact
+ * value; prima_fmt_dequant is bit-exact by contract.
+ */
+typedef enum prima_format {
+    PRIMA_FMT_Q4_K = 0, /* 144-byte super-blocks (see prima_layer); has entry points of its own */
+    PRIMA_FMT_Q5_K = 1,
+    PRIMA_FMT_Q6_K = 2,
+    PRIMA_FMT_Q8_0 = 3,
+    PRIMA_FMT_F16 = 4,
+    PRIMA_FMT_F32 = 5
+} prima_format;
+
+/* Bytes of an n_rows x n_cols tensor in format fmt (n_cols % 256 == 0); 0 for bad arguments. */
+size_t prima_fmt_tensor_bytes(int32_t fmt, int64_t n_rows, int64_t n_cols);
+
+/* Test hook: out[r*n_cols + c] = fp32 value of weight (r, c); any format.  W, out: device, 16-byte aligned. */
+prima_status prima_fmt_dequant(int32_t fmt, const void *W, int64_t n_rows, int64_t n_cols, float *out, void *hip_stream);
+
+/*
+ * Mat-vec in formats Q5_K .. F32 (PRIMA_FMT_Q4_K: PRIMA_E_SHAPE, use prima_q4k_gemv):
+ *     y[t*ldy + r] = sum_c W[r][c] * x[t*ldx + c],  r < n_rows, t < T,  1 <= T <= PRIMA_MAX_TOK.
+ * W: device, 16-byte aligned, prima_fmt_tensor_bytes(fmt, n_rows, n_cols) bytes.  x: fp32, 16-byte aligned,
+ * ldx >= n_cols, ldx % 4 == 0.  y: fp32, ldy >= n_rows, must not overlap x.  No scratch.  Results do not
+ * depend on the launch (fixed order of additions).
+ */
+prima_status prima_fmt_gemv(int32_t fmt, const void *W, int64_t n_rows, int64_t n_cols,
+                            const float *x, int64_t ldx, int32_t T, float *y, int64_t ldy, void *hip_stream);
+
+/* Output layer with w_lm in formats Q5_K .. F32 (commonly Q6_K in a "Q4K" model): as prima_lm_head, no scratch. */
+prima_status prima_lm_head_fmt(const prima_dims *d, int32_t fmt, const float *g_final, const void *w_lm, int64_t vocab,
+                               const float *x, int32_t T, float *logits, void *hip_stream);
+
 /* Bytes of scratch the window calls need for up to T tokens and kv_cap cache rows. */
 size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
 

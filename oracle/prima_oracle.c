@@ -169,15 +169,20 @@ int orc_q4k_gemv(const uint8_t *W, int64_t n_rows, int64_t n_cols,
  * row-major order (row r, block b -> index r * (n_cols / block) + b).  n = number of 256-weight
  * super-blocks of the tensor.
  *
+ * The quant bits of Q5_K and Q6_K are placed word by word (32-bit words, byte t%4 of its word holds bits
+ * of weight t), so that four weights come out of a word with one mask:
+ *   low 4 bits: one word per 8 weights; byte t%4 of word t/8 holds weight t in its low nibble when
+ *     t%8 < 4, in its high nibble otherwise;
+ *   bits 4..5 (Q6_K): one word per 16 weights; bits 2g, 2g+1 of byte t%4 of word t/16, g = (t%16)/4;
+ *   bit 4 (Q5_K): one word per 32 weights; bit g of byte t%4 of word t/32, g = (t%32)/4.
+ *
  *   Q5_K (5.5 bits per weight): plane 1, 16 bytes per super-block: d, dmin (binary16) and the sixteen
  *     6-bit fields exactly as bytes 0..15 of a Q4_K super-block; plane 2 at byte 16 n, 128 bytes per
- *     super-block: low 4 bits of weight t in byte t/2 (low nibble when t is even); plane 3 at byte
- *     144 n, 32 bytes per super-block: bit 4 of weight t is bit t%8 of byte t/8.
+ *     super-block: the low 4 bits; plane 3 at byte 144 n, 32 bytes per super-block: bit 4.
  *     w = d * sc_s * q - dmin * m_s, q in 0..31, s = t / 32.
- *   Q6_K (6.5625 bits): plane 1, 128 bytes per super-block: low 4 bits (as above); plane 2 at 128 n,
- *     64 bytes: bits 4..5 of weight t are bits 2(t%4), 2(t%4)+1 of byte t/4; plane 3 at 192 n, 16
- *     signed bytes: sc_s for s = t / 16; plane 4 at 208 n: d (binary16).
- *     w = d * sc_s * (q - 32), q in 0..63.
+ *   Q6_K (6.5625 bits): plane 1, 128 bytes per super-block: the low 4 bits; plane 2 at 128 n, 64
+ *     bytes: bits 4..5; plane 3 at 192 n, 16 signed bytes: sc_s for s = t / 16; plane 4 at 208 n:
+ *     d (binary16).   w = d * sc_s * (q - 32), q in 0..63.
  *   Q8_0 (8.5 bits): plane 1: one signed byte per weight; plane 2 at n_rows * n_cols: d (binary16) per
  *     32 weights.  w = d * q.
  *   FP16, FP32: row-major numbers.
@@ -187,6 +192,13 @@ int orc_q4k_gemv(const uint8_t *W, int64_t n_rows, int64_t n_cols,
 enum { FMT_Q4_K = 0, FMT_Q5_K = 1, FMT_Q6_K = 2, FMT_Q8_0 = 3, FMT_F16 = 4, FMT_F32 = 5 };
 
 static float half_at(const uint8_t *p) { return (float)half_to_double((uint16_t)(p[0] | (p[1] << 8))); }
+
+/* low 4 bits of weight t of a super-block whose nibble plane starts at nib */
+static int low4(const uint8_t *nib, int t)
+{
+    uint8_t byte = nib[(t / 8) * 4 + t % 4];
+    return (t % 8 < 4) ? (byte & 15) : (byte >> 4);
+}
 
 int64_t orc_fmt_tensor_bytes(int32_t fmt, int64_t n_rows, int64_t n_cols)
 {
@@ -218,8 +230,8 @@ static void decode_row(int32_t fmt, const uint8_t *W, int64_t n_rows, int64_t n_
             for (int t = 0; t < QK; ++t) {
                 int s = t / 32;
                 float sc = (float)field6(hdr, s), m = (float)field6(hdr, 8 + s); /* field6 skips the 4 bytes of d, dmin */
-                int lo = (t & 1) ? (qs[t / 2] >> 4) : (qs[t / 2] & 15);
-                int hi = (qh[t / 8] >> (t % 8)) & 1;
+                int lo = low4(qs, t);
+                int hi = (qh[(t / 32) * 4 + t % 4] >> ((t % 32) / 4)) & 1;
                 volatile float p1 = d * sc;
                 volatile float p2 = p1 * (float)(lo | (hi << 4));
                 volatile float p3 = dmin * m;
@@ -230,8 +242,8 @@ static void decode_row(int32_t fmt, const uint8_t *W, int64_t n_rows, int64_t n_
             const int8_t *sc = (const int8_t *)(W + 192 * n + blk * 16);
             float d = half_at(W + 208 * n + blk * 2);
             for (int t = 0; t < QK; ++t) {
-                int lo = (t & 1) ? (ql[t / 2] >> 4) : (ql[t / 2] & 15);
-                int hi = (qh[t / 4] >> (2 * (t % 4))) & 3;
+                int lo = low4(ql, t);
+                int hi = (qh[(t / 16) * 4 + t % 4] >> (2 * ((t % 16) / 4))) & 3;
                 volatile float p1 = d * (float)sc[t / 16];
                 o[t] = p1 * (float)((lo | (hi << 4)) - 32);
             }

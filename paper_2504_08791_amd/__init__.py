@@ -66,6 +66,52 @@ def q4k_gemv(W, x, y=None, workspace=None):
     return y
 
 
+def fmt_tensor_bytes(fmt, rows, cols):
+    return _ffi.lib().prima_fmt_tensor_bytes(_ffi.FORMATS[fmt], rows, cols)
+
+
+def fmt_dequant(fmt, W, rows, cols):
+    """W: flat uint8 tensor in format fmt ("q5_k", "q6_k", "q8_0", "f16", "f32", "q4_k") -> float32 [rows, cols]."""
+    _need(W, torch.uint8, "W")
+    if W.numel() != fmt_tensor_bytes(fmt, rows, cols):
+        raise ValueError(f"W holds {W.numel()} bytes, a {rows} x {cols} {fmt} tensor has {fmt_tensor_bytes(fmt, rows, cols)}")
+    out = torch.empty((rows, cols), dtype=torch.float32, device=W.device)
+    _ffi.check(_ffi.lib().prima_fmt_dequant(_ffi.FORMATS[fmt], _ptr(W), rows, cols, _ptr(out), _stream()), "prima_fmt_dequant")
+    return out
+
+
+def fmt_gemv(fmt, W, rows, cols, x, y=None):
+    """y[t, r] = sum_c W[r, c] x[t, c];  W flat uint8 in format fmt (not "q4_k"), x float32 [T, cols]."""
+    _need(W, torch.uint8, "W")
+    for t, name in ((x, "x"), (y, "y")):     # rows may be strided (ldx, ldy), elements of a row may not
+        if t is not None and not (t.is_cuda and t.dtype == torch.float32 and t.dim() == 2 and t.stride(1) == 1):
+            raise TypeError(f"{name}: need a 2-d CUDA float32 tensor with contiguous rows")
+    if W.numel() != fmt_tensor_bytes(fmt, rows, cols):
+        raise ValueError(f"W holds {W.numel()} bytes, a {rows} x {cols} {fmt} tensor has {fmt_tensor_bytes(fmt, rows, cols)}")
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, rows), dtype=torch.float32, device=x.device)
+    _ffi.check(_ffi.lib().prima_fmt_gemv(_ffi.FORMATS[fmt], _ptr(W), rows, cols, _ptr(x), x.stride(0), T, _ptr(y), y.stride(0),
+                                         _stream()), "prima_fmt_gemv")
+    return y
+
+
+def lm_head_fmt(dims, fmt, g_final, w_lm, vocab, x, logits=None):
+    """logits[t, v] = W_lm . rmsnorm(x[t]; g_final) with W_lm flat uint8 in format fmt (not "q4_k")."""
+    d = make_dims(dims)
+    _need(g_final, torch.float32, "g_final")
+    _need(w_lm, torch.uint8, "w_lm")
+    _need(x, torch.float32, "x")
+    if w_lm.numel() != fmt_tensor_bytes(fmt, vocab, d.e):
+        raise ValueError("w_lm has the wrong size for its format")
+    T = x.shape[0]
+    if logits is None:
+        logits = torch.empty((T, vocab), dtype=torch.float32, device=x.device)
+    _ffi.check(_ffi.lib().prima_lm_head_fmt(C.byref(d), _ffi.FORMATS[fmt], _ptr(g_final), _ptr(w_lm), vocab, _ptr(x), T,
+                                            _ptr(logits), _stream()), "prima_lm_head_fmt")
+    return logits
+
+
 def attn_workspace_bytes(dims, kv_cap, T):
     d = make_dims(dims)
     return _ffi.lib().prima_attn_workspace_bytes(C.byref(d), kv_cap, T)

@@ -13,7 +13,9 @@ STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIG
 EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", "prima_attn_decode",
            "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_window_decode_profiled", "prima_layer_decode_taps",
            "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
-           "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch"]
+           "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
+           "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt"]
+FORMATS = {"q4_k": 0, "q5_k": 1, "q6_k": 2, "q8_0": 3, "f16": 4, "f32": 5}
 
 
 class Dims(C.Structure):
@@ -61,6 +63,14 @@ def lib():
         L.prima_lm_head.argtypes = [dp, vp, vp, i64, vp, i32, vp, vp, sz, vp]
         L.prima_lm_head_workspace_bytes.argtypes = [dp, i64, i32]
         L.prima_lm_head_workspace_bytes.restype = sz
+        L.prima_fmt_tensor_bytes.argtypes = [i32, i64, i64]
+        L.prima_fmt_tensor_bytes.restype = sz
+        L.prima_fmt_dequant.argtypes = [i32, vp, i64, i64, vp, vp]
+        L.prima_fmt_dequant.restype = C.c_int
+        L.prima_fmt_gemv.argtypes = [i32, vp, i64, i64, vp, i64, i32, vp, i64, vp]
+        L.prima_fmt_gemv.restype = C.c_int
+        L.prima_lm_head_fmt.argtypes = [dp, i32, vp, vp, i64, vp, i32, vp, vp]
+        L.prima_lm_head_fmt.restype = C.c_int
         L.prima_workspace_bytes.argtypes = [dp, i32, i32]
         L.prima_workspace_bytes.restype = sz
         L.prima_stream_read_probe.argtypes = [vp, sz, vp, vp]

@@ -77,6 +77,12 @@ struct GemvArgs {
     float eps;         // X_RMSNORM
 };
 
+// the other weight formats (fmt_gemv.hip)
+size_t fmt_tensor_bytes(int fmt, int64_t n_rows, int64_t n_cols);
+prima_status launch_fmt_dequant(int fmt, const uint8_t *W, int64_t n_rows, int64_t n_cols, float *out, hipStream_t st);
+prima_status launch_fmt_gemv(int fmt, const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
+                             const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy, hipStream_t st);
+
 prima_status launch_dequant(const uint8_t *W, int64_t n_rows, int64_t n_cols, float *out, hipStream_t st);
 // ws: scratch; its first arrivals_region bytes (>= gemv_arrivals_bytes(rows)) are counters that must be
 // zero before the first launch (launch_zero_arrivals) and are left zero by every launch; the partial

@@ -252,6 +252,41 @@ prima_status prima_attn_decode(const prima_dims *d, const float *q, const void *
                        kv_cap, n_past, T, o, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
+size_t prima_fmt_tensor_bytes(int32_t fmt, int64_t n_rows, int64_t n_cols) { return fmt_tensor_bytes(fmt, n_rows, n_cols); }
+
+prima_status prima_fmt_dequant(int32_t fmt, const void *W, int64_t n_rows, int64_t n_cols, float *out, void *hip_stream)
+{
+    if (fmt == PRIMA_FMT_Q4_K) return prima_q4k_dequant(W, n_rows, n_cols, out, hip_stream);
+    if (fmt < PRIMA_FMT_Q4_K || fmt > PRIMA_FMT_F32 || n_rows < 0 || n_cols < 0 || n_cols % QK) return PRIMA_E_SHAPE;
+    if (n_rows == 0 || n_cols == 0) return PRIMA_OK;
+    if (!W || !out) return PRIMA_E_NULL;
+    if (!aligned(W, 16) || !aligned(out, 16)) return PRIMA_E_ALIGN;
+    return launch_fmt_dequant(fmt, static_cast<const uint8_t *>(W), n_rows, n_cols, out, static_cast<hipStream_t>(hip_stream));
+}
+
+prima_status prima_fmt_gemv(int32_t fmt, const void *W, int64_t n_rows, int64_t n_cols,
+                            const float *x, int64_t ldx, int32_t T, float *y, int64_t ldy, void *hip_stream)
+{
+    if (!W || !x || !y) return PRIMA_E_NULL;
+    if (fmt <= PRIMA_FMT_Q4_K || fmt > PRIMA_FMT_F32) return PRIMA_E_SHAPE;
+    if (n_rows < 0 || n_cols <= 0 || n_cols % QK || ldx < n_cols || ldy < n_rows) return PRIMA_E_SHAPE;
+    if (T < 1 || T > PRIMA_MAX_TOK) return PRIMA_E_RANGE;
+    if (!aligned(W, 16) || !aligned(x, 16) || !aligned(y, 4) || ldx % 4) return PRIMA_E_ALIGN;
+    return launch_fmt_gemv(fmt, static_cast<const uint8_t *>(W), n_rows, n_cols, x, ldx, T, nullptr, 0.f, nullptr, 0, y, ldy,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
+prima_status prima_lm_head_fmt(const prima_dims *d, int32_t fmt, const float *g_final, const void *w_lm, int64_t vocab,
+                               const float *x, int32_t T, float *logits, void *hip_stream)
+{
+    if (!d || !g_final || !w_lm || !x || !logits) return PRIMA_E_NULL;
+    if (!dims_ok(d) || vocab < 1 || fmt <= PRIMA_FMT_Q4_K || fmt > PRIMA_FMT_F32) return PRIMA_E_SHAPE;
+    if (T < 1 || T > PRIMA_MAX_TOK) return PRIMA_E_RANGE;
+    if (!aligned(w_lm, 16) || !aligned(x, 16) || !aligned(g_final, 16) || !aligned(logits, 4)) return PRIMA_E_ALIGN;
+    return launch_fmt_gemv(fmt, static_cast<const uint8_t *>(w_lm), vocab, d->e, x, d->e, T, g_final, d->rms_eps, nullptr, 0,
+                           logits, vocab, static_cast<hipStream_t>(hip_stream));
+}
+
 size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
 {
     if (!d || !dims_ok(d) || T < 1 || T > PRIMA_MAX_TOK || kv_cap < 0) return 0;

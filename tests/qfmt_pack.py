@@ -5,11 +5,13 @@ dequantised value in advance (exact rational arithmetic on the fields).
 
 Layout (version 1): every field of a tensor is a plane of its own, planes follow one another without
 padding, blocks inside a plane are in row-major order.  n = rows * cols / 256 super-blocks.
+Quant bits of q5_k / q6_k sit in 32-bit words, weight t always in byte t%4 of its word:
+  low 4 bits: word t//8, low nibble when t%8 < 4 else high nibble;
+  bits 4..5 (q6_k): word t//16, bits 2g, 2g+1 with g = (t%16)//4;   bit 4 (q5_k): word t//32, bit g = (t%32)//4.
   q5_k: [n][16] header (binary16 d, dmin, then a 96-bit little-endian stream of sixteen 6-bit fields:
-        sc_0..7, m_0..7) | [n][128] low nibbles (weight t in byte t//2, low nibble for even t) |
-        [n][32] fifth bits (weight t: bit t%8 of byte t//8).   w = d*sc_s*q - dmin*m_s, s = t//32
-  q6_k: [n][128] low nibbles | [n][64] bits 4..5 (weight t: bits 2(t%4).. of byte t//4) | [n][16] int8
-        sub-scales (s = t//16) | [n] binary16 d.               w = d*sc_s*(q-32)
+        sc_0..7, m_0..7) | [n][128] low 4 bits | [n][32] bit 4.        w = d*sc_s*q - dmin*m_s, s = t//32
+  q6_k: [n][128] low 4 bits | [n][64] bits 4..5 | [n][16] int8 sub-scales (s = t//16) | [n] binary16 d.
+                                                                       w = d*sc_s*(q-32)
   q8_0: [rows*cols] int8 | [rows*cols/32] binary16 d.          w = d*q
   f16 / f32: row-major numbers.
 Fields are given as integer arrays shaped [rows, nb, ...]; half values as uint16 bit patterns.
@@ -21,9 +23,19 @@ import numpy as np
 from q4k_pack import half_fraction
 
 
+def _words(bits, per_word, width):
+    """bits [..., 256] -> bytes [..., 256 // per_word * 4]: weight t goes to byte t%4 of word t//per_word,
+    at bit position width * ((t % per_word) // 4)."""
+    b = np.asarray(bits, dtype=np.uint8)
+    g = b.reshape(b.shape[:-1] + (256 // per_word, per_word // 4, 4))       # [word][position g][byte j]
+    out = np.zeros(b.shape[:-1] + (256 // per_word, 4), dtype=np.uint8)
+    for pos in range(per_word // 4):
+        out |= (g[..., pos, :] << (width * pos)).astype(np.uint8)
+    return out.reshape(b.shape[:-1] + (-1,))
+
+
 def _nibbles(q_lo):
-    q_lo = np.asarray(q_lo, dtype=np.uint8)
-    return (q_lo[..., 0::2] | (q_lo[..., 1::2] << 4)).astype(np.uint8)
+    return _words(q_lo, 8, 4)
 
 
 def pack_q5k(d_bits, dmin_bits, sc, m, q):
@@ -40,7 +52,7 @@ def pack_q5k(d_bits, dmin_bits, sc, m, q):
             hdr[r, b] = np.frombuffer(int(d_bits[r][b]).to_bytes(2, "little") + int(dmin_bits[r][b]).to_bytes(2, "little")
                                       + stream.to_bytes(12, "little"), dtype=np.uint8)
     lo = _nibbles(q & 15)
-    hi = np.packbits(((q >> 4) & 1).astype(np.uint8), axis=-1, bitorder="little")
+    hi = _words((q >> 4) & 1, 32, 1)
     return np.concatenate([hdr.reshape(-1), lo.reshape(-1), hi.reshape(-1)])
 
 
@@ -48,8 +60,7 @@ def pack_q6k(d_bits, sc, q):
     """d_bits [rows, nb]; sc [rows, nb, 16] in -128..127; q [rows, nb, 256] in 0..63."""
     q = np.asarray(q)
     lo = _nibbles(q & 15)
-    h = ((q >> 4) & 3).astype(np.uint8)
-    hi = (h[..., 0::4] | (h[..., 1::4] << 2) | (h[..., 2::4] << 4) | (h[..., 3::4] << 6)).astype(np.uint8)
+    hi = _words((q >> 4) & 3, 16, 2)
     scb = np.asarray(sc, dtype=np.int8).view(np.uint8)
     db = np.asarray(d_bits, dtype="<u2").view(np.uint8)
     return np.concatenate([lo.reshape(-1), hi.reshape(-1), scb.reshape(-1), db.reshape(-1)])

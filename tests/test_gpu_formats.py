@@ -1,0 +1,138 @@
+"""GPU parity of the other weight formats (Q5_K, Q6_K, Q8_0, FP16, FP32) against the CPU oracle, through
+the C ABI: dequantisation bit for bit, mat-vec and output layer within the mat-vec tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from metrics import rel_err
+from workloads import synth
+from workloads.configs import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+FORMATS = ["q5_k", "q6_k", "q8_0", "f16", "f32"]
+GEMV_TOL = 1e-4      # fp32 sums of up to 28672 terms against fp64 (the Q4_K mat-vec tests use the same bound)
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _rand_tensor(rng, fmt, rows, cols):
+    """every field uniform over its range, scales any finite binary16 of moderate size (either sign)"""
+    n = rows * cols // 256
+    nbytes = int(n * 256 * synth.FORMAT_BITS[fmt] / 8)
+    if fmt == "f32":
+        return rng.standard_normal((rows, cols)).astype(np.float32).view(np.uint8).reshape(-1)
+    if fmt == "f16":
+        return rng.standard_normal((rows, cols)).astype(np.float16).view(np.uint8).reshape(-1)
+    raw = rng.integers(0, 256, nbytes, dtype=np.uint8)
+
+    def halves(count):
+        return ((rng.integers(0, 2, count) << 15) | (rng.integers(8, 18, count) << 10) | rng.integers(0, 1024, count)).astype("<u2").view(np.uint8)
+
+    if fmt == "q5_k":
+        raw[:16 * n].reshape(n, 16)[:, 0:4] = halves(2 * n).reshape(n, 4)
+    elif fmt == "q6_k":
+        raw[208 * n:] = halves(n)
+    else:
+        raw[rows * cols:] = halves(8 * n)
+    return raw
+
+
+@pytest.mark.parametrize("fmt", FORMATS + ["q4_k"])
+def test_dequant_bit_exact(gpu_lib, fmt):
+    rng = np.random.default_rng(3)
+    for rows, cols in [(1, 256), (5, 768), (67, 2048), (3, 28672)]:
+        W = synth.fmt_tensor(0, 1, "wq", fmt, rows, cols) if fmt == "q4_k" else _rand_tensor(rng, fmt, rows, cols)
+        ref = oracle.fmt_dequant(fmt, W, rows, cols)
+        got = gpu_lib.fmt_dequant(fmt, _dev(W), rows, cols).cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (fmt, rows, cols)
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_gemv_shapes_and_token_counts(gpu_lib, fmt):
+    """Rows ragged against the 4- and 2-row groups, K from one super-block to 28672 (whole and partial pieces of
+    1024 weights per wave), every token count (passes of up to 8), activations with a different scale per token:
+    each against the oracle, and twice with identical bits."""
+    rng = np.random.default_rng(77)
+    cases = [(1, 256, 1), (2, 256, 16), (3, 512, 2), (5, 768, 3), (37, 1024, 4), (130, 1280, 5), (64, 4096, 6), (63, 4352, 7),
+             (257, 8192, 8), (33, 8192, 9), (7, 28672, 1), (18, 28672, 12), (1000, 3584, 1), (4096, 2048, 1)]
+    for rows, cols, T in cases:
+        W = _rand_tensor(rng, fmt, rows, cols)
+        x = (rng.standard_normal((T, cols)) * np.exp(2 * rng.standard_normal((T, 1)))).astype(np.float32)
+        ref = oracle.fmt_gemv(fmt, W, rows, cols, x.astype(np.float64))
+        Wd, xd = _dev(W), _dev(x)
+        got = gpu_lib.fmt_gemv(fmt, Wd, rows, cols, xd).cpu().numpy()
+        again = gpu_lib.fmt_gemv(fmt, Wd, rows, cols, xd).cpu().numpy()
+        assert rel_err(got, ref) < GEMV_TOL, (fmt, rows, cols, T, rel_err(got, ref))
+        assert np.array_equal(got.view(np.uint32), again.view(np.uint32)), (fmt, rows, cols, T)
+
+
+def test_gemv_strided_activations_and_outputs(gpu_lib):
+    rng = np.random.default_rng(8)
+    rows, cols, T = 50, 1024, 3
+    W = _rand_tensor(rng, "q6_k", rows, cols)
+    xbig = torch.full((T, cols + 64), float("nan"), device="cuda")
+    x = rng.standard_normal((T, cols)).astype(np.float32)
+    xbig[:, :cols] = _dev(x)
+    ybig = torch.full((T, rows + 7), -7.0, device="cuda")
+    gpu_lib.fmt_gemv("q6_k", _dev(W), rows, cols, xbig[:, :cols], y=ybig[:, :rows])
+    ref = oracle.fmt_gemv("q6_k", W, rows, cols, x.astype(np.float64))
+    assert rel_err(ybig[:, :rows].cpu().numpy(), ref) < GEMV_TOL
+    assert (ybig[:, rows:] == -7.0).all()
+
+
+def test_gemv_argument_errors(gpu_lib):
+    W = torch.zeros(gpu_lib.fmt_tensor_bytes("q8_0", 4, 256), dtype=torch.uint8, device="cuda")
+    x = torch.zeros((1, 256), device="cuda")
+    with pytest.raises(gpu_lib.PrimaError):
+        gpu_lib.fmt_gemv("q8_0", W, 4, 256, torch.zeros((17, 256), device="cuda"))       # too many tokens
+    with pytest.raises(gpu_lib.PrimaError):
+        gpu_lib.fmt_gemv("q4_k", torch.zeros(4 * 144, dtype=torch.uint8, device="cuda"), 4, 256, x)   # has its own entry point
+    with pytest.raises(ValueError):
+        gpu_lib.fmt_gemv("q8_0", W[:-2], 4, 256, x)
+    assert gpu_lib.fmt_tensor_bytes("q6_k", 4, 100) == 0
+
+
+@pytest.mark.parametrize("fmt,T", [("q6_k", 1), ("q6_k", 8), ("q8_0", 3), ("f16", 1)])
+def test_lm_head_in_another_format(gpu_lib, fmt, T):
+    """Output layer: final RMSNorm fused in front of the mat-vec; vocabulary ragged against the row groups."""
+    cfg = CONFIGS["c1"]
+    d = cfg.dims
+    vocab = 3001
+    W = synth.fmt_tensor(cfg.config_id, 0, "w_lm", fmt, vocab, d.e)
+    g = synth.gain_f32(cfg.config_id, 0, "g_final", d.e)
+    x = (synth.normal_f32(cfg.config_id, 0, "x_in", (T, d.e)).astype(np.float64) * 1e3).astype(np.float32)
+    ref = oracle.lm_head_fmt(d, fmt, g, W, vocab, x.astype(np.float64))
+    got = gpu_lib.lm_head_fmt(d, fmt, _dev(g), _dev(W), vocab, _dev(x)).cpu().numpy()
+    assert rel_err(got, ref) < 2e-3          # the hidden-state tolerance
+    assert rel_err(got, ref) < 1e-4, rel_err(got, ref)
+
+
+def test_lm_head_q6k_full_vocab_sampled(gpu_lib):
+    """Config 4's output layer (128256 x 8192) in Q6_K, one token: logits sampled across the vocabulary and its
+    ragged end recomputed one by one by a brute-force fp64 product on the dequantised rows."""
+    cfg = CONFIGS["c4k1"]
+    d = cfg.dims
+    vocab = cfg.vocab
+    W = synth.fmt_tensor(cfg.config_id, 0, "w_lm", "q6_k", vocab, d.e)
+    g = synth.gain_f32(cfg.config_id, 0, "g_final", d.e)
+    x = synth.normal_f32(cfg.config_id, 0, "x_in", (1, d.e))
+    got = gpu_lib.lm_head_fmt(d, "q6_k", _dev(g), _dev(W), vocab, _dev(x)).cpu().numpy()[0]
+    assert np.isfinite(got).all()
+    rows = [0, 1, 2, 3, 4, 1023, 65535, 65536, 100000, vocab - 5, vocab - 4, vocab - 1]
+    n = x[0].astype(np.float64)
+    n = n / np.sqrt((n ** 2).mean() + float(np.float32(d.rms_eps))) * g.astype(np.float64)
+    # rows one by one: a one-row tensor cut out of the planes
+    nblk = d.e // 256
+    N = vocab * nblk
+    ref = []
+    for r in rows:
+        one = np.concatenate([W[r * nblk * 128:(r + 1) * nblk * 128], W[128 * N + r * nblk * 64:128 * N + (r + 1) * nblk * 64],
+                              W[192 * N + r * nblk * 16:192 * N + (r + 1) * nblk * 16], W[208 * N + r * nblk * 2:208 * N + (r + 1) * nblk * 2]])
+        ref.append(float(oracle.fmt_dequant("q6_k", one, 1, d.e)[0].astype(np.float64) @ n))
+    ref = np.array(ref)
+    scale = np.sqrt((ref ** 2).mean())
+    assert np.abs(got[rows] - ref).max() / scale < 1e-4
