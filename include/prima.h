@@ -252,6 +252,24 @@ prima_status prima_fmt_gemv(int32_t fmt, const void *W, int64_t n_rows, int64_t 
 prima_status prima_lm_head_fmt(const prima_dims *d, int32_t fmt, const float *g_final, const void *w_lm, int64_t vocab,
                                const float *x, int32_t T, float *logits, void *hip_stream);
 
+/*
+ * Window forward for a model that keeps some matrices in other formats (the "Q4K" models of Sec. 4 / App. A.3:
+ * mostly Q4_K, some tensors Q5_K / Q6_K / Q8_0 / FP16 / FP32).  As prima_layer_window_decode, with formats[i]
+ * naming the prima_format of each of layer i's seven matrices (the pointers of prima_layer then point at
+ * tensors in those formats).  Same results as if every matrix were dequantised to fp32 and multiplied
+ * (within the tolerance of prima_layer_window_decode).  Q4_K matrices run as in prima_layer_window_decode,
+ * the others through the mat-vec of prima_fmt_gemv with the same fused RMSNorm and residual.
+ * Errors as prima_layer_window_decode; a format code outside prima_format: PRIMA_E_SHAPE.
+ */
+typedef struct {
+    int32_t wq, wk, wv, wo, wgate, wup, wdown; /* prima_format */
+} prima_layer_formats;
+
+prima_status prima_layer_window_decode_mixed(const prima_dims *d, const prima_layer *layers, const prima_layer_formats *formats,
+                                             int32_t L, int32_t kv_cap, int32_t n_past, int32_t T,
+                                             const float *x_in, float *x_out,
+                                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Bytes of scratch the window calls need for up to T tokens and kv_cap cache rows. */
 size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
 

@@ -198,11 +198,15 @@ def kv_append(dims, k, v, K, V, n_past, T):
                         C.c_int32(n_past), C.c_int32(T))
 
 
-def layer(dims, t, x, n_past, taps=False):
+WEIGHTS = ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")
+
+
+def layer(dims, t, x, n_past, taps=False, formats=None):
     """Advance one decoder layer by T = x.shape[0] tokens.
 
     t: dict of the layer's tensors (wq..wdown uint8 [r, nb, 144]; g_attn, g_ffn float32;
     k_cache, v_cache float16 [Hkv, cap, D], updated in place).  x float64 [T, e].
+    formats: optional dict tensor name -> one of FORMATS for tensors kept in another format (flat uint8).
     Returns y float64 [T, e] (and a dict of taps when asked).
     """
     x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
@@ -210,7 +214,12 @@ def layer(dims, t, x, n_past, taps=False):
     assert e == dims.e
     K, V = t["k_cache"], t["v_cache"]
     assert K.flags.c_contiguous and V.flags.c_contiguous and K.dtype == np.float16 and V.dtype == np.float16
-    ws = [np.ascontiguousarray(t[k], dtype=np.uint8) for k in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown")]
+    ws = [np.ascontiguousarray(t[k], dtype=np.uint8) for k in WEIGHTS]
+    fm = (C.c_int32 * 7)(*[FORMATS[(formats or {}).get(k, "q4_k")] for k in WEIGHTS])
+    shapes = {"wq": (dims.qd, e), "wk": (dims.kvd, e), "wv": (dims.kvd, e), "wo": (e, dims.qd),
+              "wgate": (dims.ffn, e), "wup": (dims.ffn, e), "wdown": (e, dims.ffn)}
+    for k, w in zip(WEIGHTS, ws):
+        assert w.size == fmt_tensor_bytes((formats or {}).get(k, "q4_k"), *shapes[k]), k
     ga = np.ascontiguousarray(t["g_attn"], dtype=np.float32)
     gf = np.ascontiguousarray(t["g_ffn"], dtype=np.float32)
     y = np.empty_like(x)
@@ -220,7 +229,7 @@ def layer(dims, t, x, n_past, taps=False):
               "a": np.empty((T, dims.ffn))}
     gap = C.c_double(0.0)
     dd = _dims(dims)
-    rc = lib().orc_layer(C.byref(dd), *[_p(w) for w in ws], _p(ga), _p(gf), _p(K), _p(V),
+    rc = lib().orc_layer_fmt(C.byref(dd), fm, *[_p(w) for w in ws], _p(ga), _p(gf), _p(K), _p(V),
                          C.c_int32(K.shape[1]), C.c_int32(n_past), C.c_int32(T), _p(x), _p(y),
                          _p(tp.get("q")), _p(tp.get("o")), _p(tp.get("h")), _p(tp.get("a")), C.byref(gap))
     assert rc == 0
@@ -230,11 +239,11 @@ def layer(dims, t, x, n_past, taps=False):
     return y
 
 
-def window(dims, layers, x, n_past):
-    """Compose consecutive layers (list of tensor dicts, or a callable index -> dict)."""
+def window(dims, layers, x, n_past, formats=None):
+    """Compose consecutive layers (list of tensor dicts); formats: optional list of per-layer dicts as for layer()."""
     h = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
-    for t in layers:
-        h = layer(dims, t, h, n_past)
+    for i, t in enumerate(layers):
+        h = layer(dims, t, h, n_past, formats=formats[i] if formats else None)
     return h
 
 

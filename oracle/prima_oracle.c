@@ -398,7 +398,17 @@ void orc_kv_append(const orc_dims *d, const double *k, const double *v, uint16_t
  * queries, tap_o [T][qd] attention output, tap_h [T][e] post-attention hidden state,
  * tap_a [T][ffn] SwiGLU output.
  */
-int orc_layer(const orc_dims *d,
+/* a projection in the format of its tensor (0: Q4_K, the decoder above) */
+static int gemv_any(int32_t fmt, const uint8_t *W, int64_t n_rows, int64_t n_cols,
+                    const double *x, int64_t ldx, int32_t T, double *y, int64_t ldy)
+{
+    if (fmt == FMT_Q4_K) return orc_q4k_gemv(W, n_rows, n_cols, x, ldx, T, y, ldy);
+    return orc_fmt_gemv(fmt, W, n_rows, n_cols, x, ldx, T, y, ldy);
+}
+
+/* fmts: the formats of wq, wk, wv, wo, wgate, wup, wdown (a "Q4K" model keeps some tensors in other formats,
+ * Sec. 4 / App. A.3); the layer's arithmetic does not depend on them */
+int orc_layer_fmt(const orc_dims *d, const int32_t *fmts,
               const uint8_t *wq, const uint8_t *wk, const uint8_t *wv, const uint8_t *wo,
               const uint8_t *wgate, const uint8_t *wup, const uint8_t *wdown,
               const float *g_attn, const float *g_ffn,
@@ -416,9 +426,9 @@ int orc_layer(const orc_dims *d,
     double *dn = malloc(sizeof(double) * T * e);
     int rc = 0;
     for (int j = 0; j < T; ++j) orc_rmsnorm(x_in + (int64_t)j * e, g_attn, e, d->rms_eps, n1 + (int64_t)j * e);
-    rc |= orc_q4k_gemv(wq, qd, e, n1, e, T, q, qd);
-    rc |= orc_q4k_gemv(wk, kvd, e, n1, e, T, k, kvd);
-    rc |= orc_q4k_gemv(wv, kvd, e, n1, e, T, v, kvd);
+    rc |= gemv_any(fmts[0], wq, qd, e, n1, e, T, q, qd);
+    rc |= gemv_any(fmts[1], wk, kvd, e, n1, e, T, k, kvd);
+    rc |= gemv_any(fmts[2], wv, kvd, e, n1, e, T, v, kvd);
     for (int j = 0; j < T; ++j) {
         orc_rope(q + j * qd, d->n_q_heads, D, n_past + j, d->rope_theta, d->rope_mode);
         orc_rope(k + j * kvd, d->n_kv_heads, D, n_past + j, d->rope_theta, d->rope_mode);
@@ -427,18 +437,31 @@ int orc_layer(const orc_dims *d,
     rc |= orc_attn_decode(d, q, k_cache, v_cache, kv_cap, n_past, T, a, min_gap);
     if (tap_q) memcpy(tap_q, q, sizeof(double) * T * qd);
     if (tap_o) memcpy(tap_o, a, sizeof(double) * T * qd);
-    rc |= orc_q4k_gemv(wo, e, qd, a, qd, T, h, e);
+    rc |= gemv_any(fmts[3], wo, e, qd, a, qd, T, h, e);
     for (int64_t i = 0; i < (int64_t)T * e; ++i) h[i] += x_in[i];
     if (tap_h) memcpy(tap_h, h, sizeof(double) * T * e);
     for (int j = 0; j < T; ++j) orc_rmsnorm(h + (int64_t)j * e, g_ffn, e, d->rms_eps, n1 + (int64_t)j * e);
-    rc |= orc_q4k_gemv(wgate, F, e, n1, e, T, g, F);
-    rc |= orc_q4k_gemv(wup, F, e, n1, e, T, u, F);
+    rc |= gemv_any(fmts[4], wgate, F, e, n1, e, T, g, F);
+    rc |= gemv_any(fmts[5], wup, F, e, n1, e, T, u, F);
     orc_swiglu(g, u, (int64_t)T * F, g);
     if (tap_a) memcpy(tap_a, g, sizeof(double) * T * F);
-    rc |= orc_q4k_gemv(wdown, e, F, g, F, T, dn, e);
+    rc |= gemv_any(fmts[6], wdown, e, F, g, F, T, dn, e);
     for (int64_t i = 0; i < (int64_t)T * e; ++i) x_out[i] = h[i] + dn[i];
     free(n1); free(q); free(k); free(v); free(a); free(h); free(g); free(u); free(dn);
     return rc;
+}
+
+int orc_layer(const orc_dims *d,
+              const uint8_t *wq, const uint8_t *wk, const uint8_t *wv, const uint8_t *wo,
+              const uint8_t *wgate, const uint8_t *wup, const uint8_t *wdown,
+              const float *g_attn, const float *g_ffn,
+              uint16_t *k_cache, uint16_t *v_cache, int32_t kv_cap, int32_t n_past, int32_t T,
+              const double *x_in, double *x_out,
+              double *tap_q, double *tap_o, double *tap_h, double *tap_a, double *min_gap)
+{
+    const int32_t all_q4k[7] = {0, 0, 0, 0, 0, 0, 0};
+    return orc_layer_fmt(d, all_q4k, wq, wk, wv, wo, wgate, wup, wdown, g_attn, g_ffn, k_cache, v_cache, kv_cap, n_past, T,
+                         x_in, x_out, tap_q, tap_o, tap_h, tap_a, min_gap);
 }
 
 /* output layer: logits[t][v] = W_lm . rmsnorm(x_t; g_final) */

@@ -153,8 +153,18 @@ class Window:
     """A window of decoder layers resident in HBM: keeps the tensors alive, the descriptor array
     and a workspace, so that a step is a single C call."""
 
-    def __init__(self, dims, layers, kv_cap, T_max=MAX_TOK):
+    def __init__(self, dims, layers, kv_cap, T_max=MAX_TOK, formats=None):
+        """formats: optional list (one dict per layer) naming the format of matrices that are not Q4_K, e.g.
+        {"wv": "q6_k", "wdown": "q6_k"}; such tensors are flat uint8 of fmt_tensor_bytes(...) bytes."""
         self.dims = make_dims(dims)
+        self._formats = None
+        if formats is not None:
+            if len(formats) != len(layers):
+                raise ValueError("formats needs one entry per layer")
+            self._formats = (_ffi.LayerFormats * len(layers))()
+            for i, f in enumerate(formats):
+                for k in _WEIGHTS:
+                    setattr(self._formats[i], k, _ffi.FORMATS[(f or {}).get(k, "q4_k")])
         self.layers = layers
         self.kv_cap = kv_cap
         self.T_max = T_max
@@ -180,6 +190,11 @@ class Window:
         T = x_in.shape[0]
         if x_out is None:
             x_out = torch.empty_like(x_in)
+        if self._formats is not None:
+            _ffi.check(_ffi.lib().prima_layer_window_decode_mixed(C.byref(self.dims), self._arr, self._formats, len(self.layers),
+                                                                  self.kv_cap, n_past, T, _ptr(x_in), _ptr(x_out), _ptr(self.workspace),
+                                                                  self.workspace.numel(), _stream()), "prima_layer_window_decode_mixed")
+            return x_out
         _ffi.check(_ffi.lib().prima_layer_window_decode(C.byref(self.dims), self._arr, len(self.layers), self.kv_cap,
                                                         n_past, T, _ptr(x_in), _ptr(x_out), _ptr(self.workspace),
                                                         self.workspace.numel(), _stream()), "prima_layer_window_decode")

@@ -93,6 +93,7 @@ size_t gemv_arrivals_bytes(int64_t n_rows_total);
 prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
 
 prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
+prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st);
 // the RoPE table [T][D/2] of (cos, sin) and up to three zeroed regions (null: none) in one launch.
 // positions: null (token t sits at n_past + t) or T positions, one per token (a batch of sequences)
 prima_status launch_step_init(float *tab, int T, int D, int n_past, float theta, const int *positions,

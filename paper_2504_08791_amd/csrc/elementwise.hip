@@ -62,6 +62,24 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4 *__restric
     if (acc == 0x9e3779b9u) sink[0] = acc; // practically never: keeps the loop alive without a store per thread
 }
 
+// a[i] = silu(a[i]) * u[i]: SwiGLU as a launch of its own, for gate / up projections that are not both Q4_K
+// (for Q4_K the epilogue of their shared launch does it)
+__global__ void __launch_bounds__(256) swiglu_kernel(float *__restrict__ a, const float *__restrict__ u, int64_t n)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) {
+        const float g = a[i];
+        a[i] = g / (1.0f + expf(-g)) * u[i];
+    }
+}
+
+prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st)
+{
+    if (n <= 0) return PRIMA_OK;
+    hipLaunchKernelGGL(swiglu_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st, a, u, n);
+    return last_launch_status();
+}
+
 prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st)
 {
     int dev = 0, cus = 256;

@@ -101,17 +101,22 @@ __global__ void __launch_bounds__(256) gemv_slab_reduce_kernel(PGemvArgs a)
 
 size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T)
 {
-    // any segmentation of the rows into up to three matrices adds at most two tiles
-    const int n_tiles = static_cast<int>((n_rows_total + 15) / 16) + 2;
+    // any segmentation of the rows into up to three matrices adds at most two tiles; the plan (and with it the number
+    // of slabs) can change with every tile more or less, so each possible count is planned
+    const int base = static_cast<int>((n_rows_total + 15) / 16);
+    const int n_tiles = base + 2;
     size_t worst = 0;
     for (int t0 = 0; t0 < T; t0 += MAX_T_PASS) {
         const int Tp = T - t0 < MAX_T_PASS ? T - t0 : MAX_T_PASS;
-        for (int epi : {EPI_ROWS, EPI_SWIGLU}) {
-            PPlan p = plan_for(n_tiles & ~1, static_cast<int>(n_cols / QK), Tp, epi);
-            p.n_tiles = n_tiles;
-            p.n_slabs += 1; // a slightly different tile count may need one more slab
-            const size_t b = part_bytes(p, Tp);
-            worst = b > worst ? b : worst;
+        for (int nt = base; nt <= base + 2; ++nt) {
+            for (int epi : {EPI_ROWS, EPI_SWIGLU}) {
+                if (nt < 1 || (epi == EPI_SWIGLU && (nt & 1))) continue; // gate / up: two matrices of equal height
+                PPlan p = plan_for(nt, static_cast<int>(n_cols / QK), Tp, epi);
+                if (!p.ok) continue;
+                p.n_tiles = n_tiles;
+                const size_t b = part_bytes(p, Tp);
+                worst = b > worst ? b : worst;
+            }
         }
     }
     return arrivals_bytes(n_tiles) + worst;

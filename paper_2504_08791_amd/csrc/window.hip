@@ -10,7 +10,7 @@ using namespace prima;
 namespace {
 
 struct WindowWs {
-    size_t q, k, v, o, h, a, xb0, xb1, rope, attn, gemv, gemv_bytes, arrivals_bytes, sync, total;
+    size_t q, k, v, o, h, a, u, xb0, xb1, rope, attn, gemv, gemv_bytes, arrivals_bytes, sync, total;
 };
 
 bool dims_ok(const prima_dims *d)
@@ -33,13 +33,17 @@ WindowWs carve(const prima_dims &d, int kv_cap, int T)
     w.o = take(T * qd * f);
     w.h = take(T * static_cast<size_t>(d.e) * f);
     w.a = take(T * static_cast<size_t>(d.ffn) * f);
+    w.u = take(T * static_cast<size_t>(d.ffn) * f); // up projection, when gate / up are not both Q4_K
     w.xb0 = take(T * static_cast<size_t>(d.e) * f);
     w.xb1 = take(T * static_cast<size_t>(d.e) * f);
     w.rope = take(T * static_cast<size_t>(d.head_dim) * f);
     w.attn = take(attn_ws_bytes(d, kv_cap, T));
     // mat-vec scratch: sized for the largest of the layer's (and the output layer's) launches
     const int64_t rows_max = std::max<int64_t>(2 * static_cast<int64_t>(d.ffn), static_cast<int64_t>(qd + 2 * kvd));
-    const int64_t shapes[4][2] = {{static_cast<int64_t>(qd + 2 * kvd), d.e}, {d.e, static_cast<int64_t>(qd)}, {2 * static_cast<int64_t>(d.ffn), d.e}, {d.e, d.ffn}};
+    // (the last five: subsets of a group, launched when its other matrices are in other formats)
+    const int64_t shapes[9][2] = {{static_cast<int64_t>(qd + 2 * kvd), d.e}, {d.e, static_cast<int64_t>(qd)}, {2 * static_cast<int64_t>(d.ffn), d.e}, {d.e, d.ffn},
+                                  {static_cast<int64_t>(qd), d.e}, {static_cast<int64_t>(kvd), d.e}, {static_cast<int64_t>(qd + kvd), d.e},
+                                  {static_cast<int64_t>(2 * kvd), d.e}, {d.ffn, d.e}};
     w.gemv_bytes = 0;
     w.arrivals_bytes = gemv_arrivals_bytes(rows_max);
     for (const auto &sh : shapes) w.gemv_bytes = std::max(w.gemv_bytes, gemv_ws_bytes(sh[0], sh[1], T)); // counters + partial sums
@@ -107,8 +111,18 @@ bool g_fused_enabled = false;
 // (+ residual), gate/up projections (RMSNorm fused in front, SwiGLU behind), down projection (+ residual).
 prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
                        const float *x, float *y, void *ws, const WindowWs &w, hipStream_t st,
-                       float *tap_q, float *tap_o, float *tap_h, float *tap_a, int only = -1, const AttnSeqs *seq = nullptr)
+                       float *tap_q, float *tap_o, float *tap_h, float *tap_a, int only = -1, const AttnSeqs *seq = nullptr,
+                       const prima_layer_formats *fm = nullptr)
 {
+    // fm: formats of the seven matrices (null: all Q4_K).  Q4_K matrices go through the MFMA mat-vec (those of one
+    // group in one launch), the others through the format mat-vec, one launch each, with the same fused RMSNorm /
+    // residual; SwiGLU is a launch of its own unless gate and up are both Q4_K.
+    const int f_q = fm ? fm->wq : 0, f_k = fm ? fm->wk : 0, f_v = fm ? fm->wv : 0, f_o = fm ? fm->wo : 0;
+    const int f_g = fm ? fm->wgate : 0, f_u = fm ? fm->wup : 0, f_d = fm ? fm->wdown : 0;
+    auto other = [&](int fmt, const void *W, int64_t rows, int64_t cols, const float *xin, const float *gain,
+                     const float *resid, float *out) {
+        return launch_fmt_gemv(fmt, static_cast<const uint8_t *>(W), rows, cols, xin, cols, T, gain, d.rms_eps, resid, rows, out, rows, st);
+    };
     const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
     float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
     float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *act = at<float>(ws, w.a);
@@ -116,33 +130,61 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
 #define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
 #define PRIMA_WANT(k) (only < 0 || only == (k))
     if (PRIMA_WANT(PRIMA_K_QKV)) {
-        GemvArgs ga = gemv_args(3, e, x, e, T, X_RMSNORM, L.g_attn, d.rms_eps);
-        ga.seg[0] = seg(L.wq, q, qd, qd);
-        ga.seg[1] = seg(L.wk, k, kvd, kvd);
-        ga.seg[2] = seg(L.wv, v, kvd, kvd);
-        PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+        GemvArgs ga = gemv_args(0, e, x, e, T, X_RMSNORM, L.g_attn, d.rms_eps);
+        if (f_q == PRIMA_FMT_Q4_K) ga.seg[ga.nseg++] = seg(L.wq, q, qd, qd);
+        if (f_k == PRIMA_FMT_Q4_K) ga.seg[ga.nseg++] = seg(L.wk, k, kvd, kvd);
+        if (f_v == PRIMA_FMT_Q4_K) ga.seg[ga.nseg++] = seg(L.wv, v, kvd, kvd);
+        if (ga.nseg) PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+        if (f_q != PRIMA_FMT_Q4_K) PRIMA_TRY(other(f_q, L.wq, qd, e, x, L.g_attn, nullptr, q));
+        if (f_k != PRIMA_FMT_Q4_K) PRIMA_TRY(other(f_k, L.wk, kvd, e, x, L.g_attn, nullptr, k));
+        if (f_v != PRIMA_FMT_Q4_K) PRIMA_TRY(other(f_v, L.wv, kvd, e, x, L.g_attn, nullptr, v));
     }
     if (PRIMA_WANT(PRIMA_K_ATTN))
         PRIMA_TRY(launch_attn(d, q, tap_q, k, v, at<float>(ws, w.rope), static_cast<__half *>(L.k_cache),
                               static_cast<__half *>(L.v_cache), kv_cap, n_past, T, o, at<char>(ws, w.attn), st, seq));
     if (tap_o && hipMemcpyAsync(tap_o, o, T * qd * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     if (PRIMA_WANT(PRIMA_K_WO)) {
-        GemvArgs ga = gemv_args(1, qd, o, qd, T);
-        ga.seg[0] = seg(L.wo, h, e, e, x, e);
-        PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+        if (f_o == PRIMA_FMT_Q4_K) {
+            GemvArgs ga = gemv_args(1, qd, o, qd, T);
+            ga.seg[0] = seg(L.wo, h, e, e, x, e);
+            PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+        } else {
+            PRIMA_TRY(other(f_o, L.wo, e, qd, o, nullptr, x, h));
+        }
     }
     if (tap_h && hipMemcpyAsync(tap_h, h, T * e * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     if (PRIMA_WANT(PRIMA_K_GATE_UP)) {
-        GemvArgs ga = gemv_args(2, e, h, e, T, X_RMSNORM, L.g_ffn, d.rms_eps, EPI_SWIGLU);
-        ga.seg[0] = seg(L.wgate, act, F, F); // silu(gate) * up lands here
-        ga.seg[1] = seg(L.wup, nullptr, F, F);
-        PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+        if (f_g == PRIMA_FMT_Q4_K && f_u == PRIMA_FMT_Q4_K) {
+            GemvArgs ga = gemv_args(2, e, h, e, T, X_RMSNORM, L.g_ffn, d.rms_eps, EPI_SWIGLU);
+            ga.seg[0] = seg(L.wgate, act, F, F); // silu(gate) * up lands here
+            ga.seg[1] = seg(L.wup, nullptr, F, F);
+            PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+        } else {
+            float *up = at<float>(ws, w.u);
+            const void *Wm[2] = {L.wgate, L.wup};
+            float *out[2] = {act, up};
+            const int fmt2[2] = {f_g, f_u};
+            for (int i = 0; i < 2; ++i) {
+                if (fmt2[i] == PRIMA_FMT_Q4_K) {
+                    GemvArgs ga = gemv_args(1, e, h, e, T, X_RMSNORM, L.g_ffn, d.rms_eps);
+                    ga.seg[0] = seg(Wm[i], out[i], F, F);
+                    PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+                } else {
+                    PRIMA_TRY(other(fmt2[i], Wm[i], F, e, h, L.g_ffn, nullptr, out[i]));
+                }
+            }
+            PRIMA_TRY(launch_swiglu(act, up, static_cast<int64_t>(T) * F, st));
+        }
     }
     if (tap_a && hipMemcpyAsync(tap_a, act, T * F * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return PRIMA_E_DEVICE;
     if (PRIMA_WANT(PRIMA_K_DOWN)) {
-        GemvArgs ga = gemv_args(1, F, act, F, T);
-        ga.seg[0] = seg(L.wdown, y, e, e, h, e);
-        PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+        if (f_d == PRIMA_FMT_Q4_K) {
+            GemvArgs ga = gemv_args(1, F, act, F, T);
+            ga.seg[0] = seg(L.wdown, y, e, e, h, e);
+            PRIMA_TRY(launch_gemv_mfma(ga, at<char>(ws, w.gemv), w.gemv_bytes, w.arrivals_bytes, st));
+        } else {
+            PRIMA_TRY(other(f_d, L.wdown, e, F, act, nullptr, h, y));
+        }
     }
 #undef PRIMA_WANT
 #undef PRIMA_TRY
@@ -321,6 +363,35 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
     for (int i = 0; i < L; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
         s = run_layer(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr);
+        if (s != PRIMA_OK) return s;
+        cur = dst;
+    }
+    return PRIMA_OK;
+}
+
+prima_status prima_layer_window_decode_mixed(const prima_dims *d, const prima_layer *layers, const prima_layer_formats *formats,
+                                             int32_t L, int32_t kv_cap, int32_t n_past, int32_t T,
+                                             const float *x_in, float *x_out,
+                                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!layers || !formats) return PRIMA_E_NULL;
+    prima_status s = check_window_args(d, kv_cap, n_past, T, x_in, x_out, workspace, workspace_bytes);
+    if (s != PRIMA_OK) return s;
+    if (L < 1) return PRIMA_E_RANGE;
+    for (int i = 0; i < L; ++i) {
+        if ((s = check_layer(layers[i])) != PRIMA_OK) return s;
+        const int32_t f[7] = {formats[i].wq, formats[i].wk, formats[i].wv, formats[i].wo, formats[i].wgate, formats[i].wup, formats[i].wdown};
+        for (int32_t v : f)
+            if (v < PRIMA_FMT_Q4_K || v > PRIMA_FMT_F32) return PRIMA_E_SHAPE;
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const WindowWs w = carve(*d, kv_cap, T);
+    s = step_init(*d, workspace, w, T, n_past, nullptr, true, st);
+    if (s != PRIMA_OK) return s;
+    const float *cur = x_in;
+    for (int i = 0; i < L; ++i) {
+        float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
+        s = run_layer(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr, -1, nullptr, &formats[i]);
         if (s != PRIMA_OK) return s;
         cur = dst;
     }

@@ -7,7 +7,7 @@ import torch
 import oracle
 from metrics import rel_err
 from workloads import synth
-from workloads.configs import CONFIGS
+from workloads.configs import CONFIGS, TINY
 
 pytestmark = pytest.mark.gpu
 
@@ -136,3 +136,71 @@ def test_lm_head_q6k_full_vocab_sampled(gpu_lib):
     ref = np.array(ref)
     scale = np.sqrt((ref ** 2).mean())
     assert np.abs(got[rows] - ref).max() / scale < 1e-4
+
+
+MIXES = {
+    # the usual mix of a "Q4K" model: V and down projections in Q6_K
+    "q4_k_m": [{"wv": "q6_k", "wdown": "q6_k"}, {}, {"wv": "q6_k", "wdown": "q6_k"}],
+    # every matrix in some other format, gate / up not both Q4_K (SwiGLU as its own launch), one Q4_K matrix alone in its group
+    "all_kinds": [{"wq": "q8_0", "wk": "q5_k", "wv": "f16", "wo": "q6_k", "wgate": "q5_k", "wup": "q8_0", "wdown": "f32"},
+                  {"wq": "q6_k", "wgate": "q6_k"},
+                  {"wk": "q8_0", "wv": "q8_0", "wup": "f16", "wo": "f16", "wdown": "q5_k"}],
+}
+
+
+@pytest.mark.parametrize("mix", sorted(MIXES))
+@pytest.mark.parametrize("name,T", [("t1", 1), ("t2", 5), ("c1", 4), ("c0", 11)])
+def test_window_with_mixed_formats(gpu_lib, mix, name, T):
+    """Two or three layers with matrices in several formats, one and several tokens (passes of 8 in the format mat-vec):
+    hidden state against the oracle within the hidden-state tolerance; the appended K/V rows too."""
+    # (the model-sized shapes with two layers, as in the Q4_K window tests: the synthetic hidden state grows from layer
+    # to layer until attention logits tie within rounding and a third layer amplifies the difference)
+    n_layers = 3 if name in TINY else 2
+    formats = MIXES[mix][-n_layers:]
+    cfg = {**CONFIGS, **TINY}[name].with_(n_layers=n_layers, T=T)
+    d = cfg.dims
+    cap = cfg.n_past + T
+    x = synth.window_input(cfg)
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap, formats=formats[l]) for l in range(n_layers)]
+    dev_layers = [{k: _dev(v) for k, v in t.items()} for t in host]
+    ref = oracle.window(d, host, x.astype(np.float64), cfg.n_past, formats=formats)     # appends to the host caches
+    win = gpu_lib.Window(d, dev_layers, cap, T_max=T, formats=formats)
+    win.workspace.fill_(0xFF)
+    y = win.decode(_dev(x), cfg.n_past).cpu().numpy()
+    assert rel_err(y, ref) < 2e-3, rel_err(y, ref)
+    for t, dl in zip(host, dev_layers):
+        for c in ("k_cache", "v_cache"):
+            new_ref = t[c][:, cfg.n_past:cfg.n_past + T].astype(np.float64).reshape(1, -1)
+            new_got = dl[c][:, cfg.n_past:cfg.n_past + T].float().cpu().numpy().reshape(1, -1)
+            assert rel_err(new_got, new_ref) < 2e-3
+
+
+def test_mixed_window_of_q4k_only_equals_the_q4k_window(gpu_lib):
+    """With every format Q4_K the mixed entry point runs the same launches: identical bits."""
+    cfg = CONFIGS["c1"].with_(n_layers=2)
+    d = cfg.dims
+    cap = cfg.n_past + cfg.T
+    xd = _dev(synth.window_input(cfg))
+    dev_layers = [{k: _dev(v) for k, v in synth.layer_tensors(cfg, l, kv_cap=cap).items()} for l in range(2)]
+    a = gpu_lib.Window(d, dev_layers, cap, T_max=cfg.T).decode(xd, cfg.n_past).clone()
+    b = gpu_lib.Window(d, dev_layers, cap, T_max=cfg.T, formats=[{}, {}]).decode(xd, cfg.n_past)
+    assert torch.equal(a, b)
+
+
+def test_mixed_window_full_shape(gpu_lib):
+    """Config 3's layer shape, 2 layers, V and down projections in Q6_K (the usual mix), one token."""
+    formats = [{"wv": "q6_k", "wdown": "q6_k"}] * 2
+    cfg = CONFIGS["c3"].with_(n_layers=2)
+    d = cfg.dims
+    cap = cfg.n_past + cfg.T
+    x = synth.window_input(cfg)
+    dev_layers, h = [], x.astype(np.float64)
+    for l in range(2):
+        t = synth.layer_tensors(cfg, l, kv_cap=cap, formats=formats[l])
+        dev_layers.append({k: _dev(v) for k, v in t.items()})
+        h = oracle.layer(d, t, h, cfg.n_past, formats=formats[l])
+        del t
+    win = gpu_lib.Window(d, dev_layers, cap, T_max=cfg.T, formats=formats)
+    win.workspace.fill_(0xFF)
+    y = win.decode(_dev(x), cfg.n_past).cpu().numpy()
+    assert rel_err(y, h) < 2e-3, rel_err(y, h)

@@ -137,3 +137,25 @@ def test_lm_head_in_another_format_is_norm_then_product():
     n = x / np.sqrt((x ** 2).mean(axis=1, keepdims=True) + float(np.float32(d.rms_eps))) * g.astype(np.float64)
     ref = n @ oracle.fmt_dequant("q6_k", W, vocab, d.e).astype(np.float64).T
     assert np.abs(got - ref).max() <= 1e-12 * np.abs(ref).max()
+
+
+def test_layer_does_not_depend_on_the_format_of_a_matrix():
+    """A layer whose matrix is stored as the fp32 numbers that its Q4_K tensor decodes to gives the same bits as
+    the Q4_K layer, for each of the seven matrices in turn (a format routed to the wrong projection would decode
+    garbage), and for all seven at once."""
+    from workloads import synth
+    from workloads.configs import CONFIGS
+    cfg = CONFIGS["c0"]
+    d = cfg.dims
+    t = synth.layer_tensors(cfg, 0)
+    x = synth.window_input(cfg).astype(np.float64)
+    caches = (t["k_cache"].copy(), t["v_cache"].copy())
+    ref = oracle.layer(d, t, x, cfg.n_past)
+    names = list(oracle.WEIGHTS)
+    for subset in [[n] for n in names] + [names]:
+        t2 = dict(t)
+        t2["k_cache"], t2["v_cache"] = caches[0].copy(), caches[1].copy()
+        for n in subset:
+            t2[n] = oracle.dequant(t[n]).view(np.uint8).reshape(-1)
+        got = oracle.layer(d, t2, x, cfg.n_past, formats={n: "f32" for n in subset})
+        assert np.array_equal(got, ref), subset

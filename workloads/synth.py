@@ -99,11 +99,20 @@ def kv_cache_f16(config_id, layer, tensor, n_kv_heads, kv_cap, head_dim, n_past)
     return out
 
 
-def layer_tensors(cfg, layer, kv_cap=None):
-    """All tensors of one decoder layer of window `cfg` as a dict of numpy arrays."""
+def layer_tensors(cfg, layer, kv_cap=None, formats=None):
+    """All tensors of one decoder layer of window `cfg` as a dict of numpy arrays.  formats: optional dict
+    tensor name -> format for matrices that are not Q4_K (those come as flat uint8, see fmt_tensor)."""
     d = cfg.dims
     cid = cfg.config_id
     cap = kv_cap if kv_cap is not None else cfg.n_past + cfg.T
+    if formats:
+        t = layer_tensors(cfg, layer, kv_cap)
+        shapes = {"wq": (d.qd, d.e), "wk": (d.kvd, d.e), "wv": (d.kvd, d.e), "wo": (d.e, d.qd),
+                  "wgate": (d.ffn, d.e), "wup": (d.ffn, d.e), "wdown": (d.e, d.ffn)}
+        for name, fmt in formats.items():
+            if fmt != "q4_k":
+                t[name] = fmt_tensor(cid, layer, name, fmt, *shapes[name])
+        return t
     return {
         "wq": q4k_tensor(cid, layer, "wq", d.qd, d.e),
         "wk": q4k_tensor(cid, layer, "wk", d.kvd, d.e),
