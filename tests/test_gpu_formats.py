@@ -53,12 +53,15 @@ def test_dequant_bit_exact(gpu_lib, fmt):
 
 @pytest.mark.parametrize("fmt", FORMATS)
 def test_gemv_shapes_and_token_counts(gpu_lib, fmt):
-    """Rows ragged against the 4- and 2-row groups, K from one super-block to 28672 (whole and partial pieces of
-    1024 weights per wave), every token count (passes of up to 8), activations with a different scale per token:
-    each against the oracle, and twice with identical bits."""
+    """Rows ragged against the 4-, 2- and 1-row groups (few and many rows: both choices of rows per wave), K from one
+    super-block to 40960 (whole and partial pieces of 1024 weights, one and several chunks of K in LDS), every token
+    count (passes of up to 8), activations with a different scale per token: each against the oracle, and twice with
+    identical bits."""
     rng = np.random.default_rng(77)
     cases = [(1, 256, 1), (2, 256, 16), (3, 512, 2), (5, 768, 3), (37, 1024, 4), (130, 1280, 5), (64, 4096, 6), (63, 4352, 7),
-             (257, 8192, 8), (33, 8192, 9), (7, 28672, 1), (18, 28672, 12), (1000, 3584, 1), (4096, 2048, 1)]
+             (257, 8192, 8), (33, 8192, 9), (7, 28672, 1), (18, 28672, 12), (1000, 3584, 1), (4096, 2048, 1),
+             # K beyond what LDS holds for one and two tokens (chunks of 32768 and 16384 weights), 16 tokens in two passes
+             (9, 40960, 1), (6, 33024, 2), (5, 12288, 16), (40000, 256, 1), (33000, 512, 3)]
     for rows, cols, T in cases:
         W = _rand_tensor(rng, fmt, rows, cols)
         x = (rng.standard_normal((T, cols)) * np.exp(2 * rng.standard_normal((T, 1)))).astype(np.float32)
