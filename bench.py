@@ -37,6 +37,9 @@ def main():
                     help="side measurement: B sequences of the config's context length, one token each per step")
     ap.add_argument("--format", default="", choices=["", "q5_k", "q6_k", "q8_0", "f16", "f32"],
                     help="side measurement: the mat-vec of another weight format at the output layer's and the down projection's shape")
+    ap.add_argument("--device-profile", action="store_true",
+                    help="side measurement: the device-profiler quantities of the paper's latency model on this GPU, and the "
+                         "model's estimate of the config's window step next to the measured one")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 256 MiB device copies first (reference kernel of known traffic for counter runs)")
     args = ap.parse_args()
@@ -56,6 +59,8 @@ def main():
         return bench_batch(args, cfg)
     if args.format:
         return bench_format(args)
+    if args.device_profile:
+        return bench_device_profile(args, cfg)
     d = cfg.dims
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -269,6 +274,55 @@ def bench_batch(args, cfg):
         out["max_rel_err_vs_oracle"] = float((np.abs(got - ref) / np.maximum(np.abs(ref), np.maximum(rms, 1e-30))).max())
         out["cpu_baseline"] = {"value": round(B / cpu_seconds, 4), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"the whole step once ({cpu_seconds:.1f} s of CPU time)"}
+    print(json.dumps(out), flush=True)
+
+
+def bench_device_profile(args, cfg):
+    """The GPU-side inputs of the paper's latency model (App. A.3) measured on this device with the library's own
+    kernels, the model's estimate for one step of the config's window (all layers on the GPU, one window), and the
+    measured step."""
+    import torch
+    import paper_2504_08791_amd as prima
+    from paper_2504_08791_amd import profiler
+    from workloads import synth
+
+    d = cfg.dims
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    dp = profiler.device_profile(d)
+    mp = profiler.model_profile(d)
+    est = profiler.estimate_latency(mp, dp, cfg.n_layers, cfg.n_past + cfg.T)
+    cap = cfg.n_past + cfg.T
+    dev_layers = [{k: torch.from_numpy(v).to(dev) for k, v in synth.layer_tensors(cfg, l, kv_cap=cap).items()} for l in range(cfg.n_layers)]
+    win = prima.Window(d, dev_layers, cap, T_max=cfg.T)
+    x = torch.from_numpy(synth.window_input(cfg)).to(dev)
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        win.decode(x, cfg.n_past, x_out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        win.decode(x, cfg.n_past, x_out=y)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    out = {
+        "metric": "device-profiler quantities of the latency model; estimated vs measured window step", "value": round(ms, 4),
+        "unit": "ms per step (measured)", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_layers}-layer window, T={cfg.T}, n_kv={cfg.n_past}, Q4_K weights"},
+        "device_profile": {
+            "s_gpu_tflops": {q: round(v / 1e12, 3) for q, v in dp["s_gpu"].items()}, "matvec_shape": dp["matvec_shape"],
+            "T_gpu_gbps": round(dp["T_gpu"] / 1e9, 1), "T_gpu_volume_bytes": dp["T_gpu_volume_bytes"],
+            "t_kv_cpy_us": round(dp["t_kv_cpy"] * 1e6, 2), "t_ram_vram_us": round(dp["t_ram_vram"] * 1e6, 2),
+            "t_vram_ram_us": round(dp["t_vram_ram"] * 1e6, 2)},
+        "model_profile": {"flops_per_layer": mp["flops"], "b": mp["b"], "kv_bytes_per_token": mp["kv_bytes_per_token"]},
+        "estimate_ms": {k: round(v * 1e3, 4) for k, v in est.items()},
+        "estimate_over_measured": round(est["T"] * 1e3 / ms, 3),
+        "max_of_terms_over_measured": round(max(est["T_comp"], est["T_mem"]) * 1e3 / ms, 3),
+    }
     print(json.dumps(out), flush=True)
 
 
