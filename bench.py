@@ -37,6 +37,9 @@ def main():
                     help="side measurement: B sequences of the config's context length, one token each per step")
     ap.add_argument("--format", default="", choices=["", "q5_k", "q6_k", "q8_0", "f16", "f32"],
                     help="side measurement: the mat-vec of another weight format at the output layer's and the down projection's shape")
+    ap.add_argument("--mix", action="store_true",
+                    help="side measurement: the config's window with the V and down projections of every other layer in Q6_K "
+                         "(a common mix of a \"Q4K\" model), against the oracle")
     ap.add_argument("--device-profile", action="store_true",
                     help="side measurement: the device-profiler quantities of the paper's latency model on this GPU, and the "
                          "model's estimate of the config's window step next to the measured one")
@@ -61,6 +64,8 @@ def main():
         return bench_format(args)
     if args.device_profile:
         return bench_device_profile(args, cfg)
+    if args.mix:
+        return bench_mix(args, cfg)
     d = cfg.dims
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -274,6 +279,66 @@ def bench_batch(args, cfg):
         out["max_rel_err_vs_oracle"] = float((np.abs(got - ref) / np.maximum(np.abs(ref), np.maximum(rms, 1e-30))).max())
         out["cpu_baseline"] = {"value": round(B / cpu_seconds, 4), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"the whole step once ({cpu_seconds:.1f} s of CPU time)"}
+    print(json.dumps(out), flush=True)
+
+
+def bench_mix(args, cfg):
+    """The config's window with matrices in two formats: V and down projections of every other layer in Q6_K, the rest
+    Q4_K.  One token step timed as the main measurement is; bytes are those of the tensors as stored."""
+    import numpy as np
+    import torch
+    import paper_2504_08791_amd as prima
+    from paper_2504_08791_amd import profiler
+    from workloads import synth
+
+    d = cfg.dims
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cap = cfg.n_past + cfg.T
+    formats = [({"wv": "q6_k", "wdown": "q6_k"} if l % 2 == 0 else {}) for l in range(cfg.n_layers)]
+    want_cpu = not args.no_cpu_baseline
+    x_host = synth.window_input(cfg)
+    h = x_host.astype(np.float64)
+    dev_layers, cpu_seconds = [], 0.0
+    for l in range(cfg.n_layers):
+        t = synth.layer_tensors(cfg, l, kv_cap=cap, formats=formats[l])
+        dev_layers.append({k: torch.from_numpy(v).to(dev) for k, v in t.items()})
+        if want_cpu:
+            import oracle
+            t0 = time.perf_counter()
+            h = oracle.layer(d, t, h, cfg.n_past, formats=formats[l])
+            cpu_seconds += time.perf_counter() - t0
+        del t
+    win = prima.Window(d, dev_layers, cap, T_max=cfg.T, formats=formats)
+    x = torch.from_numpy(x_host).to(dev)
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        win.decode(x, cfg.n_past, x_out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        win.decode(x, cfg.n_past, x_out=y)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    step_bytes = sum(profiler.model_profile(d, f)["b"] for f in formats) + cfg.n_layers * d.kv_bytes_per_layer(cfg.n_past + cfg.T)
+    out = {
+        "metric": "decode tokens/s per layer window, matrices in two formats", "value": round(cfg.T / (ms * 1e-3), 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_layers}-layer window, T={cfg.T}, n_kv={cfg.n_past}; V and down projections of every "
+                               "other layer in Q6_K, the rest Q4_K; fp16 KV", "tokens_per_step": cfg.T, "layers": cfg.n_layers},
+        "window_bytes_per_step": step_bytes, "window_hbm_gbps": round(step_bytes / (ms * 1e-3) / 1e9, 1),
+        "window_hbm_frac": round(step_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+    }
+    if want_cpu:
+        got = y.cpu().numpy().astype(np.float64)
+        rms = np.sqrt((h ** 2).mean(axis=1, keepdims=True))
+        out["max_rel_err_vs_oracle"] = float((np.abs(got - h) / np.maximum(np.abs(h), np.maximum(rms, 1e-30))).max())
+        out["cpu_baseline"] = {"value": round(cfg.T / cpu_seconds, 4), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"the whole window once ({cpu_seconds:.1f} s of CPU time; tensor generation excluded)"}
     print(json.dumps(out), flush=True)
 
 

@@ -61,14 +61,14 @@ struct FmtArgs {
 
 __device__ __forceinline__ float half_bits_to_float(unsigned h) { return __half2float(__ushort_as_half(static_cast<unsigned short>(h))); }
 
-// 6-bit field i of the 96-bit stream in words 1..3 of a Q5_K header
-__device__ __forceinline__ unsigned field6(const uint4 &hdr, int i)
+// Sub-scale and sub-min of sub-block s (0..7) from a Q5_K header: fields s and 8 + s of the 96-bit stream in
+// words 1..3, i.e. stream bits 6s.. (inside words 1, 2) and 48 + 6s.. (inside words 2, 3): one 64-bit shift each
+__device__ __forceinline__ void q5k_scale_min(const uint4 &hdr, int s, unsigned &sc, unsigned &m)
 {
-    const int bit = 6 * i; // 0..90
-    const uint64_t lo = hdr.y | (static_cast<uint64_t>(hdr.z) << 32);
-    unsigned v = bit < 64 ? static_cast<unsigned>(lo >> bit) : hdr.w >> (bit - 64);
-    if (bit > 58 && bit < 64) v |= hdr.w << (64 - bit); // the field that straddles bit 64
-    return v & 63u;
+    const uint64_t lo = hdr.y | (static_cast<uint64_t>(hdr.z) << 32); // stream bits 0..63
+    const uint64_t hi = hdr.z | (static_cast<uint64_t>(hdr.w) << 32); // stream bits 32..95
+    sc = static_cast<unsigned>(lo >> (6 * s)) & 63u;
+    m = static_cast<unsigned>(hi >> (16 + 6 * s)) & 63u;
 }
 
 // The bytes of the 16 weights of (row, k0..k0+15) as loaded (Raw), and as fp32 numbers q[16] with
@@ -149,8 +149,10 @@ __device__ __forceinline__ void decode(const Raw<FMT> &r, Piece &p)
         bytes_to_floats(((r.lo.x >> 4) & 0x0F0F0F0Fu) | ((h << 3) & 0x10101010u), p.q + 4);
         bytes_to_floats((r.lo.y & 0x0F0F0F0Fu) | ((h << 2) & 0x10101010u), p.q + 8);
         bytes_to_floats(((r.lo.y >> 4) & 0x0F0F0F0Fu) | ((h << 1) & 0x10101010u), p.q + 12);
-        p.scale = half_bits_to_float(r.hdr.x & 0xFFFFu) * static_cast<float>(field6(r.hdr, r.s));       // exact
-        p.offset = half_bits_to_float(r.hdr.x >> 16) * static_cast<float>(field6(r.hdr, 8 + r.s)); // exact
+        unsigned sc, m;
+        q5k_scale_min(r.hdr, r.s, sc, m);
+        p.scale = half_bits_to_float(r.hdr.x & 0xFFFFu) * static_cast<float>(sc); // exact
+        p.offset = half_bits_to_float(r.hdr.x >> 16) * static_cast<float>(m);    // exact
     } else if constexpr (FMT == PRIMA_FMT_F16) {
         const unsigned wv[8] = {r.a.x, r.a.y, r.a.z, r.a.w, r.b.x, r.b.y, r.b.z, r.b.w};
 #pragma unroll
@@ -262,14 +264,16 @@ __global__ void __launch_bounds__(FG_THREADS) fmt_gemv_kernel(FmtArgs a)
 #pragma unroll
                 for (int t = 0; t < TT; ++t) acc[r][t] = 0.f;
 
-            for (int kk = lane * FG_V; kk < len; kk += U * FG_PIECE) {
-                Raw<FMT> raw[U][R];
+            // one step: U pieces of each of the R rows: all loads requested, then decoded and used piece by piece
+            auto load_step = [&](Raw<FMT> (&raw)[U][R], int kk) __attribute__((always_inline)) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int kq = kk + u * FG_PIECE < len ? kk + u * FG_PIECE : kk; // past the end: this lane's first piece again, not used
 #pragma unroll
                     for (int r = 0; r < R; ++r) load_raw<FMT>(a.W, a.n_rows, K, rows[r], c0 + kq, raw[u][r]);
                 }
+            };
+            auto use_step = [&](const Raw<FMT> (&raw)[U][R], int kk) __attribute__((always_inline)) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if (kk + u * FG_PIECE < len) {
@@ -302,6 +306,15 @@ __global__ void __launch_bounds__(FG_THREADS) fmt_gemv_kernel(FmtArgs a)
                         }
                     }
                 }
+            };
+            constexpr int STEP = U * FG_PIECE;
+            int kk = lane * FG_V;
+            // (Requesting the next step's weights before this step's arithmetic, with a second set of registers, was
+            // measured: no gain at one token, spills beyond; the other waves of the SIMD already cover the wait.)
+            for (; kk < len; kk += STEP) {
+                Raw<FMT> raw[U][R];
+                load_step(raw, kk);
+                use_step(raw, kk);
             }
 
             // lanes; the first chunk writes y (with the residual), the others add to it (same lane, in chunk order)
