@@ -310,7 +310,8 @@ __global__ void __launch_bounds__(FG_THREADS) fmt_gemv_kernel(FmtArgs a)
             constexpr int STEP = U * FG_PIECE;
             int kk = lane * FG_V;
             // (Requesting the next step's weights before this step's arithmetic, with a second set of registers, was
-            // measured: no gain at one token, spills beyond; the other waves of the SIMD already cover the wait.)
+            // measured: no gain at one token, spills beyond; the other waves of the SIMD already cover the wait.
+            // Two workgroups per compute unit at one token (64 registers a lane, 8 waves per SIMD): 10-30 % slower.)
             for (; kk < len; kk += STEP) {
                 Raw<FMT> raw[U][R];
                 load_step(raw, kk);
