@@ -128,6 +128,45 @@ def test_batch_window_argument_errors():
     assert f(layers=bad) == 1
 
 
+def test_format_calls_argument_errors():
+    """The calls for the other weight formats refuse bad arguments before anything is launched."""
+    L = _ffi.lib()
+    d = _dims()
+    Q4, Q6, F32 = 0, 2, 5
+    assert L.prima_fmt_tensor_bytes(Q6, 4, 512) == 4 * 2 * 210 and L.prima_fmt_tensor_bytes(Q4, 4, 512) == 4 * 2 * 144
+    assert L.prima_fmt_tensor_bytes(Q6, 4, 100) == 0 and L.prima_fmt_tensor_bytes(9, 4, 256) == 0 and L.prima_fmt_tensor_bytes(Q6, -1, 256) == 0
+    g = lambda fmt=Q6, W=FAKE, r=8, c=512, x=FAKE, ldx=512, T=1, y=FAKE, ldy=8: L.prima_fmt_gemv(fmt, W, r, c, x, ldx, T, y, ldy, None)
+    assert g(W=None) == 1 and g(x=None) == 1 and g(y=None) == 1
+    assert g(fmt=Q4) == 2 and g(fmt=6) == 2 and g(fmt=-1) == 2            # Q4_K has its own entry point
+    assert g(c=500) == 2 and g(ldx=256) == 2 and g(ldy=4) == 2 and g(c=0) == 2
+    assert g(T=0) == 4 and g(T=17) == 4
+    assert g(W=FAKE + 8) == 3 and g(x=FAKE + 4) == 3 and g(ldx=514) == 3 and g(y=FAKE + 2) == 3
+    assert g(r=0) == 0                                                     # nothing to do
+    q = lambda fmt=F32, W=FAKE, r=8, c=512, out=FAKE: L.prima_fmt_dequant(fmt, W, r, c, out, None)
+    assert q(W=None) == 1 and q(out=None) == 1 and q(c=300) == 2 and q(fmt=7) == 2 and q(W=FAKE + 4) == 3
+    assert q(r=0, W=None, out=None) == 0
+    h = lambda dd=d, fmt=Q6, gf=FAKE, W=FAKE, vocab=100, x=FAKE, T=1, lo=FAKE: L.prima_lm_head_fmt(C.byref(dd), fmt, gf, W, vocab, x, T, lo, None)
+    assert h(gf=None) == 1 and h(W=None) == 1 and h(x=None) == 1 and h(lo=None) == 1
+    assert h(fmt=Q4) == 2 and h(vocab=0) == 2 and h(dd=_dims(head_dim=96)) == 2
+    assert h(T=0) == 4 and h(T=17) == 4 and h(x=FAKE + 4) == 3
+    # a window with formats: codes checked for every layer
+    lay = (_ffi.Layer * 2)()
+    for i in range(2):
+        for name, _ in _ffi.Layer._fields_:
+            setattr(lay[i], name, FAKE)
+    fm = (_ffi.LayerFormats * 2)()
+    need = L.prima_workspace_bytes(C.byref(d), 64, 1)
+    w = lambda layers=lay, formats=fm, Ln=2, cap=64, npast=10, T=1, xi=FAKE, xo=FAKE, ws=FAKE, wsb=need: \
+        L.prima_layer_window_decode_mixed(C.byref(d), layers, formats, Ln, cap, npast, T, xi, xo, ws, wsb, None)
+    assert w(formats=None) == 1 and w(layers=None) == 1 and w(xi=None) == 1
+    assert w(Ln=0) == 4 and w(npast=64) == 4 and w(wsb=need - 1) == 5
+    bad = (_ffi.LayerFormats * 2)()
+    bad[1].wdown = 6
+    assert w(formats=bad) == 2
+    bad[1].wdown = -1
+    assert w(formats=bad) == 2
+
+
 def test_missing_library_is_an_error(monkeypatch, tmp_path):
     monkeypatch.setattr(_ffi, "_lib", None)
     monkeypatch.setattr(_ffi, "LIB_PATH", str(tmp_path / "absent.so"))
