@@ -27,8 +27,9 @@
  * brute-force dense products, library fp64 matmul / softmax, invariants of
  * softmax / RMSNorm / RoPE, joint-equals-sequential for T > 1, KV rewind.
  * Unpinned against any external artefact (free choices with no outside truth
- * here): the byte layout of a super-block, the RoPE pairing default, bias-free
- * projections.  These are "parity unpinned" with respect to real checkpoints.
+ * here): the byte layout of a super-block, the placement of the fields of the
+ * other formats, the RoPE pairing default, bias-free projections.  These are
+ * "parity unpinned" with respect to real checkpoints.
  */
 #include <math.h>
 #include <stdint.h>
