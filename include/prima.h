@@ -270,6 +270,13 @@ prima_status prima_layer_window_decode_mixed(const prima_dims *d, const prima_la
                                              const float *x_in, float *x_out,
                                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Host-side check, no GPU work: PRIMA_OK if every mat-vec launch of a window step of T tokens with these
+ * dimensions (including the launches used when some matrices are in other formats) finds a launch plan and
+ * fits the scratch of prima_workspace_bytes(d, kv_cap, T); otherwise the status such a step would return.
+ */
+prima_status prima_window_plan_status(const prima_dims *d, int32_t kv_cap, int32_t T);
+
 /* Bytes of scratch the window calls need for up to T tokens and kv_cap cache rows. */
 size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
 

@@ -138,6 +138,12 @@ def workspace_bytes(dims, kv_cap, T):
     return _ffi.lib().prima_workspace_bytes(C.byref(d), kv_cap, T)
 
 
+def window_plan_status(dims, kv_cap, T):
+    """Host-side check (no GPU work): 0 if a window step of T tokens with these dimensions can be launched."""
+    d = make_dims(dims)
+    return _ffi.lib().prima_window_plan_status(C.byref(d), kv_cap, T)
+
+
 def stream_read_probe(buf, sink):
     """Measurement hook: one linear read of the uint8 tensor `buf` (discarded); `sink` any 4-byte device tensor."""
     _ffi.check(_ffi.lib().prima_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()),

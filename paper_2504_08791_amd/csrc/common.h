@@ -91,6 +91,8 @@ prima_status launch_gemv_mfma(const GemvArgs &a, void *ws, size_t ws_bytes, size
 size_t gemv_ws_bytes(int64_t n_rows_total, int64_t n_cols, int T);
 size_t gemv_arrivals_bytes(int64_t n_rows_total);
 prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
+// host only: whether every pass of this launch finds a plan and fits the scratch (nothing is launched)
+prima_status gemv_plan_status(const GemvArgs &a, void *ws, size_t ws_bytes, size_t arrivals_region);
 
 prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
 prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st);

@@ -142,6 +142,19 @@ static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
     return hipGetLastError();
 }
 
+// host only: whether every pass of this launch finds a plan and fits the scratch (nothing is launched; ws is not touched)
+prima_status gemv_plan_status(const GemvArgs &ga, void *ws, size_t ws_bytes, size_t arrivals_region)
+{
+    for (int t0 = 0; t0 < ga.T; t0 += MAX_T_PASS) {
+        const int T = ga.T - t0 < MAX_T_PASS ? ga.T - t0 : MAX_T_PASS;
+        PPlan p;
+        PGemvArgs a;
+        const prima_status bs = build_pass(ga, t0, T, ws, ws_bytes, arrivals_region, a, p);
+        if (bs != PRIMA_OK) return bs;
+    }
+    return PRIMA_OK;
+}
+
 prima_status launch_gemv_mfma(const GemvArgs &ga, void *ws, size_t ws_bytes, size_t arrivals_region, hipStream_t st)
 {
     // up to MAX_T_PASS tokens per pass over the weights

@@ -329,6 +329,31 @@ prima_status prima_lm_head_fmt(const prima_dims *d, int32_t fmt, const float *g_
                            logits, vocab, static_cast<hipStream_t>(hip_stream));
 }
 
+prima_status prima_window_plan_status(const prima_dims *d, int32_t kv_cap, int32_t T)
+{
+    if (!d) return PRIMA_E_NULL;
+    if (!dims_ok(d)) return PRIMA_E_SHAPE;
+    if (T < 1 || T > PRIMA_MAX_TOK || kv_cap < T) return PRIMA_E_RANGE;
+    const WindowWs w = carve(*d, kv_cap, T);
+    const int64_t e = d->e, qd = static_cast<int64_t>(d->n_q_heads) * d->head_dim, kvd = static_cast<int64_t>(d->n_kv_heads) * d->head_dim, F = d->ffn;
+    static float dummy[4];                       // addresses only: nothing is read or written
+    char *const ws = reinterpret_cast<char *>(dummy);
+    struct Launch { int nseg; int64_t rows[3]; int64_t cols; int xmode, epi; };
+    // the launches of a layer, and those of its groups when some of their matrices are in other formats
+    const Launch launches[] = {{3, {qd, kvd, kvd}, e, X_RMSNORM, EPI_ROWS}, {2, {qd, kvd, 0}, e, X_RMSNORM, EPI_ROWS},
+                               {2, {kvd, kvd, 0}, e, X_RMSNORM, EPI_ROWS}, {1, {qd, 0, 0}, e, X_RMSNORM, EPI_ROWS},
+                               {1, {kvd, 0, 0}, e, X_RMSNORM, EPI_ROWS}, {1, {e, 0, 0}, qd, X_PLAIN, EPI_ROWS},
+                               {2, {F, F, 0}, e, X_RMSNORM, EPI_SWIGLU}, {1, {F, 0, 0}, e, X_RMSNORM, EPI_ROWS},
+                               {1, {e, 0, 0}, F, X_PLAIN, EPI_ROWS}};
+    for (const Launch &l : launches) {
+        GemvArgs ga = gemv_args(l.nseg, l.cols, dummy, l.cols, T, l.xmode, dummy, d->rms_eps, l.epi);
+        for (int i = 0; i < l.nseg; ++i) ga.seg[i] = seg(ws, dummy, l.rows[i], l.rows[i]);
+        const prima_status s = gemv_plan_status(ga, ws, w.gemv_bytes, w.arrivals_bytes);
+        if (s != PRIMA_OK) return s;
+    }
+    return PRIMA_OK;
+}
+
 size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
 {
     if (!d || !dims_ok(d) || T < 1 || T > PRIMA_MAX_TOK || kv_cap < 0) return 0;

@@ -172,3 +172,21 @@ def test_missing_library_is_an_error(monkeypatch, tmp_path):
     monkeypatch.setattr(_ffi, "LIB_PATH", str(tmp_path / "absent.so"))
     with pytest.raises(ImportError):
         _ffi.lib()
+
+
+def test_every_model_shape_and_token_count_can_be_planned():
+    """Every mat-vec launch of a window step (the subsets launched for mixed formats included) finds a plan that fits
+    the scratch the library asks for: all benchmark shapes, the tiny test shapes and two more models' shapes, every
+    token count.  (A scratch sized from the plan of a slightly different tile count once refused config 0's shape
+    from 8 tokens on.)"""
+    from workloads.configs import CONFIGS, TINY, ModelDims
+    L = _ffi.lib()
+    shapes = {c.dims for c in list(CONFIGS.values()) + list(TINY.values())}
+    shapes |= {ModelDims(3584, 28, 4, 128, 18944, 1e6), ModelDims(2048, 16, 2, 128, 5632, 1e4), ModelDims(4096, 32, 32, 128, 11008, 1e4)}
+    for dm in shapes:
+        d = _ffi.Dims(dm.e, dm.n_q_heads, dm.n_kv_heads, dm.head_dim, dm.ffn, dm.rope_theta, dm.rms_eps, dm.rope_mode)
+        for T in range(1, 17):
+            assert L.prima_window_plan_status(C.byref(d), 4096 + T, T) == 0, (dm, T)
+    d = _dims()
+    assert L.prima_window_plan_status(None, 64, 1) == 1 and L.prima_window_plan_status(C.byref(_dims(head_dim=96)), 64, 1) == 2
+    assert L.prima_window_plan_status(C.byref(d), 64, 0) == 4 and L.prima_window_plan_status(C.byref(d), 64, 17) == 4
