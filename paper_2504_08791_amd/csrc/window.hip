@@ -39,7 +39,7 @@ WindowWs carve(const prima_dims &d, int kv_cap, int T)
     w.rope = take(T * static_cast<size_t>(d.head_dim) * f);
     w.attn = take(attn_ws_bytes(d, kv_cap, T));
     // mat-vec scratch: sized for the largest of the layer's (and the output layer's) launches
-    const int64_t rows_max = std::max<int64_t>(2 * static_cast<int64_t>(d.ffn), static_cast<int64_t>(qd + 2 * kvd));
+    const int64_t rows_max = std::max<int64_t>({2 * static_cast<int64_t>(d.ffn), static_cast<int64_t>(qd + 2 * kvd), static_cast<int64_t>(d.e)});
     // (the last five: subsets of a group, launched when its other matrices are in other formats)
     const int64_t shapes[9][2] = {{static_cast<int64_t>(qd + 2 * kvd), d.e}, {d.e, static_cast<int64_t>(qd)}, {2 * static_cast<int64_t>(d.ffn), d.e}, {d.e, d.ffn},
                                   {static_cast<int64_t>(qd), d.e}, {static_cast<int64_t>(kvd), d.e}, {static_cast<int64_t>(qd + kvd), d.e},

@@ -187,6 +187,14 @@ def test_every_model_shape_and_token_count_can_be_planned():
         d = _ffi.Dims(dm.e, dm.n_q_heads, dm.n_kv_heads, dm.head_dim, dm.ffn, dm.rope_theta, dm.rms_eps, dm.rope_mode)
         for T in range(1, 17):
             assert L.prima_window_plan_status(C.byref(d), 4096 + T, T) == 0, (dm, T)
+    # a grid of small shapes, among them hidden sizes above 2 ffn and above the Q/K/V rows (the arrival counters were
+    # once sized for those two only)
+    for D, Hkv, G in [(64, 1, 4), (64, 8, 7), (128, 2, 5), (128, 8, 8), (64, 16, 16)]:
+        for e in (256, 1536, 3584, 8192):
+            for ffn in (256, 1280, 4864, 14336):
+                d = _ffi.Dims(e, Hkv * G, Hkv, D, ffn, 1e4, 1e-5, 0)
+                for T in (1, 2, 5, 8, 11, 16):
+                    assert L.prima_window_plan_status(C.byref(d), 1100, T) == 0, (D, Hkv, G, e, ffn, T)
     d = _dims()
     assert L.prima_window_plan_status(None, 64, 1) == 1 and L.prima_window_plan_status(C.byref(_dims(head_dim=96)), 64, 1) == 2
     assert L.prima_window_plan_status(C.byref(d), 64, 0) == 4 and L.prima_window_plan_status(C.byref(d), 64, 17) == 4
