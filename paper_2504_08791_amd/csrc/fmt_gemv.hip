@@ -21,8 +21,9 @@
 // 128 KB: all of K for one token up to K = 32768; otherwise K is walked in chunks and y accumulates chunk by
 // chunk), with the RMSNorm gain already applied: read from L2 by every wave they cost as much bandwidth as
 // the weights (measured: every quantised format stuck at the same 4.6 T weights/s, FP16 alone reached the
-// HBM rate).  A wave owns its rows outright: R rows (4; 2 from five tokens on; 1 when there are few rows, for balance) times U = 4/R
-// pieces of 1024 weights per step, a lane taking 16 consecutive weights of a piece: one 4..16-byte load per
+// HBM rate).  A wave owns its rows outright: R rows (4; with few rows 1 at one or two tokens and 2 at three or
+// four, for balance; always 2 from five tokens on, for registers) times U = 4/R pieces of 1024 weights per
+// step, a lane taking 16 consecutive weights of a piece: one 4..16-byte load per
 // field, four loads in flight per lane.  The 16 weights of a lane lie in one sub-block of every format, so a
 // lane needs one scale per piece and adds  scale * (sum q x) - offset * (sum x): one multiply-add per weight
 // and token plus the unpacking, which the tokens share.  Lanes are summed by row rotations and permlane swaps;
