@@ -276,6 +276,8 @@ prima_status prima_layer_window_decode_mixed(const prima_dims *d, const prima_la
  * fits the scratch of prima_workspace_bytes(d, kv_cap, T); otherwise the status such a step would return.
  */
 prima_status prima_window_plan_status(const prima_dims *d, int32_t kv_cap, int32_t T);
+/* The same for one prima_q4k_gemv call with the scratch of prima_gemv_workspace_bytes(n_rows, n_cols, T). */
+prima_status prima_gemv_plan_status(int64_t n_rows, int64_t n_cols, int32_t T);
 
 /* Bytes of scratch the window calls need for up to T tokens and kv_cap cache rows. */
 size_t prima_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);

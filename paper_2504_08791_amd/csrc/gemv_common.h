@@ -162,7 +162,12 @@ inline PPlan plan_for(int n_tiles, int nb, int T, int epi)
         p.slab_blocks = ((nb + n_slabs - 1) / n_slabs + 1) & ~1;
         if ((nb + p.slab_blocks - 1) / p.slab_blocks != n_slabs) continue; // rounding to even merged two slabs
         const int chunks = (p.slab_blocks + PBS - 1) / PBS;
-        for (int ks = 1; ks <= 4 * GEMV_WAVES && ks <= chunks; ks *= 2) {
+        // The last slab may be shorter.  Every part of a unit must hold at least one chunk in every slab: the kernel's
+        // two cursors (requesting and consuming) exchange the units they take through a short queue in LDS, sized for
+        // the few units that the ring's stages can span; units without chunks would let the requesting cursor run
+        // past the queue's end (wrong sums, and tile numbers read from slots nobody wrote).
+        const int chunks_last = (nb - (n_slabs - 1) * p.slab_blocks + PBS - 1) / PBS;
+        for (int ks = 1; ks <= 4 * GEMV_WAVES && ks <= chunks && ks <= chunks_last; ks *= 2) {
             // ks == 1: a wave owns its tiles and stores their sums itself (a pair's two sums can only meet in
             // global memory, i.e. with several slabs); otherwise the parts meet in LDS
             const bool direct = ks == 1 && (gran == 1 || n_slabs > 1);
@@ -216,6 +221,8 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
     p = plan_for(n_tiles, static_cast<int>(ga.n_cols / QK), T, ga.epi);
     if (!p.ok) return PRIMA_E_SHAPE;
     if (static_cast<int64_t>(n_tiles) * (p.n_wg + 1) >= (int64_t{1} << 31)) return PRIMA_E_SHAPE; // the kernel's 32-bit tile arithmetic
+    // what the kernel's unit queue relies on (plan_for sees to it): every part of a unit has a chunk in every slab
+    if (p.ksplit > (p.nb - (p.n_slabs - 1) * p.slab_blocks + PBS - 1) / PBS) return PRIMA_E_SHAPE;
     a = PGemvArgs{};
     int tile0 = 0;
     for (int i = 0; i < ga.nseg; ++i) {

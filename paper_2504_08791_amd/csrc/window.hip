@@ -329,6 +329,17 @@ prima_status prima_lm_head_fmt(const prima_dims *d, int32_t fmt, const float *g_
                            logits, vocab, static_cast<hipStream_t>(hip_stream));
 }
 
+prima_status prima_gemv_plan_status(int64_t n_rows, int64_t n_cols, int32_t T)
+{
+    if (n_rows < 0 || n_cols <= 0 || n_cols % QK) return PRIMA_E_SHAPE;
+    if (T < 1 || T > PRIMA_MAX_TOK) return PRIMA_E_RANGE;
+    if (n_rows == 0) return PRIMA_OK;
+    static float dummy[4]; // addresses only: nothing is read or written
+    GemvArgs ga = gemv_args(1, n_cols, dummy, n_cols, T);
+    ga.seg[0] = seg(dummy, dummy, n_rows, n_rows);
+    return gemv_plan_status(ga, dummy, std::max<size_t>(256, gemv_ws_bytes(n_rows, n_cols, T)), gemv_arrivals_bytes(n_rows));
+}
+
 prima_status prima_window_plan_status(const prima_dims *d, int32_t kv_cap, int32_t T)
 {
     if (!d) return PRIMA_E_NULL;

@@ -128,6 +128,19 @@ def test_batch_window_argument_errors():
     assert f(layers=bad) == 1
 
 
+def test_every_mat_vec_shape_can_be_planned():
+    """Every number of super-blocks per row up to 160, every token count, few and many rows: a plan exists, fits the
+    scratch, and gives every part of a unit a chunk in every slab of K (the kernel's unit queue relies on it: a plan
+    that split K further than the short last slab allows once gave wrong sums and a memory fault, e.g. 8000 rows of
+    41 or 57 super-blocks at 2 to 4 tokens)."""
+    L = _ffi.lib()
+    for nb in range(1, 161):
+        for T in range(1, 17):
+            for rows in (1, 17, 300, 1000, 8000, 20000):
+                assert L.prima_gemv_plan_status(rows, nb * 256, T) == 0, (rows, nb, T)
+    assert L.prima_gemv_plan_status(8, 100, 1) == 2 and L.prima_gemv_plan_status(8, 256, 0) == 4 and L.prima_gemv_plan_status(0, 256, 1) == 0
+
+
 def test_format_calls_argument_errors():
     """The calls for the other weight formats refuse bad arguments before anything is launched."""
     L = _ffi.lib()

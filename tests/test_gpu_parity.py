@@ -95,6 +95,23 @@ def test_gemv_random_shapes(gpu_lib):
         assert np.array_equal(got.view(np.uint32), again.view(np.uint32)), (rows, nb, T)
 
 
+def test_gemv_short_last_slab_of_k(gpu_lib):
+    """Many rows, K cut into slabs whose last one is much shorter than the others (25, 26, 33, 41, 57 super-blocks at 2 to
+    4 tokens: slabs of 8, the last of 1 or 2): every workgroup of that slab takes many units.  (With K split further
+    than the last slab's chunks these shapes once gave wrong sums: units without a chunk overran the unit queue.)"""
+    rng = np.random.default_rng(99)
+    for rows, nb, T in [(8000, 25, 3), (8000, 25, 2), (8000, 41, 4), (8000, 57, 2), (4000, 33, 3), (8000, 26, 4), (6000, 49, 2)]:
+        print("case", rows, nb, T, flush=True)
+        W = _rand_q4k(rng, rows, nb)
+        x = rng.standard_normal((T, nb * 256)).astype(np.float32)
+        ref = oracle.gemv(W, x.astype(np.float64))
+        Wd, xd = _dev(W), _dev(x)
+        got = gpu_lib.q4k_gemv(Wd, xd).cpu().numpy()
+        again = gpu_lib.q4k_gemv(Wd, xd).cpu().numpy()
+        assert rel_err(got, ref) < 1e-4, (rows, nb, T, rel_err(got, ref))
+        assert np.array_equal(got.view(np.uint32), again.view(np.uint32)), (rows, nb, T)
+
+
 def test_gemv_wide_dynamic_range(gpu_lib):
     """Activations like the SwiGLU output of the synthetic models: huge, common-mode, with outliers."""
     rng = np.random.default_rng(5)
