@@ -22,7 +22,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes of one gate/up launch of config 3 from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs (scaled by
 # what the same counters read for a plain 256 MiB copy): see profiles/gemv_q4k_persistent_c3_hbm_traffic.txt
-GATE_UP_TRAFFIC_BYTES = 265_155_000
+GATE_UP_TRAFFIC_BYTES = 265_153_000
 
 
 def main():
