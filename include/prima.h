@@ -270,6 +270,13 @@ prima_status prima_layer_window_decode_mixed(const prima_dims *d, const prima_la
                                              const float *x_in, float *x_out,
                                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* prima_layer_window_decode_batch for layers whose matrices are in several formats (formats as above; NULL: all Q4_K). */
+prima_status prima_layer_window_decode_batch_mixed(const prima_dims *d, const prima_layer *layers, const prima_layer_formats *formats,
+                                                   int32_t L, int32_t kv_cap, int32_t B, const int32_t *n_past,
+                                                   void *const *k_caches, void *const *v_caches,
+                                                   const float *x_in, float *x_out,
+                                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /*
  * Host-side check, no GPU work: PRIMA_OK if every mat-vec launch of a window step of T tokens with these
  * dimensions (including the launches used when some matrices are in other formats) finds a launch plan and

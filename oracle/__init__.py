@@ -247,10 +247,11 @@ def window(dims, layers, x, n_past, formats=None):
     return h
 
 
-def window_batch(dims, layers, caches, x, n_past):
+def window_batch(dims, layers, caches, x, n_past, formats=None):
     """One token for each of B independent sequences (continuous batching, App. A.12): row b of x is advanced
     through the layers against sequence b's own caches, caches[l][b] = (k_cache, v_cache) with n_past[b] rows
-    (updated in place), exactly as a one-token call for that sequence alone.  The layers' own caches are not used."""
+    (updated in place), exactly as a one-token call for that sequence alone.  The layers' own caches are not used.
+    formats: optional list of per-layer dicts as for layer()."""
     x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
     y = np.empty_like(x)
     for b in range(x.shape[0]):
@@ -258,7 +259,7 @@ def window_batch(dims, layers, caches, x, n_past):
         for l, t in enumerate(layers):
             tb = dict(t)
             tb["k_cache"], tb["v_cache"] = caches[l][b]
-            h = layer(dims, tb, h, int(n_past[b]))
+            h = layer(dims, tb, h, int(n_past[b]), formats=formats[l] if formats else None)
         y[b] = h[0]
     return y
 

@@ -225,9 +225,9 @@ class Window:
         np_arr = (C.c_int32 * B)(*[int(n) for n in n_past])
         k_arr = (C.c_void_p * (L * B))(*[caches[l][b][0].data_ptr() for l in range(L) for b in range(B)])
         v_arr = (C.c_void_p * (L * B))(*[caches[l][b][1].data_ptr() for l in range(L) for b in range(B)])
-        _ffi.check(_ffi.lib().prima_layer_window_decode_batch(C.byref(self.dims), self._arr, L, self.kv_cap, B, np_arr,
-                                                              k_arr, v_arr, _ptr(x_in), _ptr(x_out), _ptr(self.workspace),
-                                                              self.workspace.numel(), _stream()),
+        _ffi.check(_ffi.lib().prima_layer_window_decode_batch_mixed(C.byref(self.dims), self._arr, self._formats, L, self.kv_cap, B,
+                                                                    np_arr, k_arr, v_arr, _ptr(x_in), _ptr(x_out), _ptr(self.workspace),
+                                                                    self.workspace.numel(), _stream()),
                    "prima_layer_window_decode_batch")
         return x_out
 

@@ -14,7 +14,7 @@ EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", 
            "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_window_decode_profiled", "prima_layer_decode_taps",
            "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
            "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
-           "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt", "prima_layer_window_decode_mixed", "prima_window_plan_status", "prima_gemv_plan_status"]
+           "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt", "prima_layer_window_decode_mixed", "prima_window_plan_status", "prima_gemv_plan_status", "prima_layer_window_decode_batch_mixed"]
 FORMATS = {"q4_k": 0, "q5_k": 1, "q6_k": 2, "q8_0": 3, "f16": 4, "f32": 5}
 
 
@@ -63,6 +63,9 @@ def lib():
         L.prima_layer_window_decode_batch.argtypes = [dp, lp, i32, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_void_p),
                                                       C.POINTER(C.c_void_p), vp, vp, vp, sz, vp]
         L.prima_layer_window_decode_batch.restype = C.c_int
+        L.prima_layer_window_decode_batch_mixed.argtypes = [dp, lp, C.POINTER(LayerFormats), i32, i32, i32, C.POINTER(C.c_int32),
+                                                            C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), vp, vp, vp, sz, vp]
+        L.prima_layer_window_decode_batch_mixed.restype = C.c_int
         L.prima_layer_decode_taps.argtypes = [dp, lp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.prima_lm_head.argtypes = [dp, vp, vp, i64, vp, i32, vp, vp, sz, vp]
         L.prima_lm_head_workspace_bytes.argtypes = [dp, i64, i32]

@@ -440,6 +440,16 @@ prima_status prima_layer_window_decode_batch(const prima_dims *d, const prima_la
                                              const float *x_in, float *x_out,
                                              void *workspace, size_t workspace_bytes, void *hip_stream)
 {
+    return prima_layer_window_decode_batch_mixed(d, layers, nullptr, L, kv_cap, B, n_past, k_caches, v_caches, x_in, x_out,
+                                                 workspace, workspace_bytes, hip_stream);
+}
+
+prima_status prima_layer_window_decode_batch_mixed(const prima_dims *d, const prima_layer *layers, const prima_layer_formats *formats,
+                                                   int32_t L, int32_t kv_cap, int32_t B, const int32_t *n_past,
+                                                   void *const *k_caches, void *const *v_caches,
+                                                   const float *x_in, float *x_out,
+                                                   void *workspace, size_t workspace_bytes, void *hip_stream)
+{
     if (!layers || !n_past || !k_caches || !v_caches) return PRIMA_E_NULL;
     prima_status s = check_window_args(d, kv_cap, 0, B, x_in, x_out, workspace, workspace_bytes);
     if (s != PRIMA_OK) return s;
@@ -448,6 +458,11 @@ prima_status prima_layer_window_decode_batch(const prima_dims *d, const prima_la
         if (n_past[b] < 0 || static_cast<int64_t>(n_past[b]) + 1 > kv_cap) return PRIMA_E_RANGE;
     for (int i = 0; i < L; ++i) {
         if ((s = check_layer(layers[i], false)) != PRIMA_OK) return s;
+        if (formats) {
+            const int32_t f[7] = {formats[i].wq, formats[i].wk, formats[i].wv, formats[i].wo, formats[i].wgate, formats[i].wup, formats[i].wdown};
+            for (int32_t v : f)
+                if (v < PRIMA_FMT_Q4_K || v > PRIMA_FMT_F32) return PRIMA_E_SHAPE;
+        }
         for (int b = 0; b < B; ++b) {
             const void *kc = k_caches[static_cast<size_t>(i) * B + b], *vc = v_caches[static_cast<size_t>(i) * B + b];
             if (!kc || !vc) return PRIMA_E_NULL;
@@ -467,7 +482,8 @@ prima_status prima_layer_window_decode_batch(const prima_dims *d, const prima_la
             vc[b] = static_cast<__half *>(v_caches[static_cast<size_t>(i) * B + b]);
         }
         const AttnSeqs seq{n_past, kc, vc};
-        s = run_layer(*d, layers[i], kv_cap, 0, B, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr, -1, &seq);
+        s = run_layer(*d, layers[i], kv_cap, 0, B, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr, -1, &seq,
+                      formats ? &formats[i] : nullptr);
         if (s != PRIMA_OK) return s;
         cur = dst;
     }

@@ -176,6 +176,11 @@ def test_format_calls_argument_errors():
     bad = (_ffi.LayerFormats * 2)()
     bad[1].wdown = 6
     assert w(formats=bad) == 2
+    ptrs = (C.c_void_p * 6)(*([FAKE] * 6))
+    lens = (C.c_int32 * 3)(0, 5, 9)
+    needb = L.prima_workspace_bytes(C.byref(d), 64, 3)
+    assert L.prima_layer_window_decode_batch_mixed(C.byref(d), lay, bad, 2, 64, 3, lens, ptrs, ptrs, FAKE, FAKE, FAKE, needb, None) == 2
+    assert L.prima_layer_window_decode_batch_mixed(C.byref(d), lay, fm, 2, 64, 3, None, ptrs, ptrs, FAKE, FAKE, FAKE, needb, None) == 1
     bad[1].wdown = -1
     assert w(formats=bad) == 2
 

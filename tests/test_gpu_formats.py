@@ -207,3 +207,34 @@ def test_mixed_window_full_shape(gpu_lib):
     win.workspace.fill_(0xFF)
     y = win.decode(_dev(x), cfg.n_past).cpu().numpy()
     assert rel_err(y, h) < 2e-3, rel_err(y, h)
+
+
+@pytest.mark.parametrize("name", ["t0", "t1", "t2"])
+def test_batch_of_sequences_with_mixed_formats(gpu_lib, name):
+    """One token for each of several sequences of different lengths (one empty, one full) through two layers whose
+    matrices are in several formats: hidden states against the oracle (each sequence alone), appended rows."""
+    formats = MIXES["all_kinds"][:2]
+    cfg = TINY[name].with_(n_layers=2)
+    d = cfg.dims
+    lens = [0, 5, cfg.n_past, 17, 5]
+    B = len(lens)
+    cap = cfg.n_past + 1
+    host = [synth.layer_tensors(cfg.with_(n_past=0), l, kv_cap=1, formats=formats[l]) for l in range(2)]
+    dev_layers = [{k: _dev(v) for k, v in t.items()} for t in host]
+    for dl in dev_layers:      # the window's own caches are not used by a batch
+        dl["k_cache"] = torch.zeros((d.n_kv_heads, cap, d.head_dim), dtype=torch.float16, device="cuda")
+        dl["v_cache"] = dl["k_cache"]
+    caches = synth.batch_caches(cfg, 2, lens, cap)
+    dev_caches = [[(_dev(k), _dev(v)) for k, v in per_layer] for per_layer in caches]
+    xb = synth.batch_input(cfg, B)
+    ref = oracle.window_batch(d, host, caches, xb.astype(np.float64), lens, formats=formats)     # appends to the host caches
+    win = gpu_lib.Window(d, dev_layers, cap, T_max=B, formats=formats)
+    win.workspace.fill_(0xFF)
+    y = win.decode_batch(_dev(xb), lens, dev_caches).cpu().numpy()
+    assert rel_err(y, ref) < 2e-3, rel_err(y, ref)
+    for l in range(2):
+        for b in range(B):
+            for i in range(2):
+                got = dev_caches[l][b][i][:, lens[b]].float().cpu().numpy().reshape(1, -1)
+                want = caches[l][b][i][:, lens[b]].astype(np.float64).reshape(1, -1)
+                assert rel_err(got, want) < 2e-3
