@@ -84,7 +84,7 @@ static uint16_t float_to_half_rne(float f)
 }
 
 /* ---------- Q4_K super-block decoding ----------
- * Semantics (benchmark config 0): 256 weights per super-block; fp16 d and dmin;
+ * Semantics (as in config 0 of workloads/configs.py): 256 weights per super-block; fp16 d and dmin;
  * eight 6-bit sub-scales sc_s and eight 6-bit sub-mins m_s; 256 4-bit quants;
  *     w = d * sc_s * q - dmin * m_s,   s = index / 32.
  * Byte layout of the 144 bytes (this repository's layout, version 1):

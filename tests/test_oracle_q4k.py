@@ -1,7 +1,7 @@
 """Pins for the oracle's Q4_K decoding and mat-vec (CPU only).
 
 Semantics pinned: 256 weights per super-block, w = d*sc_s*q - dmin*m_s with s = t // 32
-(benchmark config 0); the paper itself only names the format (App. A.3, computation latency).
+(config 0 of workloads/configs.py); the paper itself only names the format (App. A.3, computation latency).
 """
 import os
 import random
