@@ -159,3 +159,60 @@ def test_layer_does_not_depend_on_the_format_of_a_matrix():
             t2[n] = oracle.dequant(t[n]).view(np.uint8).reshape(-1)
         got = oracle.layer(d, t2, x, cfg.n_past, formats={n: "f32" for n in subset})
         assert np.array_equal(got, ref), subset
+
+
+# ---- do the pins bite?  Plausible mistakes planted in a copy of the oracle's source (on the CPU, in a temporary
+# ---- library; the oracle itself is untouched): each must fail the exact-value pin.
+_MUTANTS = [
+    ("q6_k", "(qh[(t / 16) * 4 + t % 4] >> (2 * ((t % 16) / 4))) & 3", "(qh[t / 4] >> (2 * (t % 4))) & 3", "high bits read from another placement"),
+    ("q6_k", "d * (float)sc[t / 16]", "d * (float)sc[t / 32]", "sub-scale of the wrong sub-block"),
+    ("q6_k", "(lo | (hi << 4)) - 32)", "(lo | (hi << 4)) - 31)", "offset 31 instead of 32"),
+    ("q6_k", "(lo | (hi << 4)) - 32)", "(lo | (hi << 2)) - 32)", "high bits shifted to the wrong place"),
+    ("q5_k", "(qh[(t / 32) * 4 + t % 4] >> ((t % 32) / 4)) & 1", "(qh[t / 8] >> (t % 8)) & 1", "fifth bit read from another placement"),
+    ("q5_k", "field6(hdr, 8 + s); /* field6 skips", "field6(hdr, s); /* field6 skips", "sub-min taken from the sub-scale's field"),
+    ("q5_k", "return (t % 8 < 4) ? (byte & 15) : (byte >> 4);", "return (t % 8 < 4) ? (byte >> 4) : (byte & 15);", "nibbles swapped"),
+    ("q5_k", "uint8_t byte = nib[(t / 8) * 4 + t % 4];", "uint8_t byte = nib[t / 2];", "low bits read from another placement"),
+    ("q8_0", "half_at(dp + 2 * (t / 32))", "half_at(dp + 2 * (t / 64))", "scale of the wrong block"),
+    ("q8_0", "const int8_t *q = (const int8_t *)W + blk * QK;", "const uint8_t *q = (const uint8_t *)W + blk * QK;", "quants read as unsigned"),
+]
+
+
+@pytest.mark.parametrize("fmt,old,new,what", _MUTANTS, ids=[m[3] for m in _MUTANTS])
+def test_a_planted_mistake_fails_the_exact_value_pin(tmp_path, fmt, old, new, what):
+    import ctypes as C
+    import subprocess
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "prima_oracle.c")).read()
+    assert src.count(old) == 1, "the oracle's text has changed: update this mutant"
+    bad_c, bad_so = tmp_path / "mutant.c", tmp_path / "mutant.so"
+    bad_c.write_text(src.replace(old, new))
+    subprocess.check_call(["gcc", "-O1", "-ffp-contract=off", "-fPIC", "-shared", "-o", str(bad_so), str(bad_c), "-lm"])
+    lib = C.CDLL(str(bad_so))
+    rng = np.random.default_rng(11)
+    rows, nb = 3, 2
+    if fmt == "q5_k":
+        d, dm = _finite_half_bits(rng, (rows, nb)) & 0x7FFF, _finite_half_bits(rng, (rows, nb)) & 0x7FFF
+        sc, m = rng.integers(0, 64, (rows, nb, 8)), rng.integers(0, 64, (rows, nb, 8))
+        q = rng.integers(0, 32, (rows, nb, 256))
+        W = fp.pack_q5k(d, dm, sc, m, q)
+        exact = lambda r, b, t: fp.exact_q5k(d[r, b], dm[r, b], sc[r, b, t // 32], m[r, b, t // 32], q[r, b, t])
+    elif fmt == "q6_k":
+        d = _finite_half_bits(rng, (rows, nb))
+        sc = rng.integers(-128, 128, (rows, nb, 16))
+        q = rng.integers(0, 64, (rows, nb, 256))
+        W = fp.pack_q6k(d, sc, q)
+        exact = lambda r, b, t: fp.exact_q6k(d[r, b], sc[r, b, t // 16], q[r, b, t])
+    else:
+        d = _finite_half_bits(rng, (rows, nb * 8))
+        q = rng.integers(-128, 128, (rows, nb * 256))
+        W = fp.pack_q80(d, q)
+        exact = lambda r, b, t: fp.exact_q80(d[r, b * 8 + t // 32], q[r, b * 256 + t])
+    W = np.ascontiguousarray(W, dtype=np.uint8)
+    out = np.empty((rows, nb * 256), dtype=np.float32)
+    rc = lib.orc_fmt_dequant(C.c_int32(oracle.FORMATS[fmt]), W.ctypes.data_as(C.c_void_p), C.c_int64(rows), C.c_int64(nb * 256),
+                             out.ctypes.data_as(C.c_void_p))
+    assert rc == 0
+    wrong = sum(out[r, b * 256 + t] != fraction_to_f32(exact(r, b, t)) for r in range(rows) for b in range(nb) for t in range(256))
+    assert wrong > 0, what
+    # and the untouched oracle passes the same check
+    good = oracle.fmt_dequant(fmt, W, rows, nb * 256)
+    assert all(good[r, b * 256 + t] == fraction_to_f32(exact(r, b, t)) for r in range(rows) for b in range(nb) for t in range(256))
