@@ -66,6 +66,29 @@ def q4k_gemv(W, x, y=None, workspace=None):
     return y
 
 
+def q4k_gemm(W, x, gain=None, eps=0.0, resid=None, y=None, workspace=None):
+    """Many tokens: y[t, r] = sum_c W[r, c] a[t, c] (+ resid[t, r]), a = x or RMSNorm(x; gain, eps).
+    W uint8 [rows, cols/256, 144], x float32 [T, cols] (rows may be strided)."""
+    _need(W, torch.uint8, "W")
+    if x.dtype != torch.float32 or not x.is_cuda or x.stride(1) != 1:
+        raise ValueError("x must be a float32 CUDA tensor with contiguous rows")
+    rows, cols = W.shape[0], W.shape[1] * 256
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, rows), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(256, _ffi.lib().prima_gemm_workspace_bytes(T)), dtype=torch.uint8, device=x.device)
+    if gain is not None:
+        _need(gain, torch.float32, "gain")
+    if resid is not None and (resid.dtype != torch.float32 or resid.stride(1) != 1):
+        raise ValueError("resid must be float32 with contiguous rows")
+    _ffi.check(_ffi.lib().prima_q4k_gemm(_ptr(W), rows, cols, _ptr(x), x.stride(0), T, _ptr(gain) if gain is not None else None,
+                                         float(eps), _ptr(resid) if resid is not None else None,
+                                         resid.stride(0) if resid is not None else 0, _ptr(y), y.stride(0),
+                                         _ptr(workspace), workspace.numel(), _stream()), "prima_q4k_gemm")
+    return y
+
+
 def fmt_tensor_bytes(fmt, rows, cols):
     return _ffi.lib().prima_fmt_tensor_bytes(_ffi.FORMATS[fmt], rows, cols)
 

@@ -94,6 +94,12 @@ prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
 // host only: whether every pass of this launch finds a plan and fits the scratch (nothing is launched)
 prima_status gemv_plan_status(const GemvArgs &a, void *ws, size_t ws_bytes, size_t arrivals_region);
 
+// many tokens (q4k_gemm.hip): ws holds gemm_ws_bytes(T) bytes of per-token scales
+size_t gemm_ws_bytes(int T);
+prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
+                             const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
+                             void *ws, hipStream_t st);
+
 prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
 prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st);
 // the RoPE table [T][D/2] of (cos, sin) and up to three zeroed regions (null: none) in one launch.

@@ -272,6 +272,23 @@ prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols, const
     return launch_gemv_mfma(ga, workspace, workspace_bytes, gemv_arrivals_bytes(n_rows), st);
 }
 
+size_t prima_gemm_workspace_bytes(int32_t T) { return T < 1 ? 0 : gemm_ws_bytes(T); }
+
+prima_status prima_q4k_gemm(const void *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int32_t T,
+                            const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!W || !x || !y || !workspace) return PRIMA_E_NULL;
+    if (n_rows < 0 || n_cols <= 0 || n_cols % QK || ldx < n_cols || ldy < n_rows || (resid && ldr < n_rows)) return PRIMA_E_SHAPE;
+    if (T < 1 || T > PRIMA_GEMM_MAX_TOK) return PRIMA_E_RANGE;
+    if (!aligned(W, 16) || !aligned(x, 16) || !aligned(y, 4) || ldx % 4 || (gain && !aligned(gain, 16)) || (resid && !aligned(resid, 4)) ||
+        !aligned(workspace, 256))
+        return PRIMA_E_ALIGN;
+    if (workspace_bytes < gemm_ws_bytes(T)) return PRIMA_E_WORKSPACE;
+    return launch_q4k_gemm(static_cast<const uint8_t *>(W), n_rows, n_cols, x, ldx, T, gain, eps, resid, ldr, y, ldy, workspace,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
 size_t prima_attn_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
 {
     if (!d || !dims_ok(d) || T < 1) return 0;
