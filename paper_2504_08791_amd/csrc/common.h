@@ -98,7 +98,9 @@ prima_status gemv_plan_status(const GemvArgs &a, void *ws, size_t ws_bytes, size
 size_t gemm_ws_bytes(int T);
 prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
                              const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
-                             void *ws, hipStream_t st);
+                             void *ws, hipStream_t st, bool scales_ready = false);
+// RoPE table [T][D/2] of (cos, sin) for the positions n_past .. n_past + T - 1 (any T)
+prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
 
 prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
 prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st);

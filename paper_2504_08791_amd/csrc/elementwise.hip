@@ -48,6 +48,25 @@ prima_status launch_step_init(float *tab, int T, int D, int n_past, float theta,
     return last_launch_status();
 }
 
+// the same table for any number of consecutive positions (prompt processing)
+__global__ void __launch_bounds__(256) rope_table_kernel(float2 *tab, int64_t n, int half, int n_past, double theta)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= n) return;
+    const int t = static_cast<int>(idx / half), i = static_cast<int>(idx - static_cast<int64_t>(t) * half);
+    const double ang = static_cast<double>(n_past + t) * pow(theta, -static_cast<double>(i) / static_cast<double>(half));
+    tab[idx] = make_float2(static_cast<float>(cos(ang)), static_cast<float>(sin(ang)));
+}
+
+prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st)
+{
+    const int64_t n = static_cast<int64_t>(T) * (D / 2);
+    if (n <= 0) return PRIMA_OK;
+    hipLaunchKernelGGL(rope_table_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st,
+                       reinterpret_cast<float2 *>(tab), n, D / 2, n_past, static_cast<double>(theta));
+    return last_launch_status();
+}
+
 // Read-only streaming probe: every thread reads 16 bytes per step with a grid-wide stride and folds them
 // into one word, so that the loads cannot be dropped.  States what this device delivers for a plain
 // linear read, next to the nominal HBM peak.

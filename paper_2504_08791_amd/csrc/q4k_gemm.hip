@@ -206,13 +206,14 @@ size_t gemm_ws_bytes(int T) { return round_up(static_cast<size_t>(T) * sizeof(fl
 
 prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
                              const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
-                             void *ws, hipStream_t st)
+                             void *ws, hipStream_t st, bool scales_ready)
 {
     if (n_rows == 0 || T == 0) return PRIMA_OK;
     const int64_t row_blocks = (n_rows + GM_ROWS - 1) / GM_ROWS;
     if (row_blocks >= (int64_t{1} << 31) || (T + GM_TM - 1) / GM_TM > 65535) return PRIMA_E_SHAPE;
     float2 *stat = static_cast<float2 *>(ws);
-    hipLaunchKernelGGL(gemm_token_scale_kernel, dim3(T), dim3(256), 0, st, x, ldx, n_cols, gain, eps, stat);
+    // scales_ready: ws holds the scales of these very activations (the call before this one had the same x, gain, eps)
+    if (!scales_ready) hipLaunchKernelGGL(gemm_token_scale_kernel, dim3(T), dim3(256), 0, st, x, ldx, n_cols, gain, eps, stat);
     GemmArgs a{W, n_rows, n_cols, x, ldx, gain, stat, resid, ldr, y, ldy, T};
     hipLaunchKernelGGL(q4k_gemm_kernel, dim3(static_cast<unsigned>(row_blocks), static_cast<unsigned>((T + GM_TM - 1) / GM_TM)), dim3(GM_THREADS), 0, st, a);
     return last_launch_status();

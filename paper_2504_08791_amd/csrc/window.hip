@@ -211,6 +211,65 @@ prima_status check_window_args(const prima_dims *d, int32_t kv_cap, int32_t n_pa
     return PRIMA_OK;
 }
 
+struct PrefillWs {
+    size_t q, k, v, o, h, a, u, xb0, xb1, rope, attn, stat, total;
+};
+
+// scratch of a prompt-processing call: the layer's intermediate activations for all T tokens, the RoPE table, the
+// per-token scales of the matrix product, and the attention scratch of one 16-token call
+PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
+{
+    PrefillWs w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += round_up(bytes, 256); return o; };
+    const size_t qd = static_cast<size_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<size_t>(d.n_kv_heads) * d.head_dim;
+    const size_t f = sizeof(float), t = static_cast<size_t>(T);
+    w.q = take(t * qd * f);
+    w.k = take(t * kvd * f);
+    w.v = take(t * kvd * f);
+    w.o = take(t * qd * f);
+    w.h = take(t * static_cast<size_t>(d.e) * f);
+    w.a = take(t * static_cast<size_t>(d.ffn) * f);
+    w.u = take(t * static_cast<size_t>(d.ffn) * f);
+    w.xb0 = take(t * static_cast<size_t>(d.e) * f);
+    w.xb1 = take(t * static_cast<size_t>(d.e) * f);
+    w.rope = take(t * static_cast<size_t>(d.head_dim) * f);
+    w.attn = take(attn_ws_bytes(d, kv_cap, PRIMA_MAX_TOK));
+    w.stat = take(gemm_ws_bytes(T));
+    w.total = off;
+    return w;
+}
+
+// one decoder layer for T prompt tokens: the projections as matrix products over all tokens, attention in calls of
+// up to PRIMA_MAX_TOK tokens (each sees the rows cached before it and, causally, its own)
+prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
+                               const float *x, float *y, void *ws, const PrefillWs &w, hipStream_t st)
+{
+    const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
+    float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
+    float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *act = at<float>(ws, w.a), *up = at<float>(ws, w.u);
+    void *stat = at<char>(ws, w.stat);
+    auto W = [](const void *p) { return static_cast<const uint8_t *>(p); };
+    prima_status s;
+#define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
+    PRIMA_TRY(launch_q4k_gemm(W(L.wq), qd, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, q, qd, stat, st));
+    PRIMA_TRY(launch_q4k_gemm(W(L.wk), kvd, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, k, kvd, stat, st, true));
+    PRIMA_TRY(launch_q4k_gemm(W(L.wv), kvd, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, v, kvd, stat, st, true));
+    for (int t0 = 0; t0 < T; t0 += PRIMA_MAX_TOK) {
+        const int Tc = std::min<int>(PRIMA_MAX_TOK, T - t0);
+        PRIMA_TRY(launch_attn(d, q + t0 * qd, nullptr, k + t0 * kvd, v + t0 * kvd, at<float>(ws, w.rope) + static_cast<int64_t>(t0) * d.head_dim,
+                              static_cast<__half *>(L.k_cache), static_cast<__half *>(L.v_cache), kv_cap, n_past + t0, Tc,
+                              o + t0 * qd, at<char>(ws, w.attn), st));
+    }
+    PRIMA_TRY(launch_q4k_gemm(W(L.wo), e, qd, o, qd, T, nullptr, 0.f, x, e, h, e, stat, st));
+    PRIMA_TRY(launch_q4k_gemm(W(L.wgate), F, e, h, e, T, static_cast<const float *>(L.g_ffn), d.rms_eps, nullptr, 0, act, F, stat, st));
+    PRIMA_TRY(launch_q4k_gemm(W(L.wup), F, e, h, e, T, static_cast<const float *>(L.g_ffn), d.rms_eps, nullptr, 0, up, F, stat, st, true));
+    PRIMA_TRY(launch_swiglu(act, up, static_cast<int64_t>(T) * F, st));
+    PRIMA_TRY(launch_q4k_gemm(W(L.wdown), e, F, act, F, T, nullptr, 0.f, h, e, y, e, stat, st));
+#undef PRIMA_TRY
+    return PRIMA_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -508,6 +567,41 @@ prima_status prima_layer_window_decode_batch_mixed(const prima_dims *d, const pr
 }
 
 void prima_set_fused_window(int32_t enabled) { g_fused_enabled = enabled != 0; }
+
+size_t prima_prefill_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
+{
+    if (!d || !dims_ok(d) || T < 1 || T > PRIMA_PREFILL_MAX_TOK || kv_cap < 1) return 0;
+    return carve_prefill(*d, kv_cap, T).total;
+}
+
+prima_status prima_layer_window_prefill(const prima_dims *d, const prima_layer *layers, int32_t L,
+                                        int32_t kv_cap, int32_t n_past, int32_t T,
+                                        const float *x_in, float *x_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!d || !x_in || !x_out || !workspace || !layers) return PRIMA_E_NULL;
+    if (!dims_ok(d)) return PRIMA_E_SHAPE;
+    if (L < 1 || T < 1 || T > PRIMA_PREFILL_MAX_TOK || n_past < 0 || kv_cap < 1 || static_cast<int64_t>(n_past) + T > kv_cap) return PRIMA_E_RANGE;
+    if (!aligned(x_in, 16) || !aligned(x_out, 16) || !aligned(workspace, 256)) return PRIMA_E_ALIGN;
+    const PrefillWs w = carve_prefill(*d, kv_cap, T);
+    if (workspace_bytes < w.total) return PRIMA_E_WORKSPACE;
+    for (int i = 0; i < L; ++i) {
+        const prima_status c = check_layer(layers[i]);
+        if (c != PRIMA_OK) return c;
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    prima_status s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
+    if (s != PRIMA_OK) return s;
+    s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, PRIMA_MAX_TOK), st);
+    if (s != PRIMA_OK) return s;
+    const float *cur = x_in;
+    for (int i = 0; i < L; ++i) {
+        float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
+        s = run_layer_prefill(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st);
+        if (s != PRIMA_OK) return s;
+        cur = dst;
+    }
+    return PRIMA_OK;
+}
 
 prima_status prima_window_check(const prima_dims *d, int32_t kv_cap, int32_t T, const void *workspace, size_t workspace_bytes, void *hip_stream)
 {

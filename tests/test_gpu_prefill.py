@@ -1,0 +1,129 @@
+"""GPU parity of prompt processing (all layers of a window for T consecutive tokens in one call) against the CPU
+oracle, through the C ABI.
+
+The oracle advances at most 64 tokens a call; a prompt goes through it in such pieces, each through all layers
+(the layers' caches carry what the earlier pieces appended), which is the same causal computation.
+Bar: hidden states max relative error <= 2e-3 (tests/metrics.rel_err), appended cache rows within one fp16 step.
+"""
+import copy
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from metrics import rel_err
+from workloads import synth
+from workloads.configs import CONFIGS, TINY
+
+pytestmark = pytest.mark.gpu
+
+HID_TOL = 2e-3
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _oracle_prompt(dims, host, x, n_past):
+    out = []
+    for t0 in range(0, x.shape[0], 64):
+        out.append(oracle.window(dims, host, x[t0:t0 + 64].astype(np.float64), n_past + t0))
+    return np.concatenate(out, axis=0)
+
+
+def _window(gpu_lib, cfg, cap, host):
+    dev_layers = [{k: _dev(v) for k, v in t.items()} for t in host]
+    return gpu_lib.Window(cfg.dims, dev_layers, cap, T_max=16), dev_layers
+
+
+@pytest.mark.parametrize("name,T,n_past", [("t0", 50, 37), ("t1", 70, 0), ("t2", 33, 63), ("t0", 1, 5), ("t1", 16, 130)])
+def test_prefill_vs_oracle(gpu_lib, name, T, n_past):
+    cfg = TINY[name].with_(T=T, n_past=n_past)
+    cap = n_past + T + 3
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    win, dev_layers = _window(gpu_lib, cfg, cap, host)
+    x = synth.window_input(cfg)
+    print("case", name, T, n_past, flush=True)
+    y = win.prefill(_dev(x), n_past).cpu().numpy()
+    ref = _oracle_prompt(cfg.dims, host, x, n_past)       # appends to the host caches
+    assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
+    for l in range(cfg.n_layers):
+        for key in ("k_cache", "v_cache"):
+            g = dev_layers[l][key].cpu().numpy().astype(np.float64)
+            r = host[l][key].astype(np.float64)
+            assert np.array_equal(g[:, :n_past], r[:, :n_past])
+            assert np.array_equal(g[:, n_past + T:], r[:, n_past + T:])
+            if l == 0:   # deeper layers' rows inherit the hidden states' error
+                assert rel_err(g[:, n_past:n_past + T].reshape(1, -1), r[:, n_past:n_past + T].reshape(1, -1)) < 1e-3
+
+
+def test_prefill_then_decode_continues(gpu_lib):
+    """A prompt through the prefill call, the next token through the decode call: against the oracle doing the same."""
+    cfg = TINY["t1"].with_(T=40, n_past=0)
+    cap = 48
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    win, _ = _window(gpu_lib, cfg, cap, host)
+    x = synth.window_input(cfg)
+    nxt = synth.batch_input(cfg, 1)
+    win.prefill(_dev(x), 0)
+    y = win.decode(_dev(nxt), 40).cpu().numpy()
+    _oracle_prompt(cfg.dims, host, x, 0)
+    ref = oracle.window(cfg.dims, host, nxt.astype(np.float64), 40)
+    assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
+
+
+def test_prefill_agrees_with_decode_calls(gpu_lib):
+    """The same prompt through decode calls of 16 tokens (integer-digit mat-vec) and through one prefill call
+    (binary16 matrix product): far inside the bar of each other, and prefill gives the same bits twice, in place too."""
+    cfg = TINY["t2"].with_(T=48, n_past=10)
+    cap = 64
+    x = synth.window_input(cfg)
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    wa, _ = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
+    wb, _ = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
+    wc, _ = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
+    xd = _dev(x)
+    ya = torch.cat([wa.decode(xd[t:t + 16].contiguous(), 10 + t) for t in range(0, 48, 16)]).cpu().numpy()
+    yb = wb.prefill(xd, 10)
+    assert rel_err(yb.cpu().numpy(), ya.astype(np.float64)) < HID_TOL / 4
+    xc = xd.clone()
+    yc = wc.prefill(xc, 10, x_out=xc)
+    assert torch.equal(yb, yc)
+
+
+def test_prefill_model_shape_one_layer(gpu_lib):
+    """One 70B-shaped layer (config 3's dimensions), 80 prompt tokens behind 4000 cached rows."""
+    cfg = CONFIGS["c3"].with_(T=80, n_past=4000, n_layers=1)
+    cap = 4096
+    host = [synth.layer_tensors(cfg, 0, kv_cap=cap)]
+    win, _ = _window(gpu_lib, cfg, cap, host)
+    x = synth.window_input(cfg)
+    print("case c3 one layer, 80 tokens", flush=True)
+    y = win.prefill(_dev(x), 4000).cpu().numpy()
+    ref = _oracle_prompt(cfg.dims, host, x, 4000)
+    assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
+
+
+def test_prefill_argument_errors(gpu_lib):
+    from paper_2504_08791_amd import _ffi
+    import ctypes as C
+    cfg = TINY["t0"]
+    cap = 64
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    win, _ = _window(gpu_lib, cfg, cap, host)
+    L = _ffi.lib()
+    x = torch.zeros((8, cfg.dims.e), dtype=torch.float32, device="cuda")
+    need = L.prima_prefill_workspace_bytes(C.byref(win.dims), cap, 8)
+    assert need > 0 and L.prima_prefill_workspace_bytes(C.byref(win.dims), cap, 0) == 0
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    call = lambda **k: L.prima_layer_window_prefill(C.byref(win.dims), win._arr, k.get("L", 2), cap, k.get("n_past", 0), k.get("T", 8),
+                                                    k.get("x", x.data_ptr()), x.data_ptr(), ws.data_ptr(), k.get("wsb", need), None)
+    assert _ffi.STATUS[call(x=None)] == "PRIMA_E_NULL"
+    assert _ffi.STATUS[call(T=0)] == "PRIMA_E_RANGE"
+    assert _ffi.STATUS[call(n_past=60)] == "PRIMA_E_RANGE"
+    assert _ffi.STATUS[call(L=0)] == "PRIMA_E_RANGE"
+    assert _ffi.STATUS[call(wsb=need - 256)] == "PRIMA_E_WORKSPACE"
+    assert _ffi.STATUS[call(x=x.data_ptr() + 4)] == "PRIMA_E_ALIGN"
+    assert call() == 0
+    torch.cuda.synchronize()
