@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--mix", action="store_true",
                     help="side measurement: the config's window with the V and down projections of every other layer in Q6_K "
                          "(a common mix of a \"Q4K\" model), against the oracle")
+    ap.add_argument("--prefill", type=int, default=0,
+                    help="prompt processing: the config's window for this many prompt tokens in one call (time to the first token)")
     ap.add_argument("--device-profile", action="store_true",
                     help="side measurement: the device-profiler quantities of the paper's latency model on this GPU, and the "
                          "model's estimate of the config's window step next to the measured one")
@@ -62,6 +64,8 @@ def main():
         return bench_batch(args, cfg)
     if args.format:
         return bench_format(args)
+    if args.prefill:
+        return bench_prefill(args, cfg)
     if args.device_profile:
         return bench_device_profile(args, cfg)
     if args.mix:
@@ -279,6 +283,93 @@ def bench_batch(args, cfg):
         out["max_rel_err_vs_oracle"] = float((np.abs(got - ref) / np.maximum(np.abs(ref), np.maximum(rms, 1e-30))).max())
         out["cpu_baseline"] = {"value": round(B / cpu_seconds, 4), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"the whole step once ({cpu_seconds:.1f} s of CPU time)"}
+    print(json.dumps(out), flush=True)
+
+
+def bench_prefill(args, cfg):
+    """Prompt processing (the paper's time to the first token, Sec. 4.1, for this device's window): T prompt tokens
+    through all layers in one call, empty caches.  A step is one such call."""
+    import numpy as np
+    import torch
+    import paper_2504_08791_amd as prima
+    from workloads import synth
+
+    d, T = cfg.dims, args.prefill
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = cfg.with_(T=T, n_past=0)
+    want_cpu = not args.no_cpu_baseline
+    dev_layers, host0 = [], None
+    for l in range(cfg.n_layers):
+        t = synth.layer_tensors(cfg, l, kv_cap=T)
+        dev_layers.append({k: torch.from_numpy(v).to(dev) for k, v in t.items()})
+        if l == 0 and want_cpu:
+            host0 = t
+    win = prima.Window(d, dev_layers, T, T_max=1)
+    x_host = synth.window_input(cfg)
+    x = torch.from_numpy(x_host).to(dev)
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        win.prefill(x, 0, x_out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(args.steps):
+        win.prefill(x, 0, x_out=y)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    qd, kvd = d.n_q_heads * d.head_dim, d.n_kv_heads * d.head_dim
+    weights = d.e * (qd + 2 * kvd) + qd * d.e + 3 * d.ffn * d.e
+    flops_step = 2.0 * weights * T * cfg.n_layers
+    # the dominant launch on its own: the gate projection's matrix product (RMSNorm in front), between two events
+    h = torch.randn((T, d.e), device=dev)
+    g = torch.empty((T, d.ffn), device=dev)
+    ws = torch.empty(prima._ffi.lib().prima_gemm_workspace_bytes(T, d.e), dtype=torch.uint8, device=dev)
+    wg, gain = dev_layers[0]["wgate"], dev_layers[0]["g_ffn"]
+    for _ in range(3):
+        prima.q4k_gemm(wg, h, gain=gain, eps=d.rms_eps, y=g, workspace=ws)
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record(stream)
+    for i in range(20):
+        prima.q4k_gemm(dev_layers[i % cfg.n_layers]["wgate"], h, gain=gain, eps=d.rms_eps, y=g, workspace=ws)
+    p1.record(stream)
+    torch.cuda.synchronize()
+    gate_us = p0.elapsed_time(p1) / 20 * 1e3
+    gate_flops = 2.0 * d.ffn * d.e * T
+    achieved = gate_flops / (gate_us * 1e-6) / 1e12
+    out = {
+        "metric": "prompt tokens/s per layer window (time to the first token of this window = ms_per_step)",
+        "value": round(T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 x f16 -> f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name} shape: {cfg.n_layers}-layer window, e={d.e}, ffn={d.ffn}, {T} prompt tokens, empty caches, "
+                               "Q4_K weights, fp16 KV", "tokens_per_step": T, "layers": cfg.n_layers},
+        "window_tflops": round(flops_step / (ms * 1e-3) / 1e12, 1),
+        "roofline": {
+            "bound": "mfma",
+            "kernel": "prima_q4k_gemm as called for the gate projection (token scales, activation split and q4k_gemm_kernel; RMSNorm in front)",
+            "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(achieved / 2500.0, 4),
+            "flops_per_launch": gate_flops, "avg_launch_us": round(gate_us, 1),
+            "mfma_passes": 2,   # every activation enters as hi + lo: the matrix cores do twice the algorithmic work
+            "traffic": None,
+        },
+    }
+    if want_cpu:
+        import oracle
+        n_s = min(64, T)
+        win1 = prima.Window(d, [dict(dev_layers[0], k_cache=torch.zeros_like(dev_layers[0]["k_cache"]),
+                                     v_cache=torch.zeros_like(dev_layers[0]["v_cache"]))], T, T_max=1)
+        got = win1.prefill(x[:n_s].contiguous(), 0).cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        ref = oracle.layer(d, host0, x_host[:n_s].astype(np.float64), 0)
+        cpu_seconds = time.perf_counter() - t0
+        rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+        out["max_rel_err_vs_oracle"] = float((np.abs(got - ref) / np.maximum(np.abs(ref), np.maximum(rms, 1e-30))).max())
+        out["cpu_baseline"] = {"value": round(n_s / (cpu_seconds * cfg.n_layers), 4), "unit": "tokens/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": f"layer 0 for the first {n_s} prompt tokens ({cpu_seconds:.1f} s of CPU time), "
+                                                           f"scaled to {cfg.n_layers} layers"}
     print(json.dumps(out), flush=True)
 
 

@@ -291,15 +291,16 @@ prima_status prima_window_plan_status(const prima_dims *d, int32_t kv_cap, int32
  * 1 <= T <= PRIMA_GEMM_MAX_TOK.  W: Q4_K layout v1, device, 16-byte aligned.  x: fp32 [T][ldx], 16-byte aligned,
  * ldx >= n_cols, ldx % 4 == 0.  gain: fp32 [n_cols], 16-byte aligned, or null.  resid: fp32 [T][ldr] or null (may be y).
  * y: fp32 [T][ldy], ldy >= n_rows, must not overlap x.  workspace: device, 256-byte aligned, at least
- * prima_gemm_workspace_bytes(T) bytes (per-token scales; contents need not be kept).  The activations enter the
- * matrix cores as the sum of two binary16 numbers (22 bits after a per-token power-of-two scale), products and sums
- * are fp32; results do not depend on the launch.  All pointers device; asynchronous on hip_stream.
+ * prima_gemm_workspace_bytes(T, n_cols) bytes (per-token scales and the activations laid out for the matrix cores,
+ * about 4.25 bytes per activation; contents need not be kept).  The activations enter the matrix cores as the sum of
+ * two binary16 numbers (22 bits after a per-token power-of-two scale), products and sums are fp32; results do not
+ * depend on the launch.  All pointers device; asynchronous on hip_stream.
  */
 #define PRIMA_GEMM_MAX_TOK 65536
 prima_status prima_q4k_gemm(const void *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int32_t T,
                             const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
-size_t prima_gemm_workspace_bytes(int32_t T);
+size_t prima_gemm_workspace_bytes(int32_t T, int64_t n_cols);
 
 /*
  * Prompt processing: all L layers of the window for T consecutive tokens of one sequence that has n_past rows

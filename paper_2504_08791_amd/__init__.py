@@ -77,7 +77,7 @@ def q4k_gemm(W, x, gain=None, eps=0.0, resid=None, y=None, workspace=None):
     if y is None:
         y = torch.empty((T, rows), dtype=torch.float32, device=x.device)
     if workspace is None:
-        workspace = torch.empty(max(256, _ffi.lib().prima_gemm_workspace_bytes(T)), dtype=torch.uint8, device=x.device)
+        workspace = torch.empty(max(256, _ffi.lib().prima_gemm_workspace_bytes(T, cols)), dtype=torch.uint8, device=x.device)
     if gain is not None:
         _need(gain, torch.float32, "gain")
     if resid is not None and (resid.dtype != torch.float32 or resid.stride(1) != 1):

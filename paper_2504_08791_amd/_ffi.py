@@ -57,7 +57,7 @@ def lib():
         L.prima_q4k_dequant.argtypes = [vp, i64, i64, vp, vp]
         L.prima_q4k_gemm.argtypes = [vp, i64, i64, vp, i64, i32, vp, C.c_float, vp, i64, vp, i64, vp, sz, vp]
         L.prima_q4k_gemm.restype = C.c_int
-        L.prima_gemm_workspace_bytes.argtypes = [i32]
+        L.prima_gemm_workspace_bytes.argtypes = [i32, i64]
         L.prima_gemm_workspace_bytes.restype = sz
         L.prima_layer_window_prefill.argtypes = [dp, lp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
         L.prima_layer_window_prefill.restype = C.c_int

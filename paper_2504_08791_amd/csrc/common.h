@@ -94,11 +94,11 @@ prima_status launch_zero_arrivals(void *ws, size_t bytes, hipStream_t st);
 // host only: whether every pass of this launch finds a plan and fits the scratch (nothing is launched)
 prima_status gemv_plan_status(const GemvArgs &a, void *ws, size_t ws_bytes, size_t arrivals_region);
 
-// many tokens (q4k_gemm.hip): ws holds gemm_ws_bytes(T) bytes of per-token scales
-size_t gemm_ws_bytes(int T);
+// many tokens (q4k_gemm.hip): ws holds gemm_ws_bytes(T, n_cols) bytes (per-token scales, the activations split for the matrix cores)
+size_t gemm_ws_bytes(int T, int64_t n_cols);
 prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
                              const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
-                             void *ws, hipStream_t st, bool scales_ready = false);
+                             void *ws, hipStream_t st, bool split_ready = false);
 // RoPE table [T][D/2] of (cos, sin) for the positions n_past .. n_past + T - 1 (any T)
 prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
 

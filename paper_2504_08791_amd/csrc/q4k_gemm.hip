@@ -3,18 +3,25 @@
 //
 //     y[t][r] = sum_c W[r][c] * a[t][c],   a = x (or RMSNorm(x; gain)),   + resid[t][r] (optional)
 //
-// With tens to hundreds of tokens the product is a real contraction and belongs on the matrix cores; the decode
+// With tens to thousands of tokens the product is a real contraction and belongs on the matrix cores; the decode
 // kernel (tokens as int8 digits, sub-scales applied to every MFMA result) spends four multiply-adds per MFMA and
 // token group and stops scaling at 8 tokens.  Here:
 //   * the B operand is the weight tile itself: per sub-block of 32 weights the integers sc_s * q (at most 945:
-//     exact in binary16), built once per workgroup pass and used for every token of the pass;
+//     exact in binary16), built in registers once per super-block and used for every token of the workgroup;
 //   * the A operand is the activations as two binary16 numbers hi + lo (22 bits), scaled per token by a power
-//     of two so that |a| < 4096; products of two binary16 numbers are exact in fp32, the MFMA adds in fp32;
-//   * one accumulator per super-block (256 weights, 8 MFMA steps x 2), then  y += d * acc - dmin * sum_s m_s * xs_s
-//     with xs_s the sub-block sums of the scaled activations (fp32, from the staging pass).
-// Workgroup: 8 waves = 128 rows (16 per wave) x 32 tokens (two 16-token tiles); the activations of a super-block
-// are staged once per workgroup into LDS in the A-operand order, the weights go from global memory straight into
-// registers (each wave reads only its own 16 rows).  A first kernel gives every token its scale: 2^p (times 1/rms).
+//     of two so that |a| < 1024; products of two binary16 numbers are exact in fp32, the MFMA adds in fp32;
+//   * one accumulator per super-block (256 weights, 8 MFMA steps x 2); the min term sum_s m_s * xs_s (xs_s: the
+//     sub-block sums of the scaled activations, again as hi + lo) is one more MFMA step with the m_s as B operand;
+//     then  y += d * acc - dmin * acc_m  in fp32.
+// Three kernels.  (1) per token: 1/rms (RMSNorm in front) and the power of two.  (2) the activations, split and
+// laid out in A-operand order per (16-token tile, super-block): 17 slabs of 1 KiB (8 sub-blocks x (hi, lo), and
+// the sums), so that the product kernel moves them into LDS with 16-byte global->LDS loads and no arithmetic; the
+// split is done once, not once per row block.  (3) the product: a workgroup of 8 waves owns 256 rows x 128 tokens,
+// a wave 32 rows (two B tiles in registers: every A tile read from LDS feeds two MFMAs).  Per super-block the B
+// tiles are built once and used for the workgroup's 128 tokens, which pass through LDS in two halves of four token
+// tiles (68 KiB each, two buffers): while one half is multiplied the other arrives.  The weights go from global
+// memory straight into registers, one super-block ahead.  Workgroups are numbered so that those running on one XCD (one L2) at a time are a patch
+// of 8 row blocks x 4 token blocks.
 #include <hip/hip_fp16.h>
 
 #include "common.h"
@@ -23,29 +30,37 @@ namespace prima {
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int GM_THREADS = 512;
 constexpr int GM_WAVES = GM_THREADS / 64;
-constexpr int GM_ROWS = 16 * GM_WAVES; // rows per workgroup
-constexpr int GM_TM = 32;              // tokens per workgroup
-constexpr int GM_TT = GM_TM / 16;      // 16-token tiles
+constexpr int GM_RT = 2;                        // 16-row tiles per wave
+constexpr int GM_TT = 8;                        // 16-token tiles per workgroup
+constexpr int GM_HT = GM_TT / 2;                // ... of which one half is in an LDS buffer at a time
+constexpr int GM_ROWS = 16 * GM_RT * GM_WAVES;  // rows per workgroup
+constexpr int GM_TM = 16 * GM_TT;               // tokens per workgroup
+constexpr int GM_SLABS = 17;                    // per (token tile, super-block): 8 sub-blocks x (hi, lo), sums
+constexpr int GM_TILE_BYTES = GM_SLABS * 1024;
+constexpr int GM_STAGE_BYTES = GM_HT * GM_TILE_BYTES;
+constexpr int GM_LDS_BYTES = 2 * GM_STAGE_BYTES; // one workgroup per compute unit
+constexpr int GM_XCDS = 8;
+constexpr int GM_PATCH_R = 8, GM_PATCH_C = 4; // row blocks x token blocks that share an XCD at a time
+constexpr size_t GM_STAT_ALIGN = 1024;
 
 struct GemmArgs {
     const uint8_t *W;
     int64_t n_rows, n_cols;
-    const float *x;
-    int64_t ldx;
-    const float *gain;  // null: plain activations
+    const uint8_t *A;   // split activations: [token tile][super-block][17][64 lanes] x 16 bytes
     const float2 *stat; // per token: (2^p [* 1/rms], 2^-p)
     const float *resid; // null: none
     int64_t ldr;
     float *y;
     int64_t ldy;
-    int T;
+    int T, n_tiles, n_rb, n_tb; // 16-token tiles, row blocks, token blocks
 };
 
-// per token: 1/rms (RMSNorm in front) and the power of two that brings max |a| below 4096
+// per token: 1/rms (RMSNorm in front) and the power of two that brings max |a| below 1024
 __global__ void __launch_bounds__(256) gemm_token_scale_kernel(const float *__restrict__ x, int64_t ldx, int64_t K, const float *__restrict__ gain,
                                                                float eps, float2 *__restrict__ stat)
 {
@@ -70,129 +85,230 @@ __global__ void __launch_bounds__(256) gemm_token_scale_kernel(const float *__re
         amax *= inv_rms;
         int ex = 0;
         if (amax > 0.f) frexpf(amax, &ex); // amax < 2^ex
-        int p = 12 - ex;
+        int p = 10 - ex;
         p = p > 100 ? 100 : (p < -100 ? -100 : p);
         stat[t] = make_float2(ldexpf(inv_rms, p), ldexpf(1.0f, -p));
     }
 }
 
-struct GemmLds {
-    half8 hi[GM_TT][8][64]; // A operand: [token tile][sub-block][lane = token % 16 + 16 * (k / 8)]
-    half8 lo[GM_TT][8][64];
-    float xs[GM_TM][8];     // sub-block sums of the scaled activations
-};
+// The activations of one (16-token tile, super-block) in A-operand order.  Lane (m, g) of an MFMA step holds, for
+// token m, the columns 8g .. 8g+7 of a sub-block in the order 0 4 1 5 2 6 3 7 (the order in which the product
+// kernel unpacks a dword of eight 4-bit weights into four binary16 pairs).  Tokens past T are zeros.
+__global__ void __launch_bounds__(256) gemm_split_kernel(const float *__restrict__ x, int64_t ldx, const float *__restrict__ gain,
+                                                         const float2 *__restrict__ stat, int T, int64_t nb, uint8_t *__restrict__ A)
+{
+    __shared__ float xs[16][8];
+    const int64_t b = blockIdx.x;
+    const int tile = blockIdx.y;
+    const int m = threadIdx.x >> 4, c0 = (threadIdx.x & 15) * 16;
+    const int t = tile * 16 + m;
+    const bool valid = t < T;
+    const int ts = valid ? t : T - 1;
+    const float scale = stat[ts].x;
+    const float *xp = x + ts * ldx + b * 256 + c0;
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float4 q = *reinterpret_cast<const float4 *>(xp + 4 * i);
+        v[4 * i] = q.x; v[4 * i + 1] = q.y; v[4 * i + 2] = q.z; v[4 * i + 3] = q.w;
+    }
+    if (gain) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float4 q = *reinterpret_cast<const float4 *>(gain + b * 256 + c0 + 4 * i);
+            v[4 * i] *= q.x; v[4 * i + 1] *= q.y; v[4 * i + 2] *= q.z; v[4 * i + 3] *= q.w;
+        }
+    }
+    float sum = 0.f;
+    _Float16 hh[16], ll[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        float sv = valid ? v[i] * scale : 0.f;
+        // the product as an opaque fp32 number: left visible, the compiler formed the stored hi from the rounded
+        // product and the hi that lo is taken against from the exact one (fused multiply-convert); the two differ
+        // now and then by one binary16 step, which lo then does not make up for
+        asm volatile("" : "+v"(sv));
+        hh[i] = static_cast<_Float16>(sv);
+        ll[i] = static_cast<_Float16>(sv - static_cast<float>(hh[i]));
+        sum += static_cast<float>(hh[i]) + static_cast<float>(ll[i]); // what the MFMAs will see
+    }
+    const int s8 = c0 >> 5, g0 = (c0 & 31) >> 3; // sub-block, and the first of this thread's two 8-column groups
+    uint8_t *dst = A + (static_cast<int64_t>(tile) * nb + b) * GM_TILE_BYTES;
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi) {
+        half8 h, l;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int c = 8 * gi + (j & 1) * 4 + (j >> 1);
+            h[j] = hh[c];
+            l[j] = ll[c];
+        }
+        *reinterpret_cast<half8 *>(dst + (2 * s8) * 1024 + (m + 16 * (g0 + gi)) * 16) = h;
+        *reinterpret_cast<half8 *>(dst + (2 * s8 + 1) * 1024 + (m + 16 * (g0 + gi)) * 16) = l;
+    }
+    sum += __shfl_xor(sum, 1, 64); // the two threads of a sub-block are neighbours
+    if ((threadIdx.x & 1) == 0) xs[m][s8] = sum;
+    __syncthreads();
+    if (threadIdx.x < 64) { // slab 16: lane (m, 0) the sums' hi parts, lane (m, 1) their lo parts, lanes (m, 2..3) zeros
+        const int mm = threadIdx.x & 15, gg = threadIdx.x >> 4;
+        half8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float s = xs[mm][j];
+            const _Float16 sh = static_cast<_Float16>(s);
+            const _Float16 sl = static_cast<_Float16>(s - static_cast<float>(sh));
+            o[j] = gg == 0 ? sh : (gg == 1 ? sl : static_cast<_Float16>(0.f));
+        }
+        *reinterpret_cast<half8 *>(dst + 16 * 1024 + threadIdx.x * 16) = o;
+    }
+}
 
 __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
 {
-    __shared__ GemmLds lds;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, g = lane >> 4;
+    // Consecutive workgroup numbers go to consecutive XCDs.  The 32 workgroups that run on one XCD (one L2) at a time
+    // are 8 row blocks x 4 token blocks: per super-block step they fetch 8 x 36 KiB of weights and 4 x 136 KiB of
+    // activations between them instead of 32 of either.  An XCD owns the row blocks xcd, xcd + 8, ...
+    const int xcd = blockIdx.x % GM_XCDS, seq = blockIdx.x / GM_XCDS;
+    const int patch = seq / (GM_PATCH_R * GM_PATCH_C), within = seq % (GM_PATCH_R * GM_PATCH_C);
+    const int patches_tb = (a.n_tb + GM_PATCH_C - 1) / GM_PATCH_C;
+    const int rb = ((patch / patches_tb) * GM_PATCH_R + within / GM_PATCH_C) * GM_XCDS + xcd;
+    const int tb = (patch % patches_tb) * GM_PATCH_C + within % GM_PATCH_C;
+    if (rb >= a.n_rb || tb >= a.n_tb) return; // the whole workgroup, before any barrier
     const int64_t nb = a.n_cols >> 8;
-    const int t0 = blockIdx.y * GM_TM;
-    const int64_t row = min<int64_t>(static_cast<int64_t>(blockIdx.x) * GM_ROWS + wave * 16 + n, a.n_rows - 1); // past the end: a valid row, not stored
-    const uint8_t *wrow = a.W + row * nb * 144;
-
-    // staging: thread -> (token, 16 consecutive columns of the super-block)
-    const int s_tok = threadIdx.x >> 4, s_c0 = (threadIdx.x & 15) * 16;
-    const int s_t = min(t0 + s_tok, a.T - 1); // past the last token: a valid token, not stored
-    const float2 s_stat = a.stat[s_t];
-    const int s_s8 = s_c0 >> 5, s_g0 = (s_c0 & 31) >> 3; // sub-block and first of the two 8-column groups
-
-    v4f yacc[GM_TT];
+    const int64_t row0 = static_cast<int64_t>(rb) * GM_ROWS + wave * (16 * GM_RT);
+    const uint8_t *wrow[GM_RT];
 #pragma unroll
-    for (int tt = 0; tt < GM_TT; ++tt) yacc[tt] = {0.f, 0.f, 0.f, 0.f};
+    for (int rt = 0; rt < GM_RT; ++rt)
+        wrow[rt] = a.W + min<int64_t>(row0 + 16 * rt + n, a.n_rows - 1) * nb * 144; // past the end: a valid row, not stored
+    const int tile0 = tb * GM_TT;
+    const uint32_t lds0 = lds_address(smem);
 
+    // this wave's share of the 68 slabs of a stage: the token tiles 4 half .. 4 half + 3 of super-block b, into buffer `half`
+    auto issue_stage = [&](int64_t b, int half) {
+#pragma unroll
+        for (int j = 0; j < (GM_HT * GM_SLABS + GM_WAVES - 1) / GM_WAVES; ++j) {
+            const int i = wave + GM_WAVES * j;
+            if (i < GM_HT * GM_SLABS) {
+                const int tt = i / GM_SLABS, sl = i - tt * GM_SLABS;
+                const int tile = min(tile0 + GM_HT * half + tt, a.n_tiles - 1); // past the last tile: a valid one, not stored
+                const uint8_t *src = a.A + ((static_cast<int64_t>(tile) * nb + b) * GM_SLABS + sl) * 1024 + lane * 16;
+                dma16(src, lds0 + half * GM_STAGE_BYTES + i * 1024);
+            }
+        }
+    };
+    const bool second_half = tile0 + GM_HT < a.n_tiles; // whether the workgroup has tokens in its second half at all
+    uint4 hdr[GM_RT];
+    uint32_t qw[GM_RT][8];
+
+    v4f yacc[GM_TT][GM_RT];
+#pragma unroll
+    for (int tt = 0; tt < GM_TT; ++tt)
+#pragma unroll
+        for (int rt = 0; rt < GM_RT; ++rt) yacc[tt][rt] = {0.f, 0.f, 0.f, 0.f};
+
+    // this lane's place in its rows' current super-block: the header, and its dword of every 16-byte quant chunk
+    const uint8_t *hp[GM_RT], *qp[GM_RT];
+#pragma unroll
+    for (int rt = 0; rt < GM_RT; ++rt) {
+        hp[rt] = wrow[rt];
+        qp[rt] = wrow[rt] + 16 + 4 * g;
+        hdr[rt] = *reinterpret_cast<const uint4 *>(hp[rt]);
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) qw[rt][s8] = *reinterpret_cast<const uint32_t *>(qp[rt] + 16 * s8);
+    }
+
+    issue_stage(0, 0);
     for (int64_t b = 0; b < nb; ++b) {
-        // this wave's weights of the super-block: header and the 8 columns 8g.. of every sub-block (requested before
-        // the barrier, used after it)
-        const uint4 hdr = *reinterpret_cast<const uint4 *>(wrow + b * 144);
-        uint32_t qw[8];
+        // B operands: sc_s * q as binary16 (exact).  A dword holds the eight weights of lane (n, g); masked in pairs
+        // (0,4) (1,5) (2,6) (3,7) into the mantissas of 1024 + q, then one fused multiply-add per pair: (1024 + q) sc - 1024 sc
+        half8 B[GM_RT][8], Bm[GM_RT];
+        float dd[GM_RT], dm[GM_RT];
 #pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) qw[s8] = *reinterpret_cast<const uint32_t *>(wrow + b * 144 + 16 + 16 * s8 + 4 * g);
-
-        __syncthreads(); // the previous super-block's activations have been used
-        {
-            const float *xp = a.x + s_t * a.ldx + b * 256 + s_c0;
-            float v[16];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float4 q = *reinterpret_cast<const float4 *>(xp + 4 * i);
-                v[4 * i] = q.x; v[4 * i + 1] = q.y; v[4 * i + 2] = q.z; v[4 * i + 3] = q.w;
-            }
-            if (a.gain) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float4 q = *reinterpret_cast<const float4 *>(a.gain + b * 256 + s_c0 + 4 * i);
-                    v[4 * i] *= q.x; v[4 * i + 1] *= q.y; v[4 * i + 2] *= q.z; v[4 * i + 3] *= q.w;
-                }
-            }
-            float sum = 0.f;
-            half8 h[2], l[2];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float sv = v[i] * s_stat.x;
-                // the product as an opaque fp32 number: left visible, the compiler formed the stored hi from the rounded
-                // product and the hi that lo is taken against from the exact one (fused multiply-convert); the two differ
-                // now and then by one binary16 step, which lo then does not make up for
-                asm volatile("" : "+v"(sv));
-                const _Float16 hh = static_cast<_Float16>(sv);
-                const _Float16 ll = static_cast<_Float16>(sv - static_cast<float>(hh));
-                h[i >> 3][i & 7] = hh;
-                l[i >> 3][i & 7] = ll;
-                sum += static_cast<float>(hh) + static_cast<float>(ll); // what the MFMAs will see
-            }
-            const int tt = s_tok >> 4, m = s_tok & 15;
-            lds.hi[tt][s_s8][m + 16 * s_g0] = h[0];
-            lds.hi[tt][s_s8][m + 16 * (s_g0 + 1)] = h[1];
-            lds.lo[tt][s_s8][m + 16 * s_g0] = l[0];
-            lds.lo[tt][s_s8][m + 16 * (s_g0 + 1)] = l[1];
-            sum += __shfl_xor(sum, 1, 64); // the two threads of a sub-block are neighbours
-            if ((threadIdx.x & 1) == 0) lds.xs[s_tok][s_s8] = sum;
-        }
-        __syncthreads();
-
-        // B operand: sc_s * q as binary16 (exact), lane (row n, columns 8g .. 8g+7 of sub-block s)
-        const float d = hdr_d(hdr), dmin = hdr_dmin(hdr);
-        half8 B[8];
-        float mf[8];
-#pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) {
-            const float sc = static_cast<float>(hdr_field(hdr, s8));
-            mf[s8] = static_cast<float>(hdr_field(hdr, 8 + s8));
-            const uint32_t w = qw[s8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) B[s8][e] = static_cast<_Float16>(static_cast<float>((w >> (4 * e)) & 15u) * sc);
-        }
-#pragma unroll
-        for (int tt = 0; tt < GM_TT; ++tt) {
-            v4f acc = {0.f, 0.f, 0.f, 0.f};
+        for (int rt = 0; rt < GM_RT; ++rt) {
+            dd[rt] = hdr_d(hdr[rt]);
+            dm[rt] = hdr_dmin(hdr[rt]);
 #pragma unroll
             for (int s8 = 0; s8 < 8; ++s8) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds.hi[tt][s8][lane], B[s8], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(lds.lo[tt][s8][lane], B[s8], acc, 0, 0, 0);
-            }
-            // this lane: row n, tokens 4g .. 4g+3 of the tile
+                const _Float16 sc = static_cast<_Float16>(static_cast<float>(hdr_field(hdr[rt], s8)));
+                const half2v sc2 = {sc, sc};
+                const _Float16 off = static_cast<_Float16>(-1024.f) * sc; // exact: at most 64512 in magnitude
+                const half2v off2 = {off, off};
+                Bm[rt][s8] = static_cast<_Float16>(static_cast<float>(hdr_field(hdr[rt], 8 + s8)));
+                const uint32_t w = qw[rt][s8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float4 xa = *reinterpret_cast<const float4 *>(&lds.xs[tt * 16 + 4 * g + i][0]);
-                const float4 xb = *reinterpret_cast<const float4 *>(&lds.xs[tt * 16 + 4 * g + i][4]);
-                float ms = mf[0] * xa.x;
-                ms = fmaf(mf[1], xa.y, ms); ms = fmaf(mf[2], xa.z, ms); ms = fmaf(mf[3], xa.w, ms);
-                ms = fmaf(mf[4], xb.x, ms); ms = fmaf(mf[5], xb.y, ms); ms = fmaf(mf[6], xb.z, ms); ms = fmaf(mf[7], xb.w, ms);
-                yacc[tt][i] += d * acc[i] - dmin * ms;
+                for (int pr = 0; pr < 4; ++pr) {
+                    const uint32_t bits = ((w >> (4 * pr)) & 0x000f000fu) | 0x64006400u;
+                    const half2v r = __builtin_elementwise_fma(__builtin_bit_cast(half2v, bits), sc2, off2);
+                    B[rt][s8][2 * pr] = r[0];
+                    B[rt][s8][2 * pr + 1] = r[1];
+                }
+            }
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this half's tiles have landed (this wave's share)
+            __syncthreads();                                  // everyone's share has, and the other buffer has been read
+            if (half == 0) {
+                if (second_half) issue_stage(b, 1);
+                // the next super-block's weights, into the registers the B tiles were just built from; they have a
+                // whole multiplication phase to arrive (the last step loads its own super-block again: in bounds, unused)
+                const int step = b + 1 < nb ? 144 : 0;
+#pragma unroll
+                for (int rt = 0; rt < GM_RT; ++rt) {
+                    hp[rt] += step;
+                    qp[rt] += step;
+                    hdr[rt] = *reinterpret_cast<const uint4 *>(hp[rt]);
+#pragma unroll
+                    for (int s8 = 0; s8 < 8; ++s8) qw[rt][s8] = *reinterpret_cast<const uint32_t *>(qp[rt] + 16 * s8);
+                }
+            } else if (b + 1 < nb) {
+                issue_stage(b + 1, 0);
+            }
+            if (half == 1 && !second_half) continue;
+            const uint8_t *stage = smem + half * GM_STAGE_BYTES;
+#pragma unroll
+            for (int ht = 0; ht < GM_HT; ++ht) {
+                const int tt = GM_HT * half + ht;
+                const half8 *At = reinterpret_cast<const half8 *>(stage + ht * GM_TILE_BYTES);
+                v4f acc[GM_RT];
+#pragma unroll
+                for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s8 = 0; s8 < 8; ++s8) {
+                    const half8 ah = At[(2 * s8) * 64 + lane], al = At[(2 * s8 + 1) * 64 + lane];
+#pragma unroll
+                    for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, B[rt][s8], acc[rt], 0, 0, 0);
+#pragma unroll
+                    for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, B[rt][s8], acc[rt], 0, 0, 0);
+                }
+                const half8 ax = At[16 * 64 + lane];
+#pragma unroll
+                for (int rt = 0; rt < GM_RT; ++rt) {
+                    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+                    const v4f am = __builtin_amdgcn_mfma_f32_16x16x32_f16(ax, Bm[rt], zero, 0, 0, 0);
+                    // this lane: row n of row tile rt, tokens 4g .. 4g+3 of the tile
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) yacc[tt][rt][i] = fmaf(dd[rt], acc[rt][i], fmaf(-dm[rt], am[i], yacc[tt][rt][i]));
+                }
             }
         }
     }
 
-    const int64_t out_row = static_cast<int64_t>(blockIdx.x) * GM_ROWS + wave * 16 + n;
-    if (out_row < a.n_rows) {
+#pragma unroll
+    for (int rt = 0; rt < GM_RT; ++rt) {
+        const int64_t out_row = row0 + 16 * rt + n;
+        if (out_row >= a.n_rows) continue;
 #pragma unroll
         for (int tt = 0; tt < GM_TT; ++tt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int t = t0 + tt * 16 + 4 * g + i;
+                const int t = tb * GM_TM + tt * 16 + 4 * g + i;
                 if (t < a.T) {
-                    float v = yacc[tt][i] * a.stat[t].y;
+                    float v = yacc[tt][rt][i] * a.stat[t].y;
                     if (a.resid) v += a.resid[t * a.ldr + out_row];
                     a.y[t * a.ldy + out_row] = v;
                 }
@@ -202,20 +318,38 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
 
 } // namespace
 
-size_t gemm_ws_bytes(int T) { return round_up(static_cast<size_t>(T) * sizeof(float2), 256); }
+size_t gemm_ws_bytes(int T, int64_t n_cols)
+{
+    const size_t tiles = (static_cast<size_t>(T) + 15) / 16;
+    return round_up(static_cast<size_t>(T) * sizeof(float2), GM_STAT_ALIGN) + tiles * static_cast<size_t>(n_cols / QK) * GM_TILE_BYTES;
+}
 
 prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
                              const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
-                             void *ws, hipStream_t st, bool scales_ready)
+                             void *ws, hipStream_t st, bool split_ready)
 {
     if (n_rows == 0 || T == 0) return PRIMA_OK;
-    const int64_t row_blocks = (n_rows + GM_ROWS - 1) / GM_ROWS;
-    if (row_blocks >= (int64_t{1} << 31) || (T + GM_TM - 1) / GM_TM > 65535) return PRIMA_E_SHAPE;
+    const int64_t nb = n_cols / QK;
+    const int n_tiles = (T + 15) / 16, n_tb = (T + GM_TM - 1) / GM_TM;
+    const int64_t n_rb = (n_rows + GM_ROWS - 1) / GM_ROWS;
+    const int64_t rb_per_xcd = (n_rb + GM_XCDS - 1) / GM_XCDS;
+    const int64_t grid = (rb_per_xcd + GM_PATCH_R - 1) / GM_PATCH_R * ((n_tb + GM_PATCH_C - 1) / GM_PATCH_C) * (GM_PATCH_R * GM_PATCH_C) * GM_XCDS;
+    if (grid >= (int64_t{1} << 31) || n_tiles > 65535 || nb >= (int64_t{1} << 31)) return PRIMA_E_SHAPE;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(q4k_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, GM_LDS_BYTES) != hipSuccess)
+            return PRIMA_E_DEVICE;
+        attr_set = true;
+    }
     float2 *stat = static_cast<float2 *>(ws);
-    // scales_ready: ws holds the scales of these very activations (the call before this one had the same x, gain, eps)
-    if (!scales_ready) hipLaunchKernelGGL(gemm_token_scale_kernel, dim3(T), dim3(256), 0, st, x, ldx, n_cols, gain, eps, stat);
-    GemmArgs a{W, n_rows, n_cols, x, ldx, gain, stat, resid, ldr, y, ldy, T};
-    hipLaunchKernelGGL(q4k_gemm_kernel, dim3(static_cast<unsigned>(row_blocks), static_cast<unsigned>((T + GM_TM - 1) / GM_TM)), dim3(GM_THREADS), 0, st, a);
+    uint8_t *A = static_cast<uint8_t *>(ws) + round_up(static_cast<size_t>(T) * sizeof(float2), GM_STAT_ALIGN);
+    // split_ready: ws holds the split of these very activations (the call before this one had the same x, gain, eps, T)
+    if (!split_ready) {
+        hipLaunchKernelGGL(gemm_token_scale_kernel, dim3(T), dim3(256), 0, st, x, ldx, n_cols, gain, eps, stat);
+        hipLaunchKernelGGL(gemm_split_kernel, dim3(static_cast<unsigned>(nb), n_tiles), dim3(256), 0, st, x, ldx, gain, stat, T, nb, A);
+    }
+    GemmArgs a{W, n_rows, n_cols, A, stat, resid, ldr, y, ldy, T, n_tiles, static_cast<int>(n_rb), n_tb};
+    hipLaunchKernelGGL(q4k_gemm_kernel, dim3(static_cast<unsigned>(grid)), dim3(GM_THREADS), GM_LDS_BYTES, st, a);
     return last_launch_status();
 }
 

@@ -216,7 +216,7 @@ struct PrefillWs {
 };
 
 // scratch of a prompt-processing call: the layer's intermediate activations for all T tokens, the RoPE table, the
-// per-token scales of the matrix product, and the attention scratch of one 16-token call
+// matrix product's scratch (sized for the widest matrix), and the attention scratch of one 16-token call
 PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
 {
     PrefillWs w{};
@@ -235,7 +235,7 @@ PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
     w.xb1 = take(t * static_cast<size_t>(d.e) * f);
     w.rope = take(t * static_cast<size_t>(d.head_dim) * f);
     w.attn = take(attn_ws_bytes(d, kv_cap, PRIMA_MAX_TOK));
-    w.stat = take(gemm_ws_bytes(T));
+    w.stat = take(gemm_ws_bytes(T, std::max<int64_t>({d.e, static_cast<int64_t>(qd), d.ffn})));
     w.total = off;
     return w;
 }
@@ -331,7 +331,7 @@ prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols, const
     return launch_gemv_mfma(ga, workspace, workspace_bytes, gemv_arrivals_bytes(n_rows), st);
 }
 
-size_t prima_gemm_workspace_bytes(int32_t T) { return T < 1 ? 0 : gemm_ws_bytes(T); }
+size_t prima_gemm_workspace_bytes(int32_t T, int64_t n_cols) { return (T < 1 || n_cols <= 0 || n_cols % QK) ? 0 : gemm_ws_bytes(T, n_cols); }
 
 prima_status prima_q4k_gemm(const void *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int32_t T,
                             const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
@@ -343,7 +343,7 @@ prima_status prima_q4k_gemm(const void *W, int64_t n_rows, int64_t n_cols, const
     if (!aligned(W, 16) || !aligned(x, 16) || !aligned(y, 4) || ldx % 4 || (gain && !aligned(gain, 16)) || (resid && !aligned(resid, 4)) ||
         !aligned(workspace, 256))
         return PRIMA_E_ALIGN;
-    if (workspace_bytes < gemm_ws_bytes(T)) return PRIMA_E_WORKSPACE;
+    if (workspace_bytes < gemm_ws_bytes(T, n_cols)) return PRIMA_E_WORKSPACE;
     return launch_q4k_gemm(static_cast<const uint8_t *>(W), n_rows, n_cols, x, ldx, T, gain, eps, resid, ldr, y, ldy, workspace,
                            static_cast<hipStream_t>(hip_stream));
 }

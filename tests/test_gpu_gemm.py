@@ -120,17 +120,18 @@ def test_gemm_argument_errors(gpu_lib):
     W = torch.zeros((16, 1, 144), dtype=torch.uint8, device="cuda")
     x = torch.zeros((4, 256), dtype=torch.float32, device="cuda")
     y = torch.zeros((4, 16), dtype=torch.float32, device="cuda")
-    ws = torch.zeros(256, dtype=torch.uint8, device="cuda")
+    need = L.prima_gemm_workspace_bytes(4, 256)
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
     p = lambda t: t.data_ptr()
     ok = lambda **k: L.prima_q4k_gemm(k.get("W", p(W)), k.get("rows", 16), k.get("cols", 256), k.get("x", p(x)), k.get("ldx", 256),
                                       k.get("T", 4), None, 0.0, None, 0, k.get("y", p(y)), k.get("ldy", 16), k.get("ws", p(ws)),
-                                      k.get("wsb", 256), None)
+                                      k.get("wsb", need), None)
     assert ok() == 0
     assert _ffi.STATUS[ok(W=None)] == "PRIMA_E_NULL"
     assert _ffi.STATUS[ok(cols=255)] == "PRIMA_E_SHAPE"
     assert _ffi.STATUS[ok(ldy=15)] == "PRIMA_E_SHAPE"
     assert _ffi.STATUS[ok(T=0)] == "PRIMA_E_RANGE"
     assert _ffi.STATUS[ok(x=p(x) + 4)] == "PRIMA_E_ALIGN"
-    assert _ffi.STATUS[ok(wsb=8)] == "PRIMA_E_WORKSPACE"
+    assert _ffi.STATUS[ok(wsb=need - 1)] == "PRIMA_E_WORKSPACE"
     assert ok(rows=0) == 0
     torch.cuda.synchronize()
