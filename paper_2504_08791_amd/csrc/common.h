@@ -99,6 +99,16 @@ size_t gemm_ws_bytes(int T, int64_t n_cols);
 prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
                              const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
                              void *ws, hipStream_t st, bool split_ready = false);
+// up to three matrices with the same columns against the same activations (Q / K / V), or, with pair set, two of equal
+// shape (gate, up) with silu(gate) * up stored to mats[0].y; the residual only with one matrix
+struct GemmMat {
+    const uint8_t *W;
+    float *y;
+    int64_t n_rows, ldy;
+};
+prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, int64_t n_cols, const float *x, int64_t ldx, int T,
+                                   const float *gain, float eps, const float *resid, int64_t ldr, void *ws, hipStream_t st,
+                                   bool split_ready = false);
 // RoPE table [T][D/2] of (cos, sin) for the positions n_past .. n_past + T - 1 (any T)
 prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
 

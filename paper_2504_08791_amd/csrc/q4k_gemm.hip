@@ -48,15 +48,24 @@ constexpr int GM_XCDS = 8;
 constexpr int GM_PATCH_R = 8, GM_PATCH_C = 4; // row blocks x token blocks that share an XCD at a time
 constexpr size_t GM_STAT_ALIGN = 1024;
 
-struct GemmArgs {
+struct GemmSegDev {
     const uint8_t *W;
-    int64_t n_rows, n_cols;
+    float *y;
+    int64_t n_rows, ldy;
+    int rb0; // first row block of this matrix (INT_MAX: unused)
+};
+
+// Up to three matrices with the same columns against the same activations in one launch (Q / K / V): their row blocks
+// are numbered one matrix after the other.  pair: two matrices of equal shape (gate, up); a wave's two row tiles are
+// then the same 16 rows of the one and of the other, a row block is 128 rows, and silu(gate) * up is stored to seg[0].y.
+struct GemmArgs {
+    GemmSegDev seg[3];
+    int pair;
+    int64_t n_cols;
     const uint8_t *A;   // split activations: [token tile][super-block][17][64 lanes] x 16 bytes
     const float2 *stat; // per token: (2^p [* 1/rms], 2^-p)
-    const float *resid; // null: none
+    const float *resid; // null: none (added to every stored row; launches with a residual have one matrix)
     int64_t ldr;
-    float *y;
-    int64_t ldy;
     int T, n_tiles, n_rb, n_tb; // 16-token tiles, row blocks, token blocks
 };
 
@@ -179,11 +188,16 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
     const int tb = (patch % patches_tb) * GM_PATCH_C + within % GM_PATCH_C;
     if (rb >= a.n_rb || tb >= a.n_tb) return; // the whole workgroup, before any barrier
     const int64_t nb = a.n_cols >> 8;
-    const int64_t row0 = static_cast<int64_t>(rb) * GM_ROWS + wave * (16 * GM_RT);
+    const int sg = a.pair ? 0 : (rb >= a.seg[2].rb0 ? 2 : (rb >= a.seg[1].rb0 ? 1 : 0));
+    const GemmSegDev &my = a.seg[sg];
+    const int64_t row0 = a.pair ? static_cast<int64_t>(rb) * (GM_ROWS / 2) + wave * 16
+                                : static_cast<int64_t>(rb - my.rb0) * GM_ROWS + wave * (16 * GM_RT);
     const uint8_t *wrow[GM_RT];
 #pragma unroll
-    for (int rt = 0; rt < GM_RT; ++rt)
-        wrow[rt] = a.W + min<int64_t>(row0 + 16 * rt + n, a.n_rows - 1) * nb * 144; // past the end: a valid row, not stored
+    for (int rt = 0; rt < GM_RT; ++rt) { // past the end: a valid row, not stored
+        const int64_t r = min<int64_t>(row0 + (a.pair ? 0 : 16 * rt) + n, my.n_rows - 1);
+        wrow[rt] = (a.pair ? a.seg[rt].W : my.W) + r * nb * 144;
+    }
     const int tile0 = tb * GM_TT;
     const uint32_t lds0 = lds_address(smem);
 
@@ -298,10 +312,27 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
         }
     }
 
+    if (a.pair) {
+        const int64_t out_row = row0 + n;
+        if (out_row < my.n_rows) {
+#pragma unroll
+            for (int tt = 0; tt < GM_TT; ++tt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int t = tb * GM_TM + tt * 16 + 4 * g + i;
+                    if (t < a.T) {
+                        const float sc = a.stat[t].y;
+                        const float gt = yacc[tt][0][i] * sc, up = yacc[tt][1][i] * sc;
+                        my.y[t * my.ldy + out_row] = gt / (1.0f + expf(-gt)) * up;
+                    }
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int rt = 0; rt < GM_RT; ++rt) {
         const int64_t out_row = row0 + 16 * rt + n;
-        if (out_row >= a.n_rows) continue;
+        if (out_row >= my.n_rows) continue;
 #pragma unroll
         for (int tt = 0; tt < GM_TT; ++tt)
 #pragma unroll
@@ -310,7 +341,7 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
                 if (t < a.T) {
                     float v = yacc[tt][rt][i] * a.stat[t].y;
                     if (a.resid) v += a.resid[t * a.ldr + out_row];
-                    a.y[t * a.ldy + out_row] = v;
+                    my.y[t * my.ldy + out_row] = v;
                 }
             }
     }
@@ -324,14 +355,26 @@ size_t gemm_ws_bytes(int T, int64_t n_cols)
     return round_up(static_cast<size_t>(T) * sizeof(float2), GM_STAT_ALIGN) + tiles * static_cast<size_t>(n_cols / QK) * GM_TILE_BYTES;
 }
 
-prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
-                             const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
-                             void *ws, hipStream_t st, bool split_ready)
+prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, int64_t n_cols, const float *x, int64_t ldx, int T,
+                                   const float *gain, float eps, const float *resid, int64_t ldr, void *ws, hipStream_t st, bool split_ready)
 {
-    if (n_rows == 0 || T == 0) return PRIMA_OK;
+    if (n_mats < 1 || n_mats > 3 || (pair && (n_mats != 2 || mats[0].n_rows != mats[1].n_rows || resid))) return PRIMA_E_SHAPE;
+    if (T == 0) return PRIMA_OK;
+    GemmArgs a{};
+    int64_t n_rb = 0;
+    for (int i = 0; i < 3; ++i) {
+        a.seg[i].rb0 = 0x7fffffff;
+        if (i >= n_mats || mats[i].n_rows == 0 || (pair && i == 1)) {
+            if (i < n_mats) a.seg[i] = GemmSegDev{mats[i].W, mats[i].y, mats[i].n_rows, mats[i].ldy, 0x7fffffff};
+            continue;
+        }
+        a.seg[i] = GemmSegDev{mats[i].W, mats[i].y, mats[i].n_rows, mats[i].ldy, static_cast<int>(n_rb)};
+        n_rb += pair ? (mats[i].n_rows + GM_ROWS / 2 - 1) / (GM_ROWS / 2) : (mats[i].n_rows + GM_ROWS - 1) / GM_ROWS;
+        if (n_rb >= (int64_t{1} << 30)) return PRIMA_E_SHAPE;
+    }
+    if (n_rb == 0) return PRIMA_OK;
     const int64_t nb = n_cols / QK;
     const int n_tiles = (T + 15) / 16, n_tb = (T + GM_TM - 1) / GM_TM;
-    const int64_t n_rb = (n_rows + GM_ROWS - 1) / GM_ROWS;
     const int64_t rb_per_xcd = (n_rb + GM_XCDS - 1) / GM_XCDS;
     const int64_t grid = (rb_per_xcd + GM_PATCH_R - 1) / GM_PATCH_R * ((n_tb + GM_PATCH_C - 1) / GM_PATCH_C) * (GM_PATCH_R * GM_PATCH_C) * GM_XCDS;
     if (grid >= (int64_t{1} << 31) || n_tiles > 65535 || nb >= (int64_t{1} << 31)) return PRIMA_E_SHAPE;
@@ -348,9 +391,19 @@ prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, c
         hipLaunchKernelGGL(gemm_token_scale_kernel, dim3(T), dim3(256), 0, st, x, ldx, n_cols, gain, eps, stat);
         hipLaunchKernelGGL(gemm_split_kernel, dim3(static_cast<unsigned>(nb), n_tiles), dim3(256), 0, st, x, ldx, gain, stat, T, nb, A);
     }
-    GemmArgs a{W, n_rows, n_cols, A, stat, resid, ldr, y, ldy, T, n_tiles, static_cast<int>(n_rb), n_tb};
+    a.pair = pair ? 1 : 0;
+    a.n_cols = n_cols; a.A = A; a.stat = stat; a.resid = resid; a.ldr = ldr;
+    a.T = T; a.n_tiles = n_tiles; a.n_rb = static_cast<int>(n_rb); a.n_tb = n_tb;
     hipLaunchKernelGGL(q4k_gemm_kernel, dim3(static_cast<unsigned>(grid)), dim3(GM_THREADS), GM_LDS_BYTES, st, a);
     return last_launch_status();
+}
+
+prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
+                             const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
+                             void *ws, hipStream_t st, bool split_ready)
+{
+    const GemmMat m{W, y, n_rows, ldy};
+    return launch_q4k_gemm_multi(&m, 1, false, n_cols, x, ldx, T, gain, eps, resid, ldr, ws, st, split_ready);
 }
 
 } // namespace prima

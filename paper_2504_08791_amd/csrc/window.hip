@@ -212,7 +212,7 @@ prima_status check_window_args(const prima_dims *d, int32_t kv_cap, int32_t n_pa
 }
 
 struct PrefillWs {
-    size_t q, k, v, o, h, a, u, xb0, xb1, rope, attn, stat, total;
+    size_t q, k, v, o, h, a, xb0, xb1, rope, attn, stat, total;
 };
 
 // scratch of a prompt-processing call: the layer's intermediate activations for all T tokens, the RoPE table, the
@@ -230,7 +230,6 @@ PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
     w.o = take(t * qd * f);
     w.h = take(t * static_cast<size_t>(d.e) * f);
     w.a = take(t * static_cast<size_t>(d.ffn) * f);
-    w.u = take(t * static_cast<size_t>(d.ffn) * f);
     w.xb0 = take(t * static_cast<size_t>(d.e) * f);
     w.xb1 = take(t * static_cast<size_t>(d.e) * f);
     w.rope = take(t * static_cast<size_t>(d.head_dim) * f);
@@ -247,14 +246,13 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
 {
     const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
     float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
-    float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *act = at<float>(ws, w.a), *up = at<float>(ws, w.u);
+    float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *act = at<float>(ws, w.a);
     void *stat = at<char>(ws, w.stat);
     auto W = [](const void *p) { return static_cast<const uint8_t *>(p); };
     prima_status s;
 #define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
-    PRIMA_TRY(launch_q4k_gemm(W(L.wq), qd, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, q, qd, stat, st));
-    PRIMA_TRY(launch_q4k_gemm(W(L.wk), kvd, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, k, kvd, stat, st, true));
-    PRIMA_TRY(launch_q4k_gemm(W(L.wv), kvd, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, v, kvd, stat, st, true));
+    const GemmMat qkv[3] = {{W(L.wq), q, qd, qd}, {W(L.wk), k, kvd, kvd}, {W(L.wv), v, kvd, kvd}};
+    PRIMA_TRY(launch_q4k_gemm_multi(qkv, 3, false, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, stat, st));
     for (int t0 = 0; t0 < T; t0 += PRIMA_MAX_TOK) {
         const int Tc = std::min<int>(PRIMA_MAX_TOK, T - t0);
         PRIMA_TRY(launch_attn(d, q + t0 * qd, nullptr, k + t0 * kvd, v + t0 * kvd, at<float>(ws, w.rope) + static_cast<int64_t>(t0) * d.head_dim,
@@ -262,9 +260,8 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
                               o + t0 * qd, at<char>(ws, w.attn), st));
     }
     PRIMA_TRY(launch_q4k_gemm(W(L.wo), e, qd, o, qd, T, nullptr, 0.f, x, e, h, e, stat, st));
-    PRIMA_TRY(launch_q4k_gemm(W(L.wgate), F, e, h, e, T, static_cast<const float *>(L.g_ffn), d.rms_eps, nullptr, 0, act, F, stat, st));
-    PRIMA_TRY(launch_q4k_gemm(W(L.wup), F, e, h, e, T, static_cast<const float *>(L.g_ffn), d.rms_eps, nullptr, 0, up, F, stat, st, true));
-    PRIMA_TRY(launch_swiglu(act, up, static_cast<int64_t>(T) * F, st));
+    const GemmMat gate_up[2] = {{W(L.wgate), act, F, F}, {W(L.wup), nullptr, F, F}};
+    PRIMA_TRY(launch_q4k_gemm_multi(gate_up, 2, true, e, h, e, T, static_cast<const float *>(L.g_ffn), d.rms_eps, nullptr, 0, stat, st));
     PRIMA_TRY(launch_q4k_gemm(W(L.wdown), e, F, act, F, T, nullptr, 0.f, h, e, y, e, stat, st));
 #undef PRIMA_TRY
     return PRIMA_OK;
