@@ -236,6 +236,7 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
     }
 
     issue_stage(0, 0);
+    uint32_t touch[GM_RT] = {0u, 0u};
     for (int64_t b = 0; b < nb; ++b) {
         // B operands: sc_s * q as binary16 (exact).  A dword holds the eight weights of lane (n, g); masked in pairs
         // (0,4) (1,5) (2,6) (3,7) into the mantissas of 1024 + q, then one fused multiply-add per pair: (1024 + q) sc - 1024 sc
@@ -265,6 +266,7 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this half's tiles have landed (this wave's share)
+            if (half == 1) asm volatile("" : : "v"(touch[0]), "v"(touch[1])); // (the touches' registers are free again)
             __syncthreads();                                  // everyone's share has, and the other buffer has been read
             if (half == 0) {
                 if (second_half) issue_stage(b, 1);
@@ -278,6 +280,10 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
                     hdr[rt] = *reinterpret_cast<const uint4 *>(hp[rt]);
 #pragma unroll
                     for (int s8 = 0; s8 < 8; ++s8) qw[rt][s8] = *reinterpret_cast<const uint32_t *>(qp[rt] + 16 * s8);
+                    // and one dword of the super-block three further on (the four lanes of a row between them touch
+                    // all of its 144 bytes): the rows are read nowhere else, so without this every weight load waits
+                    // for HBM; with it the loads above find their lines in the L2
+                    touch[rt] = b + 4 < nb ? *reinterpret_cast<const uint32_t *>(hp[rt] + 3 * 144 + min(48 * g, 140)) : 0u;
                 }
             } else if (b + 1 < nb) {
                 issue_stage(b + 1, 0);
