@@ -74,13 +74,16 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
     // A call for one sequence: all of its tokens.  A batch of sequences: the one token of sequence tok0, whose
     // caches and length are read by hand from the argument segment (indexing the by-value argument with a
     // run-time index would make the compiler copy all of it to scratch memory).
-    const bool batch = a.batch != 0;
-    const int gps = (G + QGM - 1) / QGM; // query groups of one token
-    const int tok0 = batch ? blockIdx.z / gps : 0;
-    const int qgrp = batch ? blockIdx.z - tok0 * gps : blockIdx.z, nqg = batch ? gps : gridDim.z;
-    const int arg_T = batch ? 1 : a.T;
+    // A prompt (batch == 2, caches complete, one key range): piece z / gps of the grid is a call of its own for the
+    // tokens 16 piece .. 16 piece + 15, which see the n_past + 16 piece rows before them and, causally, their own.
+    const bool batch = a.batch == 1, prompt = a.batch == 2, pieces = batch || prompt;
+    const int gps = prompt ? (G * PRIMA_MAX_TOK + QGM - 1) / QGM : (G + QGM - 1) / QGM; // query groups of one token / one piece
+    const int piece = pieces ? blockIdx.z / gps : 0;
+    const int tok0 = prompt ? piece * PRIMA_MAX_TOK : piece;
+    const int qgrp = pieces ? blockIdx.z - piece * gps : blockIdx.z, nqg = pieces ? gps : gridDim.z;
+    const int arg_T = batch ? 1 : (prompt ? PRIMA_MAX_TOK : a.T);
     __half *arg_K = a.K, *arg_V = a.V;
-    int arg_n_past = a.n_past;
+    int arg_n_past = a.n_past + (prompt ? tok0 : 0);
     if (batch) {
         typedef const __attribute__((address_space(4))) AttnArgs ConstAttnArgs;
         ConstAttnArgs &ka = *(ConstAttnArgs *)__builtin_amdgcn_kernarg_segment_ptr();
@@ -437,6 +440,8 @@ static int tile_num_splits(const prima_dims &d, int n_total, int T, bool batch)
     return ns;
 }
 
+static prima_status launch_attn_kernel(const prima_dims &d, dim3 grid, const AttnArgs &a, hipStream_t st);
+
 prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
                             const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
                             void *ws, hipStream_t st, const AttnSeqs *seq)
@@ -450,7 +455,32 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
     const int want = tile_num_splits(d, n_total, T, seq != nullptr);
     a.keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
     a.nsplit = (n_total + a.keys_per_split - 1) / a.keys_per_split;
-    const dim3 grid(a.nsplit, d.n_kv_heads, tile_query_groups(d, T, seq != nullptr)), block(ATT_THREADS);
+    const dim3 grid(a.nsplit, d.n_kv_heads, tile_query_groups(d, T, seq != nullptr));
+    return launch_attn_kernel(d, grid, a, st);
+}
+
+// Attention for the tokens of a prompt whose rotated K and V rows are in the caches already and whose queries are
+// rotated: n_pieces pieces of PRIMA_MAX_TOK tokens in one launch, each piece over the n_past + 16 piece rows before it
+// and, causally, its own; one key range per workgroup (there are Hkv * G workgroups per piece), no scratch.
+prima_status launch_attn_prompt(const prima_dims &d, const float *q, __half *K, __half *V, int kv_cap, int n_past, int n_pieces,
+                                float *o, hipStream_t st)
+{
+    if (n_pieces < 1) return PRIMA_OK;
+    const int G = d.n_q_heads / d.n_kv_heads;
+    const int64_t gz = static_cast<int64_t>(n_pieces) * ((G * PRIMA_MAX_TOK + QGM - 1) / QGM);
+    if (gz > 65535 || static_cast<int64_t>(n_past) + static_cast<int64_t>(n_pieces) * PRIMA_MAX_TOK > kv_cap) return PRIMA_E_SHAPE;
+    AttnArgs a{};
+    a.batch = 2;
+    a.q = q; a.K = K; a.V = V; a.o = o;
+    a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.kv_cap = kv_cap; a.n_past = n_past; a.T = PRIMA_MAX_TOK;
+    a.nsplit = 1;
+    a.keys_per_split = (n_past + n_pieces * PRIMA_MAX_TOK + 15) / 16 * 16;
+    return launch_attn_kernel(d, dim3(1, d.n_kv_heads, static_cast<unsigned>(gz)), a, st);
+}
+
+static prima_status launch_attn_kernel(const prima_dims &d, dim3 grid, const AttnArgs &a, hipStream_t st)
+{
+    const dim3 block(ATT_THREADS);
     static bool attr_set = false;
     if (!attr_set) {
         const void *fns[] = {reinterpret_cast<const void *>(attn_decode_kernel<128, 0>), reinterpret_cast<const void *>(attn_decode_kernel<128, 1>),

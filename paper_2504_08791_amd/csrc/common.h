@@ -132,6 +132,14 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
                          const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
                          void *ws, hipStream_t st, const AttnSeqs *seq = nullptr);
 
+// a prompt: rotated K / V rows already in the caches, q rotated; n_pieces pieces of PRIMA_MAX_TOK tokens in one launch
+prima_status launch_attn_prompt(const prima_dims &d, const float *q, __half *K, __half *V, int kv_cap, int n_past, int n_pieces,
+                                float *o, hipStream_t st);
+// RoPE on q (in place) and k, and k, v appended to the caches as rows n_past .. n_past + T - 1, for any T; tab from
+// launch_rope_table
+prima_status launch_rope_append(const prima_dims &d, float *q, const float *k, const float *v, const float *tab,
+                                __half *K, __half *V, int kv_cap, int n_past, int T, hipStream_t st);
+
 // one token through a whole window in one launch per FUSED_MAX_LAYERS layers (fused_window.hip); PRIMA_E_SHAPE
 // with nothing launched when the shapes do not qualify
 size_t fused_sync_bytes();

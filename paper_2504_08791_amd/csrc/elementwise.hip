@@ -67,6 +67,49 @@ prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta
     return last_launch_status();
 }
 
+// RoPE and cache append for the tokens of a prompt: one thread per (token, head of q or k, rotation pair); the
+// threads of the k heads also convert the two v elements 2i, 2i + 1.  Pair i is (i, i + D/2) (mode 0) or (2i, 2i + 1).
+__global__ void __launch_bounds__(256) rope_append_kernel(float *__restrict__ q, const float *__restrict__ k, const float *__restrict__ v,
+                                                          const float2 *__restrict__ tab, __half *__restrict__ K, __half *__restrict__ V,
+                                                          int Hq, int Hkv, int D, int mode, int kv_cap, int n_past, int64_t n)
+{
+    const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= n) return;
+    const int half = D / 2, heads = Hq + Hkv;
+    const int i = static_cast<int>(idx % half);
+    const int64_t th = idx / half;
+    const int h = static_cast<int>(th % heads);
+    const int64_t t = th / heads;
+    const float2 cs = tab[t * half + i];
+    const int ia = mode ? 2 * i : i, ib = mode ? 2 * i + 1 : i + half;
+    if (h < Hq) {
+        float *p = q + (t * Hq + h) * D;
+        const float a = p[ia], b = p[ib];
+        p[ia] = a * cs.x - b * cs.y;
+        p[ib] = a * cs.y + b * cs.x;
+    } else {
+        const int kh = h - Hq;
+        const float *p = k + (t * Hkv + kh) * D;
+        const float a = p[ia], b = p[ib];
+        const int64_t row = (static_cast<int64_t>(kh) * kv_cap + n_past + t) * D;
+        K[row + ia] = __float2half_rn(a * cs.x - b * cs.y);
+        K[row + ib] = __float2half_rn(a * cs.y + b * cs.x);
+        const float2 vv = *reinterpret_cast<const float2 *>(v + (t * Hkv + kh) * D + 2 * i);
+        *reinterpret_cast<__half2 *>(V + row + 2 * i) = __floats2half2_rn(vv.x, vv.y);
+    }
+}
+
+prima_status launch_rope_append(const prima_dims &d, float *q, const float *k, const float *v, const float *tab,
+                                __half *K, __half *V, int kv_cap, int n_past, int T, hipStream_t st)
+{
+    const int64_t n = static_cast<int64_t>(T) * (d.n_q_heads + d.n_kv_heads) * (d.head_dim / 2);
+    if (n <= 0) return PRIMA_OK;
+    if ((n + 255) / 256 >= (int64_t{1} << 31) || static_cast<int64_t>(n_past) + T > kv_cap) return PRIMA_E_SHAPE;
+    hipLaunchKernelGGL(rope_append_kernel, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st, q, k, v,
+                       reinterpret_cast<const float2 *>(tab), K, V, d.n_q_heads, d.n_kv_heads, d.head_dim, d.rope_mode, kv_cap, n_past, n);
+    return last_launch_status();
+}
+
 // Read-only streaming probe: every thread reads 16 bytes per step with a grid-wide stride and folds them
 // into one word, so that the loads cannot be dropped.  States what this device delivers for a plain
 // linear read, next to the nominal HBM peak.

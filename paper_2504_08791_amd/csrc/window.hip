@@ -239,8 +239,8 @@ PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
     return w;
 }
 
-// one decoder layer for T prompt tokens: the projections as matrix products over all tokens, attention in calls of
-// up to PRIMA_MAX_TOK tokens (each sees the rows cached before it and, causally, its own)
+// one decoder layer for T prompt tokens: the projections as matrix products over all tokens, attention for pieces of
+// PRIMA_MAX_TOK tokens (each sees the rows cached before it and, causally, its own), all pieces in one launch
 prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
                                const float *x, float *y, void *ws, const PrefillWs &w, hipStream_t st)
 {
@@ -253,12 +253,15 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
 #define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
     const GemmMat qkv[3] = {{W(L.wq), q, qd, qd}, {W(L.wk), k, kvd, kvd}, {W(L.wv), v, kvd, kvd}};
     PRIMA_TRY(launch_q4k_gemm_multi(qkv, 3, false, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, stat, st));
-    for (int t0 = 0; t0 < T; t0 += PRIMA_MAX_TOK) {
-        const int Tc = std::min<int>(PRIMA_MAX_TOK, T - t0);
-        PRIMA_TRY(launch_attn(d, q + t0 * qd, nullptr, k + t0 * kvd, v + t0 * kvd, at<float>(ws, w.rope) + static_cast<int64_t>(t0) * d.head_dim,
-                              static_cast<__half *>(L.k_cache), static_cast<__half *>(L.v_cache), kv_cap, n_past + t0, Tc,
-                              o + t0 * qd, at<char>(ws, w.attn), st));
-    }
+    // RoPE and the cache rows of all T tokens first; then the full pieces of PRIMA_MAX_TOK tokens in one launch and the
+    // rest in a launch of the decode kind (caches complete, queries rotated)
+    __half *Kc = static_cast<__half *>(L.k_cache), *Vc = static_cast<__half *>(L.v_cache);
+    PRIMA_TRY(launch_rope_append(d, q, k, v, at<float>(ws, w.rope), Kc, Vc, kv_cap, n_past, T, st));
+    const int n_pieces = T / PRIMA_MAX_TOK, rest = T - n_pieces * PRIMA_MAX_TOK;
+    PRIMA_TRY(launch_attn_prompt(d, q, Kc, Vc, kv_cap, n_past, n_pieces, o, st));
+    if (rest)
+        PRIMA_TRY(launch_attn(d, q + n_pieces * PRIMA_MAX_TOK * qd, nullptr, nullptr, nullptr, nullptr, Kc, Vc, kv_cap,
+                              n_past + n_pieces * PRIMA_MAX_TOK, rest, o + n_pieces * PRIMA_MAX_TOK * qd, at<char>(ws, w.attn), st));
     PRIMA_TRY(launch_q4k_gemm(W(L.wo), e, qd, o, qd, T, nullptr, 0.f, x, e, h, e, stat, st));
     const GemmMat gate_up[2] = {{W(L.wgate), act, F, F}, {W(L.wup), nullptr, F, F}};
     PRIMA_TRY(launch_q4k_gemm_multi(gate_up, 2, true, e, h, e, T, static_cast<const float *>(L.g_ffn), d.rms_eps, nullptr, 0, stat, st));
