@@ -96,6 +96,40 @@ def test_window_argument_errors():
     assert L.prima_workspace_bytes(C.byref(_dims(e=100)), 64, 1) == 0
 
 
+def test_matrix_product_and_prefill_argument_errors():
+    """Every call fails validation before anything is launched (no GPU here)."""
+    L = _ffi.lib()
+    need = L.prima_gemm_workspace_bytes(40, 512)
+    assert need >= 40 * 8 + 3 * 2 * 17 * 1024 and L.prima_gemm_workspace_bytes(0, 512) == 0 and L.prima_gemm_workspace_bytes(4, 300) == 0
+    f = lambda W=FAKE, rows=8, cols=512, x=FAKE, ldx=512, T=40, gain=None, resid=None, ldr=0, y=FAKE, ldy=8, ws=FAKE, wsb=need: \
+        L.prima_q4k_gemm(W, rows, cols, x, ldx, T, gain, 1e-5, resid, ldr, y, ldy, ws, wsb, None)
+    assert f(W=None) == 1 and f(x=None) == 1 and f(y=None) == 1 and f(ws=None) == 1
+    assert f(cols=300) == 2 and f(ldx=256) == 2 and f(ldy=4) == 2 and f(resid=FAKE, ldr=4) == 2
+    assert f(T=0) == 4 and f(T=65537) == 4
+    assert f(W=FAKE + 8) == 3 and f(x=FAKE + 4) == 3 and f(ldx=514) == 3 and f(gain=FAKE + 4) == 3 and f(ws=FAKE + 16) == 3
+    assert f(wsb=need - 1) == 5
+
+    d = _dims()
+    lay = (_ffi.Layer * 1)()
+    for name, _ in _ffi.Layer._fields_:
+        setattr(lay[0], name, FAKE)
+    needp = L.prima_prefill_workspace_bytes(C.byref(d), 256, 100)
+    assert needp > L.prima_prefill_workspace_bytes(C.byref(d), 256, 50) > 0
+    assert L.prima_prefill_workspace_bytes(C.byref(d), 256, 8193) == 0 and L.prima_prefill_workspace_bytes(C.byref(_dims(e=100)), 256, 8) == 0
+    g = lambda dd=d, layers=lay, Ln=1, cap=256, n_past=10, T=100, xi=FAKE, xo=FAKE, ws=FAKE, wsb=needp: \
+        L.prima_layer_window_prefill(C.byref(dd), layers, Ln, cap, n_past, T, xi, xo, ws, wsb, None)
+    assert g(xi=None) == 1 and g(ws=None) == 1 and g(layers=None) == 1
+    assert g(dd=_dims(e=500)) == 2
+    assert g(n_past=157) == 4 and g(Ln=0) == 4 and g(T=0) == 4 and g(T=8193, cap=10000) == 4
+    assert g(xi=FAKE + 4) == 3
+    assert g(wsb=needp - 1) == 5
+    bad = (_ffi.Layer * 1)()
+    for name, _ in _ffi.Layer._fields_:
+        setattr(bad[0], name, FAKE)
+    bad[0].wdown = None
+    assert g(layers=bad) == 1
+
+
 def test_batch_window_argument_errors():
     L = _ffi.lib()
     d = _dims()
