@@ -42,6 +42,9 @@ def main():
                          "(a common mix of a \"Q4K\" model), against the oracle")
     ap.add_argument("--prefill", type=int, default=0,
                     help="prompt processing: the config's window for this many prompt tokens in one call (time to the first token)")
+    ap.add_argument("--generate", type=int, default=0,
+                    help="with --prefill P: after the prompt call, this many one-token steps; reports both times (the paper's TTFT and TPOT, "
+                         "for this window)")
     ap.add_argument("--device-profile", action="store_true",
                     help="side measurement: the device-profiler quantities of the paper's latency model on this GPU, and the "
                          "model's estimate of the config's window step next to the measured one")
@@ -64,6 +67,8 @@ def main():
         return bench_batch(args, cfg)
     if args.format:
         return bench_format(args)
+    if args.prefill and args.generate:
+        return bench_generate(args, cfg)
     if args.prefill:
         return bench_prefill(args, cfg)
     if args.device_profile:
@@ -370,6 +375,61 @@ def bench_prefill(args, cfg):
         out["cpu_baseline"] = {"value": round(n_s / (cpu_seconds * cfg.n_layers), 4), "unit": "tokens/s", "cores": oracle.num_threads(),
                                "kind": "oracle", "sample": f"layer 0 for the first {n_s} prompt tokens ({cpu_seconds:.1f} s of CPU time), "
                                                            f"scaled to {cfg.n_layers} layers"}
+    print(json.dumps(out), flush=True)
+
+
+def bench_generate(args, cfg):
+    """A prompt of P tokens through the window in one call, then N one-token steps (Sec. 4.1 reports both: time to the first
+    token and time per output token).  A step is the whole sequence prompt + N tokens; `value` is the decode rate."""
+    import torch
+    import paper_2504_08791_amd as prima
+    from workloads import synth
+
+    d, P, N = cfg.dims, args.prefill, args.generate
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = cfg.with_(T=P, n_past=0)
+    cap = P + N
+    dev_layers = []
+    for l in range(cfg.n_layers):
+        t = synth.layer_tensors(cfg, l, kv_cap=cap)
+        dev_layers.append({k: torch.from_numpy(v).to(dev) for k, v in t.items()})
+    win = prima.Window(d, dev_layers, cap, T_max=1)
+    x = torch.from_numpy(synth.window_input(cfg)).to(dev)
+    nxt = torch.from_numpy(synth.batch_input(cfg, 1)).to(dev)
+    y, y1 = torch.empty_like(x), torch.empty_like(nxt)
+    stream = torch.cuda.current_stream()
+
+    def sequence(ev=None):
+        win.prefill(x, 0, x_out=y)
+        if ev is not None:
+            ev.record(stream)
+        for i in range(N):
+            win.decode(nxt, P + i, x_out=y1)
+
+    for _ in range(args.warmup):
+        sequence()
+    torch.cuda.synchronize()
+    ttft, total = 0.0, 0.0
+    for _ in range(args.steps):
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record(stream)
+        sequence(e1)
+        e2.record(stream)
+        torch.cuda.synchronize()
+        ttft += e0.elapsed_time(e1)
+        total += e0.elapsed_time(e2)
+    ttft /= args.steps
+    total /= args.steps
+    tpot = (total - ttft) / N
+    out = {
+        "metric": "output tokens/s per layer window after a prompt (1000 / TPOT of this window); TTFT of this window alongside",
+        "value": round(1e3 / tpot, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(total, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} shape: {cfg.n_layers}-layer window, {P} prompt tokens in one call, then {N} one-token steps; "
+                               "Q4_K weights, fp16 KV", "tokens_per_step": P + N, "layers": cfg.n_layers},
+        "ttft_ms": round(ttft, 3), "tpot_ms": round(tpot, 4),
+    }
     print(json.dumps(out), flush=True)
 
 

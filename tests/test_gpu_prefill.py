@@ -58,6 +58,23 @@ def test_prefill_vs_oracle(gpu_lib, name, T, n_past):
                 assert rel_err(g[:, n_past:n_past + T].reshape(1, -1), r[:, n_past:n_past + T].reshape(1, -1)) < 1e-3
 
 
+def test_prefill_fills_the_cache_to_its_last_row(gpu_lib):
+    """n_past + T == kv_cap: the last piece ends on the cache's last row; a token count with full pieces only and one
+    with a rest."""
+    for T, n_past in [(32, 5), (45, 0)]:
+        cfg = TINY["t0"].with_(T=T, n_past=n_past)
+        cap = n_past + T
+        host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+        win, dev_layers = _window(gpu_lib, cfg, cap, host)
+        x = synth.window_input(cfg)
+        print("case", T, n_past, flush=True)
+        y = win.prefill(_dev(x), n_past).cpu().numpy()
+        ref = _oracle_prompt(cfg.dims, host, x, n_past)
+        assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
+        g = dev_layers[0]["k_cache"].cpu().numpy().astype(np.float64)
+        assert rel_err(g[:, n_past:].reshape(1, -1), host[0]["k_cache"][:, n_past:].astype(np.float64).reshape(1, -1)) < 1e-3
+
+
 def test_prefill_then_decode_continues(gpu_lib):
     """A prompt through the prefill call, the next token through the decode call: against the oracle doing the same."""
     cfg = TINY["t1"].with_(T=40, n_past=0)
