@@ -307,7 +307,8 @@ size_t prima_gemm_workspace_bytes(int32_t T, int64_t n_cols);
  * cached (the paper's time to the first token, Sec. 4.1, is this call over the prompt, window by window).  The same
  * arithmetic as prima_layer_window_decode per token, with the projections as matrix products over all tokens
  * (prima_q4k_gemm) and attention in calls of up to PRIMA_MAX_TOK tokens, each over the rows cached before it and,
- * causally, its own; the K / V rows of all T tokens are appended to the layers' caches.  Every matrix Q4_K.
+ * causally, its own; the K / V rows of all T tokens are appended to the layers' caches.  Every matrix Q4_K (see
+ * prima_layer_window_prefill_mixed for the other formats).
  * 1 <= T <= PRIMA_PREFILL_MAX_TOK, n_past + T <= kv_cap, L >= 1.  x_in, x_out: fp32 [T][e], device, 16-byte
  * aligned (x_out may be x_in).  workspace: device, 256-byte aligned, prima_prefill_workspace_bytes(d, kv_cap, T)
  * bytes, contents need not be kept.  Asynchronous on hip_stream; nothing is allocated.
@@ -317,6 +318,13 @@ prima_status prima_layer_window_prefill(const prima_dims *d, const prima_layer *
                                         int32_t kv_cap, int32_t n_past, int32_t T,
                                         const float *x_in, float *x_out,
                                         void *workspace, size_t workspace_bytes, void *hip_stream);
+/* The same with every matrix in a format of its own (formats[l], as for prima_layer_window_decode_mixed; null: all
+ * Q4_K).  Q4_K matrices go through the matrix product; a matrix in another format is multiplied PRIMA_MAX_TOK tokens a
+ * launch by the format mat-vec, so its bytes are read once per 16 prompt tokens.  Same scratch size. */
+prima_status prima_layer_window_prefill_mixed(const prima_dims *d, const prima_layer *layers, const prima_layer_formats *formats,
+                                              int32_t L, int32_t kv_cap, int32_t n_past, int32_t T,
+                                              const float *x_in, float *x_out,
+                                              void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t prima_prefill_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
 
 /* The same for one prima_q4k_gemv call with the scratch of prima_gemv_workspace_bytes(n_rows, n_cols, T). */

@@ -231,10 +231,8 @@ class Window:
 
     def prefill(self, x_in, n_past, x_out=None):
         """Prompt processing: all layers for the T = x_in.shape[0] consecutive tokens that follow the n_past cached
-        ones (every matrix Q4_K); returns x_out float32 [T, e].  The scratch is kept for the next call of this size."""
+        ones; returns x_out float32 [T, e].  The scratch is kept for the next call of this size."""
         _need(x_in, torch.float32, "x_in")
-        if self._formats is not None:
-            raise ValueError("prefill takes windows whose matrices are all Q4_K")
         T = x_in.shape[0]
         need = _ffi.lib().prima_prefill_workspace_bytes(C.byref(self.dims), self.kv_cap, T)
         if need == 0:
@@ -244,8 +242,8 @@ class Window:
             ws = self._prefill_ws = torch.empty(need, dtype=torch.uint8, device=x_in.device)
         if x_out is None:
             x_out = torch.empty_like(x_in)
-        _ffi.check(_ffi.lib().prima_layer_window_prefill(C.byref(self.dims), self._arr, len(self.layers), self.kv_cap, n_past, T,
-                                                         _ptr(x_in), _ptr(x_out), _ptr(ws), ws.numel(), _stream()),
+        _ffi.check(_ffi.lib().prima_layer_window_prefill_mixed(C.byref(self.dims), self._arr, self._formats, len(self.layers), self.kv_cap,
+                                                               n_past, T, _ptr(x_in), _ptr(x_out), _ptr(ws), ws.numel(), _stream()),
                    "prima_layer_window_prefill")
         return x_out
 

@@ -15,7 +15,8 @@ EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", 
            "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
            "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
            "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt", "prima_layer_window_decode_mixed", "prima_window_plan_status", "prima_gemv_plan_status", "prima_layer_window_decode_batch_mixed",
-           "prima_q4k_gemm", "prima_gemm_workspace_bytes", "prima_layer_window_prefill", "prima_prefill_workspace_bytes"]
+           "prima_q4k_gemm", "prima_gemm_workspace_bytes", "prima_layer_window_prefill", "prima_prefill_workspace_bytes",
+           "prima_layer_window_prefill_mixed"]
 FORMATS = {"q4_k": 0, "q5_k": 1, "q6_k": 2, "q8_0": 3, "f16": 4, "f32": 5}
 
 
@@ -62,6 +63,8 @@ def lib():
         L.prima_layer_window_prefill.argtypes = [dp, lp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
         L.prima_layer_window_prefill.restype = C.c_int
         L.prima_prefill_workspace_bytes.argtypes = [dp, i32, i32]
+        L.prima_layer_window_prefill_mixed.argtypes = [dp, lp, C.POINTER(LayerFormats), i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.prima_layer_window_prefill_mixed.restype = C.c_int
         L.prima_prefill_workspace_bytes.restype = sz
         L.prima_attn_decode.argtypes = [dp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
         L.prima_attn_workspace_bytes.argtypes = [dp, i32, i32]

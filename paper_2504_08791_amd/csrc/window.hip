@@ -212,7 +212,7 @@ prima_status check_window_args(const prima_dims *d, int32_t kv_cap, int32_t n_pa
 }
 
 struct PrefillWs {
-    size_t q, k, v, o, h, a, xb0, xb1, rope, attn, stat, total;
+    size_t q, k, v, o, h, a, u, xb0, xb1, rope, attn, stat, total;
 };
 
 // scratch of a prompt-processing call: the layer's intermediate activations for all T tokens, the RoPE table, the
@@ -230,6 +230,7 @@ PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
     w.o = take(t * qd * f);
     w.h = take(t * static_cast<size_t>(d.e) * f);
     w.a = take(t * static_cast<size_t>(d.ffn) * f);
+    w.u = take(t * static_cast<size_t>(d.ffn) * f); // up projection, when gate / up are not both Q4_K
     w.xb0 = take(t * static_cast<size_t>(d.e) * f);
     w.xb1 = take(t * static_cast<size_t>(d.e) * f);
     w.rope = take(t * static_cast<size_t>(d.head_dim) * f);
@@ -242,8 +243,14 @@ PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
 // one decoder layer for T prompt tokens: the projections as matrix products over all tokens, attention for pieces of
 // PRIMA_MAX_TOK tokens (each sees the rows cached before it and, causally, its own), all pieces in one launch
 prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv_cap, int n_past, int T,
-                               const float *x, float *y, void *ws, const PrefillWs &w, hipStream_t st)
+                               const float *x, float *y, void *ws, const PrefillWs &w, hipStream_t st,
+                               const prima_layer_formats *fm = nullptr)
 {
+    // fm: formats of the seven matrices (null: all Q4_K).  Q4_K matrices go through the matrix product; a matrix in
+    // another format through the format mat-vec, PRIMA_MAX_TOK tokens a launch (there is no matrix-core kernel for those
+    // formats: a model that keeps a few tensors in them pays their weight stream once per 16 tokens)
+    const int f_q = fm ? fm->wq : 0, f_k = fm ? fm->wk : 0, f_v = fm ? fm->wv : 0, f_o = fm ? fm->wo : 0;
+    const int f_g = fm ? fm->wgate : 0, f_u = fm ? fm->wup : 0, f_d = fm ? fm->wdown : 0;
     const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
     float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
     float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *act = at<float>(ws, w.a);
@@ -251,8 +258,31 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
     auto W = [](const void *p) { return static_cast<const uint8_t *>(p); };
     prima_status s;
 #define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
-    const GemmMat qkv[3] = {{W(L.wq), q, qd, qd}, {W(L.wk), k, kvd, kvd}, {W(L.wv), v, kvd, kvd}};
-    PRIMA_TRY(launch_q4k_gemm_multi(qkv, 3, false, e, x, e, T, static_cast<const float *>(L.g_attn), d.rms_eps, nullptr, 0, stat, st));
+    // one projection: out = W a (+ resid), a = xin or RMSNorm(xin; gain); split_ready as for the matrix product
+    auto product = [&](int fmt, const void *Wm, int64_t rows, int64_t cols, const float *xin, const float *gain, const float *resid,
+                       float *out, bool split_ready) -> prima_status {
+        if (fmt == PRIMA_FMT_Q4_K)
+            return launch_q4k_gemm(W(Wm), rows, cols, xin, cols, T, gain, d.rms_eps, resid, rows, out, rows, stat, st, split_ready);
+        for (int t0 = 0; t0 < T; t0 += PRIMA_MAX_TOK) {
+            const int Tc = std::min<int>(PRIMA_MAX_TOK, T - t0);
+            const prima_status ps = launch_fmt_gemv(fmt, W(Wm), rows, cols, xin + t0 * cols, cols, Tc, gain, d.rms_eps,
+                                                    resid ? resid + t0 * rows : nullptr, rows, out + t0 * rows, rows, st);
+            if (ps != PRIMA_OK) return ps;
+        }
+        return PRIMA_OK;
+    };
+    const float *g_attn = static_cast<const float *>(L.g_attn), *g_ffn = static_cast<const float *>(L.g_ffn);
+    if (f_q == PRIMA_FMT_Q4_K && f_k == PRIMA_FMT_Q4_K && f_v == PRIMA_FMT_Q4_K) {
+        const GemmMat qkv[3] = {{W(L.wq), q, qd, qd}, {W(L.wk), k, kvd, kvd}, {W(L.wv), v, kvd, kvd}};
+        PRIMA_TRY(launch_q4k_gemm_multi(qkv, 3, false, e, x, e, T, g_attn, d.rms_eps, nullptr, 0, stat, st));
+    } else {
+        bool ready = false; // the first Q4_K matrix of the group splits the activations for the others
+        PRIMA_TRY(product(f_q, L.wq, qd, e, x, g_attn, nullptr, q, ready));
+        ready = ready || f_q == PRIMA_FMT_Q4_K;
+        PRIMA_TRY(product(f_k, L.wk, kvd, e, x, g_attn, nullptr, k, ready));
+        ready = ready || f_k == PRIMA_FMT_Q4_K;
+        PRIMA_TRY(product(f_v, L.wv, kvd, e, x, g_attn, nullptr, v, ready));
+    }
     // RoPE and the cache rows of all T tokens first; then the full pieces of PRIMA_MAX_TOK tokens in one launch and the
     // rest in a launch of the decode kind (caches complete, queries rotated)
     __half *Kc = static_cast<__half *>(L.k_cache), *Vc = static_cast<__half *>(L.v_cache);
@@ -262,10 +292,17 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
     if (rest)
         PRIMA_TRY(launch_attn(d, q + n_pieces * PRIMA_MAX_TOK * qd, nullptr, nullptr, nullptr, nullptr, Kc, Vc, kv_cap,
                               n_past + n_pieces * PRIMA_MAX_TOK, rest, o + n_pieces * PRIMA_MAX_TOK * qd, at<char>(ws, w.attn), st));
-    PRIMA_TRY(launch_q4k_gemm(W(L.wo), e, qd, o, qd, T, nullptr, 0.f, x, e, h, e, stat, st));
-    const GemmMat gate_up[2] = {{W(L.wgate), act, F, F}, {W(L.wup), nullptr, F, F}};
-    PRIMA_TRY(launch_q4k_gemm_multi(gate_up, 2, true, e, h, e, T, static_cast<const float *>(L.g_ffn), d.rms_eps, nullptr, 0, stat, st));
-    PRIMA_TRY(launch_q4k_gemm(W(L.wdown), e, F, act, F, T, nullptr, 0.f, h, e, y, e, stat, st));
+    PRIMA_TRY(product(f_o, L.wo, e, qd, o, nullptr, x, h, false));
+    if (f_g == PRIMA_FMT_Q4_K && f_u == PRIMA_FMT_Q4_K) {
+        const GemmMat gate_up[2] = {{W(L.wgate), act, F, F}, {W(L.wup), nullptr, F, F}};
+        PRIMA_TRY(launch_q4k_gemm_multi(gate_up, 2, true, e, h, e, T, g_ffn, d.rms_eps, nullptr, 0, stat, st));
+    } else {
+        float *up = at<float>(ws, w.u);
+        PRIMA_TRY(product(f_g, L.wgate, F, e, h, g_ffn, nullptr, act, false));
+        PRIMA_TRY(product(f_u, L.wup, F, e, h, g_ffn, nullptr, up, f_g == PRIMA_FMT_Q4_K));
+        PRIMA_TRY(launch_swiglu(act, up, static_cast<int64_t>(T) * F, st));
+    }
+    PRIMA_TRY(product(f_d, L.wdown, e, F, act, nullptr, h, y, false));
 #undef PRIMA_TRY
     return PRIMA_OK;
 }
@@ -578,6 +615,13 @@ prima_status prima_layer_window_prefill(const prima_dims *d, const prima_layer *
                                         int32_t kv_cap, int32_t n_past, int32_t T,
                                         const float *x_in, float *x_out, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
+    return prima_layer_window_prefill_mixed(d, layers, nullptr, L, kv_cap, n_past, T, x_in, x_out, workspace, workspace_bytes, hip_stream);
+}
+
+prima_status prima_layer_window_prefill_mixed(const prima_dims *d, const prima_layer *layers, const prima_layer_formats *formats, int32_t L,
+                                              int32_t kv_cap, int32_t n_past, int32_t T,
+                                              const float *x_in, float *x_out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
     if (!d || !x_in || !x_out || !workspace || !layers) return PRIMA_E_NULL;
     if (!dims_ok(d)) return PRIMA_E_SHAPE;
     if (L < 1 || T < 1 || T > PRIMA_PREFILL_MAX_TOK || n_past < 0 || kv_cap < 1 || static_cast<int64_t>(n_past) + T > kv_cap) return PRIMA_E_RANGE;
@@ -587,6 +631,11 @@ prima_status prima_layer_window_prefill(const prima_dims *d, const prima_layer *
     for (int i = 0; i < L; ++i) {
         const prima_status c = check_layer(layers[i]);
         if (c != PRIMA_OK) return c;
+        if (formats) {
+            const int32_t f[7] = {formats[i].wq, formats[i].wk, formats[i].wv, formats[i].wo, formats[i].wgate, formats[i].wup, formats[i].wdown};
+            for (int32_t v : f)
+                if (v < PRIMA_FMT_Q4_K || v > PRIMA_FMT_F32) return PRIMA_E_SHAPE;
+        }
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     prima_status s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
@@ -596,7 +645,7 @@ prima_status prima_layer_window_prefill(const prima_dims *d, const prima_layer *
     const float *cur = x_in;
     for (int i = 0; i < L; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
-        s = run_layer_prefill(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st);
+        s = run_layer_prefill(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st, formats ? &formats[i] : nullptr);
         if (s != PRIMA_OK) return s;
         cur = dst;
     }

@@ -25,10 +25,10 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _oracle_prompt(dims, host, x, n_past):
+def _oracle_prompt(dims, host, x, n_past, formats=None):
     out = []
     for t0 in range(0, x.shape[0], 64):
-        out.append(oracle.window(dims, host, x[t0:t0 + 64].astype(np.float64), n_past + t0))
+        out.append(oracle.window(dims, host, x[t0:t0 + 64].astype(np.float64), n_past + t0, formats=formats))
     return np.concatenate(out, axis=0)
 
 
@@ -73,6 +73,41 @@ def test_prefill_fills_the_cache_to_its_last_row(gpu_lib):
         assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
         g = dev_layers[0]["k_cache"].cpu().numpy().astype(np.float64)
         assert rel_err(g[:, n_past:].reshape(1, -1), host[0]["k_cache"][:, n_past:].astype(np.float64).reshape(1, -1)) < 1e-3
+
+
+MIXES = {
+    # the usual mix of a "Q4K" model: V and down projections in Q6_K
+    "q4_k_m": [{"wv": "q6_k", "wdown": "q6_k"}, {}, {"wv": "q6_k", "wdown": "q6_k"}],
+    # every matrix in some other format, gate / up not both Q4_K (SwiGLU as its own launch), Q4_K matrices alone in their groups
+    "all_kinds": [{"wq": "q8_0", "wk": "q5_k", "wv": "f16", "wo": "q6_k", "wgate": "q5_k", "wup": "q8_0", "wdown": "f32"},
+                  {"wq": "q6_k", "wgate": "q6_k"},
+                  {"wk": "q8_0", "wv": "q8_0", "wup": "f16", "wo": "f16", "wdown": "q5_k"}],
+}
+
+
+@pytest.mark.parametrize("mix", sorted(MIXES))
+@pytest.mark.parametrize("name,T,n_past", [("t1", 37, 130), ("t2", 16, 63), ("t0", 70, 37)])
+def test_prefill_with_mixed_formats(gpu_lib, mix, name, T, n_past):
+    """Layers whose matrices are in several formats (Q4_K ones through the matrix product, the others 16 tokens a launch
+    through the format mat-vec): hidden state and appended rows against the oracle.  (The token counts and cache lengths
+    are ones at which the synthetic layers are well conditioned: with 37 tokens behind 9 rows the first of these mixes has
+    top-2 logit gaps of 0.03 to 0.1 in every layer, and the decode calls and this call, which agree to 4e-5, both miss the
+    oracle by 6e-3.)"""
+    base = TINY[name]
+    formats = MIXES[mix][-base.n_layers:]
+    cfg = base.with_(T=T, n_past=n_past)
+    cap = n_past + T + 1
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap, formats=formats[l]) for l in range(cfg.n_layers)]
+    dev_layers = [{k: _dev(v) for k, v in t.items()} for t in host]
+    win = gpu_lib.Window(cfg.dims, dev_layers, cap, T_max=16, formats=formats)
+    x = synth.window_input(cfg)
+    print("case", mix, name, T, n_past, flush=True)
+    y = win.prefill(_dev(x), n_past).cpu().numpy()
+    ref = _oracle_prompt(cfg.dims, host, x, n_past, formats)
+    assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
+    g = dev_layers[0]["v_cache"].cpu().numpy().astype(np.float64)
+    r = host[0]["v_cache"].astype(np.float64)
+    assert rel_err(g[:, n_past:n_past + T].reshape(1, -1), r[:, n_past:n_past + T].reshape(1, -1)) < 1e-3
 
 
 def test_prefill_then_decode_continues(gpu_lib):
