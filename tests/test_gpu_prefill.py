@@ -157,6 +157,34 @@ def test_prefill_model_shape_one_layer(gpu_lib):
     assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
 
 
+def test_prefill_at_the_largest_token_count(gpu_lib):
+    """8192 prompt tokens (the call's limit) through one 8B-shaped layer, filling the cache to its last row.  The oracle
+    would take hours; checked instead: the first 8176 tokens' outputs are, bit for bit, those of a call with only them
+    (no result depends on how many tokens a call has), the last 16 agree with a decode call behind that shorter prompt,
+    and the last appended cache rows are the same."""
+    cfg = CONFIGS["c0"].with_(T=8192, n_past=0, n_layers=1)
+    cap = 8192
+    host = [synth.layer_tensors(cfg, 0, kv_cap=cap)]
+    x = _dev(synth.window_input(cfg))
+    wa, la = _window(gpu_lib, cfg, cap, host)
+    wb, lb = _window(gpu_lib, cfg, cap, host)
+    print("case c0 one layer, 8192 tokens", flush=True)
+    ya = wa.prefill(x, 0)
+    yb = wb.prefill(x[:8176].contiguous(), 0)
+    yc = wb.decode(x[8176:].contiguous(), 8176)
+    assert torch.isfinite(ya).all()
+    assert torch.equal(ya[:8176], yb)
+    # (a K or V element that rounds to the other fp16 neighbour in one of the two paths moves that token by up to ~1e-3;
+    # the others agree to 1e-6)
+    per_token = [rel_err(ya[8176 + t].cpu().numpy(), yc[t].cpu().numpy().astype(np.float64)) for t in range(16)]
+    assert max(per_token) < HID_TOL and float(np.median(per_token)) < 1e-5, per_token
+    for key in ("k_cache", "v_cache"):
+        a = la[0][key][:, 8176:].float().cpu().numpy().reshape(1, -1)
+        b = lb[0][key][:, 8176:].float().cpu().numpy().astype(np.float64).reshape(1, -1)
+        assert rel_err(a, b) < 1e-3
+        assert torch.equal(la[0][key][:, :8176], lb[0][key][:, :8176])
+
+
 def test_prefill_argument_errors(gpu_lib):
     from paper_2504_08791_amd import _ffi
     import ctypes as C
