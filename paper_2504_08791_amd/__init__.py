@@ -178,6 +178,11 @@ def set_fused_window(enabled):
     _ffi.lib().prima_set_fused_window(1 if enabled else 0)
 
 
+def set_prefill_small_tokens(n):
+    """Prompts of up to n tokens go through the decode kernels inside Window.prefill (default 128; 0: always the matrix product)."""
+    _ffi.lib().prima_set_prefill_small_tokens(int(n))
+
+
 class Window:
     """A window of decoder layers resident in HBM: keeps the tensors alive, the descriptor array
     and a workspace, so that a step is a single C call."""

@@ -106,6 +106,10 @@ void layer_gemv_args(const prima_dims &d, const prima_layer &L, int T, const flo
 // per barrier for the slowest one, which the three prefetched ring stages (~5 us of traffic) do not cover.
 bool g_fused_enabled = false;
 
+// prompts of up to this many tokens go through the decode kernels, PRIMA_MAX_TOK tokens a call (measured on config 3's shape,
+// ms per layer, matrix-product route / decode route: 17 tokens 2.01 / 0.48, 64: 2.08 / 1.46, 128: 3.15 / 2.92, 192: 3.15 / 4.39)
+int g_prefill_small_tokens = 128;
+
 // one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Five launches: Q/K/V projections
 // (RMSNorm fused), attention (RoPE + KV append fused, key ranges merged by the last arriver), output projection
 // (+ residual), gate/up projections (RMSNorm fused in front, SwiGLU behind), down projection (+ residual).
@@ -213,6 +217,8 @@ prima_status check_window_args(const prima_dims *d, int32_t kv_cap, int32_t n_pa
 
 struct PrefillWs {
     size_t q, k, v, o, h, a, u, xb0, xb1, rope, attn, stat, total;
+    size_t dec_base; // short prompts: the scratch of a decode call of PRIMA_MAX_TOK tokens, carved from here
+    WindowWs dec;
 };
 
 // scratch of a prompt-processing call: the layer's intermediate activations for all T tokens, the RoPE table, the
@@ -236,6 +242,8 @@ PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
     w.rope = take(t * static_cast<size_t>(d.head_dim) * f);
     w.attn = take(attn_ws_bytes(d, kv_cap, PRIMA_MAX_TOK));
     w.stat = take(gemm_ws_bytes(T, std::max<int64_t>({d.e, static_cast<int64_t>(qd), d.ffn})));
+    w.dec = carve(d, kv_cap, PRIMA_MAX_TOK);
+    w.dec_base = take(w.dec.total);
     w.total = off;
     return w;
 }
@@ -605,6 +613,8 @@ prima_status prima_layer_window_decode_batch_mixed(const prima_dims *d, const pr
 
 void prima_set_fused_window(int32_t enabled) { g_fused_enabled = enabled != 0; }
 
+void prima_set_prefill_small_tokens(int32_t n) { g_prefill_small_tokens = n < 0 ? 0 : n; }
+
 size_t prima_prefill_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
 {
     if (!d || !dims_ok(d) || T < 1 || T > PRIMA_PREFILL_MAX_TOK || kv_cap < 1) return 0;
@@ -638,6 +648,25 @@ prima_status prima_layer_window_prefill_mixed(const prima_dims *d, const prima_l
         }
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (T <= g_prefill_small_tokens) {
+        // a short prompt: the matrix product's workgroups would each walk all of K for a few tokens; the decode kernels,
+        // which stream the weights once per 8 tokens, are faster up to about 130 tokens
+        void *dws = at<char>(workspace, w.dec_base);
+        for (int t0 = 0; t0 < T; t0 += PRIMA_MAX_TOK) {
+            const int Tc = std::min<int>(PRIMA_MAX_TOK, T - t0);
+            prima_status cs = step_init(*d, dws, w.dec, Tc, n_past + t0, nullptr, false, st);
+            if (cs != PRIMA_OK) return cs;
+            const float *cur = x_in + static_cast<int64_t>(t0) * d->e;
+            for (int i = 0; i < L; ++i) {
+                float *dst = (i == L - 1) ? x_out + static_cast<int64_t>(t0) * d->e : at<float>(dws, (i & 1) ? w.dec.xb1 : w.dec.xb0);
+                cs = run_layer(*d, layers[i], kv_cap, n_past + t0, Tc, cur, dst, dws, w.dec, st, nullptr, nullptr, nullptr, nullptr, -1, nullptr,
+                               formats ? &formats[i] : nullptr);
+                if (cs != PRIMA_OK) return cs;
+                cur = dst;
+            }
+        }
+        return PRIMA_OK;
+    }
     prima_status s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
     if (s != PRIMA_OK) return s;
     s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, PRIMA_MAX_TOK), st);

@@ -32,13 +32,30 @@ def _oracle_prompt(dims, host, x, n_past, formats=None):
     return np.concatenate(out, axis=0)
 
 
+@pytest.fixture(params=["matrix product", "default"])
+def route(request, gpu_lib):
+    """The prompt call's two routes: always the matrix product (threshold 0), or the library's default, which advances
+    prompts of up to 128 tokens with the decode kernels."""
+    gpu_lib.set_prefill_small_tokens(0 if request.param == "matrix product" else 128)
+    yield request.param
+    gpu_lib.set_prefill_small_tokens(128)
+
+
+@pytest.fixture
+def matrix_product_route(gpu_lib):
+    gpu_lib.set_prefill_small_tokens(0)
+    yield
+    gpu_lib.set_prefill_small_tokens(128)
+
+
 def _window(gpu_lib, cfg, cap, host):
     dev_layers = [{k: _dev(v) for k, v in t.items()} for t in host]
     return gpu_lib.Window(cfg.dims, dev_layers, cap, T_max=16), dev_layers
 
 
-@pytest.mark.parametrize("name,T,n_past", [("t0", 50, 37), ("t1", 70, 0), ("t2", 33, 63), ("t0", 1, 5), ("t1", 16, 130)])
-def test_prefill_vs_oracle(gpu_lib, name, T, n_past):
+@pytest.mark.parametrize("name,T,n_past", [("t0", 50, 37), ("t1", 70, 0), ("t2", 33, 63), ("t0", 1, 5), ("t1", 16, 130), ("t0", 150, 37),
+                                           ("t2", 129, 63)])
+def test_prefill_vs_oracle(gpu_lib, route, name, T, n_past):
     cfg = TINY[name].with_(T=T, n_past=n_past)
     cap = n_past + T + 3
     host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
@@ -58,7 +75,7 @@ def test_prefill_vs_oracle(gpu_lib, name, T, n_past):
                 assert rel_err(g[:, n_past:n_past + T].reshape(1, -1), r[:, n_past:n_past + T].reshape(1, -1)) < 1e-3
 
 
-def test_prefill_fills_the_cache_to_its_last_row(gpu_lib):
+def test_prefill_fills_the_cache_to_its_last_row(gpu_lib, route):
     """n_past + T == kv_cap: the last piece ends on the cache's last row; a token count with full pieces only and one
     with a rest."""
     for T, n_past in [(32, 5), (45, 0)]:
@@ -87,7 +104,7 @@ MIXES = {
 
 @pytest.mark.parametrize("mix", sorted(MIXES))
 @pytest.mark.parametrize("name,T,n_past", [("t1", 37, 130), ("t2", 16, 63), ("t0", 70, 37)])
-def test_prefill_with_mixed_formats(gpu_lib, mix, name, T, n_past):
+def test_prefill_with_mixed_formats(gpu_lib, route, mix, name, T, n_past):
     """Layers whose matrices are in several formats (Q4_K ones through the matrix product, the others 16 tokens a launch
     through the format mat-vec): hidden state and appended rows against the oracle.  (The token counts and cache lengths
     are ones at which the synthetic layers are well conditioned: with 37 tokens behind 9 rows the first of these mixes has
@@ -110,7 +127,7 @@ def test_prefill_with_mixed_formats(gpu_lib, mix, name, T, n_past):
     assert rel_err(g[:, n_past:n_past + T].reshape(1, -1), r[:, n_past:n_past + T].reshape(1, -1)) < 1e-3
 
 
-def test_prefill_then_decode_continues(gpu_lib):
+def test_prefill_then_decode_continues(gpu_lib, route):
     """A prompt through the prefill call, the next token through the decode call: against the oracle doing the same."""
     cfg = TINY["t1"].with_(T=40, n_past=0)
     cap = 48
@@ -125,9 +142,10 @@ def test_prefill_then_decode_continues(gpu_lib):
     assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
 
 
-def test_prefill_agrees_with_decode_calls(gpu_lib):
+def test_prefill_agrees_with_decode_calls(gpu_lib, matrix_product_route):
     """The same prompt through decode calls of 16 tokens (integer-digit mat-vec) and through one prefill call
-    (binary16 matrix product): far inside the bar of each other, and prefill gives the same bits twice, in place too."""
+    (binary16 matrix product): far inside the bar of each other, and prefill gives the same bits twice, in place too.
+    On the default route a prompt this short is advanced by the decode kernels: the same bits as the decode calls."""
     cfg = TINY["t2"].with_(T=48, n_past=10)
     cap = 64
     x = synth.window_input(cfg)
@@ -142,9 +160,12 @@ def test_prefill_agrees_with_decode_calls(gpu_lib):
     xc = xd.clone()
     yc = wc.prefill(xc, 10, x_out=xc)
     assert torch.equal(yb, yc)
+    gpu_lib.set_prefill_small_tokens(128)
+    wd, _ = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
+    assert np.array_equal(wd.prefill(xd, 10).cpu().numpy(), ya)
 
 
-def test_prefill_model_shape_one_layer(gpu_lib):
+def test_prefill_model_shape_one_layer(gpu_lib, matrix_product_route):
     """One 70B-shaped layer (config 3's dimensions), 80 prompt tokens behind 4000 cached rows."""
     cfg = CONFIGS["c3"].with_(T=80, n_past=4000, n_layers=1)
     cap = 4096
