@@ -179,7 +179,7 @@ def set_fused_window(enabled):
 
 
 def set_prefill_small_tokens(n):
-    """Prompts of up to n tokens go through the decode kernels inside Window.prefill (default 128; 0: always the matrix product)."""
+    """Prompts of up to n tokens go through the decode kernels inside Window.prefill (default 96; 0: always the matrix product)."""
     _ffi.lib().prima_set_prefill_small_tokens(int(n))
 
 

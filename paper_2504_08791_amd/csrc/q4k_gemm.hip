@@ -45,6 +45,7 @@ constexpr int GM_TILE_BYTES = GM_SLABS * 1024;
 constexpr int GM_STAGE_BYTES = GM_HT * GM_TILE_BYTES;
 constexpr int GM_LDS_BYTES = 2 * GM_STAGE_BYTES; // one workgroup per compute unit
 constexpr int GM_XCDS = 8;
+constexpr int GM_CUS = 256;
 constexpr int GM_PATCH_R = 8, GM_PATCH_C = 4; // row blocks x token blocks that share an XCD at a time
 constexpr size_t GM_STAT_ALIGN = 1024;
 
@@ -67,6 +68,7 @@ struct GemmArgs {
     const float *resid; // null: none (added to every stored row; launches with a residual have one matrix)
     int64_t ldr;
     int T, n_tiles, n_rb, n_tb; // 16-token tiles, row blocks, token blocks
+    int tiles_wg;               // token tiles of a workgroup: GM_TT, or GM_HT (only its first half) when the grid would not fill the chip
 };
 
 // per token: 1/rms (RMSNorm in front) and the power of two that brings max |a| below 1024
@@ -198,7 +200,7 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
         const int64_t r = min<int64_t>(row0 + (a.pair ? 0 : 16 * rt) + n, my.n_rows - 1);
         wrow[rt] = (a.pair ? a.seg[rt].W : my.W) + r * nb * 144;
     }
-    const int tile0 = tb * GM_TT;
+    const int tile0 = tb * a.tiles_wg;
     const uint32_t lds0 = lds_address(smem);
 
     // this wave's share of the 68 slabs of a stage: the token tiles 4 half .. 4 half + 3 of super-block b, into buffer `half`
@@ -214,7 +216,7 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
             }
         }
     };
-    const bool second_half = tile0 + GM_HT < a.n_tiles; // whether the workgroup has tokens in its second half at all
+    const bool second_half = a.tiles_wg == GM_TT && tile0 + GM_HT < a.n_tiles; // whether the workgroup has a second half at all
     uint4 hdr[GM_RT];
     uint32_t qw[GM_RT][8];
 
@@ -325,8 +327,8 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
             for (int tt = 0; tt < GM_TT; ++tt)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int t = tb * GM_TM + tt * 16 + 4 * g + i;
-                    if (t < a.T) {
+                    const int t = (tile0 + tt) * 16 + 4 * g + i;
+                    if (tt < a.tiles_wg && t < a.T) {
                         const float sc = a.stat[t].y;
                         const float gt = yacc[tt][0][i] * sc, up = yacc[tt][1][i] * sc;
                         my.y[t * my.ldy + out_row] = gt / (1.0f + expf(-gt)) * up;
@@ -343,8 +345,8 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
         for (int tt = 0; tt < GM_TT; ++tt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int t = tb * GM_TM + tt * 16 + 4 * g + i;
-                if (t < a.T) {
+                const int t = (tile0 + tt) * 16 + 4 * g + i;
+                if (tt < a.tiles_wg && t < a.T) {
                     float v = yacc[tt][rt][i] * a.stat[t].y;
                     if (a.resid) v += a.resid[t * a.ldr + out_row];
                     my.y[t * my.ldy + out_row] = v;
@@ -380,7 +382,11 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
     }
     if (n_rb == 0) return PRIMA_OK;
     const int64_t nb = n_cols / QK;
-    const int n_tiles = (T + 15) / 16, n_tb = (T + GM_TM - 1) / GM_TM;
+    // 128 tokens per workgroup; 64 when the workgroups then still fit the compute units in one round (a workgroup with
+    // one half takes ~0.63 of the time of one with two; 8192 x 28672 at 512 tokens: 1138 -> 801 us)
+    const int n_tiles = (T + 15) / 16;
+    const int tiles_wg = n_rb * ((T + GM_TM / 2 - 1) / (GM_TM / 2)) <= GM_CUS ? GM_HT : GM_TT;
+    const int n_tb = (n_tiles + tiles_wg - 1) / tiles_wg;
     const int64_t rb_per_xcd = (n_rb + GM_XCDS - 1) / GM_XCDS;
     const int64_t grid = (rb_per_xcd + GM_PATCH_R - 1) / GM_PATCH_R * ((n_tb + GM_PATCH_C - 1) / GM_PATCH_C) * (GM_PATCH_R * GM_PATCH_C) * GM_XCDS;
     if (grid >= (int64_t{1} << 31) || n_tiles > 65535 || nb >= (int64_t{1} << 31)) return PRIMA_E_SHAPE;
@@ -399,7 +405,7 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
     }
     a.pair = pair ? 1 : 0;
     a.n_cols = n_cols; a.A = A; a.stat = stat; a.resid = resid; a.ldr = ldr;
-    a.T = T; a.n_tiles = n_tiles; a.n_rb = static_cast<int>(n_rb); a.n_tb = n_tb;
+    a.T = T; a.n_tiles = n_tiles; a.n_rb = static_cast<int>(n_rb); a.n_tb = n_tb; a.tiles_wg = tiles_wg;
     hipLaunchKernelGGL(q4k_gemm_kernel, dim3(static_cast<unsigned>(grid)), dim3(GM_THREADS), GM_LDS_BYTES, st, a);
     return last_launch_status();
 }

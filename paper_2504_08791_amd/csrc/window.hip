@@ -107,8 +107,9 @@ void layer_gemv_args(const prima_dims &d, const prima_layer &L, int T, const flo
 bool g_fused_enabled = false;
 
 // prompts of up to this many tokens go through the decode kernels, PRIMA_MAX_TOK tokens a call (measured on config 3's shape,
-// ms per layer, matrix-product route / decode route: 17 tokens 2.01 / 0.48, 64: 2.08 / 1.46, 128: 3.15 / 2.92, 192: 3.15 / 4.39)
-int g_prefill_small_tokens = 128;
+// ms per layer, matrix-product route / decode route: 48 tokens 2.04 / 1.09, 64: 2.06 / 1.46, 96: 2.50 / 2.19, 128: 2.54 / 2.92,
+// 192: 2.55 / 4.39)
+int g_prefill_small_tokens = 96;
 
 // one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Five launches: Q/K/V projections
 // (RMSNorm fused), attention (RoPE + KV append fused, key ranges merged by the last arriver), output projection
@@ -650,7 +651,7 @@ prima_status prima_layer_window_prefill_mixed(const prima_dims *d, const prima_l
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (T <= g_prefill_small_tokens) {
         // a short prompt: the matrix product's workgroups would each walk all of K for a few tokens; the decode kernels,
-        // which stream the weights once per 8 tokens, are faster up to about 130 tokens
+        // which stream the weights once per 8 tokens, are faster up to about 100 tokens
         void *dws = at<char>(workspace, w.dec_base);
         for (int t0 = 0; t0 < T; t0 += PRIMA_MAX_TOK) {
             const int Tc = std::min<int>(PRIMA_MAX_TOK, T - t0);
