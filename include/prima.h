@@ -306,12 +306,13 @@ size_t prima_gemm_workspace_bytes(int32_t T, int64_t n_cols);
  * Prompt processing: all L layers of the window for T consecutive tokens of one sequence that has n_past rows
  * cached (the paper's time to the first token, Sec. 4.1, is this call over the prompt, window by window).  The same
  * arithmetic as prima_layer_window_decode per token, with the projections as matrix products over all tokens
- * (prima_q4k_gemm) and attention in calls of up to PRIMA_MAX_TOK tokens, each over the rows cached before it and,
+ * (prima_q4k_gemm) and attention in pieces of PRIMA_MAX_TOK tokens, each over the rows cached before it and,
  * causally, its own; the K / V rows of all T tokens are appended to the layers' caches.  Every matrix Q4_K (see
  * prima_layer_window_prefill_mixed for the other formats).
  * 1 <= T <= PRIMA_PREFILL_MAX_TOK, n_past + T <= kv_cap, L >= 1.  x_in, x_out: fp32 [T][e], device, 16-byte
  * aligned (x_out may be x_in).  workspace: device, 256-byte aligned, prima_prefill_workspace_bytes(d, kv_cap, T)
- * bytes, contents need not be kept.  Asynchronous on hip_stream; nothing is allocated.
+ * bytes, contents need not be kept.  Asynchronous on hip_stream; nothing is allocated.  Errors as for the decode call
+ * (PRIMA_E_NULL, _SHAPE, _RANGE, _ALIGN, _WORKSPACE before anything is enqueued; PRIMA_E_DEVICE for a failed launch).
  */
 #define PRIMA_PREFILL_MAX_TOK 8192
 prima_status prima_layer_window_prefill(const prima_dims *d, const prima_layer *layers, int32_t L,
