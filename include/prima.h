@@ -211,12 +211,18 @@ size_t prima_lm_head_workspace_bytes(const prima_dims *d, int64_t vocab, int32_t
  * field sizes and value rules are the formats' own, the placement is this library's (version 1): every
  * field of a tensor is a plane of its own, planes follow one another without padding, blocks inside a
  * plane are in row-major order (row r, block b -> r * n_cols / block + b).  n = n_rows * n_cols / 256.
+ * The quant bits of Q5_K and Q6_K are placed word by word: a super-block's bits of one kind are consecutive
+ * 32-bit little-endian words, and weight t (0..255 inside its super-block) always sits in byte t%4 of its word
+ * (byte j of a word = the byte at offset 4*word + j of the super-block's share of the plane):
+ *     low 4 bits  (Q5_K, Q6_K): word t/8  (128 bytes per super-block); the low nibble of byte t%4 when t%8 < 4,
+ *                               the high nibble when t%8 >= 4;
+ *     bits 4..5   (Q6_K):       word t/16 (64 bytes); bits 2g and 2g+1 of byte t%4, g = (t%16)/4;
+ *     bit 4       (Q5_K):       word t/32 (32 bytes); bit g of byte t%4, g = (t%32)/4.
  *   Q5_K  [n][16]: d, dmin (binary16, little endian), then sixteen 6-bit fields sc_0..7, m_0..7 as a
- *         96-bit little-endian stream (bytes 0..15 of a Q4_K super-block) | [n][128]: bits 0..3 of
- *         weight t in byte t/2, low nibble when t is even | [n][32]: bit 4 of weight t = bit t%8 of byte
- *         t/8.   w = d sc_s q - dmin m_s, q in 0..31, s = t/32.
- *   Q6_K  [n][128]: bits 0..3 (as above) | [n][64]: bits 4..5 of weight t = bits 2(t%4), 2(t%4)+1 of byte
- *         t/4 | [n][16]: signed bytes sc_s, s = t/16 | [n]: d (binary16).   w = d sc_s (q - 32), q in 0..63.
+ *         96-bit little-endian stream (bytes 0..15 of a Q4_K super-block) | [n][128]: the low 4 bits |
+ *         [n][32]: bit 4.   q = low + 16 * bit4 in 0..31;  w = d sc_s q - dmin m_s, s = t/32.
+ *   Q6_K  [n][128]: the low 4 bits | [n][64]: bits 4..5 | [n][16]: signed bytes sc_s, s = t/16 |
+ *         [n]: d (binary16, little endian).   q = low + 16 * bits45 in 0..63;  w = d sc_s (q - 32).
  *   Q8_0  [n_rows*n_cols]: one signed byte per weight | [n_rows*n_cols/32]: d (binary16) per 32 weights.
  *         w = d q.
  *   F16, F32: row-major numbers.
