@@ -165,7 +165,9 @@ prima_status prima_window_check(const prima_dims *d, int32_t kv_cap, int32_t T,
  * once per layer (L different weight sets), bracketed by two HIP events on `hip_stream`, and
  * returns per kind the elapsed time of its L back-to-back launches.  SYNCHRONISES the stream before
  * returning and creates/destroys events (host-side allocation), so it is not for the serving
- * path.  x_out receives the ordinary step's result.  ms_by_kind and launches_by_kind are HOST
+ * path.  The replayed launches overwrite the step's new cache rows with other values, so the call
+ * ends with a second ordinary step: x_out and rows n_past .. n_past+T-1 of every cache are then
+ * bit-equal to what prima_layer_window_decode leaves.  ms_by_kind and launches_by_kind are HOST
  * arrays of PRIMA_N_KINDS entries (milliseconds for all launches of the kind; number of launches).
  */
 enum {

@@ -709,13 +709,17 @@ prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const WindowWs w = carve(*d, kv_cap, T);
     // one ordinary step first: every intermediate buffer then holds this step's values
-    s = step_init(*d, workspace, w, T, n_past, nullptr, false, st);
-    const float *cur = x_in;
-    for (int i = 0; i < L && s == PRIMA_OK; ++i) {
-        float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
-        s = run_layer(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr);
-        cur = dst;
-    }
+    auto ordinary_step = [&]() {
+        prima_status os = step_init(*d, workspace, w, T, n_past, nullptr, false, st);
+        const float *cur = x_in;
+        for (int i = 0; i < L && os == PRIMA_OK; ++i) {
+            float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
+            os = run_layer(*d, layers[i], kv_cap, n_past, T, cur, dst, workspace, w, st, nullptr, nullptr, nullptr, nullptr);
+            cur = dst;
+        }
+        return os;
+    };
+    s = ordinary_step();
     // then each kind of launch on its own, once per layer (L different weight sets, so nothing is
     // served from a cache that the real step would not have), between two events
     hipEvent_t ev[PRIMA_N_KINDS + 1];
@@ -735,6 +739,10 @@ prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima
             s = run_layer(*d, layers[i], kv_cap, n_past, T, x_in, scratch_out, workspace, w, st, nullptr, nullptr, nullptr, nullptr, kinds[ki]);
         if (s == PRIMA_OK && !mark()) s = PRIMA_E_DEVICE;
     }
+    // The replayed attention launches appended rows n_past .. n_past+T-1 of every layer's caches from whatever the
+    // replayed projections left in the scratch (each layer's projections of x_in, not of that layer's own input).
+    // The ordinary step once more writes the right rows again (and x_out): the same bits as a plain decode call.
+    if (s == PRIMA_OK) s = ordinary_step();
     if (s == PRIMA_OK && hipStreamSynchronize(st) != hipSuccess) s = PRIMA_E_DEVICE;
     for (int ki = 0; ki < n_kinds && s == PRIMA_OK; ++ki) {
         float ms = 0.f;

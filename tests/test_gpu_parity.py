@@ -364,6 +364,28 @@ def test_rerun_is_bit_identical(gpu_lib):
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("name", ["t0", "t1", "t2"])
+def test_profiled_step_leaves_what_a_plain_step_leaves(gpu_lib, name):
+    """The measurement hook replays each kind of launch on its own; afterwards x_out and every layer's caches
+    (the step's new rows included) must be bit-equal to those after prima_layer_window_decode, so that a caller
+    who advances n_past after it attends over the right rows."""
+    cfg = TINY[name]
+    cap = cfg.n_past + cfg.T + 2
+    host = [synth.layer_tensors(cfg, l, kv_cap=cap) for l in range(cfg.n_layers)]
+    wa, la = _window(gpu_lib, cfg, cap, host)
+    wb, lb = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
+    x = _dev(synth.window_input(cfg))
+    ya = wa.decode(x, cfg.n_past)
+    yb, kinds = wb.decode_profiled(x, cfg.n_past)
+    assert torch.equal(ya, yb)
+    assert kinds["gate_up"][1] == cfg.n_layers
+    for a, b in zip(la, lb):
+        assert torch.equal(a["k_cache"], b["k_cache"]) and torch.equal(a["v_cache"], b["v_cache"])
+    # the next step, which attends over the rows the profiled step appended
+    x2 = _dev(synth.normal_f32(cfg.config_id, 1, "x_in", (1, cfg.dims.e)))
+    assert torch.equal(wa.decode(x2, cfg.n_past + cfg.T), wb.decode(x2, cfg.n_past + cfg.T))
+
+
 def test_attention_random_shapes(gpu_lib):
     """Head counts (groups of 1 to 16 queries per KV head, not only powers of two), both head sizes, context
     lengths around the tile and key-range boundaries and token counts drawn at random."""
