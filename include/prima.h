@@ -81,6 +81,22 @@ prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols,
 size_t prima_gemv_workspace_bytes(int64_t n_rows, int64_t n_cols, int32_t T);
 
 /*
+ * prima_q4k_gemv for callers that cannot allocate or pass scratch: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same bits as prima_q4k_gemv, but
+ * the scratch (arrival counters and the partial sums of the slabs of K) is a fixed array of
+ * PRIMA_NOALLOC_SCRATCH_BYTES in the library's device image instead of a caller buffer; each GPU the library
+ * runs on holds its own copy until the process ends.  A shape whose scratch (prima_gemv_workspace_bytes) exceeds
+ * that size returns PRIMA_E_WORKSPACE and launches nothing.  The call allocates and frees nothing (the array's
+ * device address is looked up once per device, on the first call made with that device current).  Every call on
+ * a GPU shares that GPU's array: the counters are cleared by a small fill kernel at the start of each call, and
+ * calls that overlap on one GPU (two streams, two threads) race; calls on one stream are safe.
+ */
+#define PRIMA_NOALLOC_SCRATCH_BYTES (4u << 20)
+prima_status prima_q4k_gemv_noalloc(const void *W, int64_t n_rows, int64_t n_cols,
+                                    const float *x, int64_t ldx, int32_t T,
+                                    float *y, int64_t ldy, void *hip_stream);
+
+/*
  * Measurement hook: reads `bytes` (rounded down to 16) of device memory at `src` once, linearly, with
  * 128-bit loads from about 8 workgroups per compute unit, and discards them; `sink` is 4 bytes of device
  * memory that is (practically never) written.  Timed by the caller it states what a plain read of HBM

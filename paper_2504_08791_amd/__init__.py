@@ -66,6 +66,18 @@ def q4k_gemv(W, x, y=None, workspace=None):
     return y
 
 
+def q4k_gemv_noalloc(W, x, y):
+    """q4k_gemv with the library's fixed scratch (no workspace argument, nothing allocated): y must be given."""
+    _need(W, torch.uint8, "W")
+    _need(x, torch.float32, "x")
+    if not (y.is_cuda and y.dtype == torch.float32 and y.dim() == 2 and y.stride(1) == 1):
+        raise TypeError("y: need a 2-d CUDA float32 tensor with contiguous rows")
+    rows, cols = W.shape[0], W.shape[1] * 256
+    _ffi.check(_ffi.lib().prima_q4k_gemv_noalloc(_ptr(W), rows, cols, _ptr(x), x.stride(0), x.shape[0], _ptr(y), y.stride(0),
+                                                 _stream()), "prima_q4k_gemv_noalloc")
+    return y
+
+
 def q4k_gemm(W, x, gain=None, eps=0.0, resid=None, y=None, workspace=None):
     """Many tokens: y[t, r] = sum_c W[r, c] a[t, c] (+ resid[t, r]), a = x or RMSNorm(x; gain, eps).
     W uint8 [rows, cols/256, 144], x float32 [T, cols] (rows may be strided)."""

@@ -6,6 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libprima_hip.so")
 
 MAX_TOK = 16
+NOALLOC_SCRATCH_BYTES = 4 << 20
 KINDS = ("qkv", "rope_kv", "attn", "wo", "gate_up", "down")
 STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIGN", 4: "PRIMA_E_RANGE",
           5: "PRIMA_E_WORKSPACE", 6: "PRIMA_E_DEVICE"}
@@ -16,7 +17,7 @@ EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", 
            "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
            "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt", "prima_layer_window_decode_mixed", "prima_window_plan_status", "prima_gemv_plan_status", "prima_layer_window_decode_batch_mixed",
            "prima_q4k_gemm", "prima_gemm_workspace_bytes", "prima_layer_window_prefill", "prima_prefill_workspace_bytes",
-           "prima_layer_window_prefill_mixed", "prima_set_prefill_small_tokens"]
+           "prima_layer_window_prefill_mixed", "prima_set_prefill_small_tokens", "prima_q4k_gemv_noalloc"]
 FORMATS = {"q4_k": 0, "q5_k": 1, "q6_k": 2, "q8_0": 3, "f16": 4, "f32": 5}
 
 
@@ -53,6 +54,8 @@ def lib():
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         dp, lp = C.POINTER(Dims), C.POINTER(Layer)
         L.prima_q4k_gemv.argtypes = [vp, i64, i64, vp, i64, i32, vp, i64, vp, sz, vp]
+        L.prima_q4k_gemv_noalloc.argtypes = [vp, i64, i64, vp, i64, i32, vp, i64, vp]
+        L.prima_q4k_gemv_noalloc.restype = C.c_int
         L.prima_gemv_workspace_bytes.argtypes = [i64, i64, i32]
         L.prima_gemv_workspace_bytes.restype = sz
         L.prima_q4k_dequant.argtypes = [vp, i64, i64, vp, vp]

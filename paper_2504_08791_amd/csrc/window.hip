@@ -2,6 +2,7 @@
 // launch sequence of a layer window (arXiv 2504.08791, Sec. 3.1: a device advances its window
 // of consecutive layers and hands e FP32 values per token to its successor).
 #include <algorithm>
+#include <mutex>
 
 #include "attn_common.h"
 
@@ -375,6 +376,57 @@ prima_status prima_q4k_gemv(const void *W, int64_t n_rows, int64_t n_cols, const
     prima_status s = launch_zero_arrivals(workspace, gemv_arrivals_bytes(n_rows), st);
     if (s != PRIMA_OK) return s;
     return launch_gemv_mfma(ga, workspace, workspace_bytes, gemv_arrivals_bytes(n_rows), st);
+}
+
+} // extern "C"
+
+// Scratch of prima_q4k_gemv_noalloc: part of the device image, one copy per GPU.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels and fills get the device address looked up below.
+static __device__ __align__(256) unsigned char scratch[PRIMA_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[NOALLOC_MAX_DEVICES]; // device address of `scratch` on each GPU, null until looked up
+
+// the current device's copy of the array (looked up once per device, with that device current)
+prima_status noalloc_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES) return PRIMA_E_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PRIMA_E_DEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PRIMA_OK;
+}
+} // namespace
+
+extern "C" {
+
+prima_status prima_q4k_gemv_noalloc(const void *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int32_t T,
+                                    float *y, int64_t ldy, void *hip_stream)
+{
+    if (!W || !x || !y) return PRIMA_E_NULL;
+    if (n_rows < 0 || n_cols <= 0 || n_cols % QK || ldx < n_cols || ldy < n_rows) return PRIMA_E_SHAPE;
+    if (T < 1 || T > PRIMA_MAX_TOK) return PRIMA_E_RANGE;
+    if (!aligned(W, 16) || !aligned(x, 16) || !aligned(y, 4) || ldx % 4) return PRIMA_E_ALIGN;
+    const size_t need = std::max<size_t>(256, gemv_ws_bytes(n_rows, n_cols, T));
+    if (need > PRIMA_NOALLOC_SCRATCH_BYTES) return PRIMA_E_WORKSPACE; // beyond the fixed array: use prima_q4k_gemv
+    if (n_rows == 0) return PRIMA_OK;
+    void *ws = nullptr;
+    prima_status s = noalloc_scratch(&ws);
+    if (s != PRIMA_OK) return s;
+    GemvArgs ga = gemv_args(1, n_cols, x, ldx, T);
+    ga.seg[0] = seg(W, y, n_rows, ldy);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // the array keeps what the last call left: the counters are cleared by a fill kernel (not a memset node)
+    s = launch_zero_arrivals(ws, gemv_arrivals_bytes(n_rows), st);
+    if (s != PRIMA_OK) return s;
+    return launch_gemv_mfma(ga, ws, PRIMA_NOALLOC_SCRATCH_BYTES, gemv_arrivals_bytes(n_rows), st);
 }
 
 size_t prima_gemm_workspace_bytes(int32_t T, int64_t n_cols) { return (T < 1 || n_cols <= 0 || n_cols % QK) ? 0 : gemm_ws_bytes(T, n_cols); }

@@ -53,6 +53,21 @@ def test_gemv_argument_errors():
     assert f(wsb=0) == 5
 
 
+def test_noalloc_gemv_argument_errors():
+    """The variant with the library's fixed scratch: every refusal comes before any device call."""
+    L = _ffi.lib()
+    f = lambda W=FAKE, rows=8, cols=512, x=FAKE, ldx=512, T=1, y=FAKE, ldy=8: \
+        L.prima_q4k_gemv_noalloc(W, rows, cols, x, ldx, T, y, ldy, None)
+    assert f(W=None) == 1 and f(x=None) == 1 and f(y=None) == 1
+    assert f(cols=300) == 2 and f(ldx=256) == 2 and f(ldy=4) == 2
+    assert f(T=0) == 4 and f(T=17) == 4
+    assert f(W=FAKE + 8) == 3 and f(x=FAKE + 4) == 3 and f(ldx=514) == 3
+    # a shape whose scratch exceeds the fixed array (the output layer at 8 tokens) is refused, nothing is launched
+    assert L.prima_gemv_workspace_bytes(128256, 8192, 8) > _ffi.NOALLOC_SCRATCH_BYTES
+    assert f(rows=128256, cols=8192, ldx=8192, T=8, ldy=128256) == 5
+    assert f(rows=0) == 0
+
+
 def test_dequant_argument_errors():
     L = _ffi.lib()
     assert L.prima_q4k_dequant(None, 1, 256, FAKE, None) == 1
