@@ -281,3 +281,160 @@ def half_to_double(bits):
 
 def float_to_half(f):
     return lib().orc_float_to_half(float(np.float32(f)))
+
+
+# ---------- conditioning of a case: how far the oracle's own output moves under perturbations of the size of one
+# fp32 rounding.  Any implementation that carries fp32 intermediates (the benchmark's boundary dtype, Sec. 3.1 /
+# App. A.3: FP32 hidden states) differs from this fp64 evaluation by at least such perturbations, so where they
+# move the fp64 result itself by more than the tolerance, the tolerance cannot be asked of that case.  Everything
+# here is computed from the oracle alone. ----------
+
+ONE_ULP = 2.0 ** -23  # relative spacing of fp32 numbers
+
+
+def rel_err(y, r):
+    """The parity metric: max_i |y_i - r_i| / max(|r_i|, rms(r), 1e-30) per token vector (row), worst row."""
+    y = np.atleast_2d(np.asarray(y, dtype=np.float64))
+    r = np.atleast_2d(np.asarray(r, dtype=np.float64))
+    y, r = y.reshape(y.shape[0], -1), r.reshape(r.shape[0], -1)
+    rms = np.sqrt((r ** 2).mean(axis=1, keepdims=True))
+    return float((np.abs(y - r) / np.maximum(np.abs(r), np.maximum(rms, 1e-30))).max())
+
+
+def conditioning(fn, x, signs, eps=ONE_ULP):
+    """max over the sign patterns s in `signs` (arrays of +-1 shaped like x) of rel_err(fn(x * (1 + eps * s)), fn(x)).
+    fn: float64 array -> float64 array; it must not keep state between calls."""
+    x = np.asarray(x, dtype=np.float64)
+    base = fn(x)
+    worst = 0.0
+    for s in signs:
+        s = np.asarray(s, dtype=np.float64)
+        assert s.shape == x.shape and np.all(np.abs(s) == 1.0)
+        worst = max(worst, rel_err(fn(x * (1.0 + eps * s)), base))
+    return worst
+
+
+def _fresh(layers):
+    """the layers with private copies of their caches (a window call appends to them)"""
+    out = []
+    for t in layers:
+        c = dict(t)
+        c["k_cache"], c["v_cache"] = t["k_cache"].copy(), t["v_cache"].copy()
+        out.append(c)
+    return out
+
+
+def window_long(dims, layers, x, n_past, formats=None, chunk=64):
+    """window() for any number of consecutive tokens: pieces of `chunk` tokens one after the other, each seeing
+    the rows the earlier ones appended (joint and sequential evaluation are the same function)."""
+    x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
+    return np.concatenate([window(dims, layers, x[t0:t0 + chunk], n_past + t0, formats=formats)
+                           for t0 in range(0, x.shape[0], chunk)], axis=0)
+
+
+def layer_stepwise(dims, t, x, n_past, formats=None, perturb=None):
+    """layer() evaluated step by step through the oracle's own operators (with perturb=None it returns exactly what
+    layer() returns: a CPU test holds the two together).  perturb(name, array): called on every intermediate that an
+    implementation with FP32 activations between its operators has to store (the projections' outputs q, k, v, the
+    rotated q and k, the attention output o, the hidden state h after the first residual, the SwiGLU output a, the
+    layer's output y); it returns the array to go on with."""
+    pt = perturb if perturb is not None else (lambda name, arr: arr)
+    fm = formats or {}
+    x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
+    T, e = x.shape
+    shapes = {"wq": (dims.qd, e), "wk": (dims.kvd, e), "wv": (dims.kvd, e), "wo": (e, dims.qd),
+              "wgate": (dims.ffn, e), "wup": (dims.ffn, e), "wdown": (e, dims.ffn)}
+
+    def product(name, act):
+        return fmt_gemv(fm.get(name, "q4_k"), t[name], shapes[name][0], shapes[name][1], act)
+
+    n1 = rmsnorm(x, t["g_attn"], dims.rms_eps)
+    q, k, v = pt("q", product("wq", n1)), pt("k", product("wk", n1)), pt("v", product("wv", n1))
+    for j in range(T):
+        q[j] = rope(q[j], dims.n_q_heads, dims.head_dim, n_past + j, dims.rope_theta, dims.rope_mode)
+        k[j] = rope(k[j], dims.n_kv_heads, dims.head_dim, n_past + j, dims.rope_theta, dims.rope_mode)
+    q, k = pt("q_rot", q), pt("k_rot", k)
+    kv_append(dims, k, v, t["k_cache"], t["v_cache"], n_past, T)
+    o = pt("o", attn_decode(dims, q, t["k_cache"], t["v_cache"], n_past, T).reshape(T, dims.qd))
+    h = pt("h", x + product("wo", o))
+    n2 = rmsnorm(h, t["g_ffn"], dims.rms_eps)
+    a = pt("a", swiglu(product("wgate", n2), product("wup", n2)))
+    return pt("y", h + product("wdown", a))
+
+
+def window_stepwise(dims, layers, x, n_past, formats=None, perturb=None, chunk=64):
+    """Consecutive layers (their caches are updated in place) for any number of consecutive tokens, `chunk` tokens
+    at a time, every layer through layer_stepwise()."""
+    x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
+    out = []
+    for t0 in range(0, x.shape[0], chunk):
+        hcur = x[t0:t0 + chunk]
+        for i, t in enumerate(layers):
+            hcur = layer_stepwise(dims, t, hcur, n_past + t0, formats=formats[i] if formats else None, perturb=perturb)
+        out.append(hcur)
+    return np.concatenate(out, axis=0)
+
+
+_APPENDED = ("k_rot", "v")  # the intermediates whose values are rounded to binary16 into the caches
+
+
+def _append_ties(arr, eps):
+    """Elements of `arr` (values about to be appended to an fp16 cache) that lie within eps |v| of the midpoint
+    between two neighbouring binary16 numbers, i.e. whose stored value a relative perturbation of eps can change.
+    Returns (mask, moved, closeness): moved = the array with those elements placed just beyond their midpoint (still
+    a perturbation of at most about eps), closeness = |v - midpoint| / |v| (inf where there is no such tie)."""
+    v = np.asarray(arr, dtype=np.float64)
+    h = v.astype(np.float32).astype(np.float16)  # where the append rounds it to (fp64 -> fp32 -> binary16)
+    hv = h.astype(np.float64)
+    toward = np.where(v >= hv, np.float16(np.inf), np.float16(-np.inf)).astype(np.float16)
+    other = np.nextafter(h, toward).astype(np.float64)  # the neighbour on v's side of hv
+    mid = 0.5 * (hv + other)
+    mag = np.maximum(np.abs(v), 1e-300)
+    close = np.abs(v - mid) / mag
+    mask = np.isfinite(other) & (close <= eps)
+    moved = np.where(mask, mid + np.sign(mid - hv) * eps * mag * 1.000001, v)
+    return mask, moved, np.where(mask, close, np.inf)
+
+
+def window_conditioning(dims, layers, x, n_past, formats=None, probes=4, singles=12, seed=0, eps=ONE_ULP):
+    """How far the oracle's own result for this window step moves when every FP32-stored intermediate (see
+    layer_stepwise) is perturbed by a relative eps: the largest rel_err against the unperturbed result over
+      - `probes` evaluations with v_i -> v_i (1 + eps s_i), random signs s_i (numpy's default generator seeded with
+        (seed, probe)): the smooth sensitivity;
+      - the evaluations in which appended K / V values within eps (and within eps / 2) of a binary16 rounding
+        boundary are all rounded the other way, and those in which one of the `singles` closest ones alone is:
+        the discontinuities that perturbations of that size reach (see _append_ties).
+    The layers' caches are not modified."""
+    x = np.ascontiguousarray(np.atleast_2d(x), dtype=np.float64)
+
+    def run(hook):
+        return window_stepwise(dims, _fresh(layers), x, n_past, formats=formats, perturb=hook)
+
+    found = []  # (closeness, site, flat index) of the ties of the unperturbed evaluation
+
+    def record(name, arr):
+        if name in _APPENDED:
+            record.site += 1
+            mask, _, close = _append_ties(arr, eps)
+            found.extend((float(close.flat[i]), record.site, int(i)) for i in np.flatnonzero(mask))
+        return arr
+    record.site = -1
+    base = run(record)
+    worst = 0.0
+    for p in range(probes):
+        rng = np.random.default_rng([int(seed), p])
+        worst = max(worst, rel_err(run(lambda name, arr: arr * (1.0 + eps * (rng.integers(0, 2, size=arr.shape) * 2.0 - 1.0))), base))
+    for e in (eps, 0.5 * eps):
+        worst = max(worst, rel_err(run(lambda name, arr: _append_ties(arr, e)[1] if name in _APPENDED else arr), base))
+    for _, site, idx in sorted(found)[:singles]:
+        def one(name, arr, state={"site": -1}):
+            if name not in _APPENDED:
+                return arr
+            state["site"] += 1
+            if state["site"] != site:
+                return arr
+            out = np.array(arr, dtype=np.float64, copy=True)
+            out.flat[idx] = _append_ties(arr, eps)[1].flat[idx]
+            return out
+        worst = max(worst, rel_err(run(one), base))
+    return worst
