@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--config", default="c3")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true", help="config 3 only: skip the short runs of configs 1, 2 and 4")
     ap.add_argument("--batch", type=int, default=0,
                     help="side measurement: B sequences of the config's context length, one token each per step")
     ap.add_argument("--format", default="", choices=["", "q5_k", "q6_k", "q8_0", "f16", "f32"],
@@ -75,14 +76,73 @@ def main():
         return bench_device_profile(args, cfg)
     if args.mix:
         return bench_mix(args, cfg)
-    d = cfg.dims
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    want_cpu = not args.no_cpu_baseline
+    if args.config == "c0":
+        return bench_c0(args, cfg)
+    main_run = run_window_config(args, cfg, args.steps, args.warmup, want_cpu, True, args.copy_calibration)
+    out = main_run["line"]
+    if args.config == "c3" and not args.layers and not args.no_other_configs:
+        # the other benchmark configurations, shorter: config 1 (12 layers), config 2 (16 layers, 4 tokens verified
+        # jointly) and config 4's shape at 20 of its 80 layers with the output layer, 8 tokens verified jointly
+        others = {}
+        for name, layers in (("c1", 0), ("c2", 0), ("c4k8", 20)):
+            ocfg = CONFIGS[name].with_(n_layers=layers) if layers else CONFIGS[name]
+            r = run_window_config(args, ocfg, 20, 5, False, False, False)["line"]
+            others[name] = {"workload": r["config"]["workload"], "tokens_per_step": ocfg.T, "ms_per_step": r["ms_per_step"],
+                            "median_ms_per_step": r["median_ms_per_step"], "tokens_per_s": r["value"],
+                            "window_hbm_gbps": r["window_hbm_gbps"], "window_hbm_frac": r["window_hbm_frac"],
+                            "per_launch_us": r["per_launch_us"], "gate_up_frac": r["roofline"]["frac"]}
+        out["other_configs"] = others
+    print(json.dumps(out), flush=True)
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def time_steps(step, stream, warmup, steps):
+    """W untimed steps, then K steps between two events (the mean) with an event after every step (the median); all on
+    `stream`, nothing waits in between."""
+    import torch
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record(stream)
+    for i in range(steps):
+        step()
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    each = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(steps))
+    median = each[steps // 2] if steps % 2 else 0.5 * (each[steps // 2 - 1] + each[steps // 2])
+    return evs[0].elapsed_time(evs[steps]) / steps, median, wall_ms / steps
+
+
+def run_window_config(args, cfg, steps, warmup, want_cpu, with_probe, copy_calibration):
+    """Builds the window of `cfg` in HBM (and walks the oracle over the same layers when asked), times it, measures
+    every kind of launch on its own, and returns the JSON line as a dict."""
+    import numpy as np
+    import torch
+    import paper_2504_08791_amd as prima
+    from workloads import synth
+
+    d = cfg.dims
+    dev = torch.device("cuda:0")
     cap = cfg.n_past + cfg.T
     x_host = synth.window_input(cfg)
 
     # --- build the window in HBM, one layer at a time; the oracle walks the same layers on the host ---
-    want_cpu = not args.no_cpu_baseline
     if want_cpu:
         import oracle
     dev_layers = []
@@ -122,42 +182,33 @@ def main():
         if head is not None:
             prima.lm_head(d, head["g_final"], head["w_lm"], y, logits, head_ws)
 
-    if args.copy_calibration:
+    if copy_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record(stream)
-    for _ in range(args.steps):
-        step()
-    e1.record(stream)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    ms_per_step, median_ms, wall_ms_step = time_steps(step, stream, warmup, steps)
     tokens_per_s = cfg.T / (ms_per_step * 1e-3)
     bytes_step = cfg.bytes_per_step()   # the output layer's bytes included when there is one
 
     # --- what a plain linear read reaches on this device (4 GiB, far beyond the last-level cache) ---
-    probe = torch.empty(4 * 1024 ** 3, dtype=torch.uint8, device=dev)
-    probe.zero_()
-    sink = torch.zeros(1, dtype=torch.int32, device=dev)
-    for _ in range(2):
-        prima.stream_read_probe(probe, sink)
-    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    p0.record(stream)
-    for _ in range(5):
-        prima.stream_read_probe(probe, sink)
-    p1.record(stream)
-    torch.cuda.synchronize()
-    stream_read_gbps = probe.numel() * 5 / (p0.elapsed_time(p1) * 1e-3) / 1e9
-    del probe
+    stream_read_gbps = None
+    if with_probe:
+        probe = torch.empty(4 * 1024 ** 3, dtype=torch.uint8, device=dev)
+        probe.zero_()
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        for _ in range(2):
+            prima.stream_read_probe(probe, sink)
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record(stream)
+        for _ in range(5):
+            prima.stream_read_probe(probe, sink)
+        p1.record(stream)
+        torch.cuda.synchronize()
+        stream_read_gbps = probe.numel() * 5 / (p0.elapsed_time(p1) * 1e-3) / 1e9
+        del probe
 
     # --- per kind of launch: each replayed on its own, once per layer, between two HIP events on the
     #     same stream (the dominant kernel is the gate/up projection) ---
@@ -173,14 +224,17 @@ def main():
     gate_up_bytes = 2 * d.ffn * (d.e // 256) * 144      # algorithmic bytes of one gate/up launch
     gu_us = per_launch_us["gate_up"]
     achieved = gate_up_bytes / (gu_us * 1e-6) / 1e9
+    qd, kvd = d.n_q_heads * d.head_dim, d.n_kv_heads * d.head_dim
+    kind_bytes = {"qkv": (qd + 2 * kvd) * (d.e // 256) * 144, "attn": d.kv_bytes_per_layer(cfg.n_past + cfg.T),
+                  "wo": d.e * (qd // 256) * 144, "gate_up": gate_up_bytes, "down": d.e * (d.ffn // 256) * 144}
 
     out = {
         "metric": "decode tokens/s per layer window; achieved HBM GB/s vs MI355X peak",
         "value": round(tokens_per_s, 2),
         "unit": "tokens/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True,
         "scaling": "weak",
@@ -189,17 +243,21 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"{cfg.name}: {cfg.n_layers}-layer window, e={d.e}, Hq/Hkv={d.n_q_heads}/{d.n_kv_heads}, "
-                        f"ffn={d.ffn}, T={cfg.T}, n_kv={cfg.n_past}, Q4_K weights, fp16 KV",
+                        f"ffn={d.ffn}, T={cfg.T}, n_kv={cfg.n_past}, Q4_K weights, fp16 KV"
+                        + (f", final RMSNorm + {cfg.vocab}-row Q4_K output layer" if cfg.vocab else ""),
             "tokens_per_step": cfg.T,
             "layers": cfg.n_layers,
             "kv_context": cfg.n_past,
         },
+        "median_ms_per_step": round(median_ms, 4),
         "window_bytes_per_step": bytes_step,
         "window_hbm_gbps": round(bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
         "window_hbm_frac": round(bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "wall_ms_per_step": round(wall_ms / args.steps, 4),
+        "wall_ms_per_step": round(wall_ms_step, 4),
         "per_launch_us": {k: round(v, 2) for k, v in per_launch_us.items()},
-        "plain_read_gbps": round(stream_read_gbps, 1),  # linear 128-bit read of 4 GiB: the practical ceiling
+        # every kind of launch against the same peak: algorithmic bytes of the launch / its duration / 8 TB/s
+        "per_launch_hbm_frac": {k: round(kind_bytes[k] / (per_launch_us[k] * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)
+                                for k in kind_bytes if k in per_launch_us},
         "roofline": {
             "bound": "hbm",
             "kernel": f"gemv_q4k_persistent_kernel<{cfg.T}> as launched for the gate/up projections (RMSNorm in front, SwiGLU behind)",
@@ -209,9 +267,11 @@ def main():
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "bytes_per_launch": gate_up_bytes,
             "avg_launch_us": round(gu_us, 2),
-            "traffic": GATE_UP_TRAFFIC_BYTES if (cfg.name == "c3" and cfg.T == 1) else None,
+            "traffic": GATE_UP_TRAFFIC_BYTES if (cfg.name == "c3" and cfg.T == 1 and GATE_UP_TRAFFIC_BYTES) else None,
         },
     }
+    if stream_read_gbps is not None:
+        out["plain_read_gbps"] = round(stream_read_gbps, 1)  # linear 128-bit read of 4 GiB: the practical ceiling
     if want_cpu:
         got = y.cpu().numpy().astype(np.float64)
         rms = np.sqrt((h_ref ** 2).mean(axis=1, keepdims=True))
@@ -225,10 +285,78 @@ def main():
             "value": round(cfg.T / cpu_seconds, 4),
             "unit": "tokens/s",
             "cores": oracle.num_threads(),
+            "cpu_model": cpu_model(),
             "kind": "oracle",
             "sample": f"the whole {cfg.n_layers}-layer window, {cfg.T} token(s), once ({cpu_seconds:.1f} s of CPU time; "
                       "tensor generation excluded)",
         }
+        # config 0 (one 8B-shaped layer, one token) on one thread and on all of them
+        from workloads.configs import CONFIGS as _C
+        c0 = _C["c0"]
+        t0l = synth.layer_tensors(c0, 0)
+        x0 = synth.window_input(c0).astype(np.float64)
+        n_thr = oracle.num_threads()
+        res = {}
+        for label, thr in (("all_threads", n_thr), ("one_thread", 1)):
+            oracle.set_num_threads(thr)
+            tt = time.perf_counter()
+            oracle.layer(c0.dims, {k: (v.copy() if k.endswith("cache") else v) for k, v in t0l.items()}, x0, c0.n_past)
+            res[label] = round(1.0 / (time.perf_counter() - tt), 3)
+        oracle.set_num_threads(n_thr)
+        out["cpu_baseline"]["config0_layer_tokens_per_s"] = res
+    del dev_layers, win
+    torch.cuda.empty_cache()
+    return {"line": out}
+
+
+def bench_c0(args, cfg):
+    """Config 0 (one 8B-shaped layer, 125 MB): the layer fits the 256 MB last-level cache, so the same layer timed
+    again and again measures that cache.  Cold: six copies of the layer (750 MB) taken in rotation, one per step;
+    warm: one copy every step.  Launch-bound either way (five launches for 15.6 us of traffic at the peak rate)."""
+    import numpy as np
+    import torch
+    import paper_2504_08791_amd as prima
+    from workloads import synth
+
+    d = cfg.dims
+    dev = torch.device("cuda:0")
+    cap = cfg.n_past + cfg.T
+    host = synth.layer_tensors(cfg, 0, kv_cap=cap)
+    copies = 6
+    wins = [prima.Window(d, [{k: torch.from_numpy(v).to(dev) for k, v in host.items()}], cap, T_max=cfg.T) for _ in range(copies)]
+    x = torch.from_numpy(synth.window_input(cfg)).to(dev)
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    counter = [0]
+
+    def cold():
+        wins[counter[0] % copies].decode(x, cfg.n_past, x_out=y)
+        counter[0] += 1
+
+    def warm():
+        wins[0].decode(x, cfg.n_past, x_out=y)
+
+    cold_ms, cold_med, wall = time_steps(cold, stream, args.warmup, args.steps)
+    warm_ms, warm_med, _ = time_steps(warm, stream, args.warmup, args.steps)
+    bytes_step = cfg.bytes_per_step()
+    out = {
+        "metric": "decode tokens/s per layer window; achieved HBM GB/s vs MI355X peak", "value": round(1e3 / cold_ms, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(cold_ms, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"c0: one layer, e={d.e}, ffn={d.ffn}, T=1, n_kv={cfg.n_past}; cold = {copies} copies of the layer in rotation "
+                               f"({copies * bytes_step / 1e6:.0f} MB, beyond the 256 MB last-level cache)", "tokens_per_step": 1, "layers": 1},
+        "cold": {"ms_per_step": round(cold_ms, 5), "median_ms_per_step": round(cold_med, 5), "window_hbm_gbps": round(bytes_step / cold_ms / 1e6, 1),
+                 "window_hbm_frac": round(bytes_step / cold_ms / 1e6 / HBM_PEAK_GBPS, 4)},
+        "warm_cache_resident": {"ms_per_step": round(warm_ms, 5), "median_ms_per_step": round(warm_med, 5),
+                                "note": "the same 125 MB layer every step: served by the last-level cache, not an HBM figure"},
+        "window_bytes_per_step": bytes_step, "wall_ms_per_step": round(wall, 5),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        ref = oracle.layer(d, host, synth.window_input(cfg).astype(np.float64), cfg.n_past)
+        got = y.cpu().numpy().astype(np.float64)
+        rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+        out["max_rel_err_vs_oracle"] = float((np.abs(got - ref) / np.maximum(np.abs(ref), rms)).max())
     print(json.dumps(out), flush=True)
 
 
