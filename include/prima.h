@@ -163,16 +163,12 @@ prima_status prima_layer_window_decode_batch(const prima_dims *d, const prima_la
                                              void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Optional single-launch path for one token (T = 1): the layers' kernels run back to back on one persistent
- * grid (one launch per 24 layers), separated by grid barriers; same mat-vec arithmetic and bits, an attention
- * phase of its own (same results within rounding).  It is OFF by
- * default (measured slower than one launch per projection); prima_set_fused_window(1) switches it on for the
- * process.  Shapes that do not fill the device evenly, and T > 1, always run one kernel per projection.
- * The barriers poll with a bound; prima_window_check() waits for `hip_stream` (it SYNCHRONISES) and returns
- * PRIMA_E_DEVICE if a barrier of the last call on this workspace gave up, in which case x_out of that call
- * is not valid.
+ * Some kernels of a window step wait, inside the launch, for records that other workgroups of the same launch write
+ * (the workgroup that merges the key ranges of the attention, the one that adds the slabs of a long mat-vec).  These
+ * waits are bounded; one that gives up (it never should) raises a flag in the workspace and the step's results are
+ * invalid.  prima_window_check() waits for `hip_stream` (it SYNCHRONISES) and returns PRIMA_E_DEVICE if a wait of the
+ * last window call on this workspace gave up, else PRIMA_OK.
  */
-void prima_set_fused_window(int32_t enabled);
 prima_status prima_window_check(const prima_dims *d, int32_t kv_cap, int32_t T,
                                 const void *workspace, size_t workspace_bytes, void *hip_stream);
 

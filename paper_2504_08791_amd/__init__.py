@@ -185,11 +185,6 @@ def stream_read_probe(buf, sink):
                "prima_stream_read_probe")
 
 
-def set_fused_window(enabled):
-    """Single-launch window steps for one token on or off (default), process-wide."""
-    _ffi.lib().prima_set_fused_window(1 if enabled else 0)
-
-
 def set_prefill_small_tokens(n):
     """Prompts of up to n tokens go through the decode kernels inside Window.prefill (default 96; 0: always the matrix product)."""
     _ffi.lib().prima_set_prefill_small_tokens(int(n))
@@ -290,7 +285,7 @@ class Window:
         return x_out
 
     def check(self, T=1):
-        """Waits for the stream; raises if a grid barrier of the last single-launch step gave up."""
+        """Waits for the stream; raises if a bounded wait inside a kernel of the last step gave up."""
         _ffi.check(_ffi.lib().prima_window_check(C.byref(self.dims), self.kv_cap, T, _ptr(self.workspace),
                                                  self.workspace.numel(), _stream()), "prima_window_check")
 

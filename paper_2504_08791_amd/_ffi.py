@@ -14,7 +14,7 @@ STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIG
 EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", "prima_attn_decode",
            "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_window_decode_profiled", "prima_layer_decode_taps",
            "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
-           "prima_set_fused_window", "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
+           "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
            "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt", "prima_layer_window_decode_mixed", "prima_window_plan_status", "prima_gemv_plan_status", "prima_layer_window_decode_batch_mixed",
            "prima_q4k_gemm", "prima_gemm_workspace_bytes", "prima_layer_window_prefill", "prima_prefill_workspace_bytes",
            "prima_layer_window_prefill_mixed", "prima_set_prefill_small_tokens", "prima_q4k_gemv_noalloc"]
@@ -102,7 +102,6 @@ def lib():
         L.prima_workspace_bytes.argtypes = [dp, i32, i32]
         L.prima_workspace_bytes.restype = sz
         L.prima_stream_read_probe.argtypes = [vp, sz, vp, vp]
-        L.prima_set_fused_window.argtypes = [i32]
         L.prima_window_check.argtypes = [dp, i32, i32, vp, sz, vp]
         L.prima_status_str.argtypes = [C.c_int]
         L.prima_status_str.restype = C.c_char_p
@@ -111,7 +110,6 @@ def lib():
                      "prima_layer_window_decode_profiled",
                      "prima_layer_decode_taps", "prima_lm_head", "prima_window_check", "prima_stream_read_probe"):
             getattr(L, name).restype = C.c_int
-        L.prima_set_fused_window.restype = None
         L.prima_set_prefill_small_tokens.argtypes = [i32]
         L.prima_set_prefill_small_tokens.restype = None
         _lib = L

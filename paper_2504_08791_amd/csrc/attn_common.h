@@ -1,5 +1,4 @@
-// Declarations shared by the stand-alone attention kernel and the fused window kernel (the design is
-// described in attn_decode.hip); the body itself is attn_body.inc.
+// Declarations of the attention kernel (the design is described in attn_decode.hip).
 #pragma once
 #include "common.h"
 
@@ -9,7 +8,7 @@ namespace prima {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int QG = 8;        // queries per workgroup
+constexpr int QG = 8;        // queries per group in the sizing of the scratch
 constexpr int ATT_WAVES = 8; // waves per workgroup
 constexpr int ATT_THREADS = ATT_WAVES * 64;
 constexpr int MAX_SPLITS = 64;
@@ -120,17 +119,7 @@ __device__ __forceinline__ void load_slices(const float *p, int c, float (&v)[D 
     }
 }
 
-// dynamic LDS of the attention body
-template <int D>
-struct AttnLds {
-    float p[ATT_WAVES][16][QG]; // probabilities of the current tile [key][query]
-    float corr[ATT_WAVES][QG];
-    float m[ATT_WAVES][QG], l[ATT_WAVES][QG];
-    float o[ATT_WAVES][QG][D];
-    __half knew[PRIMA_MAX_TOK][D], vnew[PRIMA_MAX_TOK][D]; // the step's new rows (fused append)
-    int last;
-};
-
+// query groups as the scratch is sized for (groups of QG queries; the kernel's own groups are larger, so fewer)
 inline int query_groups(const prima_dims &d, int T)
 {
     const int G = d.n_q_heads / d.n_kv_heads;

@@ -140,14 +140,9 @@ prima_status launch_attn_prompt(const prima_dims &d, const float *q, __half *K, 
 prima_status launch_rope_append(const prima_dims &d, float *q, const float *k, const float *v, const float *tab,
                                 __half *K, __half *V, int kv_cap, int n_past, int T, hipStream_t st);
 
-// one token through a whole window in one launch per FUSED_MAX_LAYERS layers (fused_window.hip); PRIMA_E_SHAPE
-// with nothing launched when the shapes do not qualify
-size_t fused_sync_bytes();
-prima_status launch_fused_window(const prima_dims &d, const prima_layer *layers, int L, const GemvArgs ga[4],
-                                 void *gemv_ws, size_t gemv_ws_bytes, size_t arrivals_region,
-                                 const float *q, const float *k_new, const float *v_new, const float *rope_tab,
-                                 int kv_cap, int n_past, float *o, void *attn_ws,
-                                 const float *x_in, float *x_out, float *xb0, float *xb1, void *sync, hipStream_t st);
+// Bounded waits inside kernels (a workgroup that waits for records of other workgroups of its launch) raise this
+// flag when they give up; it lives in the window scratch and prima_window_check reports it.
+constexpr size_t WAIT_FLAG_BYTES = 256; // the flag is the first word
 
 // 16 bytes per lane from global memory straight into LDS: lane l writes bytes [16 l, 16 l + 16) of the
 // 1 KiB at LDS byte address lds_addr (wave-uniform, goes through M0).  Written as inline assembly on

@@ -1,5 +1,5 @@
-// Declarations shared by the stand-alone Q4_K mat-vec kernel and the fused window kernel (the design is
-// described in q4k_gemv_mfma.hip); the body of the mat-vec itself is gemv_body.inc.
+// Declarations of the Q4_K mat-vec kernels (the design is described in q4k_gemv_mfma.hip); the body of the
+// mat-vec itself is gemv_body.inc.
 #pragma once
 #include "common.h"
 

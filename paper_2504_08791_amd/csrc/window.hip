@@ -50,7 +50,7 @@ WindowWs carve(const prima_dims &d, int kv_cap, int T)
     for (const auto &sh : shapes) w.gemv_bytes = std::max(w.gemv_bytes, gemv_ws_bytes(sh[0], sh[1], T)); // counters + partial sums
     w.gemv_bytes += w.arrivals_bytes; // the counter region is sized for the tallest matrix
     w.gemv = take(w.gemv_bytes);
-    w.sync = take(fused_sync_bytes());
+    w.sync = take(WAIT_FLAG_BYTES);
     w.total = off;
     return w;
 }
@@ -100,12 +100,6 @@ void layer_gemv_args(const prima_dims &d, const prima_layer &L, int T, const flo
     ga[3] = gemv_args(1, F, act, F, T);
     ga[3].seg[0] = seg(L.wdown, y, e, e, h, e);
 }
-
-// whether windows of one token try the single-launch path first.  Off unless asked for: it gives the same
-// bits, but measured slower than one launch per projection (config 3: 186 vs 129 us per layer): a grid barrier
-// costs ~3 us, the activations then take a device-scope round trip (~2.5 us) and the workgroups wait 6-11 us
-// per barrier for the slowest one, which the three prefetched ring stages (~5 us of traffic) do not cover.
-bool g_fused_enabled = false;
 
 // prompts of up to this many tokens go through the decode kernels, PRIMA_MAX_TOK tokens a call (measured on config 3's shape,
 // ms per layer, matrix-product route / decode route: 48 tokens 2.04 / 1.09, 64: 2.06 / 1.46, 96: 2.50 / 2.19, 128: 2.54 / 2.92,
@@ -202,7 +196,7 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
 prima_status step_init(const prima_dims &d, void *ws, const WindowWs &w, int T, int n_past, const int *positions, bool with_sync, hipStream_t st)
 {
     void *const zp[3] = {at<char>(ws, w.gemv), at<char>(ws, w.attn), with_sync ? at<char>(ws, w.sync) : nullptr};
-    const size_t zb[3] = {w.arrivals_bytes, attn_counter_bytes(d, T), fused_sync_bytes()};
+    const size_t zb[3] = {w.arrivals_bytes, attn_counter_bytes(d, T), WAIT_FLAG_BYTES};
     return launch_step_init(at<float>(ws, w.rope), T, d.head_dim, n_past, d.rope_theta, positions, zp, zb, st);
 }
 
@@ -560,15 +554,6 @@ prima_status prima_layer_window_decode(const prima_dims *d, const prima_layer *l
     const WindowWs w = carve(*d, kv_cap, T);
     s = step_init(*d, workspace, w, T, n_past, nullptr, true, st);
     if (s != PRIMA_OK) return s;
-    if (T == 1 && g_fused_enabled) {
-        GemvArgs ga[4];
-        layer_gemv_args(*d, layers[0], T, x_in, x_out, workspace, w, ga);
-        s = launch_fused_window(*d, layers, L, ga, at<char>(workspace, w.gemv), w.gemv_bytes, w.arrivals_bytes,
-                                at<float>(workspace, w.q), at<float>(workspace, w.k), at<float>(workspace, w.v), at<float>(workspace, w.rope),
-                                kv_cap, n_past, at<float>(workspace, w.o), at<char>(workspace, w.attn),
-                                x_in, x_out, at<float>(workspace, w.xb0), at<float>(workspace, w.xb1), at<char>(workspace, w.sync), st);
-        if (s != PRIMA_E_SHAPE) return s; // ran (or failed for good); E_SHAPE: not eligible, nothing was launched
-    }
     const float *cur = x_in;
     for (int i = 0; i < L; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
@@ -664,8 +649,6 @@ prima_status prima_layer_window_decode_batch_mixed(const prima_dims *d, const pr
     return PRIMA_OK;
 }
 
-void prima_set_fused_window(int32_t enabled) { g_fused_enabled = enabled != 0; }
-
 void prima_set_prefill_small_tokens(int32_t n) { g_prefill_small_tokens = n < 0 ? 0 : n; }
 
 size_t prima_prefill_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)
@@ -742,7 +725,7 @@ prima_status prima_window_check(const prima_dims *d, int32_t kv_cap, int32_t T, 
     if (workspace_bytes < w.total) return PRIMA_E_WORKSPACE;
     if (hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) return PRIMA_E_DEVICE;
     int flag = 0;
-    if (hipMemcpy(&flag, static_cast<const char *>(workspace) + w.sync + 128, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) return PRIMA_E_DEVICE;
+    if (hipMemcpy(&flag, static_cast<const char *>(workspace) + w.sync, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) return PRIMA_E_DEVICE;
     return flag == 0 ? PRIMA_OK : PRIMA_E_DEVICE;
 }
 
