@@ -20,8 +20,8 @@ struct AttnArgs {
     const float *v_new;   // fused append: v [T][Hkv][D]
     const float2 *rope_tab; // [T][D/2] (cos, sin) or null
     __half *K, *V;        // caches [Hkv][kv_cap][D]
-    float *part;          // [T*Hq][nsplit][2 + D]
-    unsigned *arrivals;   // [Hkv * query groups], zero between launches
+    float *part;          // the key ranges' records [T*Hq][nsplit][4 + D], every word "not written" between launches
+    unsigned *err;        // raised when the merging workgroup's bounded wait gives up
     float *o;             // [T][Hq][D]
     int Hq, Hkv, kv_cap, n_past, T, nsplit, keys_per_split;
     // Batch of sequences (continuous batching, App. A.12: one token each): token b is the next token of a
@@ -158,7 +158,7 @@ inline AttnArgs build_attn_args(const prima_dims &d, const float *q, float *q_ro
     a.q = q; a.q_rot_out = q_rot_out; a.k_new = k_new; a.v_new = v_new;
     a.rope_tab = reinterpret_cast<const float2 *>(rope_tab);
     a.K = K; a.V = V;
-    a.arrivals = static_cast<unsigned *>(ws);
+    a.err = static_cast<unsigned *>(ws);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + attn_counter_bytes(d, T));
     a.o = o;
     a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.kv_cap = kv_cap; a.n_past = n_past; a.T = T;

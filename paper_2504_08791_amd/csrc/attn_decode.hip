@@ -17,12 +17,20 @@
 //  * RoPE + KV append fused: a workgroup whose key range holds new rows builds them once from the projection
 //    output (rotate k, round k and v to fp16, nearest even), keeps them in LDS (they replace what the tile
 //    loads brought from the cache) and stores them to the cache on the side: no store-to-load round trip.
-//  * Waves meet in LDS, key ranges in global memory; the workgroup that arrives last merges them.
+//  * Waves meet in LDS, key ranges in global memory: every workgroup writes its record (max, sum, D columns) per query
+//    with device-scope stores, and the workgroup of the first key range merges them.  It does not wait for an
+//    arrival count (a store acknowledgement, an atomic and two dependent loads: four trips through global memory):
+//    the records say themselves whether they are complete.  Before a launch every word of a record holds a NaN
+//    pattern that no arithmetic produces; the merging workgroup requests (max, sum) and the columns of all ranges
+//    in one go and repeats the request until no word shows the pattern (the ranges finish together, so the first or
+//    second request succeeds), merges, and writes the pattern back for the next launch.  The polling is bounded
+//    (error flag in the scratch); the other workgroups wait for nothing, so the launch always drains.
 #include "attn_common.h"
 
 namespace prima {
 
 constexpr int QGM = 16; // queries per workgroup
+constexpr int MERGE_TRIES = 20000; // requests of the merging workgroup before it gives up (each takes a trip through global memory, ~2 us)
 
 // key ranges of the single-launch window kernel's attention phase (groups of 8 queries, attn_body.inc)
 int attn_num_splits(const prima_dims &d, int n_total, int T, bool batch)
@@ -41,13 +49,17 @@ size_t attn_counter_bytes(const prima_dims &d, int T)
     return round_up(static_cast<size_t>(d.n_kv_heads) * query_groups_batch(d, T) * sizeof(unsigned), 256); // >= query_groups(d, T)
 }
 
+// a key range's record for one query: max, sum, two unused words (the columns start 16-byte aligned), D columns
+constexpr int REC_HDR = 4;
+
 size_t attn_ws_bytes(const prima_dims &d, int, int T)
 {
-    return attn_counter_bytes(d, T) + round_up(static_cast<size_t>(T) * d.n_q_heads * MAX_SPLITS * (2 + d.head_dim) * sizeof(float), 256);
+    return attn_counter_bytes(d, T) + round_up(static_cast<size_t>(T) * d.n_q_heads * MAX_SPLITS * (REC_HDR + d.head_dim) * sizeof(float), 256);
 }
 
 
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 
 template <int D>
 struct AttnTileLds {
@@ -355,68 +367,97 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
             a.o[head * D + e] = accv / ll;
             continue;
         }
-        float *rec = a.part + (head * a.nsplit + split) * (2 + D);
+        float *rec = a.part + (head * a.nsplit + split) * (REC_HDR + D);
         if (e == 0) {
             __hip_atomic_store(rec, mm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(rec + 1, ll, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        __hip_atomic_store(rec + 2 + e, accv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(rec + REC_HDR + e, accv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (a.nsplit == 1) return;
+    if (a.nsplit == 1 || split != 0) return;
 
-    // ---- the last workgroup of this (KV head, query group) merges the key ranges ----
+    // ---- the workgroup of the first key range merges the ranges of its (KV head, query group) ----
     // o[t][h][:] = sum_i part_i.o * exp(m_i - M) / sum_i part_i.l * exp(m_i - M); a key range that held no
-    // visible key has (max, sum) = (-inf, 0) and drops out.  The records were written with device-scope
-    // stores; vmcnt(0) + barrier makes them complete before the arrival is counted.
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (threadIdx.x == 0) {
-        unsigned *ctr = a.arrivals + (tok0 * a.Hkv + kvh) * nqg + qgrp;
-        const unsigned prev = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool last = prev + 1 == static_cast<unsigned>(a.nsplit);
-        if (last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); // ready for the next launch
-        lds.last = last ? 1 : 0;
-    }
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    if (!lds.last) return;
-    // one wave per query at a time: lane s takes (max, sum) of key range s, every lane its columns of all ranges
+    // visible key has (max, sum) = (-inf, 0) and drops out.  One wave per query at a time: lane s takes (max, sum) of
+    // range s; a load instruction brings RPI whole records' columns (16 bytes a lane), MERGE_LD instructions a request.
+    constexpr int LPR = D / 4;        // lanes per record
+    constexpr int RPI = 64 / LPR;     // records per load instruction
+    constexpr int MERGE_LD = 16;      // load instructions per request: 32 (D = 128) or 64 (D = 64) records
+    const int sub = lane / LPR, c4 = (lane % LPR) * 4;
     for (int qq = wave; qq < nq; qq += ATT_WAVES) {
         const int qj = q0 + qq, t = qj / G, hg = qj - t * G;
         const int64_t head = static_cast<int64_t>(tok0 + t) * a.Hq + kvh * G + hg;
-        const float *rec0 = a.part + head * a.nsplit * (2 + D);
-        // 2 + D is even and the records start 8-byte aligned: (max, sum) is one 64-bit load
-        const uint64_t ml = __hip_atomic_load(reinterpret_cast<const uint64_t *>(rec0 + min(lane, a.nsplit - 1) * (2 + D)),
-                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float ms = lane < a.nsplit ? __uint_as_float(static_cast<uint32_t>(ml)) : -INFINITY;
-        const float ls = lane < a.nsplit ? __uint_as_float(static_cast<uint32_t>(ml >> 32)) : 0.f;
-        float mm = ms;
+        // this query's records: a scalar base (the query is the wave's) and one offset per lane, so that the requests
+        // of a pass need no address registers of their own.  Records past the last range are read too (they lie
+        // inside the scratch, which is sized for MAX_SPLITS ranges per query) and ignored.
+        const uint64_t rec_addr = reinterpret_cast<uint64_t>(a.part + head * a.nsplit * (REC_HDR + D));
+        // (the builtin returns a signed int: through uint32_t, or the low half's sign would spill into the high half)
+        const uint32_t rec_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(rec_addr))));
+        const uint32_t rec_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(rec_addr >> 32))));
+        const char *const rec0 = reinterpret_cast<const char *>(static_cast<uint64_t>(rec_lo) | (static_cast<uint64_t>(rec_hi) << 32));
+        constexpr int REC_BYTES = (REC_HDR + D) * 4;
+        const uint32_t col_off = static_cast<uint32_t>(sub * REC_BYTES + (REC_HDR + c4) * 4);
+        const uint32_t ml_off = static_cast<uint32_t>(min(lane, a.nsplit - 1) * REC_BYTES);
+        float mm = 0.f, wgt = 0.f;
+        v4f accq = {0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < a.nsplit; s0 += MERGE_LD * RPI) {
+            const char *const pass0 = rec0 + static_cast<int64_t>(s0) * REC_BYTES;
+            v4f v[MERGE_LD];
+            v2f ml = {0.f, 0.f};
+            int tries = 0;
+            for (;;) {
+                if (s0 == 0) asm volatile("global_load_dwordx2 %0, %1, %2 sc1" : "=&v"(ml) : "v"(ml_off), "s"(rec0) : "memory");
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) mm = fmaxf(mm, __shfl_xor(mm, off, 64));
-        const float w = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
-        float ll = ls * w;
+                for (int i = 0; i < MERGE_LD; ++i)
+                    asm volatile("global_load_dwordx4 %0, %1, %2 sc1" : "=&v"(v[i]) : "v"(col_off), "s"(pass0 + i * RPI * REC_BYTES) : "memory");
+                // the compiler does not know these loads: one wait that names every register
+                asm volatile("s_waitcnt vmcnt(0)"
+                             : "+v"(ml), "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]),
+                               "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]), "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])
+                             :: "memory");
+                bool missing = s0 == 0 && (__float_as_uint(ml[0]) == ATTN_REC_EMPTY || __float_as_uint(ml[1]) == ATTN_REC_EMPTY);
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) ll += __shfl_xor(ll, off, 64);
-        const float wgt = w / ll; // lanes past the last range carry weight 0
-        constexpr int CPL = D / 64; // columns per lane
-        float accq[CPL];
+                for (int i = 0; i < MERGE_LD; ++i)
+                    missing = missing || (s0 + i * RPI + sub < a.nsplit &&
+                                          (__float_as_uint(v[i][0]) == ATTN_REC_EMPTY || __float_as_uint(v[i][1]) == ATTN_REC_EMPTY ||
+                                           __float_as_uint(v[i][2]) == ATTN_REC_EMPTY || __float_as_uint(v[i][3]) == ATTN_REC_EMPTY));
+                if (__ballot(missing) == 0ull) break;
+                if (++tries > MERGE_TRIES) { // never expected: give up, say so, and go on with what there is
+                    if (lane == 0) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+            }
+            if (s0 == 0) {
+                const float ms = lane < a.nsplit ? ml[0] : -INFINITY;
+                const float ls = lane < a.nsplit ? ml[1] : 0.f;
+                mm = wave_max(ms);
+                const float w = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
+                const float ll = wave_sum(ls * w);
+                wgt = w / ll; // lanes past the last range carry weight 0
+                if (lane < a.nsplit) // "not written" again, for the next launch
+                    *reinterpret_cast<uint2 *>(const_cast<char *>(rec0) + ml_off) = make_uint2(ATTN_REC_EMPTY, ATTN_REC_EMPTY);
+            }
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) accq[c] = 0.f;
-        // sixteen ranges at a time: all their loads are out before the first is used
-        for (int s0 = 0; s0 < a.nsplit; s0 += 16) {
-            float v[16][CPL];
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj)
-#pragma unroll
-                for (int c = 0; c < CPL; ++c)
-                    v[jj][c] = __hip_atomic_load(rec0 + min(s0 + jj, a.nsplit - 1) * (2 + D) + 2 + lane + 64 * c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-                const float ws = (s0 + jj < a.nsplit) ? __shfl(wgt, s0 + jj, 64) : 0.f; // (the clamped loads above are then unused)
-#pragma unroll
-                for (int c = 0; c < CPL; ++c) accq[c] = fmaf(v[jj][c], ws, accq[c]);
+            for (int i = 0; i < MERGE_LD; ++i) {
+                const int r = s0 + i * RPI + sub;
+                const float ws = __shfl(wgt, min(r, 63), 64);
+                if (r < a.nsplit) {
+                    accq[0] = fmaf(v[i][0], ws, accq[0]);
+                    accq[1] = fmaf(v[i][1], ws, accq[1]);
+                    accq[2] = fmaf(v[i][2], ws, accq[2]);
+                    accq[3] = fmaf(v[i][3], ws, accq[3]);
+                    *reinterpret_cast<uint4 *>(const_cast<char *>(pass0) + i * RPI * REC_BYTES + col_off) =
+                        make_uint4(ATTN_REC_EMPTY, ATTN_REC_EMPTY, ATTN_REC_EMPTY, ATTN_REC_EMPTY);
+                }
             }
         }
+        // the RPI groups of lanes hold different ranges' shares of the same columns
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) a.o[head * D + lane + 64 * c] = accq[c];
+        for (int k = 0; k < 4; ++k) {
+            if (RPI == 4) accq[k] = add_across_16(accq[k]);
+            accq[k] = add_across_32(accq[k]);
+        }
+        if (lane < LPR) *reinterpret_cast<float4 *>(a.o + head * D + c4) = make_float4(accq[0], accq[1], accq[2], accq[3]);
     }
 }
 
@@ -432,7 +473,7 @@ static int tile_num_splits(const prima_dims &d, int n_total, int T, bool batch)
     const int wgs = d.n_kv_heads * tile_query_groups(d, T, batch);
     // at least two 16-key tiles per wave: every key range costs a record, an arrival and a share of the merge
     // (4096 rows, one token: 16 ranges 14.8 us, 32 ranges 16.0 us, 8 ranges 16.8 us)
-    const int by_len = (n_total + 32 * ATT_WAVES - 1) / (32 * ATT_WAVES);
+    const int by_len = n_total / (32 * ATT_WAVES); // (rounded down: 4097 rows are 16 ranges of 257, not 16 of 256 and one of 1)
     const int by_grid = (256 + wgs - 1) / wgs; // measured: 128, 192 and 384 workgroups are slower
     int ns = by_len < by_grid ? by_len : by_grid;
     if (ns < 1) ns = 1;
@@ -441,6 +482,21 @@ static int tile_num_splits(const prima_dims &d, int n_total, int T, bool batch)
 }
 
 static prima_status launch_attn_kernel(const prima_dims &d, dim3 grid, const AttnArgs &a, hipStream_t st);
+
+// key ranges of a launch: multiples of 16 keys, none empty
+static void attn_ranges(const prima_dims &d, int n_total, int T, bool batch, int &keys_per_split, int &nsplit)
+{
+    const int want = tile_num_splits(d, n_total, T, batch);
+    keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
+    nsplit = (n_total + keys_per_split - 1) / keys_per_split;
+}
+
+size_t attn_records_bytes(const prima_dims &d, int n_total, int T, bool batch)
+{
+    int kps, ns;
+    attn_ranges(d, n_total, T, batch, kps, ns);
+    return ns == 1 ? 0 : static_cast<size_t>(T) * d.n_q_heads * ns * (REC_HDR + d.head_dim) * sizeof(float);
+}
 
 prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, const float *k_new, const float *v_new,
                             const float *rope_tab, __half *K, __half *V, int kv_cap, int n_past, int T, float *o,
@@ -452,9 +508,7 @@ prima_status launch_attn(const prima_dims &d, const float *q, float *q_rot_out, 
         n_total = 0;
         for (int b = 0; b < T; ++b) n_total = seq->n_past[b] + 1 > n_total ? seq->n_past[b] + 1 : n_total;
     }
-    const int want = tile_num_splits(d, n_total, T, seq != nullptr);
-    a.keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
-    a.nsplit = (n_total + a.keys_per_split - 1) / a.keys_per_split;
+    attn_ranges(d, n_total, T, seq != nullptr, a.keys_per_split, a.nsplit);
     const dim3 grid(a.nsplit, d.n_kv_heads, tile_query_groups(d, T, seq != nullptr));
     return launch_attn_kernel(d, grid, a, st);
 }

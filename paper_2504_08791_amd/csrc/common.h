@@ -114,15 +114,21 @@ prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta
 
 prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
 prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st);
-// the RoPE table [T][D/2] of (cos, sin) and up to three zeroed regions (null: none) in one launch.
+// the RoPE table [T][D/2] of (cos, sin) and up to four regions filled with a word each (null: none) in one launch.
 // positions: null (token t sits at n_past + t) or T positions, one per token (a batch of sequences)
 prima_status launch_step_init(float *tab, int T, int D, int n_past, float theta, const int *positions,
-                              void *const zero_ptr[3], const size_t zero_bytes[3], hipStream_t st);
+                              void *const fill_ptr[4], const size_t fill_bytes[4], const unsigned fill_word[4], hipStream_t st);
+prima_status launch_fill_words(void *a, size_t a_bytes, unsigned a_word, void *b, size_t b_bytes, unsigned b_word, hipStream_t st);
 int attn_num_splits(const prima_dims &d, int n_total, int T, bool batch = false);
 size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);
-// the first attn_counter_bytes() of the attention scratch are arrival counters: zero before the first
-// launch (launch_zero_arrivals), left zero by every launch
+// The attention scratch: attn_counter_bytes() whose first word is the flag a bounded wait raises when it gives up
+// (zero before a launch), then the key ranges' records.  A record that has not been written holds ATTN_REC_EMPTY in
+// every word: before the first launch the records a launch will use (attn_records_bytes) must be filled with it
+// (launch_step_init / launch_fill_words); every launch leaves them so.
 size_t attn_counter_bytes(const prima_dims &d, int T);
+constexpr unsigned ATTN_REC_EMPTY = 0x7fa5c3e1u; // a NaN pattern that no arithmetic produces
+// bytes of records (from the start of the record area) that a launch for T tokens over n_total rows uses
+size_t attn_records_bytes(const prima_dims &d, int n_total, int T, bool batch);
 // q: [T][Hq][D].  With rope_tab set, q and k_new are un-rotated and the kernel rotates them and
 // appends k_new / v_new to the caches; otherwise q is used as is and the caches are complete.
 // seq: null, or (a batch of T sequences, one token each) per token its sequence's caches and length; K, V and

@@ -8,20 +8,22 @@ struct RopePositions {
     int pos[PRIMA_MAX_TOK];
 };
 
-// Everything a window step needs before its first layer, in one launch: zeroed counter regions and the RoPE
-// table, tab[t][i] = (cos, sin) of pos_t * theta^(-2i/D) with pos_t = n_past + t (or the token's own position in
+// Everything a window step needs before its first layer, in one launch: counter regions zeroed, the attention's
+// records marked "not written" and the RoPE table, tab[t][i] = (cos, sin) of pos_t * theta^(-2i/D) with pos_t = n_past + t (or the token's own position in
 // a batch of sequences), evaluated in fp64: at positions of several thousand an fp32 angle would already be off
 // by ~1e-4 rad.
-struct ZeroRegions {
-    unsigned *p[3];
-    unsigned n[3]; // 32-bit words
+struct FillRegions {
+    unsigned *p[4];
+    unsigned n[4]; // 32-bit words
+    unsigned v[4]; // the word each region is filled with
 };
-__global__ void step_init_kernel(float2 *tab, int T, int half, RopePositions p, double theta, ZeroRegions z)
+__global__ void step_init_kernel(float2 *tab, int T, int half, RopePositions p, double theta, FillRegions z)
 {
     const unsigned idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx < z.n[0]) z.p[0][idx] = 0u;
-    if (idx < z.n[1]) z.p[1][idx] = 0u;
-    if (idx < z.n[2]) z.p[2][idx] = 0u;
+    if (idx < z.n[0]) z.p[0][idx] = z.v[0];
+    if (idx < z.n[1]) z.p[1][idx] = z.v[1];
+    if (idx < z.n[2]) z.p[2][idx] = z.v[2];
+    if (idx < z.n[3]) z.p[3][idx] = z.v[3];
     if (idx >= static_cast<unsigned>(T * half)) return;
     const int t = idx / half, i = idx - t * half;
     int pos = 0;
@@ -32,19 +34,38 @@ __global__ void step_init_kernel(float2 *tab, int T, int half, RopePositions p, 
 }
 
 prima_status launch_step_init(float *tab, int T, int D, int n_past, float theta, const int *positions,
-                              void *const zero_ptr[3], const size_t zero_bytes[3], hipStream_t st)
+                              void *const fill_ptr[4], const size_t fill_bytes[4], const unsigned fill_word[4], hipStream_t st)
 {
     RopePositions p{};
     for (int t = 0; t < T && t < PRIMA_MAX_TOK; ++t) p.pos[t] = positions ? positions[t] : n_past + t;
-    ZeroRegions z{};
+    FillRegions z{};
     unsigned n = static_cast<unsigned>(T * (D / 2));
-    for (int k = 0; k < 3; ++k) {
-        z.p[k] = static_cast<unsigned *>(zero_ptr[k]);
-        z.n[k] = zero_ptr[k] ? static_cast<unsigned>(zero_bytes[k] / sizeof(unsigned)) : 0u;
+    for (int k = 0; k < 4; ++k) {
+        z.p[k] = static_cast<unsigned *>(fill_ptr[k]);
+        z.n[k] = fill_ptr[k] ? static_cast<unsigned>(fill_bytes[k] / sizeof(unsigned)) : 0u;
+        z.v[k] = fill_word[k];
         n = z.n[k] > n ? z.n[k] : n;
     }
     hipLaunchKernelGGL(step_init_kernel, dim3((n + 255) / 256), dim3(256), 0, st,
                        reinterpret_cast<float2 *>(tab), T, D / 2, p, static_cast<double>(theta), z);
+    return last_launch_status();
+}
+
+// two regions filled with a word each (null: none), in one launch
+__global__ void __launch_bounds__(256) fill_words_kernel(unsigned *a, unsigned na, unsigned va, unsigned *b, unsigned nb, unsigned vb)
+{
+    const unsigned idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx < na) a[idx] = va;
+    if (idx < nb) b[idx] = vb;
+}
+
+prima_status launch_fill_words(void *a, size_t a_bytes, unsigned a_word, void *b, size_t b_bytes, unsigned b_word, hipStream_t st)
+{
+    const unsigned na = a ? static_cast<unsigned>(a_bytes / 4) : 0u, nb = b ? static_cast<unsigned>(b_bytes / 4) : 0u;
+    const unsigned n = na > nb ? na : nb;
+    if (n == 0) return PRIMA_OK;
+    hipLaunchKernelGGL(fill_words_kernel, dim3((n + 255) / 256), dim3(256), 0, st, static_cast<unsigned *>(a), na, a_word,
+                       static_cast<unsigned *>(b), nb, b_word);
     return last_launch_status();
 }
 

@@ -195,9 +195,17 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
 // scratch zeroed, in one launch
 prima_status step_init(const prima_dims &d, void *ws, const WindowWs &w, int T, int n_past, const int *positions, bool with_sync, hipStream_t st)
 {
-    void *const zp[3] = {at<char>(ws, w.gemv), at<char>(ws, w.attn), with_sync ? at<char>(ws, w.sync) : nullptr};
-    const size_t zb[3] = {w.arrivals_bytes, attn_counter_bytes(d, T), WAIT_FLAG_BYTES};
-    return launch_step_init(at<float>(ws, w.rope), T, d.head_dim, n_past, d.rope_theta, positions, zp, zb, st);
+    // rows the longest sequence of the step holds after it: sets the attention's key ranges, hence the records it uses
+    int n_total = n_past + T;
+    if (positions) {
+        n_total = 1;
+        for (int t = 0; t < T; ++t) n_total = positions[t] + 1 > n_total ? positions[t] + 1 : n_total;
+    }
+    char *const attn = at<char>(ws, w.attn);
+    void *const fp[4] = {at<char>(ws, w.gemv), attn, with_sync ? at<char>(ws, w.sync) : nullptr, attn + attn_counter_bytes(d, T)};
+    const size_t fb[4] = {w.arrivals_bytes, attn_counter_bytes(d, T), WAIT_FLAG_BYTES, attn_records_bytes(d, n_total, T, positions != nullptr)};
+    const unsigned fw[4] = {0u, 0u, 0u, ATTN_REC_EMPTY};
+    return launch_step_init(at<float>(ws, w.rope), T, d.head_dim, n_past, d.rope_theta, positions, fp, fb, fw, st);
 }
 
 prima_status check_window_args(const prima_dims *d, int32_t kv_cap, int32_t n_past, int32_t T,
@@ -455,7 +463,9 @@ prima_status prima_attn_decode(const prima_dims *d, const float *q, const void *
     if (T < 1 || T > PRIMA_MAX_TOK || n_past < 0 || kv_cap < 1 || static_cast<int64_t>(n_past) + T > kv_cap) return PRIMA_E_RANGE;
     if (!aligned(q, 16) || !aligned(o, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) || !aligned(workspace, 256)) return PRIMA_E_ALIGN;
     if (workspace_bytes < attn_ws_bytes(*d, kv_cap, T)) return PRIMA_E_WORKSPACE;
-    const prima_status s = launch_zero_arrivals(workspace, attn_counter_bytes(*d, T), static_cast<hipStream_t>(hip_stream));
+    // the give-up flag cleared, the records this launch uses marked "not written"
+    const prima_status s = launch_fill_words(workspace, attn_counter_bytes(*d, T), 0u, static_cast<char *>(workspace) + attn_counter_bytes(*d, T),
+                                             attn_records_bytes(*d, n_past + T, T, false), ATTN_REC_EMPTY, static_cast<hipStream_t>(hip_stream));
     if (s != PRIMA_OK) return s;
     return launch_attn(*d, q, nullptr, nullptr, nullptr, nullptr,
                        static_cast<__half *>(const_cast<void *>(k_cache)), static_cast<__half *>(const_cast<void *>(v_cache)),
@@ -705,8 +715,13 @@ prima_status prima_layer_window_prefill_mixed(const prima_dims *d, const prima_l
     }
     prima_status s = launch_rope_table(at<float>(workspace, w.rope), T, d->head_dim, n_past, d->rope_theta, st);
     if (s != PRIMA_OK) return s;
-    s = launch_zero_arrivals(at<char>(workspace, w.attn), attn_counter_bytes(*d, PRIMA_MAX_TOK), st);
-    if (s != PRIMA_OK) return s;
+    {   // the attention launch for the last T mod 16 tokens (the only one with key ranges to merge): its records marked "not written"
+        const int rest = T % PRIMA_MAX_TOK;
+        char *const attn = at<char>(workspace, w.attn);
+        const size_t head_bytes = attn_counter_bytes(*d, rest ? rest : 1); // the records of that launch start behind it
+        s = launch_fill_words(attn, head_bytes, 0u, attn + head_bytes, rest ? attn_records_bytes(*d, n_past + T, rest, false) : 0, ATTN_REC_EMPTY, st);
+        if (s != PRIMA_OK) return s;
+    }
     const float *cur = x_in;
     for (int i = 0; i < L; ++i) {
         float *dst = (i == L - 1) ? x_out : at<float>(workspace, (i & 1) ? w.xb1 : w.xb0);
@@ -724,9 +739,10 @@ prima_status prima_window_check(const prima_dims *d, int32_t kv_cap, int32_t T, 
     const WindowWs w = carve(*d, kv_cap, T);
     if (workspace_bytes < w.total) return PRIMA_E_WORKSPACE;
     if (hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)) != hipSuccess) return PRIMA_E_DEVICE;
-    int flag = 0;
+    int flag = 0, attn_flag = 0; // the flags of the mat-vec's and the attention's bounded waits
     if (hipMemcpy(&flag, static_cast<const char *>(workspace) + w.sync, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) return PRIMA_E_DEVICE;
-    return flag == 0 ? PRIMA_OK : PRIMA_E_DEVICE;
+    if (hipMemcpy(&attn_flag, static_cast<const char *>(workspace) + w.attn, sizeof(attn_flag), hipMemcpyDeviceToHost) != hipSuccess) return PRIMA_E_DEVICE;
+    return (flag | attn_flag) == 0 ? PRIMA_OK : PRIMA_E_DEVICE;
 }
 
 prima_status prima_layer_window_decode_profiled(const prima_dims *d, const prima_layer *layers, int32_t L,
