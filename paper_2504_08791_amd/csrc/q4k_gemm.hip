@@ -303,22 +303,30 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
                 v4f acc[GM_RT];
 #pragma unroll
                 for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = {0.f, 0.f, 0.f, 0.f};
+                // The lo parts first: their sums are 2^-11 of the hi parts', so the fp32 roundings of the first eight
+                // steps do not count and only the eight hi steps round at the accumulator's full magnitude.
 #pragma unroll
                 for (int s8 = 0; s8 < 8; ++s8) {
-                    const half8 ah = At[(2 * s8) * 64 + lane], al = At[(2 * s8 + 1) * 64 + lane];
-#pragma unroll
-                    for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, B[rt][s8], acc[rt], 0, 0, 0);
+                    const half8 al = At[(2 * s8 + 1) * 64 + lane];
 #pragma unroll
                     for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, B[rt][s8], acc[rt], 0, 0, 0);
+                }
+#pragma unroll
+                for (int s8 = 0; s8 < 8; ++s8) {
+                    const half8 ah = At[(2 * s8) * 64 + lane];
+#pragma unroll
+                    for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, B[rt][s8], acc[rt], 0, 0, 0);
                 }
                 const half8 ax = At[16 * 64 + lane];
 #pragma unroll
                 for (int rt = 0; rt < GM_RT; ++rt) {
                     const v4f zero = {0.f, 0.f, 0.f, 0.f};
                     const v4f am = __builtin_amdgcn_mfma_f32_16x16x32_f16(ax, Bm[rt], zero, 0, 0, 0);
-                    // this lane: row n of row tile rt, tokens 4g .. 4g+3 of the tile
+                    // this lane: row n of row tile rt, tokens 4g .. 4g+3 of the tile.  The super-block's term is formed
+                    // first, at its own magnitude, and added in one step: one rounding per super-block at the magnitude
+                    // of the running sum (the chain of these roundings is the larger part of the product's error)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) yacc[tt][rt][i] = fmaf(dd[rt], acc[rt][i], fmaf(-dm[rt], am[i], yacc[tt][rt][i]));
+                    for (int i = 0; i < 4; ++i) yacc[tt][rt][i] += fmaf(dd[rt], acc[rt][i], -(dm[rt] * am[i]));
                 }
             }
         }
