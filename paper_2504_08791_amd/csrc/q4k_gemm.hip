@@ -16,13 +16,12 @@
 // Three kernels.  (1) per token: 1/rms (RMSNorm in front) and the power of two.  (2) the activations, split and
 // laid out in A-operand order per (16-token tile, super-block): 17 slabs of 1 KiB (8 sub-blocks x (hi, lo), and
 // the sums), so that the product kernel moves them into LDS with 16-byte global->LDS loads and no arithmetic; the
-// split is done once, not once per row block.  (3) the product: a workgroup of 8 waves owns 256 rows x 128 tokens,
-// a wave 32 rows (two B tiles in registers: every A tile read from LDS feeds two MFMAs).  Per super-block the B
-// tiles are built once and used for the workgroup's 128 tokens, which pass through LDS in two halves of four token
-// tiles (68 KiB each, two buffers): while one half is multiplied the other arrives.  The weights go from global
-// memory straight into registers, one super-block ahead.  Workgroups are numbered so that those running on one XCD
-// (one L2) at a time are a patch of 8 row blocks x 4 token blocks.  A launch whose workgroups would still fit the
-// compute units in one round with 64 tokens each runs only the first half of that loop per workgroup.  Up to three
+// split is done once, not once per row block.  (3) the product: a workgroup of 4 waves owns 256 rows x 64 tokens,
+// a wave 64 rows (four B tiles in registers: every A tile read from LDS feeds four MFMAs per part); two workgroups
+// share a compute unit, so that one's VALU and LDS phases run under the other's MFMAs.  The super-block is walked
+// sub-block by sub-block through a ring of LDS slots that global->LDS loads fill four positions ahead (activations
+// and the wave's own weight bytes alike; the comment at the kernel has the details).  Workgroups are numbered so
+// that those running on one XCD (one L2) at a time are patches of 4 row blocks x 8 token blocks.  Up to three
 // matrices with the same columns share a launch (Q / K / V), and so do a gate and an up matrix, with SwiGLU behind.
 // The weights stay exact: dequantised to binary16 (one accumulator for all of K) they would be off by ~1e-3 per
 // product, measured in the metric of the tests.
@@ -37,20 +36,20 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int GM_THREADS = 512;
-constexpr int GM_WAVES = GM_THREADS / 64;
-constexpr int GM_RT = 2;                        // 16-row tiles per wave
-constexpr int GM_TT = 8;                        // 16-token tiles per workgroup
-constexpr int GM_HT = GM_TT / 2;                // ... of which one half is in an LDS buffer at a time
+constexpr int GM_THREADS = 256;
+constexpr int GM_WAVES = GM_THREADS / 64;       // one wave per SIMD and workgroup
+constexpr int GM_RT = 4;                        // 16-row tiles per wave
+constexpr int GM_TT = 4;                        // 16-token tiles per workgroup
 constexpr int GM_ROWS = 16 * GM_RT * GM_WAVES;  // rows per workgroup
 constexpr int GM_TM = 16 * GM_TT;               // tokens per workgroup
 constexpr int GM_SLABS = 17;                    // per (token tile, super-block): 8 sub-blocks x (hi, lo), sums
 constexpr int GM_TILE_BYTES = GM_SLABS * 1024;
-constexpr int GM_STAGE_BYTES = GM_HT * GM_TILE_BYTES;
-constexpr int GM_LDS_BYTES = 2 * GM_STAGE_BYTES; // one workgroup per compute unit
+constexpr int GM_NS = 5;                        // ring slots: sub-block positions in LDS or on their way
+constexpr int GM_SLOT = GM_TT * 2048 + GM_WAVES * 1024;                   // 12 KiB
+constexpr int GM_LDS_BYTES = GM_NS * GM_SLOT + 2 * GM_WAVES * 1024;       // 68 KiB: two workgroups per compute unit
 constexpr int GM_XCDS = 8;
 constexpr int GM_CUS = 256;
-constexpr int GM_PATCH_R = 8, GM_PATCH_C = 4; // row blocks x token blocks that share an XCD at a time
+constexpr int GM_PATCH_R = 4, GM_PATCH_C = 8; // row blocks x token blocks that share an XCD at a time
 constexpr size_t GM_STAT_ALIGN = 1024;
 
 struct GemmSegDev {
@@ -72,7 +71,6 @@ struct GemmArgs {
     const float *resid; // null: none (added to every stored row; launches with a residual have one matrix)
     int64_t ldr;
     int T, n_tiles, n_rb, n_tb; // 16-token tiles, row blocks, token blocks
-    int tiles_wg;               // token tiles of a workgroup: GM_TT, or GM_HT (only its first half) when the grid would not fill the chip
 };
 
 // per token: 1/rms (RMSNorm in front) and the power of two that brings max |a| below 1024
@@ -178,171 +176,280 @@ __global__ void __launch_bounds__(256) gemm_split_kernel(const float *__restrict
     }
 }
 
-__global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
+// 16 bytes per lane from global memory straight into LDS (as dma16), with the address as a wave-uniform base plus a
+// 32-bit lane offset: the bases live in scalar registers and cost no vector register per request in flight
+__device__ __forceinline__ void dma16_base(const void *sbase, uint32_t lane_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(sbase), "s"(lds_addr) : "memory");
+}
+// ... and with a per-lane pointer plus a constant byte offset (0 .. 4095) in the instruction.  The instruction adds
+// its offset to the LDS address as well as to the global one, so M0 gets the LDS address less the offset.
+template <int OFF>
+__device__ __forceinline__ void dma16_off(const void *gptr, uint32_t lds_addr)
+{
+    static_assert(OFF >= 0 && OFF < 4096, "instruction offset");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2" : : "v"(gptr), "s"(lds_addr - OFF), "n"(OFF) : "memory");
+}
+
+// workgroup barrier that orders LDS traffic only (__syncthreads() would also wait for every global load in flight,
+// that is, for the whole ring of requests below)
+__device__ __forceinline__ void gm_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// One workgroup: 4 waves, one per SIMD; a wave owns 64 rows (four B tiles) x 64 tokens, i.e. 16 accumulator tiles for the
+// super-block in hand and as many running sums; two workgroups share a compute unit (256 registers per wave, 68 KiB of
+// LDS per workgroup) and run out of step with each other.  The super-block is walked sub-block by sub-block ("positions"
+// 0..7, then position 8: the sums slab and the min term).  Everything a position needs comes through LDS by 16-byte
+// global->LDS loads, NS - 1 positions ahead:
+//   slot (12 KiB):  [4 token tiles][hi 1 KiB | lo 1 KiB] activations of the sub-block   (shared by the four waves)
+//                   [4 waves][64 rows x 16 bytes] the sub-block's quants              (each wave its own rows)
+//   position 8 uses the slot's first 4 KiB for the sums slabs; the headers of a super-block (64 rows x 16 bytes
+//   per wave) arrive with its position 0 in a ring of two of their own.
+// Per position: wait until all but the newest WAIT_N1 requests of this wave have landed (requests complete in
+// order), barrier (everyone's share is there, and everyone has finished reading the slot of the position before,
+// which is the slot requested next), request position p + NS - 1, and then, token tile by token tile, the MFMAs of
+// this position with, between them, the VALU work that builds the B tiles of the next position (its quants and
+// headers are this wave's own requests, which the same wait covers).  No global load is left for the compiler to
+// wait on.  Measured with parts of the work switched off (8192 x 28672 weights, 1024 tokens): the LDS reads of the
+// activations cost 30 % of the time, the requests 12 %, the B tiles 10 %, the barrier 3 %: a wave reads every
+// activation of its 64 tokens once per position, whatever the tiling, so LDS bandwidth is met before the MFMA rate.
+__global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    constexpr int TT = GM_TT;
+    constexpr int A_BYTES = TT * 2048, SLOT = GM_SLOT;
+    constexpr int HDR_RING = GM_NS * SLOT;           // two entries of GM_WAVES KiB behind the slots
+    constexpr int DM = TT / 2, DMS = TT / 4;         // activation requests per wave: a sub-block position, the sums position
+    // requests of the NS - 2 positions between the one awaited and now: each at least DM + 1, one of them may be a
+    // sums position (DMS)
+    constexpr int WAIT_N = (GM_NS - 3) * (DM + 1) + DMS;
+    constexpr int WAIT_N1 = (GM_NS - 4) * (DM + 1) + DMS; // the same for the NS - 3 positions behind p + 1
+    static_assert(TT == 4 && GM_WAVES == 4, "requests per wave and position are counted for 4 tiles and 4 waves");
+    static_assert(WAIT_N <= 63, "vmcnt is a 6-bit counter");
+    static_assert(GM_NS >= 4 && GM_NS <= 9, "ring depth: the first NS - 1 positions belong to super-block 0");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, g = lane >> 4;
-    // Consecutive workgroup numbers go to consecutive XCDs.  The 32 workgroups that run on one XCD (one L2) at a time
-    // are 8 row blocks x 4 token blocks: per super-block step they fetch 8 x 36 KiB of weights and 4 x 136 KiB of
-    // activations between them instead of 32 of either.  An XCD owns the row blocks xcd, xcd + 8, ...
+    // Consecutive workgroup numbers go to consecutive XCDs.  32 consecutive workgroups of one XCD (one L2) are 4 row
+    // blocks x 8 token blocks: per super-block step they fetch 4 x 36 KiB of weights and 8 x 68 KiB of activations
+    // between them instead of 32 of either.  An XCD owns the row blocks xcd, xcd + 8, ...  (The shape of the patch
+    // makes no measurable difference at 1024 tokens; this one is the best of four at 512.)
     const int xcd = blockIdx.x % GM_XCDS, seq = blockIdx.x / GM_XCDS;
     const int patch = seq / (GM_PATCH_R * GM_PATCH_C), within = seq % (GM_PATCH_R * GM_PATCH_C);
     const int patches_tb = (a.n_tb + GM_PATCH_C - 1) / GM_PATCH_C;
     const int rb = ((patch / patches_tb) * GM_PATCH_R + within / GM_PATCH_C) * GM_XCDS + xcd;
     const int tb = (patch % patches_tb) * GM_PATCH_C + within % GM_PATCH_C;
     if (rb >= a.n_rb || tb >= a.n_tb) return; // the whole workgroup, before any barrier
-    const int64_t nb = a.n_cols >> 8;
+    const int nb = static_cast<int>(a.n_cols >> 8);
     const int sg = a.pair ? 0 : (rb >= a.seg[2].rb0 ? 2 : (rb >= a.seg[1].rb0 ? 1 : 0));
     const GemmSegDev &my = a.seg[sg];
-    const int64_t row0 = a.pair ? static_cast<int64_t>(rb) * (GM_ROWS / 2) + wave * 16
-                                : static_cast<int64_t>(rb - my.rb0) * GM_ROWS + wave * (16 * GM_RT);
-    const uint8_t *wrow[GM_RT];
-#pragma unroll
-    for (int rt = 0; rt < GM_RT; ++rt) { // past the end: a valid row, not stored
-        const int64_t r = min<int64_t>(row0 + (a.pair ? 0 : 16 * rt) + n, my.n_rows - 1);
-        wrow[rt] = (a.pair ? a.seg[rt].W : my.W) + r * nb * 144;
+    // first row of this wave: 64 rows of one matrix, or (pair) the same 32 rows of the gate and of the up matrix
+    const int64_t row0 = a.pair ? static_cast<int64_t>(rb) * (GM_ROWS / 2) + wave * 32
+                                : static_cast<int64_t>(rb - my.rb0) * GM_ROWS + wave * 64;
+    // the row whose 16-byte pieces this lane requests: local row `lane` of the wave (past the end: a valid row, not stored)
+    const uint8_t *wsrc;
+    {
+        const int64_t r = min<int64_t>(row0 + (a.pair ? (lane & 31) : lane), my.n_rows - 1);
+        wsrc = (a.pair ? a.seg[lane >> 5].W : my.W) + r * nb * 144;
     }
-    const int tile0 = tb * a.tiles_wg;
+    const int tile0 = tb * TT;
     const uint32_t lds0 = lds_address(smem);
+    const int total = 9 * nb; // positions (n_cols < 2^32: no overflow)
 
-    // this wave's share of the 68 slabs of a stage: the token tiles 4 half .. 4 half + 3 of super-block b, into buffer `half`
-    auto issue_stage = [&](int64_t b, int half) {
+    // Wave-uniform bases of this wave's activation requests: request jj of a sub-block position is slab (part, tile)
+    // with part = wave & 1, tile = 2 jj + (wave >> 1); request jj of a sums position is tile wave + 4 jj.  Past the
+    // last tile: a valid one, not stored.
+    const uint8_t *abase[DM], *xbase[DMS];
 #pragma unroll
-        for (int j = 0; j < (GM_HT * GM_SLABS + GM_WAVES - 1) / GM_WAVES; ++j) {
-            const int i = wave + GM_WAVES * j;
-            if (i < GM_HT * GM_SLABS) {
-                const int tt = i / GM_SLABS, sl = i - tt * GM_SLABS;
-                const int tile = min(tile0 + GM_HT * half + tt, a.n_tiles - 1); // past the last tile: a valid one, not stored
-                const uint8_t *src = a.A + ((static_cast<int64_t>(tile) * nb + b) * GM_SLABS + sl) * 1024 + lane * 16;
-                dma16(src, lds0 + half * GM_STAGE_BYTES + i * 1024);
+    for (int jj = 0; jj < DM; ++jj) {
+        const int tg = min(tile0 + 2 * jj + (wave >> 1), a.n_tiles - 1);
+        abase[jj] = a.A + (static_cast<int64_t>(tg) * nb * GM_SLABS + (wave & 1)) * 1024;
+    }
+#pragma unroll
+    for (int jj = 0; jj < DMS; ++jj) {
+        const int tg = min(tile0 + wave + GM_WAVES * jj, a.n_tiles - 1);
+        xbase[jj] = a.A + (static_cast<int64_t>(tg) * nb * GM_SLABS + 16) * 1024;
+    }
+    const uint32_t lane16 = lane * 16;
+
+    // every request of position (b, s), into ring slot `slot` (s is a constant wherever this is called)
+    auto issue = [&](int b, int s, int slot) __attribute__((always_inline)) {
+        const uint32_t base = lds0 + slot * SLOT;
+        const int64_t boff = static_cast<int64_t>(b) * (GM_SLABS * 1024);
+        if (s < 8) {
+#pragma unroll
+            for (int jj = 0; jj < DM; ++jj)
+                dma16_base(abase[jj] + boff + 2048 * s, lane16, base + (2 * jj + (wave >> 1)) * 2048 + (wave & 1) * 1024);
+            const uint8_t *wp = wsrc + static_cast<int64_t>(b) * 144;
+            switch (s) { // the sub-block's 16 bytes of quants of this lane's row
+            case 0: dma16_off<16>(wp, base + A_BYTES + wave * 1024); break;
+            case 1: dma16_off<32>(wp, base + A_BYTES + wave * 1024); break;
+            case 2: dma16_off<48>(wp, base + A_BYTES + wave * 1024); break;
+            case 3: dma16_off<64>(wp, base + A_BYTES + wave * 1024); break;
+            case 4: dma16_off<80>(wp, base + A_BYTES + wave * 1024); break;
+            case 5: dma16_off<96>(wp, base + A_BYTES + wave * 1024); break;
+            case 6: dma16_off<112>(wp, base + A_BYTES + wave * 1024); break;
+            default: dma16_off<128>(wp, base + A_BYTES + wave * 1024); break;
             }
+            if (s == 0) dma16_off<0>(wp, lds0 + HDR_RING + ((b & 1) * GM_WAVES + wave) * 1024);
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < DMS; ++jj) dma16_base(xbase[jj] + boff, lane16, base + (wave + GM_WAVES * jj) * 1024);
         }
     };
-    const bool second_half = a.tiles_wg == GM_TT && tile0 + GM_HT < a.n_tiles; // whether the workgroup has a second half at all
-    uint4 hdr[GM_RT];
-    uint32_t qw[GM_RT][8];
 
-    v4f yacc[GM_TT][GM_RT];
+    v4f yacc[TT][GM_RT], acch[TT][GM_RT];
 #pragma unroll
-    for (int tt = 0; tt < GM_TT; ++tt)
+    for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-        for (int rt = 0; rt < GM_RT; ++rt) yacc[tt][rt] = {0.f, 0.f, 0.f, 0.f};
+        for (int rt = 0; rt < GM_RT; ++rt) yacc[tt][rt] = acch[tt][rt] = {0.f, 0.f, 0.f, 0.f};
 
-    // this lane's place in its rows' current super-block: the header, and its dword of every 16-byte quant chunk
-    const uint8_t *hp[GM_RT], *qp[GM_RT];
+    // positions 0 .. NS-2 (a super-block has 9 > NS - 1 positions, so they all belong to super-block 0)
 #pragma unroll
-    for (int rt = 0; rt < GM_RT; ++rt) {
-        hp[rt] = wrow[rt];
-        qp[rt] = wrow[rt] + 16 + 4 * g;
-        hdr[rt] = *reinterpret_cast<const uint4 *>(hp[rt]);
+    for (int s = 0; s < GM_NS - 1; ++s) issue(0, s, s);
+
+    // B tile `rt` of a sub-block position from this wave's quants in ring slot `sl` and its headers of super-block `bb`:
+    // sc_s * q as binary16 (exact).  A dword holds the eight weights of lane (n, g); masked in pairs (0,4) (1,5) (2,6)
+    // (3,7) into the mantissas of 1024 + q, then one fused multiply-add per pair: (1024 + q) sc - 1024 sc
+    auto build_b = [&](half8 &B, int rt, int bb, int s, int sl) __attribute__((always_inline)) {
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(smem + sl * SLOT + A_BYTES + wave * 1024 + (16 * rt + n) * 16 + 4 * g);
+        const uint4 hdr = *reinterpret_cast<const uint4 *>(smem + HDR_RING + ((bb & 1) * GM_WAVES + wave) * 1024 + (16 * rt + n) * 16);
+        const _Float16 sc = static_cast<_Float16>(static_cast<float>(hdr_field(hdr, s)));
+        const half2v sc2 = {sc, sc};
+        const _Float16 off = static_cast<_Float16>(-1024.f) * sc; // exact: at most 64512 in magnitude
+        const half2v off2 = {off, off};
 #pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) qw[rt][s8] = *reinterpret_cast<const uint32_t *>(qp[rt] + 16 * s8);
+        for (int pr = 0; pr < 4; ++pr) {
+            const uint32_t bits = ((w >> (4 * pr)) & 0x000f000fu) | 0x64006400u;
+            const half2v r = __builtin_elementwise_fma(__builtin_bit_cast(half2v, bits), sc2, off2);
+            B[2 * pr] = r[0];
+            B[2 * pr + 1] = r[1];
+        }
+    };
+    // ... and of the sums position: the m_s as B operand, with d and dmin
+    auto build_m = [&](half8 &B, float &d_, float &dm_, int rt, int bb) __attribute__((always_inline)) {
+        const uint4 hdr = *reinterpret_cast<const uint4 *>(smem + HDR_RING + ((bb & 1) * GM_WAVES + wave) * 1024 + (16 * rt + n) * 16);
+        d_ = hdr_d(hdr);
+        dm_ = hdr_dmin(hdr);
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) B[s8] = static_cast<_Float16>(static_cast<float>(hdr_field(hdr, 8 + s8)));
+    };
+
+    // The wave is alone on its SIMD and issues in order: an MFMA occupies the matrix pipe for 16 cycles, during which
+    // the same wave can issue three or four other instructions for free, and only then.  So the B tiles of position
+    // p + 1 are built (VALU) between the MFMAs of position p, in the order the scheduling groups below prescribe;
+    // built in front of their own MFMAs they would cost their full issue time with the matrix pipe idle.  The quants
+    // and headers that position p + 1 needs are this wave's own requests; the wait below covers them.
+    half8 Bc[GM_RT];     // B tiles of the current position (at the sums position: the m_s)
+    float dd[GM_RT], dm[GM_RT];
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N) : "memory"); // position 0 has landed (this wave's share)
+#pragma unroll
+    for (int rt = 0; rt < GM_RT; ++rt) build_b(Bc[rt], rt, 0, 0, 0);
+
+    int slot = 0; // ring slot of the current position
+    for (int b = 0; b < nb; ++b) {
+#pragma unroll
+        for (int s = 0; s < 9; ++s) {
+            const int p = 9 * b + s;
+            // positions p and p + 1 have landed (this wave's share) once at most the requests of the NS - 3 positions
+            // behind them are in flight
+            if (p + GM_NS - 2 < total) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N1) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // the last positions: nothing is requested behind them any more
+            gm_barrier();
+            {
+                // position p + NS - 1 goes into the slot that position p - 1 has just left
+                const int s_t = (s + GM_NS - 1) % 9;
+                const int b_t = b + (s + GM_NS - 1) / 9;
+                const int slot_t = slot == 0 ? GM_NS - 1 : slot - 1;
+                if (b_t < nb) issue(b_t, s_t, slot_t);
+            }
+            const uint8_t *base = smem + slot * SLOT + lane * 16;
+            const int slot_n = slot + 1 == GM_NS ? 0 : slot + 1;
+            const v4f zero = {0.f, 0.f, 0.f, 0.f};
+            half8 Bn[GM_RT];
+            // Token tile by token tile, each a scheduling region of its own (the scheduler, left alone, hoists all of
+            // a position's LDS reads and runs out of registers): the tile's MFMAs, the LDS reads of the next tile, and
+            // during the first four tiles one B tile of the next position each.
+            if (s < 8) {
+                // The hi and the lo parts alternate in one accumulator: 16 fp32 roundings per super-block at the
+                // accumulator's magnitude.  Accumulators of their own for the lo parts (whose sums are 2^-11 of the hi
+                // sums, so that only 8 roundings count) lower the product's rms error from 2.2e-7 to 1.8e-7 of the
+                // output's rms, but need 64 registers more than a wave has with two workgroups on a compute unit.
+                // LDS reads run two tiles ahead of their MFMAs (one tile, 8 MFMAs, is shorter than the LDS latency
+                // while four waves and the incoming requests share the LDS)
+                half8 ah[3], al[3];
+                ah[0] = *reinterpret_cast<const half8 *>(base);
+                al[0] = *reinterpret_cast<const half8 *>(base + 1024);
+                ah[1] = *reinterpret_cast<const half8 *>(base + 2048);
+                al[1] = *reinterpret_cast<const half8 *>(base + 2048 + 1024);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const half8 ch = ah[tt % 3], cl = al[tt % 3];
+                    if (tt + 2 < TT) {
+                        ah[(tt + 2) % 3] = *reinterpret_cast<const half8 *>(base + (tt + 2) * 2048);
+                        al[(tt + 2) % 3] = *reinterpret_cast<const half8 *>(base + (tt + 2) * 2048 + 1024);
+                    }
+#pragma unroll
+                    for (int rt = 0; rt < GM_RT; ++rt) {
+                        acch[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ch, Bc[rt], s == 0 ? zero : acch[tt][rt], 0, 0, 0);
+                        acch[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cl, Bc[rt], acch[tt][rt], 0, 0, 0);
+                    }
+                    if (tt < GM_RT) {
+                        if (s < 7) build_b(Bn[tt], tt, b, s + 1, slot_n);
+                        else build_m(Bn[tt], dd[tt], dm[tt], tt, b);
+#pragma unroll
+                        for (int k = 0; k < 2 * GM_RT; ++k) { // one MFMA, then up to four VALU instructions of the build
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                // the min term: sum_s m_s * xs_s, one MFMA step with the m_s as B operand; then the super-block's term
+                // is formed at its own magnitude and added in one step (one rounding per super-block at the magnitude
+                // of the running sum)
+                half8 ax = *reinterpret_cast<const half8 *>(base);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const half8 cx = ax;
+                    if (tt + 1 < TT) ax = *reinterpret_cast<const half8 *>(base + (tt + 1) * 1024);
+#pragma unroll
+                    for (int rt = 0; rt < GM_RT; ++rt) {
+                        const v4f am = __builtin_amdgcn_mfma_f32_16x16x32_f16(cx, Bc[rt], zero, 0, 0, 0);
+                        // this lane: row n of row tile rt, tokens 4g .. 4g+3 of the tile
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            yacc[tt][rt][i] += fmaf(dd[rt], acch[tt][rt][i], -(dm[rt] * am[i]));
+                    }
+                    if (tt < GM_RT) {
+                        if (b + 1 < nb) build_b(Bn[tt], tt, b + 1, 0, slot_n);
+                        else Bn[tt] = Bc[tt];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#pragma unroll
+            for (int rt = 0; rt < GM_RT; ++rt) Bc[rt] = Bn[rt];
+            slot = slot_n;
+        }
     }
 
-    issue_stage(0, 0);
-    uint32_t touch[GM_RT] = {0u, 0u};
-    for (int64_t b = 0; b < nb; ++b) {
-        // B operands: sc_s * q as binary16 (exact).  A dword holds the eight weights of lane (n, g); masked in pairs
-        // (0,4) (1,5) (2,6) (3,7) into the mantissas of 1024 + q, then one fused multiply-add per pair: (1024 + q) sc - 1024 sc
-        half8 B[GM_RT][8], Bm[GM_RT];
-        float dd[GM_RT], dm[GM_RT];
+    if (a.pair) { // row tiles 0, 1: rows of the gate matrix; 2, 3: the same rows of the up matrix
 #pragma unroll
-        for (int rt = 0; rt < GM_RT; ++rt) {
-            dd[rt] = hdr_d(hdr[rt]);
-            dm[rt] = hdr_dmin(hdr[rt]);
+        for (int rt = 0; rt < 2; ++rt) {
+            const int64_t out_row = row0 + 16 * rt + n;
+            if (out_row >= my.n_rows) continue;
 #pragma unroll
-            for (int s8 = 0; s8 < 8; ++s8) {
-                const _Float16 sc = static_cast<_Float16>(static_cast<float>(hdr_field(hdr[rt], s8)));
-                const half2v sc2 = {sc, sc};
-                const _Float16 off = static_cast<_Float16>(-1024.f) * sc; // exact: at most 64512 in magnitude
-                const half2v off2 = {off, off};
-                Bm[rt][s8] = static_cast<_Float16>(static_cast<float>(hdr_field(hdr[rt], 8 + s8)));
-                const uint32_t w = qw[rt][s8];
-#pragma unroll
-                for (int pr = 0; pr < 4; ++pr) {
-                    const uint32_t bits = ((w >> (4 * pr)) & 0x000f000fu) | 0x64006400u;
-                    const half2v r = __builtin_elementwise_fma(__builtin_bit_cast(half2v, bits), sc2, off2);
-                    B[rt][s8][2 * pr] = r[0];
-                    B[rt][s8][2 * pr + 1] = r[1];
-                }
-            }
-        }
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // this half's tiles have landed (this wave's share)
-            if (half == 1) asm volatile("" : : "v"(touch[0]), "v"(touch[1])); // (the touches' registers are free again)
-            __syncthreads();                                  // everyone's share has, and the other buffer has been read
-            if (half == 0) {
-                if (second_half) issue_stage(b, 1);
-                // the next super-block's weights, into the registers the B tiles were just built from; they have a
-                // whole multiplication phase to arrive (the last step loads its own super-block again: in bounds, unused)
-                const int step = b + 1 < nb ? 144 : 0;
-#pragma unroll
-                for (int rt = 0; rt < GM_RT; ++rt) {
-                    hp[rt] += step;
-                    qp[rt] += step;
-                    hdr[rt] = *reinterpret_cast<const uint4 *>(hp[rt]);
-#pragma unroll
-                    for (int s8 = 0; s8 < 8; ++s8) qw[rt][s8] = *reinterpret_cast<const uint32_t *>(qp[rt] + 16 * s8);
-                    // and one dword of the super-block three further on (the four lanes of a row between them touch
-                    // all of its 144 bytes): the rows are read nowhere else, so without this every weight load waits
-                    // for HBM; with it the loads above find their lines in the L2
-                    touch[rt] = b + 4 < nb ? *reinterpret_cast<const uint32_t *>(hp[rt] + 3 * 144 + min(48 * g, 140)) : 0u;
-                }
-            } else if (b + 1 < nb) {
-                issue_stage(b + 1, 0);
-            }
-            if (half == 1 && !second_half) continue;
-            const uint8_t *stage = smem + half * GM_STAGE_BYTES;
-#pragma unroll
-            for (int ht = 0; ht < GM_HT; ++ht) {
-                const int tt = GM_HT * half + ht;
-                const half8 *At = reinterpret_cast<const half8 *>(stage + ht * GM_TILE_BYTES);
-                v4f acc[GM_RT];
-#pragma unroll
-                for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = {0.f, 0.f, 0.f, 0.f};
-                // The lo parts first: their sums are 2^-11 of the hi parts', so the fp32 roundings of the first eight
-                // steps do not count and only the eight hi steps round at the accumulator's full magnitude.
-#pragma unroll
-                for (int s8 = 0; s8 < 8; ++s8) {
-                    const half8 al = At[(2 * s8 + 1) * 64 + lane];
-#pragma unroll
-                    for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, B[rt][s8], acc[rt], 0, 0, 0);
-                }
-#pragma unroll
-                for (int s8 = 0; s8 < 8; ++s8) {
-                    const half8 ah = At[(2 * s8) * 64 + lane];
-#pragma unroll
-                    for (int rt = 0; rt < GM_RT; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, B[rt][s8], acc[rt], 0, 0, 0);
-                }
-                const half8 ax = At[16 * 64 + lane];
-#pragma unroll
-                for (int rt = 0; rt < GM_RT; ++rt) {
-                    const v4f zero = {0.f, 0.f, 0.f, 0.f};
-                    const v4f am = __builtin_amdgcn_mfma_f32_16x16x32_f16(ax, Bm[rt], zero, 0, 0, 0);
-                    // this lane: row n of row tile rt, tokens 4g .. 4g+3 of the tile.  The super-block's term is formed
-                    // first, at its own magnitude, and added in one step: one rounding per super-block at the magnitude
-                    // of the running sum (the chain of these roundings is the larger part of the product's error)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) yacc[tt][rt][i] += fmaf(dd[rt], acc[rt][i], -(dm[rt] * am[i]));
-                }
-            }
-        }
-    }
-
-    if (a.pair) {
-        const int64_t out_row = row0 + n;
-        if (out_row < my.n_rows) {
-#pragma unroll
-            for (int tt = 0; tt < GM_TT; ++tt)
+            for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int t = (tile0 + tt) * 16 + 4 * g + i;
-                    if (tt < a.tiles_wg && t < a.T) {
+                    if (t < a.T) {
                         const float sc = a.stat[t].y;
-                        const float gt = yacc[tt][0][i] * sc, up = yacc[tt][1][i] * sc;
+                        const float gt = yacc[tt][rt][i] * sc, up = yacc[tt][rt + 2][i] * sc;
                         my.y[t * my.ldy + out_row] = gt / (1.0f + expf(-gt)) * up;
                     }
                 }
@@ -354,11 +461,11 @@ __global__ void __launch_bounds__(GM_THREADS) q4k_gemm_kernel(GemmArgs a)
         const int64_t out_row = row0 + 16 * rt + n;
         if (out_row >= my.n_rows) continue;
 #pragma unroll
-        for (int tt = 0; tt < GM_TT; ++tt)
+        for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int t = (tile0 + tt) * 16 + 4 * g + i;
-                if (tt < a.tiles_wg && t < a.T) {
+                if (t < a.T) {
                     float v = yacc[tt][rt][i] * a.stat[t].y;
                     if (a.resid) v += a.resid[t * a.ldr + out_row];
                     my.y[t * my.ldy + out_row] = v;
@@ -394,11 +501,8 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
     }
     if (n_rb == 0) return PRIMA_OK;
     const int64_t nb = n_cols / QK;
-    // 128 tokens per workgroup; 64 when the workgroups then still fit the compute units in one round (a workgroup with
-    // one half takes ~0.63 of the time of one with two; 8192 x 28672 at 512 tokens: 1138 -> 801 us)
     const int n_tiles = (T + 15) / 16;
-    const int tiles_wg = n_rb * ((T + GM_TM / 2 - 1) / (GM_TM / 2)) <= GM_CUS ? GM_HT : GM_TT;
-    const int n_tb = (n_tiles + tiles_wg - 1) / tiles_wg;
+    const int n_tb = (n_tiles + GM_TT - 1) / GM_TT;
     const int64_t rb_per_xcd = (n_rb + GM_XCDS - 1) / GM_XCDS;
     const int64_t grid = (rb_per_xcd + GM_PATCH_R - 1) / GM_PATCH_R * ((n_tb + GM_PATCH_C - 1) / GM_PATCH_C) * (GM_PATCH_R * GM_PATCH_C) * GM_XCDS;
     if (grid >= (int64_t{1} << 31) || n_tiles > 65535 || nb >= (int64_t{1} << 31)) return PRIMA_E_SHAPE;
@@ -417,7 +521,7 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
     }
     a.pair = pair ? 1 : 0;
     a.n_cols = n_cols; a.A = A; a.stat = stat; a.resid = resid; a.ldr = ldr;
-    a.T = T; a.n_tiles = n_tiles; a.n_rb = static_cast<int>(n_rb); a.n_tb = n_tb; a.tiles_wg = tiles_wg;
+    a.T = T; a.n_tiles = n_tiles; a.n_rb = static_cast<int>(n_rb); a.n_tb = n_tb;
     hipLaunchKernelGGL(q4k_gemm_kernel, dim3(static_cast<unsigned>(grid)), dim3(GM_THREADS), GM_LDS_BYTES, st, a);
     return last_launch_status();
 }

@@ -13,7 +13,7 @@ from metrics import rel_err
 pytestmark = pytest.mark.gpu
 
 HID_TOL = 2e-3
-ARITH_TOL = 2e-5   # 22-bit activations and fp32 accumulation over at most 28672 columns
+ARITH_TOL = 3e-6   # 22-bit activations and fp32 accumulation over at most 28672 columns: observed at most 1.7e-6
 
 
 def _dev(a):
