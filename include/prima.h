@@ -348,7 +348,7 @@ prima_status prima_layer_window_prefill_mixed(const prima_dims *d, const prima_l
                                               void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t prima_prefill_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
 /* Prompts of up to n tokens are advanced by the decode kernels, PRIMA_MAX_TOK tokens at a time, inside the prompt call
- * (default 96: below about 100 tokens that is faster than the matrix product, whose workgroups each walk all of K).
+ * (default 64: up to about 70 tokens that is faster than the matrix product, whose workgroups each walk all of K).
  * 0: always the matrix product (tests).  Process-wide; not to be changed while a call is being enqueued. */
 void prima_set_prefill_small_tokens(int32_t n);
 

@@ -102,9 +102,9 @@ void layer_gemv_args(const prima_dims &d, const prima_layer &L, int T, const flo
 }
 
 // prompts of up to this many tokens go through the decode kernels, PRIMA_MAX_TOK tokens a call (measured on config 3's shape,
-// ms per layer, matrix-product route / decode route: 48 tokens 2.04 / 1.09, 64: 2.06 / 1.46, 96: 2.50 / 2.19, 128: 2.54 / 2.92,
-// 192: 2.55 / 4.39)
-int g_prefill_small_tokens = 96;
+// ms per layer, matrix-product route / decode route: 32 tokens 1.57 / 0.74, 48: 1.59 / 1.10, 64: 1.62 / 1.47, 80: 1.61 / 1.84,
+// 128: 1.62 / 2.94, 256: 1.67 / 5.89).  A process-wide setting, read when a prompt call is enqueued.
+int g_prefill_small_tokens = 64;
 
 // one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Five launches: Q/K/V projections
 // (RMSNorm fused), attention (RoPE + KV append fused, key ranges merged by the last arriver), output projection

@@ -38,17 +38,17 @@ def _oracle_prompt(dims, host, x, n_past, formats=None):
 @pytest.fixture(params=["matrix product", "default"])
 def route(request, gpu_lib):
     """The prompt call's two routes: always the matrix product (threshold 0), or the library's default, which advances
-    prompts of up to 96 tokens with the decode kernels."""
-    gpu_lib.set_prefill_small_tokens(0 if request.param == "matrix product" else 96)
+    prompts of up to 64 tokens with the decode kernels."""
+    gpu_lib.set_prefill_small_tokens(0 if request.param == "matrix product" else gpu_lib.PREFILL_SMALL_TOKENS)
     yield request.param
-    gpu_lib.set_prefill_small_tokens(96)
+    gpu_lib.set_prefill_small_tokens(gpu_lib.PREFILL_SMALL_TOKENS)
 
 
 @pytest.fixture
 def matrix_product_route(gpu_lib):
     gpu_lib.set_prefill_small_tokens(0)
     yield
-    gpu_lib.set_prefill_small_tokens(96)
+    gpu_lib.set_prefill_small_tokens(gpu_lib.PREFILL_SMALL_TOKENS)
 
 
 def _window(gpu_lib, cfg, cap, host):
@@ -163,7 +163,7 @@ def test_prefill_agrees_with_decode_calls(gpu_lib, matrix_product_route):
     xc = xd.clone()
     yc = wc.prefill(xc, 10, x_out=xc)
     assert torch.equal(yb, yc)
-    gpu_lib.set_prefill_small_tokens(96)
+    gpu_lib.set_prefill_small_tokens(gpu_lib.PREFILL_SMALL_TOKENS)
     wd, _ = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
     assert np.array_equal(wd.prefill(xd, 10).cpu().numpy(), ya)
 

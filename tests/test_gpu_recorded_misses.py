@@ -56,7 +56,7 @@ def test_recorded_mixed_format_window(gpu_lib):
     check_hidden("recorded mixed-format window", err, cfg.dims, host, x.astype(np.float64), 0, formats=[fm], eps=EPS_FP32)
 
 
-@pytest.mark.parametrize("small_tokens", [0, 96])
+@pytest.mark.parametrize("small_tokens", [0, 64])
 @pytest.mark.parametrize("cid,dims", [(533, ModelDims(512, 20, 4, 128, 768, 1e4, rope_mode=1)),
                                       (572, ModelDims(1024, 2, 1, 128, 1280, 1e4, rope_mode=1))])
 def test_recorded_prompt_calls(gpu_lib, cid, dims, small_tokens):
@@ -72,7 +72,7 @@ def test_recorded_prompt_calls(gpu_lib, cid, dims, small_tokens):
         wa = gpu_lib.Window(dims, [{k: _dev(v) for k, v in host[0].items()}], cap, T_max=16)
         yp = wa.prefill(xd, 0).cpu().numpy()
     finally:
-        gpu_lib.set_prefill_small_tokens(96)
+        gpu_lib.set_prefill_small_tokens(gpu_lib.PREFILL_SMALL_TOKENS)
     wb = gpu_lib.Window(dims, [{k: _dev(v) for k, v in host[0].items()}], cap, T_max=16)
     yd = torch.cat([wb.decode(xd[t:t + 16].contiguous(), t) for t in range(0, 150, 16)]).cpu().numpy()
     ep, ed = rel_err(yp, ref), rel_err(yd, ref)
@@ -140,7 +140,7 @@ def test_sweep_of_mixed_format_windows(gpu_lib):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("small_tokens", [0, 96])
+@pytest.mark.parametrize("small_tokens", [0, 64])
 def test_sweep_of_prompt_calls(gpu_lib, small_tokens):
     """40 prompt calls of random shape and length (1 to 150 tokens behind 0 to 200 rows, one or two layers), on the
     matrix-product route and on the default route."""
@@ -163,7 +163,7 @@ def test_sweep_of_prompt_calls(gpu_lib, small_tokens):
             err = rel_err(y, _oracle_any_T(dims, host, x, n_past))
             check_hidden(f"prompt call {n} (threshold {small_tokens})", err, dims, host, x.astype(np.float64), n_past)
     finally:
-        gpu_lib.set_prefill_small_tokens(96)
+        gpu_lib.set_prefill_small_tokens(gpu_lib.PREFILL_SMALL_TOKENS)
     used = len(tolerance.excused) - before
     print("prompt sweep: cases excused by the computed bound:", used, "of 40", flush=True)
     assert used <= 8
