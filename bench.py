@@ -20,9 +20,21 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 
-# HBM bytes of one gate/up launch of config 3 from the rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs (scaled by
-# what the same counters read for a plain 256 MiB copy): see profiles/gemv_q4k_persistent_c3_hbm_traffic.txt
-GATE_UP_TRAFFIC_BYTES = 265_153_000
+def gate_up_traffic_bytes():
+    """HBM bytes of one gate/up launch of config 3 (one token) as the committed counter summary states them:
+    rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a plain 256 MiB copy
+    (profiles/gemv_q4k_persistent_c3_hbm_traffic.txt, the "gate/up projections" row).  None if the file or the row is
+    not there."""
+    import re
+    try:
+        with open(os.path.join(ROOT, "profiles", "gemv_q4k_persistent_c3_hbm_traffic.txt")) as f:
+            for line in f:
+                if line.startswith("gate/up projections"):
+                    m = re.search(r"\)\s+[0-9.]+\s+([0-9][0-9 ]+[0-9])\s+\(read", line)
+                    return int(m.group(1).replace(" ", "")) if m else None
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -267,7 +279,7 @@ def run_window_config(args, cfg, steps, warmup, want_cpu, with_probe, copy_calib
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "bytes_per_launch": gate_up_bytes,
             "avg_launch_us": round(gu_us, 2),
-            "traffic": GATE_UP_TRAFFIC_BYTES if (cfg.name == "c3" and cfg.T == 1 and GATE_UP_TRAFFIC_BYTES) else None,
+            "traffic": gate_up_traffic_bytes() if (cfg.name == "c3" and cfg.T == 1) else None,
         },
     }
     if stream_read_gbps is not None:
