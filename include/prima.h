@@ -24,6 +24,12 @@
  *      16-143 quants (weight t in byte 16 + t/2, low nibble when t is even);
  *      w[t] = d*sc_s*q[t] - dmin*m_s with s = t/32.
  *  - T (tokens advanced jointly) must satisfy 1 <= T <= PRIMA_MAX_TOK.
+ *  - Threads and devices.  One device per process: kernel attributes and the number of compute units are looked
+ *    up once, for the device that is current at the first call; calls with another device current may be refused
+ *    with PRIMA_E_DEVICE.  Entry points may be called from several host threads as long as no two calls that share
+ *    a workspace, a cache or an output are in flight together (the library keeps no state of its own between
+ *    calls, apart from the scratch of prima_q4k_gemv_noalloc and one process-wide setting,
+ *    prima_set_prefill_small_tokens, which must not change while another thread enqueues a prompt call).
  */
 #ifndef PRIMA_H
 #define PRIMA_H

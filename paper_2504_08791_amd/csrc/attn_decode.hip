@@ -25,6 +25,8 @@
 //    in one go and repeats the request until no word shows the pattern (the ranges finish together, so the first or
 //    second request succeeds), merges, and writes the pattern back for the next launch.  The polling is bounded
 //    (error flag in the scratch); the other workgroups wait for nothing, so the launch always drains.
+#include <atomic>
+
 #include "attn_common.h"
 
 namespace prima {
@@ -535,7 +537,7 @@ prima_status launch_attn_prompt(const prima_dims &d, const float *q, __half *K, 
 static prima_status launch_attn_kernel(const prima_dims &d, dim3 grid, const AttnArgs &a, hipStream_t st)
 {
     const dim3 block(ATT_THREADS);
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false}; // set twice by two threads at worst: the attribute call is idempotent
     if (!attr_set) {
         const void *fns[] = {reinterpret_cast<const void *>(attn_decode_kernel<128, 0>), reinterpret_cast<const void *>(attn_decode_kernel<128, 1>),
                              reinterpret_cast<const void *>(attn_decode_kernel<64, 0>), reinterpret_cast<const void *>(attn_decode_kernel<64, 1>)};

@@ -31,6 +31,8 @@
 // multiplies the finished sums; every workgroup computes the mean squares itself.  Residual behind (optional).
 #include <hip/hip_fp16.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace prima {
@@ -343,7 +345,7 @@ __global__ void __launch_bounds__(FG_THREADS) fmt_gemv_kernel(FmtArgs a)
 template <int FMT, int TT, int R>
 prima_status launch_ttr(const FmtArgs &a, size_t lds, hipStream_t st)
 {
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false}; // set twice by two threads at worst: the attribute call is idempotent
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(fmt_gemv_kernel<FMT, TT, R>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 FG_X_BYTES + FG_TAIL_BYTES) != hipSuccess)

@@ -1,6 +1,7 @@
 // Declarations of the Q4_K mat-vec kernels (the design is described in q4k_gemv_mfma.hip); the body of the
 // mat-vec itself is gemv_body.inc.
 #pragma once
+#include <atomic>
 #include "common.h"
 
 namespace prima {
@@ -118,14 +119,17 @@ struct PPlan {
     bool ok;
 };
 
+// compute units of the device that is current at the first call (the library serves one device per process)
 inline int device_cu_count()
 {
-    static int cus = 0;
+    static std::atomic<int> cached{0};
+    int cus = cached.load(std::memory_order_relaxed);
     if (cus == 0) {
         int dev = 0;
         hipDeviceProp_t prop;
         if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
         if (cus <= 0) cus = 256;
+        cached.store(cus, std::memory_order_relaxed);
     }
     return cus;
 }

@@ -27,6 +27,8 @@
 // product, measured in the metric of the tests.
 #include <hip/hip_fp16.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace prima {
@@ -506,7 +508,7 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
     const int64_t rb_per_xcd = (n_rb + GM_XCDS - 1) / GM_XCDS;
     const int64_t grid = (rb_per_xcd + GM_PATCH_R - 1) / GM_PATCH_R * ((n_tb + GM_PATCH_C - 1) / GM_PATCH_C) * (GM_PATCH_R * GM_PATCH_C) * GM_XCDS;
     if (grid >= (int64_t{1} << 31) || n_tiles > 65535 || nb >= (int64_t{1} << 31)) return PRIMA_E_SHAPE;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false}; // set twice by two threads at worst: the attribute call is idempotent
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(q4k_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, GM_LDS_BYTES) != hipSuccess)
             return PRIMA_E_DEVICE;

@@ -39,6 +39,8 @@
 // Several tokens: a second small kernel adds them (the last arriver would be one workgroup for
 // nearly all tiles).  The epilogue adds the residual, or applies SwiGLU to a (gate, up) pair of tiles.
 // The body is gemv_body.inc (shared with the single-launch window kernel).
+#include <atomic>
+
 #include "gemv_common.h"
 
 namespace prima {
@@ -127,7 +129,7 @@ size_t gemv_arrivals_bytes(int64_t n_rows_total) { return arrivals_bytes(static_
 template <int TT>
 static hipError_t launch_tt(const PGemvArgs &a, const PPlan &p, hipStream_t st)
 {
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false}; // set twice by two threads at worst: the attribute call is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemv_q4k_persistent_kernel<TT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(LDS_BUDGET));

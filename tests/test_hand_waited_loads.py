@@ -7,15 +7,19 @@ import re
 import shutil
 import subprocess
 
-import pytest
-
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2504_08791_amd", "csrc")
 KERNEL = "_ZN5prima26gemv_q4k_persistent_kernelILi1EEEvNS_9PGemvArgsE"
 
 
-@pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
+def _need_hipcc():
+    # no skip: the library cannot be built without hipcc either, and a silently skipped check of hand-waited loads
+    # is worse than a red one
+    assert shutil.which("hipcc") is not None, "hipcc not found: the assembly of the hand-waited loads cannot be checked"
+
+
 def test_registers_of_early_loads_are_untouched_until_the_wait(tmp_path):
+    _need_hipcc()
     out = tmp_path / "k.s"
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-S", "--cuda-device-only", "-o", str(out),
@@ -56,8 +60,8 @@ def _regs_of(code):
     return used
 
 
-@pytest.mark.skipif(shutil.which("hipcc") is None, reason="needs hipcc")
 def test_registers_of_the_attention_merge_requests_are_untouched_until_the_wait(tmp_path):
+    _need_hipcc()
     """Every instantiation of the attention kernel: the 17 requests of a merge pass (one 8-byte, sixteen 16-byte,
     device scope, scalar base + lane offset) are followed by the hand-written wait with nothing but requests and
     scalar arithmetic in between, write 66 distinct registers, and nothing is spilled anywhere in the kernel."""
