@@ -13,7 +13,7 @@ import torch
 
 import oracle
 from metrics import rel_err
-from tolerance import EPS_FP32, EPS_Q4K, check_hidden
+from tolerance import EPS_FP32, EPS_GEMM, EPS_Q4K, check_hidden
 from workloads import synth
 from workloads.configs import CONFIGS, TINY
 
@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
 
 HID_TOL = 2e-3
 # the accuracy class of the prompt call's matrix product, asserted on the products themselves in tests/test_gpu_gemm.py
-PREFILL_EPS = EPS_Q4K
+PREFILL_EPS = EPS_GEMM
 
 
 def _dev(a):
