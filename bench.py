@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--device-profile", action="store_true",
                     help="side measurement: the device-profiler quantities of the paper's latency model on this GPU, and the "
                          "model's estimate of the config's window step next to the measured one")
+    ap.add_argument("--launch-cost", action="store_true",
+                    help="side measurement: one-token Q4_K mat-vecs of 8192 columns and 2048 to 114688 rows, cold weights; a straight "
+                         "line through time against bytes gives the fixed cost of a launch and the rate of its streaming phase")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run three plain 256 MiB device copies first (reference kernel of known traffic for counter runs)")
     args = ap.parse_args()
@@ -86,6 +89,8 @@ def main():
         return bench_prefill(args, cfg)
     if args.device_profile:
         return bench_device_profile(args, cfg)
+    if args.launch_cost:
+        return bench_launch_cost(args)
     if args.mix:
         return bench_mix(args, cfg)
     dev = torch.device("cuda:0")
@@ -631,6 +636,52 @@ def bench_mix(args, cfg):
         out["cpu_baseline"] = {"value": round(cfg.T / cpu_seconds, 4), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"the whole window once ({cpu_seconds:.1f} s of CPU time; tensor generation excluded)"}
     print(json.dumps(out), flush=True)
+
+
+def bench_launch_cost(args):
+    """Time of a one-token mat-vec launch against its bytes: launches of 8192 columns and a growing number of rows,
+    every launch on weights that the launches before it did not touch (nothing comes from the last-level cache),
+    enqueued back to back as in a window.  The least-squares line t = t0 + bytes / rate separates what a launch costs
+    whatever its size (hand-over from the launch before, prologue, tail) from the rate of its streaming phase."""
+    import numpy as np
+    import torch
+    import paper_2504_08791_amd as prima
+
+    dev = torch.device("cuda:0")
+    cols = 8192
+    stream = torch.cuda.current_stream()
+    x = torch.randn((1, cols), device=dev)
+    points = []
+    for rows in (2048, 4096, 8192, 10240, 16384, 32768, 57344, 114688):
+        nbytes = rows * (cols // 256) * 144
+        copies = max(3, int(700_000_000 // nbytes) + 1)
+        Ws = [torch.randint(0, 60, (rows, cols // 256, 144), dtype=torch.uint8, device=dev) for _ in range(copies)]
+        y = torch.empty((1, rows), device=dev)
+        ws = torch.empty(max(256, prima.gemv_workspace_bytes(rows, cols, 1)), dtype=torch.uint8, device=dev)
+        for i in range(copies):
+            prima.q4k_gemv(Ws[i], x, y=y, workspace=ws)
+        torch.cuda.synchronize()
+        n = max(args.steps, 2 * copies)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(n):
+            prima.q4k_gemv(Ws[i % copies], x, y=y, workspace=ws)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / n
+        points.append((nbytes, us))
+        del Ws
+    b = np.array([p[0] for p in points], float)
+    t = np.array([p[1] for p in points], float)
+    slope, t0 = np.polyfit(b, t, 1)
+    print(json.dumps({
+        "metric": "fixed cost of a one-token Q4_K mat-vec launch (us) and the rate of its streaming phase",
+        "value": round(float(t0), 2), "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": 0, "higher_is_better": False,
+        "dtype": "i8 x i8 -> i32", "data": "synthetic",
+        "config": {"workload": "Q4_K mat-vec, 8192 columns, 2048 to 114688 rows, one token, cold weights, launches back to back"},
+        "stream_rate_gbps": round(1e-3 / float(slope), 1),
+        "points": [{"rows": int(nb // ((cols // 256) * 144)), "MB": round(nb / 1e6, 1), "us": round(u, 2),
+                    "line_us": round(float(t0 + slope * nb), 2)} for nb, u in points]}))
 
 
 def bench_device_profile(args, cfg):
