@@ -163,9 +163,7 @@ inline AttnArgs build_attn_args(const prima_dims &d, const float *q, float *q_ro
     a.o = o;
     a.Hq = d.n_q_heads; a.Hkv = d.n_kv_heads; a.kv_cap = kv_cap; a.n_past = n_past; a.T = T;
     // key ranges are multiples of 16 so that tiles never straddle two workgroups, and none is empty
-    const int want = attn_num_splits(d, n_total, T, seq != nullptr);
-    a.keys_per_split = ((n_total + want - 1) / want + 15) / 16 * 16;
-    a.nsplit = (n_total + a.keys_per_split - 1) / a.keys_per_split;
+    attn_ranges(d, n_total, T, seq != nullptr, a.keys_per_split, a.nsplit);
     return a;
 }
 

@@ -119,7 +119,7 @@ prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st);
 prima_status launch_step_init(float *tab, int T, int D, int n_past, float theta, const int *positions,
                               void *const fill_ptr[4], const size_t fill_bytes[4], const unsigned fill_word[4], hipStream_t st);
 prima_status launch_fill_words(void *a, size_t a_bytes, unsigned a_word, void *b, size_t b_bytes, unsigned b_word, hipStream_t st);
-int attn_num_splits(const prima_dims &d, int n_total, int T, bool batch = false);
+void attn_ranges(const prima_dims &d, int n_total, int T, bool batch, int &keys_per_split, int &nsplit);
 size_t attn_ws_bytes(const prima_dims &d, int kv_cap, int T);
 // The attention scratch: attn_counter_bytes() whose first word is the flag a bounded wait raises when it gives up
 // (zero before a launch), then the key ranges' records.  A record that has not been written holds ATTN_REC_EMPTY in
