@@ -113,6 +113,8 @@ constexpr int STATIC_UNITS = NST; // units per wave assigned by position (up to 
 constexpr int FIFO = 8;         // units a wave may have requested and not yet consumed (a power of two > NST)
 
 // ------------------------------------------------------------------------------------------
+constexpr int DEFER_MIN_TILES = 6; // several tokens: more tiles per workgroup than this and a second kernel adds the slabs (measured with 6 and 16: at 16 the down projection of a 5120-wide model and the output projection of an 8192-wide one at 8 tokens get 2 and 6 us slower)
+
 struct PPlan {
     int n_tiles, nb, n_wg, ksplit, slab_blocks, n_slabs, units_cap, direct;
     size_t lds_bytes;
@@ -254,7 +256,10 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
     // Several tokens: a workgroup has many tiles and the slabs finish together, so "whoever arrives last" is
     // one workgroup for nearly all of them (measured: the slowest one adds for 50-70 us while the rest idle);
     // a second small launch does the additions in parallel instead.
-    a.defer = (p.n_slabs > 1 && T > 1) ? 1 : 0;
+    // With few tiles per workgroup (the Q/K/V and output projections of a 5120-wide model: 3 or 4) the arrivals are
+    // spread over the workgroups and adding in place is cheaper than the second launch's hand-over.
+    const int tiles_per_wg = (p.n_tiles * p.n_slabs + p.n_wg - 1) / p.n_wg;
+    a.defer = (p.n_slabs > 1 && T > 1 && tiles_per_wg > DEFER_MIN_TILES) ? 1 : 0;
     a.n_wg = p.n_wg;
     if (p.n_slabs > 1) {
         // the counters sit in a region of fixed size at the start of the scratch, so that launches of
