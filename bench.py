@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--device-profile", action="store_true",
                     help="side measurement: the device-profiler quantities of the paper's latency model on this GPU, and the "
                          "model's estimate of the config's window step next to the measured one")
+    ap.add_argument("--halda", action="store_true",
+                    help="side measurement (CPU only, no GPU needed): the scheduler's time for rings of 4 to 32 devices and an "
+                         "80-layer model (the paper: 10-12 ms)")
     ap.add_argument("--launch-cost", action="store_true",
                     help="side measurement: one-token Q4_K mat-vecs of 8192 columns and 2048 to 114688 rows, cold weights; a straight "
                          "line through time against bytes gives the fixed cost of a launch and the rate of its streaming phase")
@@ -69,6 +72,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)")
+    if args.halda:
+        return bench_halda(args)
 
     import numpy as np
     import torch
@@ -636,6 +641,49 @@ def bench_mix(args, cfg):
         out["cpu_baseline"] = {"value": round(cfg.T / cpu_seconds, 4), "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"the whole window once ({cpu_seconds:.1f} s of CPU time; tensor generation excluded)"}
     print(json.dumps(out), flush=True)
+
+
+def bench_halda(args):
+    """Scheduling latency of Halda (Sec. 3.3: 10-12 ms on 4 to 32 devices) on seeded synthetic rings: devices of mixed
+    operating systems and GPUs, an 80-layer model (its divisors below 80 that leave every device a layer are the candidate
+    numbers of rounds).  Algorithm 1 as the paper gives it, and with this repository's refinement over the set assignment
+    behind it.  Runs on the CPU alone."""
+    import statistics
+    from paper_2504_08791_amd import halda
+    from workloads.lda import random_instance
+
+    def objects(model, devices):
+        mo = halda.Model(L=model["L"], flops=dict(model["flops"]), flops_out=dict(model["flops_out"]), b=model["b"], b_i=model["b_i"],
+                         b_o=model["b_o"], V=model["V"], kv_bytes_per_token=model["kv"], n_kv=model["n_kv"], c_cpu=model["c_cpu"],
+                         c_gpu=model["c_gpu"])
+        ds = [halda.Device(name=f"d{m}", os=d["os"], gpu=d["gpu"], uma=d["uma"], d_avail=d["d_avail"], d_gpu_avail=d["d_gpu_avail"],
+                           d_swapout=d["swap_cap"], s_disk=d["s_disk"], s_cpu=dict(d["s_cpu"]), s_gpu=dict(d["s_gpu"]), T_cpu=d["T_cpu"],
+                           T_gpu=d["T_gpu"], t_kv_cpy_cpu=d["t_kv_cpy_cpu"], t_kv_cpy_gpu=d["t_kv_cpy_gpu"], t_ram_vram=d["t_ram_vram"],
+                           t_vram_ram=d["t_vram_ram"], t_comm=d["t_comm"]) for m, d in enumerate(devices)]
+        return mo, ds
+
+    halda.halda(*objects(*random_instance(1, n_devices=4, L=80)))  # the solver's first call loads it
+    rows, plain_all = [], []
+    for M in (4, 8, 16, 32):
+        plain, refined = [], []
+        for seed in range(5):
+            mo, ds = objects(*random_instance(1000 + seed, n_devices=M, L=80))
+            t0 = time.perf_counter()
+            halda.halda(mo, ds, refine=False)
+            t1 = time.perf_counter()
+            halda.halda(mo, ds, refine=True)
+            t2 = time.perf_counter()
+            plain.append((t1 - t0) * 1e3)
+            refined.append((t2 - t1) * 1e3)
+        plain_all += plain
+        rows.append({"devices": M, "algorithm_1_ms": round(statistics.median(plain), 2), "with_refinement_ms": round(statistics.median(refined), 1)})
+    value = statistics.median(plain_all)
+    print(json.dumps({
+        "metric": "Halda scheduling latency (Algorithm 1), median over rings of 4, 8, 16 and 32 devices, 80 layers", "value": round(value, 2),
+        "unit": "ms", "n_gpus": 0, "steps": 20, "warmup": 1, "higher_is_better": False, "vs_baseline": round(value / 11.0, 3),
+        "baseline": "10-12 ms on 4-32 devices (Sec. 3.3); vs_baseline = value / 11 ms", "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "seeded rings of mixed devices (workloads/lda.py), 80-layer model, HiGHS through scipy.optimize.milp"},
+        "cpu_model": cpu_model(), "by_ring_size": rows}))
 
 
 def bench_launch_cost(args):
