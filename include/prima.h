@@ -13,7 +13,10 @@
  *    buffer; the library allocates and frees nothing on these paths, never synchronises the
  *    device and never changes the current device.
  *  - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default
- *    stream).  Results are ready when that stream has drained.
+ *    stream).  Results are ready when that stream has drained.  The window, prompt, mat-vec, matrix-product and
+ *    attention calls may be recorded into a HIP graph (stream capture) and replayed: they enqueue kernels only and
+ *    clear their scratch with fill kernels; call each once outside the capture first (kernel attributes are set
+ *    on a kernel's first launch).  prima_window_check and prima_layer_window_decode_profiled synchronise and may not.
  *  - Arguments are validated on the host before anything is launched; a bad argument returns
  *    a status code and launches nothing.  A fault inside a kernel surfaces at the caller's
  *    next synchronisation; PRIMA_E_DEVICE reports launch-time failures only.
