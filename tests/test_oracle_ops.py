@@ -83,6 +83,31 @@ def test_rope_invariants():
     assert not np.allclose(oracle.rope(v, H, D, 5, theta, 0), oracle.rope(v, H, D, 5, theta, 1))
 
 
+def test_rope_closed_forms():
+    """The angle schedule pinned without retyping it: a unit vector in every pair shows its angle directly (atan2);
+    pair 0 turns by `pos` radians, the pair a quarter of the way through the head by pos / sqrt(theta) (theta = 1e4:
+    pos / 100, so position 200 turns it by 2 rad, cos 2 and sin 2 as printed in any table), and the angles fall
+    geometrically with a constant ratio that would reach pos / theta one pair past the last."""
+    H, D, theta = 1, 64, 1e4
+    for mode in (0, 1):
+        pair = lambda i: (2 * i, 2 * i + 1) if mode else (i, i + D // 2)
+        v = np.zeros(D)
+        for i in range(D // 2):
+            v[pair(i)[0]] = 1.0                      # (1, 0) in every pair
+        r = oracle.rope(v, H, D, 200, theta, mode)
+        a16, b16 = pair(16)
+        assert abs(r[a16] - (-0.4161468365471424)) < 1e-12 and abs(r[b16] - 0.9092974268256817) < 1e-12
+        # small position: every angle below pi, so atan2 returns it
+        pos = 3
+        r = oracle.rope(v, H, D, pos, theta, mode)
+        ang = np.array([math.atan2(r[pair(i)[1]], r[pair(i)[0]]) for i in range(D // 2)])
+        assert abs(ang[0] - pos) < 1e-12                                  # pair 0: pos radians, counter-clockwise
+        ratio = ang[1:] / ang[:-1]
+        assert np.allclose(ratio, ratio[0], rtol=1e-9) and ratio[0] < 1   # geometric, falling
+        assert abs(ang[-1] * ratio[0] - pos / theta) < 1e-15              # D/2 steps from pos to pos / theta
+        assert abs(ang[D // 4] - pos / 100.0) < 1e-13
+
+
 def test_silu_swiglu():
     z = np.array([0.0, 30.0, -30.0, 1.5, -1.5, 700.0, -700.0])
     one = np.ones_like(z)
