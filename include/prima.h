@@ -322,14 +322,24 @@ prima_status prima_window_plan_status(const prima_dims *d, int32_t kv_cap, int32
  * y: fp32 [T][ldy], ldy >= n_rows, must not overlap x.  workspace: device, 256-byte aligned, at least
  * prima_gemm_workspace_bytes(T, n_cols) bytes (per-token scales and the activations laid out for the matrix cores,
  * about 4.25 bytes per activation; contents need not be kept).  The activations enter the matrix cores as the sum of
- * two binary16 numbers (22 bits after a per-token power-of-two scale), products and sums are fp32; results do not
- * depend on the launch.  All pointers device; asynchronous on hip_stream.
+ * two binary16 numbers (22 bits after a per-token power-of-two scale), products and sums are fp32; the same arguments
+ * always give the same bits.  All pointers device; asynchronous on hip_stream.
+ *
+ * Few rows and few tokens (an output projection against a prompt of a hundred tokens) give fewer workgroups than the
+ * device has compute units.  With a workspace of prima_gemm_workspace_bytes_ksplit(T, n_rows, n_cols) bytes the call
+ * then divides K among prima_gemm_ksplit(T, n_rows, n_cols) workgroups per block of rows and tokens, each leaving its
+ * sums behind the first prima_gemm_workspace_bytes(T, n_cols) bytes (rounded up to 256), and a second launch adds them
+ * in a fixed order (and the residual).  prima_gemm_ksplit returns 1 where K is not divided (the two sizes are then
+ * equal up to that rounding) and 0 for arguments the product would refuse; with less than the larger size the call
+ * does not divide K.
  */
 #define PRIMA_GEMM_MAX_TOK 65536
 prima_status prima_q4k_gemm(const void *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int32_t T,
                             const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t prima_gemm_workspace_bytes(int32_t T, int64_t n_cols);
+size_t prima_gemm_workspace_bytes_ksplit(int32_t T, int64_t n_rows, int64_t n_cols);
+int32_t prima_gemm_ksplit(int32_t T, int64_t n_rows, int64_t n_cols);
 
 /*
  * Prompt processing: all L layers of the window for T consecutive tokens of one sequence that has n_past rows

@@ -78,6 +78,18 @@ def q4k_gemv_noalloc(W, x, y):
     return y
 
 
+def gemm_ksplit(T, rows, cols):
+    """Into how many shares prima_q4k_gemm divides K for this shape when its workspace has room for them (1: none)."""
+    return _ffi.lib().prima_gemm_ksplit(T, rows, cols)
+
+
+def gemm_workspace_bytes(T, rows, cols, ksplit=True):
+    """Workspace of q4k_gemm: the minimum, or (ksplit) the size with which few rows x few tokens divide K."""
+    if ksplit:
+        return _ffi.lib().prima_gemm_workspace_bytes_ksplit(T, rows, cols)
+    return _ffi.lib().prima_gemm_workspace_bytes(T, cols)
+
+
 def q4k_gemm(W, x, gain=None, eps=0.0, resid=None, y=None, workspace=None):
     """Many tokens: y[t, r] = sum_c W[r, c] a[t, c] (+ resid[t, r]), a = x or RMSNorm(x; gain, eps).
     W uint8 [rows, cols/256, 144], x float32 [T, cols] (rows may be strided)."""
@@ -89,7 +101,7 @@ def q4k_gemm(W, x, gain=None, eps=0.0, resid=None, y=None, workspace=None):
     if y is None:
         y = torch.empty((T, rows), dtype=torch.float32, device=x.device)
     if workspace is None:
-        workspace = torch.empty(max(256, _ffi.lib().prima_gemm_workspace_bytes(T, cols)), dtype=torch.uint8, device=x.device)
+        workspace = torch.empty(max(256, _ffi.lib().prima_gemm_workspace_bytes_ksplit(T, rows, cols)), dtype=torch.uint8, device=x.device)
     if gain is not None:
         _need(gain, torch.float32, "gain")
     if resid is not None and (resid.dtype != torch.float32 or resid.stride(1) != 1):

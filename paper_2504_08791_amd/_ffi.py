@@ -16,7 +16,7 @@ EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", 
            "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
            "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
            "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt", "prima_layer_window_decode_mixed", "prima_window_plan_status", "prima_gemv_plan_status", "prima_layer_window_decode_batch_mixed",
-           "prima_q4k_gemm", "prima_gemm_workspace_bytes", "prima_layer_window_prefill", "prima_prefill_workspace_bytes",
+           "prima_q4k_gemm", "prima_gemm_workspace_bytes", "prima_gemm_workspace_bytes_ksplit", "prima_gemm_ksplit", "prima_layer_window_prefill", "prima_prefill_workspace_bytes",
            "prima_layer_window_prefill_mixed", "prima_set_prefill_small_tokens", "prima_q4k_gemv_noalloc"]
 FORMATS = {"q4_k": 0, "q5_k": 1, "q6_k": 2, "q8_0": 3, "f16": 4, "f32": 5}
 
@@ -63,6 +63,10 @@ def lib():
         L.prima_q4k_gemm.restype = C.c_int
         L.prima_gemm_workspace_bytes.argtypes = [i32, i64]
         L.prima_gemm_workspace_bytes.restype = sz
+        L.prima_gemm_workspace_bytes_ksplit.argtypes = [i32, i64, i64]
+        L.prima_gemm_workspace_bytes_ksplit.restype = sz
+        L.prima_gemm_ksplit.argtypes = [i32, i64, i64]
+        L.prima_gemm_ksplit.restype = i32
         L.prima_layer_window_prefill.argtypes = [dp, lp, i32, i32, i32, i32, vp, vp, vp, sz, vp]
         L.prima_layer_window_prefill.restype = C.c_int
         L.prima_prefill_workspace_bytes.argtypes = [dp, i32, i32]

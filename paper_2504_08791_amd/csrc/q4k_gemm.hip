@@ -73,6 +73,12 @@ struct GemmArgs {
     const float *resid; // null: none (added to every stored row; launches with a residual have one matrix)
     int64_t ldr;
     int T, n_tiles, n_rb, n_tb; // 16-token tiles, row blocks, token blocks
+    // K divided among ksplit workgroups per (row block, token block): workgroup blockIdx.y walks its share of the
+    // super-blocks and stores its sums to part[split][token][ldp] (column: row block * GM_ROWS + row in the block);
+    // gemm_ksplit_reduce_kernel adds the shares in order.  ksplit == 1: the sums go straight to y.
+    int ksplit;
+    float *part;
+    int64_t ldp;
 };
 
 // per token: 1/rms (RMSNorm in front) and the power of two that brings max |a| below 1024
@@ -258,7 +264,12 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     }
     const int tile0 = tb * TT;
     const uint32_t lds0 = lds_address(smem);
-    const int total = 9 * nb; // positions (n_cols < 2^32: no overflow)
+    // this workgroup's share of K: super-blocks [b_lo, b_lo + nbl) (all of them unless K is divided; never empty: the
+    // host keeps ksplit <= nb); below, `b` counts from b_lo
+    const int b_lo = static_cast<int>(static_cast<int64_t>(blockIdx.y) * nb / a.ksplit);
+    const int nbl = static_cast<int>(static_cast<int64_t>(blockIdx.y + 1) * nb / a.ksplit) - b_lo;
+    wsrc += static_cast<int64_t>(b_lo) * 144;
+    const int total = 9 * nbl; // positions (n_cols < 2^32: no overflow)
 
     // Wave-uniform bases of this wave's activation requests: request jj of a sub-block position is slab (part, tile)
     // with part = wave & 1, tile = 2 jj + (wave >> 1); request jj of a sums position is tile wave + 4 jj.  Past the
@@ -267,12 +278,12 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
 #pragma unroll
     for (int jj = 0; jj < DM; ++jj) {
         const int tg = min(tile0 + 2 * jj + (wave >> 1), a.n_tiles - 1);
-        abase[jj] = a.A + (static_cast<int64_t>(tg) * nb * GM_SLABS + (wave & 1)) * 1024;
+        abase[jj] = a.A + ((static_cast<int64_t>(tg) * nb + b_lo) * GM_SLABS + (wave & 1)) * 1024;
     }
 #pragma unroll
     for (int jj = 0; jj < DMS; ++jj) {
         const int tg = min(tile0 + wave + GM_WAVES * jj, a.n_tiles - 1);
-        xbase[jj] = a.A + (static_cast<int64_t>(tg) * nb * GM_SLABS + 16) * 1024;
+        xbase[jj] = a.A + ((static_cast<int64_t>(tg) * nb + b_lo) * GM_SLABS + 16) * 1024;
     }
     const uint32_t lane16 = lane * 16;
 
@@ -351,7 +362,7 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     for (int rt = 0; rt < GM_RT; ++rt) build_b(Bc[rt], rt, 0, 0, 0);
 
     int slot = 0; // ring slot of the current position
-    for (int b = 0; b < nb; ++b) {
+    for (int b = 0; b < nbl; ++b) {
 #pragma unroll
         for (int s = 0; s < 9; ++s) {
             const int p = 9 * b + s;
@@ -365,7 +376,7 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                 const int s_t = (s + GM_NS - 1) % 9;
                 const int b_t = b + (s + GM_NS - 1) / 9;
                 const int slot_t = slot == 0 ? GM_NS - 1 : slot - 1;
-                if (b_t < nb) issue(b_t, s_t, slot_t);
+                if (b_t < nbl) issue(b_t, s_t, slot_t);
             }
             const uint8_t *base = smem + slot * SLOT + lane * 16;
             const int slot_n = slot + 1 == GM_NS ? 0 : slot + 1;
@@ -427,7 +438,7 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                             yacc[tt][rt][i] += fmaf(dd[rt], acch[tt][rt][i], -(dm[rt] * am[i]));
                     }
                     if (tt < GM_RT) {
-                        if (b + 1 < nb) build_b(Bn[tt], tt, b + 1, 0, slot_n);
+                        if (b + 1 < nbl) build_b(Bn[tt], tt, b + 1, 0, slot_n);
                         else Bn[tt] = Bc[tt];
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -469,14 +480,64 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                 const int t = (tile0 + tt) * 16 + 4 * g + i;
                 if (t < a.T) {
                     float v = yacc[tt][rt][i] * a.stat[t].y;
-                    if (a.resid) v += a.resid[t * a.ldr + out_row];
-                    my.y[t * my.ldy + out_row] = v;
+                    if (a.ksplit > 1) {
+                        a.part[(static_cast<int64_t>(blockIdx.y) * a.T + t) * a.ldp + static_cast<int64_t>(rb) * GM_ROWS + wave * 64 + 16 * rt + n] = v;
+                    } else {
+                        if (a.resid) v += a.resid[t * a.ldr + out_row];
+                        my.y[t * my.ldy + out_row] = v;
+                    }
                 }
             }
     }
 }
 
+// y = the shares of K added in order (+ resid): one thread per (token, column of the shares)
+__global__ void __launch_bounds__(256) gemm_ksplit_reduce_kernel(GemmArgs a)
+{
+    const int64_t col = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int t = blockIdx.y;
+    if (col >= a.ldp) return;
+    const int rb = static_cast<int>(col / GM_ROWS);
+    const int sg = rb >= a.seg[2].rb0 ? 2 : (rb >= a.seg[1].rb0 ? 1 : 0);
+    const GemmSegDev &my = a.seg[sg];
+    const int64_t row = col - static_cast<int64_t>(my.rb0) * GM_ROWS;
+    if (row >= my.n_rows) return;
+    float v = a.part[static_cast<int64_t>(t) * a.ldp + col];
+    for (int ks = 1; ks < a.ksplit; ++ks) v += a.part[(static_cast<int64_t>(ks) * a.T + t) * a.ldp + col];
+    if (a.resid) v += a.resid[t * a.ldr + row];
+    my.y[t * my.ldy + row] = v;
+}
+
+// Into how many shares K is cut: none while the row and token blocks alone give every compute unit a workgroup; else as
+// many as fill the workgroup slots of the device (two per compute unit), each share at least GM_MIN_SHARE super-blocks
+constexpr int GM_MIN_SHARE = 4, GM_MAX_KSPLIT = 16;
+int ksplit_for(int64_t n_rb, int64_t n_tb, int64_t nb, bool pair)
+{
+    const int64_t wgs = n_rb * n_tb, slots = 2 * GM_CUS;
+    if (pair || wgs <= 0 || wgs * 2 > slots) return 1;
+    const int64_t s = std::min<int64_t>({slots / wgs, nb / GM_MIN_SHARE, GM_MAX_KSPLIT});
+    return s < 2 ? 1 : static_cast<int>(s);
+}
+int64_t row_blocks(int64_t n_rows) { return (n_rows + GM_ROWS - 1) / GM_ROWS; }
+int token_blocks(int T) { return ((T + 15) / 16 + GM_TT - 1) / GM_TT; }
+
 } // namespace
+
+int gemm_ksplit(int T, const int64_t *n_rows, int n_mats, int64_t n_cols)
+{
+    int64_t n_rb = 0;
+    for (int i = 0; i < n_mats; ++i) n_rb += row_blocks(n_rows[i]);
+    return ksplit_for(n_rb, token_blocks(T), n_cols / QK, false);
+}
+
+size_t gemm_part_bytes(int T, const int64_t *n_rows, int n_mats, int64_t n_cols)
+{
+    const int s = gemm_ksplit(T, n_rows, n_mats, n_cols);
+    if (s == 1) return 0;
+    int64_t n_rb = 0;
+    for (int i = 0; i < n_mats; ++i) n_rb += row_blocks(n_rows[i]);
+    return static_cast<size_t>(s) * static_cast<size_t>(T) * static_cast<size_t>(n_rb) * GM_ROWS * sizeof(float);
+}
 
 size_t gemm_ws_bytes(int T, int64_t n_cols)
 {
@@ -485,7 +546,8 @@ size_t gemm_ws_bytes(int T, int64_t n_cols)
 }
 
 prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, int64_t n_cols, const float *x, int64_t ldx, int T,
-                                   const float *gain, float eps, const float *resid, int64_t ldr, void *ws, hipStream_t st, bool split_ready)
+                                   const float *gain, float eps, const float *resid, int64_t ldr, void *ws, hipStream_t st, bool split_ready,
+                                   void *part, size_t part_bytes)
 {
     if (n_mats < 1 || n_mats > 3 || (pair && (n_mats != 2 || mats[0].n_rows != mats[1].n_rows || resid))) return PRIMA_E_SHAPE;
     if (T == 0) return PRIMA_OK;
@@ -524,16 +586,26 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
     a.pair = pair ? 1 : 0;
     a.n_cols = n_cols; a.A = A; a.stat = stat; a.resid = resid; a.ldr = ldr;
     a.T = T; a.n_tiles = n_tiles; a.n_rb = static_cast<int>(n_rb); a.n_tb = n_tb;
-    hipLaunchKernelGGL(q4k_gemm_kernel, dim3(static_cast<unsigned>(grid)), dim3(GM_THREADS), GM_LDS_BYTES, st, a);
+    // K is divided when that fills the device and the caller's scratch holds the shares
+    a.ksplit = part && T <= 65535 ? ksplit_for(n_rb, n_tb, nb, pair) : 1; // (the shares are added by a launch with T as a grid dimension)
+    a.ldp = n_rb * GM_ROWS;
+    if (a.ksplit > 1 && part_bytes < static_cast<size_t>(a.ksplit) * static_cast<size_t>(T) * static_cast<size_t>(a.ldp) * sizeof(float)) a.ksplit = 1;
+    a.part = a.ksplit > 1 ? static_cast<float *>(part) : nullptr;
+    hipLaunchKernelGGL(q4k_gemm_kernel, dim3(static_cast<unsigned>(grid), a.ksplit), dim3(GM_THREADS), GM_LDS_BYTES, st, a);
+    if (a.ksplit > 1) {
+        const prima_status ps = last_launch_status();
+        if (ps != PRIMA_OK) return ps;
+        hipLaunchKernelGGL(gemm_ksplit_reduce_kernel, dim3(static_cast<unsigned>((a.ldp + 255) / 256), T), dim3(256), 0, st, a);
+    }
     return last_launch_status();
 }
 
 prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int T,
                              const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
-                             void *ws, hipStream_t st, bool split_ready)
+                             void *ws, hipStream_t st, bool split_ready, void *part, size_t part_bytes)
 {
     const GemmMat m{W, y, n_rows, ldy};
-    return launch_q4k_gemm_multi(&m, 1, false, n_cols, x, ldx, T, gain, eps, resid, ldr, ws, st, split_ready);
+    return launch_q4k_gemm_multi(&m, 1, false, n_cols, x, ldx, T, gain, eps, resid, ldr, ws, st, split_ready, part, part_bytes);
 }
 
 } // namespace prima

@@ -220,7 +220,7 @@ prima_status check_window_args(const prima_dims *d, int32_t kv_cap, int32_t n_pa
 }
 
 struct PrefillWs {
-    size_t q, k, v, o, h, a, u, xb0, xb1, rope, attn, stat, total;
+    size_t q, k, v, o, h, a, u, xb0, xb1, rope, attn, stat, part, part_bytes, total;
     size_t dec_base; // short prompts: the scratch of a decode call of PRIMA_MAX_TOK tokens, carved from here
     WindowWs dec;
 };
@@ -246,6 +246,15 @@ PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
     w.rope = take(t * static_cast<size_t>(d.head_dim) * f);
     w.attn = take(attn_ws_bytes(d, kv_cap, PRIMA_MAX_TOK));
     w.stat = take(gemm_ws_bytes(T, std::max<int64_t>({d.e, static_cast<int64_t>(qd), d.ffn})));
+    {
+        // the shares of K of the launches that divide it (few rows, few tokens): the largest of the layer's products
+        const int64_t r_qkv[3] = {static_cast<int64_t>(qd), static_cast<int64_t>(kvd), static_cast<int64_t>(kvd)}, r_e[1] = {d.e}, r_f[1] = {d.ffn};
+        size_t pb = gemm_part_bytes(T, r_qkv, 3, d.e);
+        for (int i = 0; i < 3; ++i) pb = std::max(pb, gemm_part_bytes(T, r_qkv + i, 1, d.e)); // one by one when the formats differ
+        pb = std::max({pb, gemm_part_bytes(T, r_e, 1, static_cast<int64_t>(qd)), gemm_part_bytes(T, r_e, 1, d.ffn), gemm_part_bytes(T, r_f, 1, d.e)});
+        w.part_bytes = pb;
+        w.part = take(pb);
+    }
     w.dec = carve(d, kv_cap, PRIMA_MAX_TOK);
     w.dec_base = take(w.dec.total);
     w.total = off;
@@ -266,7 +275,7 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
     const int64_t e = d.e, qd = static_cast<int64_t>(d.n_q_heads) * d.head_dim, kvd = static_cast<int64_t>(d.n_kv_heads) * d.head_dim, F = d.ffn;
     float *q = at<float>(ws, w.q), *k = at<float>(ws, w.k), *v = at<float>(ws, w.v);
     float *o = at<float>(ws, w.o), *h = at<float>(ws, w.h), *act = at<float>(ws, w.a);
-    void *stat = at<char>(ws, w.stat);
+    void *stat = at<char>(ws, w.stat), *part = at<char>(ws, w.part);
     auto W = [](const void *p) { return static_cast<const uint8_t *>(p); };
     prima_status s;
 #define PRIMA_TRY(call) do { s = (call); if (s != PRIMA_OK) return s; } while (0)
@@ -274,7 +283,8 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
     auto product = [&](int fmt, const void *Wm, int64_t rows, int64_t cols, const float *xin, const float *gain, const float *resid,
                        float *out, bool split_ready) -> prima_status {
         if (fmt == PRIMA_FMT_Q4_K)
-            return launch_q4k_gemm(W(Wm), rows, cols, xin, cols, T, gain, d.rms_eps, resid, rows, out, rows, stat, st, split_ready);
+            return launch_q4k_gemm(W(Wm), rows, cols, xin, cols, T, gain, d.rms_eps, resid, rows, out, rows, stat, st, split_ready, part,
+                                   w.part_bytes);
         for (int t0 = 0; t0 < T; t0 += PRIMA_MAX_TOK) {
             const int Tc = std::min<int>(PRIMA_MAX_TOK, T - t0);
             const prima_status ps = launch_fmt_gemv(fmt, W(Wm), rows, cols, xin + t0 * cols, cols, Tc, gain, d.rms_eps,
@@ -286,7 +296,7 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
     const float *g_attn = static_cast<const float *>(L.g_attn), *g_ffn = static_cast<const float *>(L.g_ffn);
     if (f_q == PRIMA_FMT_Q4_K && f_k == PRIMA_FMT_Q4_K && f_v == PRIMA_FMT_Q4_K) {
         const GemmMat qkv[3] = {{W(L.wq), q, qd, qd}, {W(L.wk), k, kvd, kvd}, {W(L.wv), v, kvd, kvd}};
-        PRIMA_TRY(launch_q4k_gemm_multi(qkv, 3, false, e, x, e, T, g_attn, d.rms_eps, nullptr, 0, stat, st));
+        PRIMA_TRY(launch_q4k_gemm_multi(qkv, 3, false, e, x, e, T, g_attn, d.rms_eps, nullptr, 0, stat, st, false, part, w.part_bytes));
     } else {
         bool ready = false; // the first Q4_K matrix of the group splits the activations for the others
         PRIMA_TRY(product(f_q, L.wq, qd, e, x, g_attn, nullptr, q, ready));
@@ -433,6 +443,17 @@ prima_status prima_q4k_gemv_noalloc(const void *W, int64_t n_rows, int64_t n_col
 
 size_t prima_gemm_workspace_bytes(int32_t T, int64_t n_cols) { return (T < 1 || n_cols <= 0 || n_cols % QK) ? 0 : gemm_ws_bytes(T, n_cols); }
 
+int32_t prima_gemm_ksplit(int32_t T, int64_t n_rows, int64_t n_cols)
+{
+    return (T < 1 || n_rows < 0 || n_cols <= 0 || n_cols % QK) ? 0 : gemm_ksplit(T, &n_rows, 1, n_cols);
+}
+
+size_t prima_gemm_workspace_bytes_ksplit(int32_t T, int64_t n_rows, int64_t n_cols)
+{
+    if (T < 1 || n_rows < 0 || n_cols <= 0 || n_cols % QK) return 0;
+    return round_up(gemm_ws_bytes(T, n_cols), 256) + gemm_part_bytes(T, &n_rows, 1, n_cols);
+}
+
 prima_status prima_q4k_gemm(const void *W, int64_t n_rows, int64_t n_cols, const float *x, int64_t ldx, int32_t T,
                             const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
                             void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -444,8 +465,11 @@ prima_status prima_q4k_gemm(const void *W, int64_t n_rows, int64_t n_cols, const
         !aligned(workspace, 256))
         return PRIMA_E_ALIGN;
     if (workspace_bytes < gemm_ws_bytes(T, n_cols)) return PRIMA_E_WORKSPACE;
+    // what lies behind the minimum holds the shares of K, if it holds them all
+    const size_t part_off = round_up(gemm_ws_bytes(T, n_cols), 256);
+    void *part = workspace_bytes > part_off ? static_cast<char *>(workspace) + part_off : nullptr;
     return launch_q4k_gemm(static_cast<const uint8_t *>(W), n_rows, n_cols, x, ldx, T, gain, eps, resid, ldr, y, ldy, workspace,
-                           static_cast<hipStream_t>(hip_stream));
+                           static_cast<hipStream_t>(hip_stream), false, part, part ? workspace_bytes - part_off : 0);
 }
 
 size_t prima_attn_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T)

@@ -145,6 +145,33 @@ def test_matrix_product_and_prefill_argument_errors():
     assert g(layers=bad) == 1
 
 
+def test_matrix_product_k_division_policy():
+    """Host logic, no GPU: K is divided only where row blocks (256 rows) x token blocks (64 tokens) leave at least half of
+    the device's 512 workgroup slots empty; the shares fill the slots, hold at least four super-blocks each and are at
+    most 16; the larger workspace holds shares x T x (rows rounded up to 256) floats behind the minimum."""
+    L = _ffi.lib()
+    for T in (1, 16, 64, 65, 100, 128, 256, 512, 1024, 5000):
+        for rows in (1, 256, 257, 1024, 8192, 10240, 28672, 57344):
+            for cols in (256, 1024, 4096, 8192, 28672):
+                s = L.prima_gemm_ksplit(T, rows, cols)
+                wgs = -(-rows // 256) * -(-T // 64)
+                nb = cols // 256
+                assert 1 <= s <= 16
+                if s > 1:
+                    assert s * wgs <= 512 and nb // s >= 4
+                    assert (s + 1) * wgs > 512 or nb // (s + 1) < 4 or s == 16     # as many shares as the limits allow
+                else:
+                    assert wgs * 2 > 512 or nb < 8
+                base = L.prima_gemm_workspace_bytes(T, cols)
+                full = L.prima_gemm_workspace_bytes_ksplit(T, rows, cols)
+                part = s * T * (-(-rows // 256) * 256) * 4 if s > 1 else 0
+                assert full == -(-base // 256) * 256 + part
+    # 70B-shaped projections against a prompt of 128 tokens
+    assert [L.prima_gemm_ksplit(128, r, c) for r, c in ((8192, 8192), (8192, 28672), (28672, 8192))] == [8, 8, 2]
+    assert L.prima_gemm_ksplit(0, 8, 256) == 0 and L.prima_gemm_ksplit(4, 8, 300) == 0 and L.prima_gemm_ksplit(4, -1, 256) == 0
+    assert L.prima_gemm_workspace_bytes_ksplit(0, 8, 256) == 0 and L.prima_gemm_workspace_bytes_ksplit(4, 8, 300) == 0
+
+
 def test_batch_window_argument_errors():
     L = _ffi.lib()
     d = _dims()

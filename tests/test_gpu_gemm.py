@@ -114,6 +114,53 @@ def test_gemm_model_shape_sampled(gpu_lib):
     assert rel_err(got[:, pick], ref) < ARITH_TOL, rel_err(got[:, pick], ref)
 
 
+def test_gemm_k_divided_among_workgroups(gpu_lib):
+    """Few rows x few tokens: with the larger workspace K is cut into shares that a second launch adds.  Both routes
+    against the oracle (RMSNorm in front, residual in the output buffer, ragged rows and tokens), the same bits on a
+    rerun, and nothing written beside the output."""
+    from paper_2504_08791_amd import _ffi
+    rng = np.random.default_rng(36)
+    for rows, nb, T, want in [(64, 16, 31, 4), (300, 8, 129, 2), (1000, 40, 70, 10), (257, 64, 16, 16), (520, 33, 200, 8)]:
+        print("case", rows, nb, T, flush=True)
+        assert gpu_lib.gemm_ksplit(T, rows, nb * 256) == want
+        W = _rand_q4k(rng, rows, nb)
+        x = (rng.standard_normal((T, nb * 256)) * np.exp(rng.standard_normal((T, 1)))).astype(np.float32)
+        gain = (1 + 0.2 * rng.standard_normal(nb * 256)).astype(np.float32)
+        resid = rng.standard_normal((T, rows)).astype(np.float32)
+        ref = _oracle_product(W, oracle.rmsnorm(x.astype(np.float64), gain, 1e-5)) + resid.astype(np.float64)
+        Wd, xd, gd = _dev(W), _dev(x), _dev(gain)
+        out = {}
+        for split in (False, True):
+            nbytes = gpu_lib.gemm_workspace_bytes(T, rows, nb * 256, ksplit=split)
+            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            ybuf = torch.full((T, rows + 8), 7.0, dtype=torch.float32, device="cuda")
+            ybuf[:, :rows] = _dev(resid)
+            got = gpu_lib.q4k_gemm(Wd, xd, gain=gd, eps=1e-5, resid=ybuf[:, :rows], y=ybuf[:, :rows], workspace=ws)
+            assert torch.all(ybuf[:, rows:] == 7.0)
+            out[split] = got.cpu().numpy()
+            for t in range(T):
+                assert rel_err(out[split][t], ref[t]) < ARITH_TOL, (rows, nb, T, split, t, rel_err(out[split][t], ref[t]))
+            ybuf[:, :rows] = _dev(resid)
+            again = gpu_lib.q4k_gemm(Wd, xd, gain=gd, eps=1e-5, resid=ybuf[:, :rows], y=ybuf[:, :rows], workspace=ws).cpu().numpy()
+            assert np.array_equal(out[split].view(np.uint32), again.view(np.uint32))
+        assert not np.array_equal(out[False], out[True])      # the two routes add in different orders
+        assert rel_err(out[True], out[False].astype(np.float64)) < ARITH_TOL
+
+
+def test_gemm_k_divided_model_shape_sampled(gpu_lib):
+    """A 70B-shaped down projection (8192 x 28672) against 128 tokens (8 shares of K): sampled rows against the oracle."""
+    rng = np.random.default_rng(37)
+    rows, nb, T = 8192, 112, 128
+    assert gpu_lib.gemm_ksplit(T, rows, nb * 256) == 8
+    W = _rand_q4k(rng, rows, nb)
+    x = rng.standard_normal((T, nb * 256)).astype(np.float32)
+    print("case", rows, nb, T, flush=True)
+    got = gpu_lib.q4k_gemm(_dev(W), _dev(x)).cpu().numpy()
+    pick = np.unique(np.concatenate([[0, 15, 16, 255, 256, rows - 1], rng.integers(0, rows, 40)]))
+    ref = _oracle_product(np.ascontiguousarray(W[pick]), x.astype(np.float64))
+    assert rel_err(got[:, pick], ref) < ARITH_TOL, rel_err(got[:, pick], ref)
+
+
 def test_gemm_argument_errors(gpu_lib):
     from paper_2504_08791_amd import _ffi
     L = _ffi.lib()
