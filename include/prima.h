@@ -367,8 +367,7 @@ prima_status prima_layer_window_prefill_mixed(const prima_dims *d, const prima_l
                                               void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t prima_prefill_workspace_bytes(const prima_dims *d, int32_t kv_cap, int32_t T);
 /* Prompts of up to n tokens are advanced by the decode kernels, PRIMA_MAX_TOK tokens at a time, inside the prompt call
- * (default 64: up to about 70 tokens that is faster than the matrix product, whose workgroups each walk all of K).
- * 0: always the matrix product (tests).  Process-wide; not to be changed while a call is being enqueued. */
+ * (default 16, one decode call: from 17 tokens on the matrix product is faster).  0: always the matrix product (tests).  Process-wide; not to be changed while a call is being enqueued. */
 void prima_set_prefill_small_tokens(int32_t n);
 
 /* The same for one prima_q4k_gemv call with the scratch of prima_gemv_workspace_bytes(n_rows, n_cols, T). */

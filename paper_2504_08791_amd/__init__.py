@@ -197,11 +197,11 @@ def stream_read_probe(buf, sink):
                "prima_stream_read_probe")
 
 
-PREFILL_SMALL_TOKENS = 64   # the library's default threshold (prima_set_prefill_small_tokens)
+PREFILL_SMALL_TOKENS = 16   # the library's default threshold (prima_set_prefill_small_tokens)
 
 
 def set_prefill_small_tokens(n):
-    """Prompts of up to n tokens go through the decode kernels inside Window.prefill (default 64; 0: always the matrix product)."""
+    """Prompts of up to n tokens go through the decode kernels inside Window.prefill (default 16; 0: always the matrix product)."""
     _ffi.lib().prima_set_prefill_small_tokens(int(n))
 
 

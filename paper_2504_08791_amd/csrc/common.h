@@ -100,10 +100,11 @@ prima_status launch_q4k_gemm(const uint8_t *W, int64_t n_rows, int64_t n_cols, c
                              const float *gain, float eps, const float *resid, int64_t ldr, float *y, int64_t ldy,
                              void *ws, hipStream_t st, bool split_ready = false, void *part = nullptr, size_t part_bytes = 0);
 // K divided among workgroups (a launch whose rows and tokens alone would leave most of the device idle): the number of
-// shares for T tokens and n_mats matrices of these rows sharing a launch (1: none), and the bytes of `part` that hold the
-// shares' sums (0: none).  A launch divides K only if it is given that much.
-int gemm_ksplit(int T, const int64_t *n_rows, int n_mats, int64_t n_cols);
-size_t gemm_part_bytes(int T, const int64_t *n_rows, int n_mats, int64_t n_cols);
+// shares for T tokens and n_mats matrices of these rows sharing a launch, or (pair) a gate and an up matrix of n_rows[0]
+// each (1: none), and the bytes of `part` that hold the shares' sums (0: none).  A launch divides K only if it is given
+// that much.
+int gemm_ksplit(int T, const int64_t *n_rows, int n_mats, int64_t n_cols, bool pair = false);
+size_t gemm_part_bytes(int T, const int64_t *n_rows, int n_mats, int64_t n_cols, bool pair = false);
 // up to three matrices with the same columns against the same activations (Q / K / V), or, with pair set, two of equal
 // shape (gate, up) with silu(gate) * up stored to mats[0].y; the residual only with one matrix
 struct GemmMat {

@@ -51,7 +51,11 @@ constexpr int GM_SLOT = GM_TT * 2048 + GM_WAVES * 1024;                   // 12 
 constexpr int GM_LDS_BYTES = GM_NS * GM_SLOT + 2 * GM_WAVES * 1024;       // 68 KiB: two workgroups per compute unit
 constexpr int GM_XCDS = 8;
 constexpr int GM_CUS = 256;
-constexpr int GM_PATCH_R = 4, GM_PATCH_C = 8; // row blocks x token blocks that share an XCD at a time
+// Workgroups that share an XCD at a time: a patch of 4 row blocks x 8 token blocks; with fewer than 8 token blocks all of
+// them and more row blocks, with few row blocks per XCD only those.  A workgroup number that falls outside the matrix
+// costs its dispatch (about 0.1 us): with one token block and patches of 4 x 8, seven numbers in eight were idle and a
+// launch took no less than 260 us whatever its work.
+constexpr int GM_PATCH = 32, GM_PATCH_C = 8;
 constexpr size_t GM_STAT_ALIGN = 1024;
 
 struct GemmSegDev {
@@ -73,6 +77,7 @@ struct GemmArgs {
     const float *resid; // null: none (added to every stored row; launches with a residual have one matrix)
     int64_t ldr;
     int T, n_tiles, n_rb, n_tb; // 16-token tiles, row blocks, token blocks
+    int patch_r, patch_c;       // row blocks x token blocks of a patch
     // K divided among ksplit workgroups per (row block, token block): workgroup blockIdx.y walks its share of the
     // super-blocks and stores its sums to part[split][token][ldp] (column: row block * GM_ROWS + row in the block);
     // gemm_ksplit_reduce_kernel adds the shares in order.  ksplit == 1: the sums go straight to y.
@@ -243,12 +248,14 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     // Consecutive workgroup numbers go to consecutive XCDs.  32 consecutive workgroups of one XCD (one L2) are 4 row
     // blocks x 8 token blocks: per super-block step they fetch 4 x 36 KiB of weights and 8 x 68 KiB of activations
     // between them instead of 32 of either.  An XCD owns the row blocks xcd, xcd + 8, ...  (The shape of the patch
-    // makes no measurable difference at 1024 tokens; this one is the best of four at 512.)
+    // makes no measurable difference at 1024 tokens; this one is the best of four at 512.  The host narrows the patch
+    // when there are fewer token blocks or row blocks than that, so that few workgroup numbers fall outside.)
     const int xcd = blockIdx.x % GM_XCDS, seq = blockIdx.x / GM_XCDS;
-    const int patch = seq / (GM_PATCH_R * GM_PATCH_C), within = seq % (GM_PATCH_R * GM_PATCH_C);
-    const int patches_tb = (a.n_tb + GM_PATCH_C - 1) / GM_PATCH_C;
-    const int rb = ((patch / patches_tb) * GM_PATCH_R + within / GM_PATCH_C) * GM_XCDS + xcd;
-    const int tb = (patch % patches_tb) * GM_PATCH_C + within % GM_PATCH_C;
+    const int patch_c = a.patch_c, patch_r = a.patch_r;
+    const int patch = seq / (patch_r * patch_c), within = seq % (patch_r * patch_c);
+    const int patches_tb = (a.n_tb + patch_c - 1) / patch_c;
+    const int rb = ((patch / patches_tb) * patch_r + within / patch_c) * GM_XCDS + xcd;
+    const int tb = (patch % patches_tb) * patch_c + within % patch_c;
     if (rb >= a.n_rb || tb >= a.n_tb) return; // the whole workgroup, before any barrier
     const int nb = static_cast<int>(a.n_cols >> 8);
     const int sg = a.pair ? 0 : (rb >= a.seg[2].rb0 ? 2 : (rb >= a.seg[1].rb0 ? 1 : 0));
@@ -450,6 +457,22 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
         }
     }
 
+    if (a.ksplit > 1) { // this share's sums, scaled back, for gemm_ksplit_reduce_kernel
+#pragma unroll
+        for (int rt = 0; rt < GM_RT; ++rt) {
+            const int64_t out_row = row0 + (a.pair ? 16 * (rt & 1) : 16 * rt) + n;
+            if (out_row >= my.n_rows) continue;
+            float *dst = a.part + static_cast<int64_t>(rb) * GM_ROWS + wave * 64 + 16 * rt + n;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int t = (tile0 + tt) * 16 + 4 * g + i;
+                    if (t < a.T) dst[(static_cast<int64_t>(blockIdx.y) * a.T + t) * a.ldp] = yacc[tt][rt][i] * a.stat[t].y;
+                }
+        }
+        return;
+    }
     if (a.pair) { // row tiles 0, 1: rows of the gate matrix; 2, 3: the same rows of the up matrix
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
@@ -480,12 +503,8 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                 const int t = (tile0 + tt) * 16 + 4 * g + i;
                 if (t < a.T) {
                     float v = yacc[tt][rt][i] * a.stat[t].y;
-                    if (a.ksplit > 1) {
-                        a.part[(static_cast<int64_t>(blockIdx.y) * a.T + t) * a.ldp + static_cast<int64_t>(rb) * GM_ROWS + wave * 64 + 16 * rt + n] = v;
-                    } else {
-                        if (a.resid) v += a.resid[t * a.ldr + out_row];
-                        my.y[t * my.ldy + out_row] = v;
-                    }
+                    if (a.resid) v += a.resid[t * a.ldr + out_row];
+                    my.y[t * my.ldy + out_row] = v;
                 }
             }
     }
@@ -496,6 +515,19 @@ __global__ void __launch_bounds__(256) gemm_ksplit_reduce_kernel(GemmArgs a)
 {
     const int64_t col = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const int t = blockIdx.y;
+    if (a.pair) {
+        // output row `col` of silu(gate) * up: its gate sums sit at column (row block, wave, row in the wave's 32) of the
+        // shares, its up sums 32 columns further
+        if (col >= a.seg[0].n_rows) return;
+        const int64_t gc = (col / (GM_ROWS / 2)) * GM_ROWS + ((col % (GM_ROWS / 2)) / 32) * 64 + col % 32;
+        float gt = a.part[static_cast<int64_t>(t) * a.ldp + gc], up = a.part[static_cast<int64_t>(t) * a.ldp + gc + 32];
+        for (int ks = 1; ks < a.ksplit; ++ks) {
+            gt += a.part[(static_cast<int64_t>(ks) * a.T + t) * a.ldp + gc];
+            up += a.part[(static_cast<int64_t>(ks) * a.T + t) * a.ldp + gc + 32];
+        }
+        a.seg[0].y[t * a.seg[0].ldy + col] = gt / (1.0f + expf(-gt)) * up;
+        return;
+    }
     if (col >= a.ldp) return;
     const int rb = static_cast<int>(col / GM_ROWS);
     const int sg = rb >= a.seg[2].rb0 ? 2 : (rb >= a.seg[1].rb0 ? 1 : 0);
@@ -511,31 +543,32 @@ __global__ void __launch_bounds__(256) gemm_ksplit_reduce_kernel(GemmArgs a)
 // Into how many shares K is cut: none while the row and token blocks alone give every compute unit a workgroup; else as
 // many as fill the workgroup slots of the device (two per compute unit), each share at least GM_MIN_SHARE super-blocks
 constexpr int GM_MIN_SHARE = 4, GM_MAX_KSPLIT = 16;
-int ksplit_for(int64_t n_rb, int64_t n_tb, int64_t nb, bool pair)
+int ksplit_for(int64_t n_rb, int64_t n_tb, int64_t nb)
 {
     const int64_t wgs = n_rb * n_tb, slots = 2 * GM_CUS;
-    if (pair || wgs <= 0 || wgs * 2 > slots) return 1;
+    if (wgs <= 0 || wgs * 2 > slots) return 1;
     const int64_t s = std::min<int64_t>({slots / wgs, nb / GM_MIN_SHARE, GM_MAX_KSPLIT});
     return s < 2 ? 1 : static_cast<int>(s);
 }
-int64_t row_blocks(int64_t n_rows) { return (n_rows + GM_ROWS - 1) / GM_ROWS; }
+// row blocks of one matrix; of a (gate, up) pair of n_rows each: 128 rows of both per block
+int64_t row_blocks(int64_t n_rows, bool pair = false) { return pair ? (n_rows + GM_ROWS / 2 - 1) / (GM_ROWS / 2) : (n_rows + GM_ROWS - 1) / GM_ROWS; }
 int token_blocks(int T) { return ((T + 15) / 16 + GM_TT - 1) / GM_TT; }
 
 } // namespace
 
-int gemm_ksplit(int T, const int64_t *n_rows, int n_mats, int64_t n_cols)
+int gemm_ksplit(int T, const int64_t *n_rows, int n_mats, int64_t n_cols, bool pair)
 {
     int64_t n_rb = 0;
-    for (int i = 0; i < n_mats; ++i) n_rb += row_blocks(n_rows[i]);
-    return ksplit_for(n_rb, token_blocks(T), n_cols / QK, false);
+    for (int i = 0; i < (pair ? 1 : n_mats); ++i) n_rb += row_blocks(n_rows[i], pair);
+    return ksplit_for(n_rb, token_blocks(T), n_cols / QK);
 }
 
-size_t gemm_part_bytes(int T, const int64_t *n_rows, int n_mats, int64_t n_cols)
+size_t gemm_part_bytes(int T, const int64_t *n_rows, int n_mats, int64_t n_cols, bool pair)
 {
-    const int s = gemm_ksplit(T, n_rows, n_mats, n_cols);
+    const int s = gemm_ksplit(T, n_rows, n_mats, n_cols, pair);
     if (s == 1) return 0;
     int64_t n_rb = 0;
-    for (int i = 0; i < n_mats; ++i) n_rb += row_blocks(n_rows[i]);
+    for (int i = 0; i < (pair ? 1 : n_mats); ++i) n_rb += row_blocks(n_rows[i], pair);
     return static_cast<size_t>(s) * static_cast<size_t>(T) * static_cast<size_t>(n_rb) * GM_ROWS * sizeof(float);
 }
 
@@ -568,7 +601,9 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
     const int n_tiles = (T + 15) / 16;
     const int n_tb = (n_tiles + GM_TT - 1) / GM_TT;
     const int64_t rb_per_xcd = (n_rb + GM_XCDS - 1) / GM_XCDS;
-    const int64_t grid = (rb_per_xcd + GM_PATCH_R - 1) / GM_PATCH_R * ((n_tb + GM_PATCH_C - 1) / GM_PATCH_C) * (GM_PATCH_R * GM_PATCH_C) * GM_XCDS;
+    const int patch_c = std::min(n_tb, GM_PATCH_C);
+    const int patch_r = static_cast<int>(std::min<int64_t>(std::max(1, GM_PATCH / patch_c), rb_per_xcd));
+    const int64_t grid = (rb_per_xcd + patch_r - 1) / patch_r * ((n_tb + patch_c - 1) / patch_c) * (patch_r * patch_c) * GM_XCDS;
     if (grid >= (int64_t{1} << 31) || n_tiles > 65535 || nb >= (int64_t{1} << 31)) return PRIMA_E_SHAPE;
     static std::atomic<bool> attr_set{false}; // set twice by two threads at worst: the attribute call is idempotent
     if (!attr_set) {
@@ -585,9 +620,9 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
     }
     a.pair = pair ? 1 : 0;
     a.n_cols = n_cols; a.A = A; a.stat = stat; a.resid = resid; a.ldr = ldr;
-    a.T = T; a.n_tiles = n_tiles; a.n_rb = static_cast<int>(n_rb); a.n_tb = n_tb;
+    a.T = T; a.n_tiles = n_tiles; a.n_rb = static_cast<int>(n_rb); a.n_tb = n_tb; a.patch_r = patch_r; a.patch_c = patch_c;
     // K is divided when that fills the device and the caller's scratch holds the shares
-    a.ksplit = part && T <= 65535 ? ksplit_for(n_rb, n_tb, nb, pair) : 1; // (the shares are added by a launch with T as a grid dimension)
+    a.ksplit = part && T <= 65535 ? ksplit_for(n_rb, n_tb, nb) : 1; // (the shares are added by a launch with T as a grid dimension)
     a.ldp = n_rb * GM_ROWS;
     if (a.ksplit > 1 && part_bytes < static_cast<size_t>(a.ksplit) * static_cast<size_t>(T) * static_cast<size_t>(a.ldp) * sizeof(float)) a.ksplit = 1;
     a.part = a.ksplit > 1 ? static_cast<float *>(part) : nullptr;

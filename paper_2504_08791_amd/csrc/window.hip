@@ -102,9 +102,9 @@ void layer_gemv_args(const prima_dims &d, const prima_layer &L, int T, const flo
 }
 
 // prompts of up to this many tokens go through the decode kernels, PRIMA_MAX_TOK tokens a call (measured on config 3's shape,
-// ms per layer, matrix-product route / decode route: 32 tokens 1.57 / 0.74, 48: 1.59 / 1.10, 64: 1.62 / 1.47, 80: 1.61 / 1.84,
-// 128: 1.62 / 2.94, 256: 1.67 / 5.89).  A process-wide setting, read when a prompt call is enqueued.
-int g_prefill_small_tokens = 64;
+// ms per layer, matrix-product route / decode route: 8 tokens 0.39 / 0.19, 16: 0.38 / 0.37, 24: 0.40 / 0.56, 32: 0.40 / 0.73,
+// 64: 0.43 / 1.46, 128: 0.60 / 2.93, 256: 1.04 / 5.87).  A process-wide setting, read when a prompt call is enqueued.
+int g_prefill_small_tokens = 16;
 
 // one decoder layer; x -> y (fp32 [T][e]); taps may be null.  Five launches: Q/K/V projections
 // (RMSNorm fused), attention (RoPE + KV append fused, key ranges merged by the last arriver), output projection
@@ -251,7 +251,8 @@ PrefillWs carve_prefill(const prima_dims &d, int kv_cap, int T)
         const int64_t r_qkv[3] = {static_cast<int64_t>(qd), static_cast<int64_t>(kvd), static_cast<int64_t>(kvd)}, r_e[1] = {d.e}, r_f[1] = {d.ffn};
         size_t pb = gemm_part_bytes(T, r_qkv, 3, d.e);
         for (int i = 0; i < 3; ++i) pb = std::max(pb, gemm_part_bytes(T, r_qkv + i, 1, d.e)); // one by one when the formats differ
-        pb = std::max({pb, gemm_part_bytes(T, r_e, 1, static_cast<int64_t>(qd)), gemm_part_bytes(T, r_e, 1, d.ffn), gemm_part_bytes(T, r_f, 1, d.e)});
+        pb = std::max({pb, gemm_part_bytes(T, r_e, 1, static_cast<int64_t>(qd)), gemm_part_bytes(T, r_e, 1, d.ffn), gemm_part_bytes(T, r_f, 1, d.e),
+                       gemm_part_bytes(T, r_f, 1, d.e, true)});
         w.part_bytes = pb;
         w.part = take(pb);
     }
@@ -317,7 +318,7 @@ prima_status run_layer_prefill(const prima_dims &d, const prima_layer &L, int kv
     PRIMA_TRY(product(f_o, L.wo, e, qd, o, nullptr, x, h, false));
     if (f_g == PRIMA_FMT_Q4_K && f_u == PRIMA_FMT_Q4_K) {
         const GemmMat gate_up[2] = {{W(L.wgate), act, F, F}, {W(L.wup), nullptr, F, F}};
-        PRIMA_TRY(launch_q4k_gemm_multi(gate_up, 2, true, e, h, e, T, g_ffn, d.rms_eps, nullptr, 0, stat, st));
+        PRIMA_TRY(launch_q4k_gemm_multi(gate_up, 2, true, e, h, e, T, g_ffn, d.rms_eps, nullptr, 0, stat, st, false, part, w.part_bytes));
     } else {
         float *up = at<float>(ws, w.u);
         PRIMA_TRY(product(f_g, L.wgate, F, e, h, g_ffn, nullptr, act, false));
@@ -719,8 +720,8 @@ prima_status prima_layer_window_prefill_mixed(const prima_dims *d, const prima_l
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (T <= g_prefill_small_tokens) {
-        // a short prompt: the matrix product's workgroups would each walk all of K for a few tokens; the decode kernels,
-        // which stream the weights once per 8 tokens, are faster up to about 100 tokens
+        // a short prompt: a matrix-product workgroup does the work of 64 tokens whatever their number; up to one decode call's
+        // worth of tokens the decode kernels are faster
         void *dws = at<char>(workspace, w.dec_base);
         for (int t0 = 0; t0 < T; t0 += PRIMA_MAX_TOK) {
             const int Tc = std::min<int>(PRIMA_MAX_TOK, T - t0);

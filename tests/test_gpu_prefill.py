@@ -35,11 +35,14 @@ def _oracle_prompt(dims, host, x, n_past, formats=None):
     return np.concatenate(out, axis=0)
 
 
-@pytest.fixture(params=["matrix product", "default"])
+DECODE_ROUTE = 64   # a threshold that sends these tests' short prompts through the decode kernels (the default is 16)
+
+
+@pytest.fixture(params=["matrix product", "decode kernels"])
 def route(request, gpu_lib):
-    """The prompt call's two routes: always the matrix product (threshold 0), or the library's default, which advances
-    prompts of up to 64 tokens with the decode kernels."""
-    gpu_lib.set_prefill_small_tokens(0 if request.param == "matrix product" else gpu_lib.PREFILL_SMALL_TOKENS)
+    """The prompt call's two routes: always the matrix product (threshold 0), or prompts of up to 64 tokens advanced by
+    the decode kernels, 16 tokens a call (the library's default does that up to 16 tokens)."""
+    gpu_lib.set_prefill_small_tokens(0 if request.param == "matrix product" else DECODE_ROUTE)
     yield request.param
     gpu_lib.set_prefill_small_tokens(gpu_lib.PREFILL_SMALL_TOKENS)
 
@@ -148,7 +151,7 @@ def test_prefill_then_decode_continues(gpu_lib, route):
 def test_prefill_agrees_with_decode_calls(gpu_lib, matrix_product_route):
     """The same prompt through decode calls of 16 tokens (integer-digit mat-vec) and through one prefill call
     (binary16 matrix product): far inside the bar of each other, and prefill gives the same bits twice, in place too.
-    On the default route a prompt this short is advanced by the decode kernels: the same bits as the decode calls."""
+    With the threshold above its length the prompt is advanced by the decode kernels: the same bits as the decode calls."""
     cfg = TINY["t2"].with_(T=48, n_past=10)
     cap = 64
     x = synth.window_input(cfg)
@@ -163,19 +166,23 @@ def test_prefill_agrees_with_decode_calls(gpu_lib, matrix_product_route):
     xc = xd.clone()
     yc = wc.prefill(xc, 10, x_out=xc)
     assert torch.equal(yb, yc)
-    gpu_lib.set_prefill_small_tokens(gpu_lib.PREFILL_SMALL_TOKENS)
+    gpu_lib.set_prefill_small_tokens(DECODE_ROUTE)
     wd, _ = _window(gpu_lib, cfg, cap, copy.deepcopy(host))
     assert np.array_equal(wd.prefill(xd, 10).cpu().numpy(), ya)
+    gpu_lib.set_prefill_small_tokens(gpu_lib.PREFILL_SMALL_TOKENS)
 
 
-def test_prefill_model_shape_one_layer(gpu_lib, matrix_product_route):
-    """One 70B-shaped layer (config 3's dimensions), 80 prompt tokens behind 4000 cached rows."""
-    cfg = CONFIGS["c3"].with_(T=80, n_past=4000, n_layers=1)
+@pytest.mark.parametrize("T", [80, 40])
+def test_prefill_model_shape_one_layer(gpu_lib, matrix_product_route, T):
+    """One 70B-shaped layer (config 3's dimensions), 80 or 40 prompt tokens behind 4000 cached rows.  At these token counts
+    the Q/K/V, output and down products divide K among workgroups (6 or 8 shares), at 40 tokens the gate / up product does
+    too (2 shares, SwiGLU behind the addition)."""
+    cfg = CONFIGS["c3"].with_(T=T, n_past=4000, n_layers=1)
     cap = 4096
     host = [synth.layer_tensors(cfg, 0, kv_cap=cap)]
     win, _ = _window(gpu_lib, cfg, cap, host)
     x = synth.window_input(cfg)
-    print("case c3 one layer, 80 tokens", flush=True)
+    print(f"case c3 one layer, {T} tokens", flush=True)
     y = win.prefill(_dev(x), 4000).cpu().numpy()
     ref = _oracle_prompt(cfg.dims, host, x, 4000)
     assert rel_err(y, ref) < HID_TOL, rel_err(y, ref)
