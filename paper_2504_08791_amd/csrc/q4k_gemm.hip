@@ -19,8 +19,8 @@
 // split is done once, not once per row block.  (3) the product: a workgroup of 4 waves owns 256 rows x 64 tokens,
 // a wave 64 rows (four B tiles in registers: every A tile read from LDS feeds four MFMAs per part); two workgroups
 // share a compute unit, so that one's VALU and LDS phases run under the other's MFMAs.  The super-block is walked
-// sub-block by sub-block through a ring of LDS slots that global->LDS loads fill four positions ahead (activations
-// and the wave's own weight bytes alike; the comment at the kernel has the details).  Workgroups are numbered so
+// sub-block by sub-block; global->LDS loads fill a ring of activation slots four positions ahead and, per wave,
+// two buffers with half a super-block of its rows' quants each (the comment at the kernel has the details).  Workgroups are numbered so
 // that those running on one XCD (one L2) at a time are patches of 4 row blocks x 8 token blocks.  Up to three
 // matrices with the same columns share a launch (Q / K / V), and so do a gate and an up matrix, with SwiGLU behind.
 // The weights stay exact: dequantised to binary16 (one accumulator for all of K) they would be off by ~1e-3 per
@@ -28,6 +28,7 @@
 #include <hip/hip_fp16.h>
 
 #include <atomic>
+#include <type_traits>
 
 #include "common.h"
 
@@ -47,8 +48,9 @@ constexpr int GM_TM = 16 * GM_TT;               // tokens per workgroup
 constexpr int GM_SLABS = 17;                    // per (token tile, super-block): 8 sub-blocks x (hi, lo), sums
 constexpr int GM_TILE_BYTES = GM_SLABS * 1024;
 constexpr int GM_NS = 5;                        // ring slots: sub-block positions in LDS or on their way
-constexpr int GM_SLOT = GM_TT * 2048 + GM_WAVES * 1024;                   // 12 KiB
-constexpr int GM_LDS_BYTES = GM_NS * GM_SLOT + 2 * GM_WAVES * 1024;       // 68 KiB: two workgroups per compute unit
+constexpr int GM_SLOT = GM_TT * 2048;                                     // 8 KiB of activations
+constexpr int GM_WQ = 2 * 4096;                                           // per wave: the quants of half a super-block, twice
+constexpr int GM_LDS_BYTES = GM_NS * GM_SLOT + GM_WAVES * (GM_WQ + 2 * 1024); // 80 KiB: two workgroups per compute unit
 constexpr int GM_XCDS = 8;
 constexpr int GM_CUS = 256;
 // Workgroups that share an XCD at a time: a patch of 4 row blocks x 8 token blocks; with fewer than 8 token blocks all of
@@ -204,6 +206,23 @@ __device__ __forceinline__ void dma16_off(const void *gptr, uint32_t lds_addr)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off offset:%2" : : "v"(gptr), "s"(lds_addr - OFF), "n"(OFF) : "memory");
 }
 
+// Requests a wave makes at the positions p - 3 .. p - 1 behind position p = (b, s) of the product kernel's schedule
+// (activations four positions ahead: 2, or 1 where the target is the sums position; at s == 3, 4, 7 of a super-block with
+// a successor 4, 1, 4 weight requests).  successor: whether super-block b has one; the one before b always had.
+constexpr int requests_at(int sk, bool successor) // sk < 0: a position of the super-block before (or the prologue)
+{
+    const int sp = sk < 0 ? sk + 9 : sk;
+    return ((sp + 4) % 9 < 8 ? 2 : 1) + ((sk < 0 || successor) ? (sp == 3 ? 4 : (sp == 4 ? 1 : (sp == 7 ? 4 : 0))) : 0);
+}
+constexpr int requests_behind(int s, bool successor)
+{
+    return requests_at(s - 1, successor) + requests_at(s - 2, successor) + requests_at(s - 3, successor);
+}
+static_assert(requests_behind(0, true) == 10 && requests_behind(0, false) == 10 && requests_behind(2, true) == 6 &&
+              requests_behind(4, true) == 10 && requests_behind(4, false) == 6 && requests_behind(5, false) == 5 &&
+              requests_behind(7, true) == 6 && requests_behind(8, true) == 10 && requests_behind(8, false) == 6,
+              "request counts of the product kernel's schedule");
+
 // workgroup barrier that orders LDS traffic only (__syncthreads() would also wait for every global load in flight,
 // that is, for the whole ring of requests below)
 __device__ __forceinline__ void gm_barrier()
@@ -212,36 +231,32 @@ __device__ __forceinline__ void gm_barrier()
 }
 
 // One workgroup: 4 waves, one per SIMD; a wave owns 64 rows (four B tiles) x 64 tokens, i.e. 16 accumulator tiles for the
-// super-block in hand and as many running sums; two workgroups share a compute unit (256 registers per wave, 68 KiB of
+// super-block in hand and as many running sums; two workgroups share a compute unit (238 registers per wave, 80 KiB of
 // LDS per workgroup) and run out of step with each other.  The super-block is walked sub-block by sub-block ("positions"
-// 0..7, then position 8: the sums slab and the min term).  Everything a position needs comes through LDS by 16-byte
-// global->LDS loads, NS - 1 positions ahead:
-//   slot (12 KiB):  [4 token tiles][hi 1 KiB | lo 1 KiB] activations of the sub-block   (shared by the four waves)
-//                   [4 waves][64 rows x 16 bytes] the sub-block's quants              (each wave its own rows)
-//   position 8 uses the slot's first 4 KiB for the sums slabs; the headers of a super-block (64 rows x 16 bytes
-//   per wave) arrive with its position 0 in a ring of two of their own.
-// Per position: wait until all but the newest WAIT_N1 requests of this wave have landed (requests complete in
-// order), barrier (everyone's share is there, and everyone has finished reading the slot of the position before,
-// which is the slot requested next), request position p + NS - 1, and then, token tile by token tile, the MFMAs of
-// this position with, between them, the VALU work that builds the B tiles of the next position (its quants and
-// headers are this wave's own requests, which the same wait covers).  No global load is left for the compiler to
-// wait on.  Measured with parts of the work switched off (8192 x 28672 weights, 1024 tokens): the LDS reads of the
+// 0..7, then position 8: the sums slab and the min term).  Everything comes through LDS by 16-byte global->LDS loads:
+//   activations: a ring of NS slots of 8 KiB, [4 token tiles][hi 1 KiB | lo 1 KiB] of a sub-block, shared by the four
+//     waves, requested NS - 1 positions ahead (position 8 uses the slot's first 4 KiB for the sums slabs);
+//   quants: per wave two buffers of 4 KiB, sub-blocks 0-3 and 4-7 of its 64 rows, each filled by four requests of 64
+//     bytes x 16 rows as soon as the B tiles of the half super-block before have been built from it;
+//   headers: 64 rows x 16 bytes per wave and super-block, a ring of two.
+// Per position: wait until everything this wave requested four positions ago or earlier has landed (requests complete
+// in order; the wait names the number of requests made since, which the schedule fixes), barrier (everyone's share of
+// the activations is there, and everyone has finished reading the slot of the position before, which is the slot
+// requested next), the position's requests, and then, token tile by token tile, the MFMAs of this position with,
+// between them, the VALU work that builds the B tiles of the next position.  No global load is left for the compiler
+// to wait on.  Measured with parts of the work switched off (8192 x 28672 weights, 1024 tokens): the LDS reads of the
 // activations cost 30 % of the time, the requests 12 %, the B tiles 10 %, the barrier 3 %: a wave reads every
 // activation of its 64 tokens once per position, whatever the tiling, so LDS bandwidth is met before the MFMA rate.
 __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr int TT = GM_TT;
-    constexpr int A_BYTES = TT * 2048, SLOT = GM_SLOT;
-    constexpr int HDR_RING = GM_NS * SLOT;           // two entries of GM_WAVES KiB behind the slots
+    constexpr int SLOT = GM_SLOT;
+    constexpr int WQ_BASE = GM_NS * SLOT;            // per wave two buffers of 4 KiB: quants of sub-blocks 0-3, of 4-7
+    constexpr int HDR_RING = WQ_BASE + GM_WAVES * GM_WQ; // two entries of GM_WAVES KiB
     constexpr int DM = TT / 2, DMS = TT / 4;         // activation requests per wave: a sub-block position, the sums position
-    // requests of the NS - 2 positions between the one awaited and now: each at least DM + 1, one of them may be a
-    // sums position (DMS)
-    constexpr int WAIT_N = (GM_NS - 3) * (DM + 1) + DMS;
-    constexpr int WAIT_N1 = (GM_NS - 4) * (DM + 1) + DMS; // the same for the NS - 3 positions behind p + 1
     static_assert(TT == 4 && GM_WAVES == 4, "requests per wave and position are counted for 4 tiles and 4 waves");
-    static_assert(WAIT_N <= 63, "vmcnt is a 6-bit counter");
-    static_assert(GM_NS >= 4 && GM_NS <= 9, "ring depth: the first NS - 1 positions belong to super-block 0");
+    static_assert(GM_NS == 5, "the request schedule below is written for activations four positions ahead");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, g = lane >> 4;
@@ -263,12 +278,19 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     // first row of this wave: 64 rows of one matrix, or (pair) the same 32 rows of the gate and of the up matrix
     const int64_t row0 = a.pair ? static_cast<int64_t>(rb) * (GM_ROWS / 2) + wave * 32
                                 : static_cast<int64_t>(rb - my.rb0) * GM_ROWS + wave * 64;
-    // the row whose 16-byte pieces this lane requests: local row `lane` of the wave (past the end: a valid row, not stored)
-    const uint8_t *wsrc;
-    {
-        const int64_t r = min<int64_t>(row0 + (a.pair ? (lane & 31) : lane), my.n_rows - 1);
-        wsrc = (a.pair ? a.seg[lane >> 5].W : my.W) + r * nb * 144;
-    }
+    // Weight requests of this lane.  Headers: 16 bytes of local row `lane`.  Quants: request k of a half super-block
+    // brings 64 bytes (four sub-blocks) of each of the local rows 16k .. 16k+15, this lane the 16 bytes of sub-block
+    // (lane & 3) of row 16k + (lane >> 2): 16 runs of 64 bytes per request (16 bytes of each of 64 rows per request cost
+    // about 12 % at 1024 tokens and more).  Local row r: row0 + r of the matrix, or (pair) row0 + (r & 31) of the gate
+    // (r < 32) or the up matrix; past the end: a valid row, not stored.
+    auto row_ptr = [&](int r) __attribute__((always_inline)) -> const uint8_t * {
+        const int64_t gr = min<int64_t>(row0 + (a.pair ? (r & 31) : r), my.n_rows - 1);
+        return (a.pair ? a.seg[r >> 5].W : my.W) + gr * nb * 144;
+    };
+    const uint8_t *wsrc = row_ptr(lane);
+    const uint8_t *wq[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) wq[k] = row_ptr(16 * k + (lane >> 2)) + 16 + (lane & 3) * 16;
     const int tile0 = tb * TT;
     const uint32_t lds0 = lds_address(smem);
     // this workgroup's share of K: super-blocks [b_lo, b_lo + nbl) (all of them unless K is divided; never empty: the
@@ -276,6 +298,8 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     const int b_lo = static_cast<int>(static_cast<int64_t>(blockIdx.y) * nb / a.ksplit);
     const int nbl = static_cast<int>(static_cast<int64_t>(blockIdx.y + 1) * nb / a.ksplit) - b_lo;
     wsrc += static_cast<int64_t>(b_lo) * 144;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) wq[k] += static_cast<int64_t>(b_lo) * 144;
     const int total = 9 * nbl; // positions (n_cols < 2^32: no overflow)
 
     // Wave-uniform bases of this wave's activation requests: request jj of a sub-block position is slab (part, tile)
@@ -294,7 +318,26 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     }
     const uint32_t lane16 = lane * 16;
 
-    // every request of position (b, s), into ring slot `slot` (s is a constant wherever this is called)
+    // the quants of half `half` (sub-blocks 4 half .. 4 half + 3) of super-block b: four requests; its headers: one
+    auto issue_quants = [&](int b, int half) __attribute__((always_inline)) {
+        const uint32_t dst = lds0 + WQ_BASE + wave * GM_WQ + half * 4096;
+        const int64_t off = static_cast<int64_t>(b) * 144;
+        if (half == 0) {
+            dma16_off<0>(wq[0] + off, dst);
+            dma16_off<0>(wq[1] + off, dst + 1024);
+            dma16_off<0>(wq[2] + off, dst + 2048);
+            dma16_off<0>(wq[3] + off, dst + 3072);
+        } else {
+            dma16_off<64>(wq[0] + off, dst);
+            dma16_off<64>(wq[1] + off, dst + 1024);
+            dma16_off<64>(wq[2] + off, dst + 2048);
+            dma16_off<64>(wq[3] + off, dst + 3072);
+        }
+    };
+    auto issue_headers = [&](int b) __attribute__((always_inline)) {
+        dma16_off<0>(wsrc + static_cast<int64_t>(b) * 144, lds0 + HDR_RING + ((b & 1) * GM_WAVES + wave) * 1024);
+    };
+    // the activation requests of position (b, s), into ring slot `slot` (s is a constant wherever this is called)
     auto issue = [&](int b, int s, int slot) __attribute__((always_inline)) {
         const uint32_t base = lds0 + slot * SLOT;
         const int64_t boff = static_cast<int64_t>(b) * (GM_SLABS * 1024);
@@ -302,18 +345,6 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
 #pragma unroll
             for (int jj = 0; jj < DM; ++jj)
                 dma16_base(abase[jj] + boff + 2048 * s, lane16, base + (2 * jj + (wave >> 1)) * 2048 + (wave & 1) * 1024);
-            const uint8_t *wp = wsrc + static_cast<int64_t>(b) * 144;
-            switch (s) { // the sub-block's 16 bytes of quants of this lane's row
-            case 0: dma16_off<16>(wp, base + A_BYTES + wave * 1024); break;
-            case 1: dma16_off<32>(wp, base + A_BYTES + wave * 1024); break;
-            case 2: dma16_off<48>(wp, base + A_BYTES + wave * 1024); break;
-            case 3: dma16_off<64>(wp, base + A_BYTES + wave * 1024); break;
-            case 4: dma16_off<80>(wp, base + A_BYTES + wave * 1024); break;
-            case 5: dma16_off<96>(wp, base + A_BYTES + wave * 1024); break;
-            case 6: dma16_off<112>(wp, base + A_BYTES + wave * 1024); break;
-            default: dma16_off<128>(wp, base + A_BYTES + wave * 1024); break;
-            }
-            if (s == 0) dma16_off<0>(wp, lds0 + HDR_RING + ((b & 1) * GM_WAVES + wave) * 1024);
         } else {
 #pragma unroll
             for (int jj = 0; jj < DMS; ++jj) dma16_base(xbase[jj] + boff, lane16, base + (wave + GM_WAVES * jj) * 1024);
@@ -326,15 +357,26 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
 #pragma unroll
         for (int rt = 0; rt < GM_RT; ++rt) yacc[tt][rt] = acch[tt][rt] = {0.f, 0.f, 0.f, 0.f};
 
-    // positions 0 .. NS-2 (a super-block has 9 > NS - 1 positions, so they all belong to super-block 0)
-#pragma unroll
-    for (int s = 0; s < GM_NS - 1; ++s) issue(0, s, s);
+    // Requests complete in the order in which a wave made them, and every wait below names how many of the newest may
+    // still be out.  Per position (b, s), behind the barrier: the activations of position p + 4; at s == 3 the first
+    // half of super-block b + 1's quants (their buffer was last read for position (b, 3), built during (b, 2)), at
+    // s == 4 its headers, at s == 7 the second half (last read during (b, 6)).  The prologue makes its requests in the
+    // order a super-block before this one would have: headers, first half, the activations of positions 0 1 2, second
+    // half, the activations of position 3.
+    issue_headers(0);
+    issue_quants(0, 0);
+    issue(0, 0, 0);
+    issue(0, 1, 1);
+    issue(0, 2, 2);
+    issue_quants(0, 1);
+    issue(0, 3, 3);
 
-    // B tile `rt` of a sub-block position from this wave's quants in ring slot `sl` and its headers of super-block `bb`:
+    // B tile `rt` of sub-block s from this wave's quants and its headers of super-block `bb`:
     // sc_s * q as binary16 (exact).  A dword holds the eight weights of lane (n, g); masked in pairs (0,4) (1,5) (2,6)
     // (3,7) into the mantissas of 1024 + q, then one fused multiply-add per pair: (1024 + q) sc - 1024 sc
-    auto build_b = [&](half8 &B, int rt, int bb, int s, int sl) __attribute__((always_inline)) {
-        const uint32_t w = *reinterpret_cast<const uint32_t *>(smem + sl * SLOT + A_BYTES + wave * 1024 + (16 * rt + n) * 16 + 4 * g);
+    auto build_b = [&](half8 &B, int rt, int bb, int s) __attribute__((always_inline)) {
+        // request rt of the half brought rows 16 rt .. 16 rt + 15: [row][sub-block of the half][16 bytes]
+        const uint32_t w = *reinterpret_cast<const uint32_t *>(smem + WQ_BASE + wave * GM_WQ + (s >> 2) * 4096 + rt * 1024 + n * 64 + (s & 3) * 16 + 4 * g);
         const uint4 hdr = *reinterpret_cast<const uint4 *>(smem + HDR_RING + ((bb & 1) * GM_WAVES + wave) * 1024 + (16 * rt + n) * 16);
         const _Float16 sc = static_cast<_Float16>(static_cast<float>(hdr_field(hdr, s)));
         const half2v sc2 = {sc, sc};
@@ -364,19 +406,25 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     // and headers that position p + 1 needs are this wave's own requests; the wait below covers them.
     half8 Bc[GM_RT];     // B tiles of the current position (at the sums position: the m_s)
     float dd[GM_RT], dm[GM_RT];
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N) : "memory"); // position 0 has landed (this wave's share)
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(3 * DM + 4 + DM) : "memory"); // headers and first half of super-block 0 have landed
 #pragma unroll
-    for (int rt = 0; rt < GM_RT; ++rt) build_b(Bc[rt], rt, 0, 0, 0);
+    for (int rt = 0; rt < GM_RT; ++rt) build_b(Bc[rt], rt, 0, 0);
 
     int slot = 0; // ring slot of the current position
     for (int b = 0; b < nbl; ++b) {
-#pragma unroll
-        for (int s = 0; s < 9; ++s) {
+        // one position; s as a constant of the type system (a loop over s with "#pragma unroll" is refused by the
+        // optimizer once its body, which holds every case of s until it is unrolled, passes a size limit)
+        auto position = [&](auto s_const) __attribute__((always_inline)) {
+            constexpr int s = decltype(s_const)::value;
             const int p = 9 * b + s;
-            // positions p and p + 1 have landed (this wave's share) once at most the requests of the NS - 3 positions
-            // behind them are in flight
-            if (p + GM_NS - 2 < total) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WAIT_N1) : "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); // the last positions: nothing is requested behind them any more
+            // Everything requested at position p - 4 or before has landed (this wave's share of position p's
+            // activations; the quants and headers that the B tiles built during this position need are older) once at
+            // most the requests of positions p - 3 .. p - 1 are out: their activation requests (DM each, DMS where the
+            // target is a sums position) and, where they fall on s == 3, 4, 7 of a super-block that has a successor,
+            // 4, 1, 4 weight requests.  The last three positions wait for everything.
+            if (p + 3 >= total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            else if (b + 1 < nbl) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(requests_behind(s, true)) : "memory");
+            else asm volatile("s_waitcnt vmcnt(%0)" : : "n"(requests_behind(s, false)) : "memory"); // the last super-block requests no weights
             gm_barrier();
             {
                 // position p + NS - 1 goes into the slot that position p - 1 has just left
@@ -384,6 +432,11 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                 const int b_t = b + (s + GM_NS - 1) / 9;
                 const int slot_t = slot == 0 ? GM_NS - 1 : slot - 1;
                 if (b_t < nbl) issue(b_t, s_t, slot_t);
+                if (b + 1 < nbl) {
+                    if (s == 3) issue_quants(b + 1, 0);
+                    if (s == 4) issue_headers(b + 1);
+                    if (s == 7) issue_quants(b + 1, 1);
+                }
             }
             const uint8_t *base = smem + slot * SLOT + lane * 16;
             const int slot_n = slot + 1 == GM_NS ? 0 : slot + 1;
@@ -417,7 +470,7 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                         acch[tt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cl, Bc[rt], acch[tt][rt], 0, 0, 0);
                     }
                     if (tt < GM_RT) {
-                        if (s < 7) build_b(Bn[tt], tt, b, s + 1, slot_n);
+                        if (s < 7) build_b(Bn[tt], tt, b, s + 1);
                         else build_m(Bn[tt], dd[tt], dm[tt], tt, b);
 #pragma unroll
                         for (int k = 0; k < 2 * GM_RT; ++k) { // one MFMA, then up to four VALU instructions of the build
@@ -445,7 +498,7 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                             yacc[tt][rt][i] += fmaf(dd[rt], acch[tt][rt][i], -(dm[rt] * am[i]));
                     }
                     if (tt < GM_RT) {
-                        if (b + 1 < nbl) build_b(Bn[tt], tt, b + 1, 0, slot_n);
+                        if (b + 1 < nbl) build_b(Bn[tt], tt, b + 1, 0);
                         else Bn[tt] = Bc[tt];
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -454,7 +507,16 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
 #pragma unroll
             for (int rt = 0; rt < GM_RT; ++rt) Bc[rt] = Bn[rt];
             slot = slot_n;
-        }
+        };
+        position(std::integral_constant<int, 0>{});
+        position(std::integral_constant<int, 1>{});
+        position(std::integral_constant<int, 2>{});
+        position(std::integral_constant<int, 3>{});
+        position(std::integral_constant<int, 4>{});
+        position(std::integral_constant<int, 5>{});
+        position(std::integral_constant<int, 6>{});
+        position(std::integral_constant<int, 7>{});
+        position(std::integral_constant<int, 8>{});
     }
 
     if (a.ksplit > 1) { // this share's sums, scaled back, for gemm_ksplit_reduce_kernel
