@@ -19,7 +19,7 @@
 // split is done once, not once per row block.  (3) the product: a workgroup of 4 waves owns 256 rows x 64 tokens,
 // a wave 64 rows (four B tiles in registers: every A tile read from LDS feeds four MFMAs per part); two workgroups
 // share a compute unit, so that one's VALU and LDS phases run under the other's MFMAs.  The super-block is walked
-// sub-block by sub-block; global->LDS loads fill a ring of activation slots four positions ahead and, per wave,
+// sub-block by sub-block; global->LDS loads fill a ring of activation slots two positions ahead and, per wave,
 // two buffers with half a super-block of its rows' quants each (the comment at the kernel has the details).  Workgroups are numbered so
 // that those running on one XCD (one L2) at a time are patches of 4 row blocks x 8 token blocks.  Up to three
 // matrices with the same columns share a launch (Q / K / V), and so do a gate and an up matrix, with SwiGLU behind.
@@ -47,10 +47,12 @@ constexpr int GM_ROWS = 16 * GM_RT * GM_WAVES;  // rows per workgroup
 constexpr int GM_TM = 16 * GM_TT;               // tokens per workgroup
 constexpr int GM_SLABS = 17;                    // per (token tile, super-block): 8 sub-blocks x (hi, lo), sums
 constexpr int GM_TILE_BYTES = GM_SLABS * 1024;
-constexpr int GM_NS = 5;                        // ring slots: sub-block positions in LDS or on their way
+constexpr int GM_NS = 3;                        // ring slots: positions whose activations are in LDS or on their way (a divisor
+                                                // of the 9 positions of a super-block: the slot of a position is a constant; 4
+                                                // and 5 slots measured the same)
 constexpr int GM_SLOT = GM_TT * 2048;                                     // 8 KiB of activations
 constexpr int GM_WQ = 2 * 4096;                                           // per wave: the quants of half a super-block, twice
-constexpr int GM_LDS_BYTES = GM_NS * GM_SLOT + GM_WAVES * (GM_WQ + 2 * 1024); // 80 KiB: two workgroups per compute unit
+constexpr int GM_LDS_BYTES = GM_NS * GM_SLOT + GM_WAVES * (GM_WQ + 2 * 1024); // 64 KiB: two workgroups per compute unit
 constexpr int GM_XCDS = 8;
 constexpr int GM_CUS = 256;
 // Workgroups that share an XCD at a time: a patch of 4 row blocks x 8 token blocks; with fewer than 8 token blocks all of
@@ -209,19 +211,24 @@ __device__ __forceinline__ void dma16_off(const void *gptr, uint32_t lds_addr)
 // Requests a wave makes at the positions p - 3 .. p - 1 behind position p = (b, s) of the product kernel's schedule
 // (activations four positions ahead: 2, or 1 where the target is the sums position; at s == 3, 4, 7 of a super-block with
 // a successor 4, 1, 4 weight requests).  successor: whether super-block b has one; the one before b always had.
+constexpr int GM_AHEAD = GM_NS - 1; // positions between an activation request and its use
 constexpr int requests_at(int sk, bool successor) // sk < 0: a position of the super-block before (or the prologue)
 {
     const int sp = sk < 0 ? sk + 9 : sk;
-    return ((sp + 4) % 9 < 8 ? 2 : 1) + ((sk < 0 || successor) ? (sp == 3 ? 4 : (sp == 4 ? 1 : (sp == 7 ? 4 : 0))) : 0);
+    return ((sp + GM_AHEAD) % 9 < 8 ? 2 : 1) + ((sk < 0 || successor) ? (sp == 3 ? 4 : (sp == 4 ? 1 : (sp == 7 ? 4 : 0))) : 0);
 }
 constexpr int requests_behind(int s, bool successor)
 {
-    return requests_at(s - 1, successor) + requests_at(s - 2, successor) + requests_at(s - 3, successor);
+    int n = 0;
+    for (int k = 1; k < GM_AHEAD; ++k) n += requests_at(s - k, successor);
+    return n;
 }
-static_assert(requests_behind(0, true) == 10 && requests_behind(0, false) == 10 && requests_behind(2, true) == 6 &&
-              requests_behind(4, true) == 10 && requests_behind(4, false) == 6 && requests_behind(5, false) == 5 &&
-              requests_behind(7, true) == 6 && requests_behind(8, true) == 10 && requests_behind(8, false) == 6,
+static_assert(GM_AHEAD != 4 ||
+                  (requests_behind(0, true) == 10 && requests_behind(0, false) == 10 && requests_behind(2, true) == 6 &&
+                   requests_behind(4, true) == 10 && requests_behind(4, false) == 6 && requests_behind(5, false) == 5 &&
+                   requests_behind(7, true) == 6 && requests_behind(8, true) == 10 && requests_behind(8, false) == 6),
               "request counts of the product kernel's schedule");
+static_assert(GM_AHEAD >= 2 && GM_AHEAD <= 4, "the weight requests at s == 3, 4, 7 must be older than the activation requests a wait lets pass");
 
 // workgroup barrier that orders LDS traffic only (__syncthreads() would also wait for every global load in flight,
 // that is, for the whole ring of requests below)
@@ -231,7 +238,7 @@ __device__ __forceinline__ void gm_barrier()
 }
 
 // One workgroup: 4 waves, one per SIMD; a wave owns 64 rows (four B tiles) x 64 tokens, i.e. 16 accumulator tiles for the
-// super-block in hand and as many running sums; two workgroups share a compute unit (238 registers per wave, 80 KiB of
+// super-block in hand and as many running sums; two workgroups share a compute unit (237 registers per wave, 64 KiB of
 // LDS per workgroup) and run out of step with each other.  The super-block is walked sub-block by sub-block ("positions"
 // 0..7, then position 8: the sums slab and the min term).  Everything comes through LDS by 16-byte global->LDS loads:
 //   activations: a ring of NS slots of 8 KiB, [4 token tiles][hi 1 KiB | lo 1 KiB] of a sub-block, shared by the four
@@ -256,7 +263,7 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     constexpr int HDR_RING = WQ_BASE + GM_WAVES * GM_WQ; // two entries of GM_WAVES KiB
     constexpr int DM = TT / 2, DMS = TT / 4;         // activation requests per wave: a sub-block position, the sums position
     static_assert(TT == 4 && GM_WAVES == 4, "requests per wave and position are counted for 4 tiles and 4 waves");
-    static_assert(GM_NS == 5, "the request schedule below is written for activations four positions ahead");
+
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n = lane & 15, g = lane >> 4;
@@ -358,18 +365,18 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
         for (int rt = 0; rt < GM_RT; ++rt) yacc[tt][rt] = acch[tt][rt] = {0.f, 0.f, 0.f, 0.f};
 
     // Requests complete in the order in which a wave made them, and every wait below names how many of the newest may
-    // still be out.  Per position (b, s), behind the barrier: the activations of position p + 4; at s == 3 the first
+    // still be out.  Per position (b, s), behind the barrier: the activations of position p + NS - 1; at s == 3 the first
     // half of super-block b + 1's quants (their buffer was last read for position (b, 3), built during (b, 2)), at
     // s == 4 its headers, at s == 7 the second half (last read during (b, 6)).  The prologue makes its requests in the
-    // order a super-block before this one would have: headers, first half, the activations of positions 0 1 2, second
-    // half, the activations of position 3.
+    // order a super-block before this one would have: headers, first half, then the activations of the first NS - 1
+    // positions with the second half where position (b - 1, 7) would have requested it.
     issue_headers(0);
     issue_quants(0, 0);
-    issue(0, 0, 0);
-    issue(0, 1, 1);
-    issue(0, 2, 2);
-    issue_quants(0, 1);
-    issue(0, 3, 3);
+#pragma unroll
+    for (int q = 0; q < GM_AHEAD; ++q) {
+        issue(0, q, q);
+        if (q == GM_AHEAD - 2) issue_quants(0, 1); // as position (b - 1, 7) would have
+    }
 
     // B tile `rt` of sub-block s from this wave's quants and its headers of super-block `bb`:
     // sc_s * q as binary16 (exact).  A dword holds the eight weights of lane (n, g); masked in pairs (0,4) (1,5) (2,6)
@@ -406,23 +413,24 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
     // and headers that position p + 1 needs are this wave's own requests; the wait below covers them.
     half8 Bc[GM_RT];     // B tiles of the current position (at the sums position: the m_s)
     float dd[GM_RT], dm[GM_RT];
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(3 * DM + 4 + DM) : "memory"); // headers and first half of super-block 0 have landed
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(GM_AHEAD * DM + 4) : "memory"); // headers and first half of super-block 0 have landed
 #pragma unroll
     for (int rt = 0; rt < GM_RT; ++rt) build_b(Bc[rt], rt, 0, 0);
 
-    int slot = 0; // ring slot of the current position
     for (int b = 0; b < nbl; ++b) {
         // one position; s as a constant of the type system (a loop over s with "#pragma unroll" is refused by the
         // optimizer once its body, which holds every case of s until it is unrolled, passes a size limit)
         auto position = [&](auto s_const) __attribute__((always_inline)) {
             constexpr int s = decltype(s_const)::value;
+            constexpr int slot = s % GM_NS; // ring slot of this position
+            static_assert(9 % GM_NS == 0, "a position's slot must not depend on the super-block");
             const int p = 9 * b + s;
             // Everything requested at position p - 4 or before has landed (this wave's share of position p's
             // activations; the quants and headers that the B tiles built during this position need are older) once at
             // most the requests of positions p - 3 .. p - 1 are out: their activation requests (DM each, DMS where the
             // target is a sums position) and, where they fall on s == 3, 4, 7 of a super-block that has a successor,
             // 4, 1, 4 weight requests.  The last three positions wait for everything.
-            if (p + 3 >= total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (p + GM_AHEAD - 1 >= total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             else if (b + 1 < nbl) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(requests_behind(s, true)) : "memory");
             else asm volatile("s_waitcnt vmcnt(%0)" : : "n"(requests_behind(s, false)) : "memory"); // the last super-block requests no weights
             gm_barrier();
@@ -430,7 +438,7 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                 // position p + NS - 1 goes into the slot that position p - 1 has just left
                 const int s_t = (s + GM_NS - 1) % 9;
                 const int b_t = b + (s + GM_NS - 1) / 9;
-                const int slot_t = slot == 0 ? GM_NS - 1 : slot - 1;
+                constexpr int slot_t = (slot + GM_NS - 1) % GM_NS;
                 if (b_t < nbl) issue(b_t, s_t, slot_t);
                 if (b + 1 < nbl) {
                     if (s == 3) issue_quants(b + 1, 0);
@@ -439,7 +447,6 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
                 }
             }
             const uint8_t *base = smem + slot * SLOT + lane * 16;
-            const int slot_n = slot + 1 == GM_NS ? 0 : slot + 1;
             const v4f zero = {0.f, 0.f, 0.f, 0.f};
             half8 Bn[GM_RT];
             // Token tile by token tile, each a scheduling region of its own (the scheduler, left alone, hoists all of
@@ -506,7 +513,6 @@ __global__ void __launch_bounds__(GM_THREADS, 2) q4k_gemm_kernel(GemmArgs a)
             }
 #pragma unroll
             for (int rt = 0; rt < GM_RT; ++rt) Bc[rt] = Bn[rt];
-            slot = slot_n;
         };
         position(std::integral_constant<int, 0>{});
         position(std::integral_constant<int, 1>{});
