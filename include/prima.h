@@ -282,6 +282,26 @@ prima_status prima_lm_head_fmt(const prima_dims *d, int32_t fmt, const float *g_
                                const float *x, int32_t T, float *logits, void *hip_stream);
 
 /*
+ * Tensors as they lie in a GGUF model file -> this library's layouts, on the device, once at load time.  The paper's
+ * checkpoints are "Q4K" GGUF files of Llama and Qwen models (Sec. 4, experimental setup; App. A.3, the format list).
+ * Field meanings and values do not change, only the placement of the bits; F16 and F32 are copied.
+ * Source block order, as read here (little endian; t = index of a weight in its block; restated from the public
+ * description of the formats: no file or specification was at hand, so agreement with real files is untested):
+ *   Q4_K 144 B / 256 weights: d | dmin (binary16) | scales[12] | qs[128].
+ *        j < 4: sc_j = scales[j] & 63, m_j = scales[j+4] & 63;  j >= 4: sc_j = (scales[j+4] & 15) | (scales[j-4] >> 6) << 4,
+ *        m_j = (scales[j+4] >> 4) | (scales[j] >> 6) << 4.  q_t = low (t % 64 < 32) or high nibble of qs[32 (t/64) + t % 32].
+ *   Q5_K 176 B: d | dmin | scales[12] | qh[32] | qs[128]; low bits as Q4_K, bit 4 of q_t = bit 2 (t/64) + (t % 64 >= 32) of qh[t % 32].
+ *   Q6_K 210 B: ql[128] | qh[64] | scales[16] (signed) | d.  h = t/128, k = (t % 128)/32, l = t % 32: low bits = low (k < 2)
+ *        or high nibble of ql[64h + 32 (k & 1) + l]; bits 4..5 = (qh[32h + l] >> 2k) & 3; sub-scale scales[t/16].
+ *   Q8_0 34 B / 32 weights: d | qs[32] (signed).
+ * Rows one after the other, a row's blocks one after the other.  src: device, prima_gguf_tensor_bytes(fmt, ..) bytes,
+ * any alignment.  dst: device, 16-byte aligned, prima_fmt_tensor_bytes(fmt, ..) bytes (the same number), must not
+ * overlap src (PRIMA_E_RANGE).  n_cols % 256 == 0.  One launch on hip_stream; no scratch.
+ */
+size_t prima_gguf_tensor_bytes(int32_t fmt, int64_t n_rows, int64_t n_cols);
+prima_status prima_repack_gguf(int32_t fmt, const void *src, int64_t n_rows, int64_t n_cols, void *dst, void *hip_stream);
+
+/*
  * Window forward for a model that keeps some matrices in other formats (the "Q4K" models of Sec. 4 / App. A.3:
  * mostly Q4_K, some tensors Q5_K / Q6_K / Q8_0 / FP16 / FP32).  As prima_layer_window_decode, with formats[i]
  * naming the prima_format of each of layer i's seven matrices (the pointers of prima_layer then point at

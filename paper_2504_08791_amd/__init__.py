@@ -127,6 +127,24 @@ def fmt_dequant(fmt, W, rows, cols):
     return out
 
 
+def gguf_tensor_bytes(fmt, rows, cols):
+    return _ffi.lib().prima_gguf_tensor_bytes(_ffi.FORMATS[fmt], rows, cols)
+
+
+def repack_gguf(fmt, raw, rows, cols, out=None):
+    """raw: flat uint8 CUDA tensor holding a rows x cols tensor in GGUF block order -> flat uint8 in this library's layout."""
+    _need(raw, torch.uint8, "raw")
+    if raw.numel() != gguf_tensor_bytes(fmt, rows, cols):
+        raise ValueError(f"raw holds {raw.numel()} bytes, a {rows} x {cols} {fmt} tensor has {gguf_tensor_bytes(fmt, rows, cols)}")
+    if out is None:
+        out = torch.empty(fmt_tensor_bytes(fmt, rows, cols), dtype=torch.uint8, device=raw.device)
+    _need(out, torch.uint8, "out")
+    if out.numel() != fmt_tensor_bytes(fmt, rows, cols):
+        raise ValueError("out has the wrong size")
+    _ffi.check(_ffi.lib().prima_repack_gguf(_ffi.FORMATS[fmt], _ptr(raw), rows, cols, _ptr(out), _stream()), "prima_repack_gguf")
+    return out
+
+
 def fmt_gemv(fmt, W, rows, cols, x, y=None):
     """y[t, r] = sum_c W[r, c] x[t, c];  W flat uint8 in format fmt (not "q4_k"), x float32 [T, cols]."""
     _need(W, torch.uint8, "W")

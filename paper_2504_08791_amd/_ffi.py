@@ -17,7 +17,8 @@ EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", 
            "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
            "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt", "prima_layer_window_decode_mixed", "prima_window_plan_status", "prima_gemv_plan_status", "prima_layer_window_decode_batch_mixed",
            "prima_q4k_gemm", "prima_gemm_workspace_bytes", "prima_gemm_workspace_bytes_ksplit", "prima_gemm_ksplit", "prima_layer_window_prefill", "prima_prefill_workspace_bytes",
-           "prima_layer_window_prefill_mixed", "prima_set_prefill_small_tokens", "prima_q4k_gemv_noalloc"]
+           "prima_layer_window_prefill_mixed", "prima_set_prefill_small_tokens", "prima_q4k_gemv_noalloc",
+           "prima_gguf_tensor_bytes", "prima_repack_gguf"]
 FORMATS = {"q4_k": 0, "q5_k": 1, "q6_k": 2, "q8_0": 3, "f16": 4, "f32": 5}
 
 
@@ -114,6 +115,10 @@ def lib():
                      "prima_layer_window_decode_profiled",
                      "prima_layer_decode_taps", "prima_lm_head", "prima_window_check", "prima_stream_read_probe"):
             getattr(L, name).restype = C.c_int
+        L.prima_gguf_tensor_bytes.argtypes = [i32, i64, i64]
+        L.prima_gguf_tensor_bytes.restype = sz
+        L.prima_repack_gguf.argtypes = [i32, vp, i64, i64, vp, vp]
+        L.prima_repack_gguf.restype = C.c_int
         L.prima_set_prefill_small_tokens.argtypes = [i32]
         L.prima_set_prefill_small_tokens.restype = None
         _lib = L
