@@ -229,6 +229,7 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
     if (static_cast<int64_t>(n_tiles) * (p.n_wg + 1) >= (int64_t{1} << 31)) return PRIMA_E_SHAPE; // the kernel's 32-bit tile arithmetic
     // what the kernel's unit queue relies on (plan_for sees to it): every part of a unit has a chunk in every slab
     if (p.ksplit > (p.nb - (p.n_slabs - 1) * p.slab_blocks + PBS - 1) / PBS) return PRIMA_E_SHAPE;
+    if (p.ksplit < 1 || (p.ksplit & (p.ksplit - 1))) return PRIMA_E_SHAPE; // the kernel finds a unit's tile and part by shift and mask
     a = PGemvArgs{};
     int tile0 = 0;
     for (int i = 0; i < ga.nseg; ++i) {
