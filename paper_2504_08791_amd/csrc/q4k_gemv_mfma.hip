@@ -77,9 +77,19 @@ __global__ void __launch_bounds__(256) gemv_slab_reduce_kernel(PGemvArgs a)
     const int rem = static_cast<int>(idx - static_cast<int64_t>(gl) * (16 * TT));
     const int t = rem >> 4, jj = rem & 15;
     const int64_t slab_stride = static_cast<int64_t>(a.n_tiles) * 16 * TT;
+    // slab order, eight loads out before the first is added (one at a time every slab costs a trip to memory)
+    const int n_slabs = a.n_slabs;
     auto all_slabs = [&](int tile) {
+        const float *p = a.part + static_cast<int64_t>(tile) * 16 * TT + rem;
         float v = 0.f;
-        for (int sl = 0; sl < a.n_slabs; ++sl) v += a.part[sl * slab_stride + static_cast<int64_t>(tile) * 16 * TT + rem]; // fixed order
+        for (int s0 = 0; s0 < n_slabs; s0 += 8) {
+            float w[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = p[min(s0 + i, n_slabs - 1) * slab_stride]; // (past the last slab: a valid address, not added)
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (s0 + i < n_slabs) v += w[i];
+        }
         return v;
     };
     if (pairs) {
