@@ -40,6 +40,11 @@ struct PGemvArgs {
     int direct;      // a wave owns whole rows of the slab (ksplit == 1) and stores their sums itself
     int defer;       // n_slabs > 1: the slabs are added by a second kernel instead of the workgroup that arrives last
     int n_wg;
+    // tile ranges, divided on the host: workgroup w has slab w % n_slabs and rank w / n_slabs = umulhi(w, slab_magic);
+    // slabs below wg_more have one workgroup more than the others; class c (0: one more, 1: the others) gives every
+    // workgroup grp_base[c] groups of tiles (tiles, or gate/up pairs) and the first grp_extra[c] ranks one more
+    uint32_t slab_magic;
+    int wg_more, grp_base[2], grp_extra[2];
     float *part;        // n_slabs > 1: partial sums [n_slabs][n_tiles*16][T]
     unsigned *arrivals; // n_slabs > 1: per-tile arrival counters, zero between launches
 };
@@ -262,6 +267,17 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
     const int tiles_per_wg = (p.n_tiles * p.n_slabs + p.n_wg - 1) / p.n_wg;
     a.defer = (p.n_slabs > 1 && T > 1 && tiles_per_wg > DEFER_MIN_TILES) ? 1 : 0;
     a.n_wg = p.n_wg;
+    {
+        const int gran = ga.epi == EPI_SWIGLU ? 2 : 1, n_groups = n_tiles / gran;
+        const int q = p.n_wg / p.n_slabs; // >= 1: plan_for keeps n_wg >= n_slabs
+        a.slab_magic = static_cast<uint32_t>(((uint64_t{1} << 32) + p.n_slabs - 1) / p.n_slabs); // exact for w < 2^32 / n_slabs
+        if (static_cast<int64_t>(p.n_wg) * p.n_slabs >= (int64_t{1} << 32)) return PRIMA_E_SHAPE;
+        a.wg_more = p.n_wg % p.n_slabs;
+        a.grp_base[0] = n_groups / (q + 1);
+        a.grp_extra[0] = n_groups % (q + 1);
+        a.grp_base[1] = n_groups / q;
+        a.grp_extra[1] = n_groups % q;
+    }
     if (p.n_slabs > 1) {
         // the counters sit in a region of fixed size at the start of the scratch, so that launches of
         // different shapes that share the scratch never write partial sums over each other's counters
