@@ -85,6 +85,17 @@ __device__ __forceinline__ long pack64(uint32_t lo, uint32_t hi)
 
 // eight consecutive activations of token t starting at column c0, before the RMSNorm scale:
 // X_PLAIN x, X_RMSNORM x*gain (the 1/rms factor is applied by the caller)
+// Sum of the squares of eight values in one fixed sequence of roundings (explicit fused multiply-adds and additions:
+// left to the compiler, each copy of the expression may be contracted differently, and workgroups that look at the
+// same row through different copies would disagree in the last bit of 1/rms).
+template <typename V4>
+__device__ __forceinline__ float sumsq8(const V4 &v0, const V4 &v1)
+{
+    const float a = __fmaf_rn(v0.x, v0.x, __fmul_rn(v0.y, v0.y)), b = __fmaf_rn(v0.z, v0.z, __fmul_rn(v0.w, v0.w));
+    const float c = __fmaf_rn(v1.x, v1.x, __fmul_rn(v1.y, v1.y)), d = __fmaf_rn(v1.z, v1.z, __fmul_rn(v1.w, v1.w));
+    return __fadd_rn(__fadd_rn(a, b), __fadd_rn(c, d));
+}
+
 __device__ __forceinline__ void load_act8(const float *x, const float *gain, int64_t ldx, bool rmsnorm, int t, int c0, float *f)
 {
     const float *xp = x + t * ldx + c0;
