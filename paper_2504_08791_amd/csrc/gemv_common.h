@@ -243,6 +243,8 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
     p = plan_for(n_tiles, static_cast<int>(ga.n_cols / QK), T, ga.epi);
     if (!p.ok) return PRIMA_E_SHAPE;
     if (static_cast<int64_t>(n_tiles) * (p.n_wg + 1) >= (int64_t{1} << 31)) return PRIMA_E_SHAPE; // the kernel's 32-bit tile arithmetic
+    for (int i = 0; i < ga.nseg; ++i) // the kernel's 32-bit row numbers and offsets in 16-byte units (16 rows past the end included)
+        if (ga.seg[i].n_rows >= (int64_t{1} << 31) - 16 || (ga.seg[i].n_rows + 16) * (ga.n_cols / QK) * 9 >= (int64_t{1} << 32)) return PRIMA_E_SHAPE;
     // what the kernel's unit queue relies on (plan_for sees to it): every part of a unit has a chunk in every slab
     if (p.ksplit > (p.nb - (p.n_slabs - 1) * p.slab_blocks + PBS - 1) / PBS) return PRIMA_E_SHAPE;
     if (p.ksplit < 1 || (p.ksplit & (p.ksplit - 1))) return PRIMA_E_SHAPE; // the kernel finds a unit's tile and part by shift and mask
