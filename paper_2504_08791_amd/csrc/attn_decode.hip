@@ -374,18 +374,102 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
     constexpr int RPI = 64 / LPR;     // records per load instruction
     constexpr int MERGE_LD = 16;      // load instructions per request: 32 (D = 128) or 64 (D = 64) records
     const int sub = lane / LPR, c4 = (lane % LPR) * 4;
-    for (int qq = wave; qq < nq; qq += ATT_WAVES) {
+    constexpr int REC_BYTES = (REC_HDR + D) * 4;
+    constexpr int HALF_LD = MERGE_LD / 2;
+    // scalar base of query qq's records
+    auto records_of = [&](int qq, int64_t &head) __attribute__((always_inline)) {
         const int qj = q0 + qq, t = qj / G, hg = qj - t * G;
-        const int64_t head = static_cast<int64_t>(tok0 + t) * a.Hq + kvh * G + hg;
-        // this query's records: a scalar base (the query is the wave's) and one offset per lane, so that the requests
-        // of a pass need no address registers of their own.  Records past the last range are read too (they lie
-        // inside the scratch, which is sized for MAX_SPLITS ranges per query) and ignored.
+        head = static_cast<int64_t>(tok0 + t) * a.Hq + kvh * G + hg;
         const uint64_t rec_addr = reinterpret_cast<uint64_t>(a.part + head * a.nsplit * (REC_HDR + D));
         // (the builtin returns a signed int: through uint32_t, or the low half's sign would spill into the high half)
         const uint32_t rec_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(rec_addr))));
         const uint32_t rec_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(rec_addr >> 32))));
-        const char *const rec0 = reinterpret_cast<const char *>(static_cast<uint64_t>(rec_lo) | (static_cast<uint64_t>(rec_hi) << 32));
-        constexpr int REC_BYTES = (REC_HDR + D) * 4;
+        return reinterpret_cast<const char *>(static_cast<uint64_t>(rec_lo) | (static_cast<uint64_t>(rec_hi) << 32));
+    };
+    if (nq > ATT_WAVES && a.nsplit <= HALF_LD * RPI) {
+        // More queries than waves and few ranges: a request brings the records of TWO queries of the wave (qq and
+        // qq + ATT_WAVES; half of its load instructions each), so the second query costs no trip through memory of
+        // its own.  Per query the same records are added in the same order as below: the same bits.
+        for (int qq = wave; qq < nq; qq += 2 * ATT_WAVES) {
+            const bool two = qq + ATT_WAVES < nq;
+            int64_t head[2];
+            const char *const recA = records_of(qq, head[0]);
+            const char *const recB = records_of(two ? qq + ATT_WAVES : qq, head[1]);
+            const uint32_t col_off = static_cast<uint32_t>(sub * REC_BYTES + (REC_HDR + c4) * 4);
+            const uint32_t ml_off = static_cast<uint32_t>(min(lane, a.nsplit - 1) * REC_BYTES);
+            v4f v[MERGE_LD];
+            v2f mlA = {0.f, 0.f}, mlB = {0.f, 0.f};
+            int tries = 0;
+            for (;;) {
+                asm volatile("global_load_dwordx2 %0, %1, %2 sc1" : "=&v"(mlA) : "v"(ml_off), "s"(recA) : "memory");
+                asm volatile("global_load_dwordx2 %0, %1, %2 sc1" : "=&v"(mlB) : "v"(ml_off), "s"(recB) : "memory");
+#pragma unroll
+                for (int i = 0; i < HALF_LD; ++i)
+                    asm volatile("global_load_dwordx4 %0, %1, %2 sc1" : "=&v"(v[i]) : "v"(col_off), "s"(recA + i * RPI * REC_BYTES) : "memory");
+#pragma unroll
+                for (int i = 0; i < HALF_LD; ++i)
+                    asm volatile("global_load_dwordx4 %0, %1, %2 sc1" : "=&v"(v[HALF_LD + i]) : "v"(col_off), "s"(recB + i * RPI * REC_BYTES) : "memory");
+                asm volatile("s_waitcnt vmcnt(0)"
+                             : "+v"(mlA), "+v"(mlB), "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]), "+v"(v[4]), "+v"(v[5]), "+v"(v[6]), "+v"(v[7]),
+                               "+v"(v[8]), "+v"(v[9]), "+v"(v[10]), "+v"(v[11]), "+v"(v[12]), "+v"(v[13]), "+v"(v[14]), "+v"(v[15])
+                             :: "memory");
+                bool missing = __float_as_uint(mlA[0]) == ATTN_REC_EMPTY || __float_as_uint(mlA[1]) == ATTN_REC_EMPTY ||
+                               __float_as_uint(mlB[0]) == ATTN_REC_EMPTY || __float_as_uint(mlB[1]) == ATTN_REC_EMPTY;
+#pragma unroll
+                for (int i = 0; i < MERGE_LD; ++i)
+                    missing = missing || ((i % HALF_LD) * RPI + sub < a.nsplit &&
+                                          (__float_as_uint(v[i][0]) == ATTN_REC_EMPTY || __float_as_uint(v[i][1]) == ATTN_REC_EMPTY ||
+                                           __float_as_uint(v[i][2]) == ATTN_REC_EMPTY || __float_as_uint(v[i][3]) == ATTN_REC_EMPTY));
+                if (__ballot(missing) == 0ull) break;
+                if (++tries > MERGE_TRIES) { // never expected: give up, say so, and go on with what there is
+                    if (lane == 0) __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                if (x == 1 && !two) break;
+                const v2f ml = x ? mlB : mlA;
+                const char *const rec0 = x ? recB : recA;
+                const float ms = lane < a.nsplit ? ml[0] : -INFINITY;
+                const float ls = lane < a.nsplit ? ml[1] : 0.f;
+                const float mm = wave_max(ms);
+                const float w = (ms == -INFINITY) ? 0.f : __expf(ms - mm);
+                const float ll = wave_sum(ls * w);
+                const float wgt = w / ll; // lanes past the last range carry weight 0
+                if (lane < a.nsplit) // "not written" again, for the next launch
+                    *reinterpret_cast<uint2 *>(const_cast<char *>(rec0) + ml_off) = make_uint2(ATTN_REC_EMPTY, ATTN_REC_EMPTY);
+                v4f accq = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int i = 0; i < HALF_LD; ++i) {
+                    const int r = i * RPI + sub;
+                    const float ws = __shfl(wgt, min(r, 63), 64);
+                    if (r < a.nsplit) {
+                        const v4f vv = v[x * HALF_LD + i];
+                        accq[0] = fmaf(vv[0], ws, accq[0]);
+                        accq[1] = fmaf(vv[1], ws, accq[1]);
+                        accq[2] = fmaf(vv[2], ws, accq[2]);
+                        accq[3] = fmaf(vv[3], ws, accq[3]);
+                        *reinterpret_cast<uint4 *>(const_cast<char *>(rec0) + i * RPI * REC_BYTES + col_off) =
+                            make_uint4(ATTN_REC_EMPTY, ATTN_REC_EMPTY, ATTN_REC_EMPTY, ATTN_REC_EMPTY);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (RPI == 4) accq[k] = add_across_16(accq[k]);
+                    accq[k] = add_across_32(accq[k]);
+                }
+                if (lane < LPR) *reinterpret_cast<float4 *>(a.o + head[x] * D + c4) = make_float4(accq[0], accq[1], accq[2], accq[3]);
+            }
+        }
+        return;
+    }
+    for (int qq = wave; qq < nq; qq += ATT_WAVES) {
+        // this query's records: a scalar base (the query is the wave's) and one offset per lane, so that the requests
+        // of a pass need no address registers of their own.  Records past the last range are read too (they lie
+        // inside the scratch, which is sized for MAX_SPLITS ranges per query) and ignored.
+        int64_t head;
+        const char *const rec0 = records_of(qq, head);
         const uint32_t col_off = static_cast<uint32_t>(sub * REC_BYTES + (REC_HDR + c4) * 4);
         const uint32_t ml_off = static_cast<uint32_t>(min(lane, a.nsplit - 1) * REC_BYTES);
         float mm = 0.f, wgt = 0.f;

@@ -63,8 +63,9 @@ def _regs_of(code):
 def test_registers_of_the_attention_merge_requests_are_untouched_until_the_wait(tmp_path):
     _need_hipcc()
     """Every instantiation of the attention kernel: the 17 requests of a merge pass (one 8-byte, sixteen 16-byte,
-    device scope, scalar base + lane offset) are followed by the hand-written wait with nothing but requests and
-    scalar arithmetic in between, write 66 distinct registers, and nothing is spilled anywhere in the kernel."""
+    device scope, scalar base + lane offset; 18 in the pass that serves two queries) are followed by the hand-written
+    wait with nothing but requests and scalar arithmetic in between, write 66 (68) distinct registers, and nothing is
+    spilled anywhere in the kernel."""
     out = tmp_path / "a.s"
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-S", "--cuda-device-only", "-o", str(out),
@@ -93,7 +94,8 @@ def test_registers_of_the_attention_merge_requests_are_untouched_until_the_wait(
                 dst = set(range(int(m.group(1)), int(m.group(2)) + 1))
                 assert not (dst & regs), "two requests share a destination register"
                 regs |= dst
-            assert len(regs) in (64, 66), len(regs)     # the first pass also fetches (max, sum)
+            # the first pass of a query also fetches (max, sum); a pass for two queries fetches both queries' (max, sum)
+            assert len(regs) in (64, 66, 68), len(regs)
             lines_of_group = {k for k, _ in group}
             for k in range(first + 1, wait):
                 if k in lines_of_group:
@@ -102,4 +104,4 @@ def test_registers_of_the_attention_merge_requests_are_untouched_until_the_wait(
                 assert not (_regs_of(code) & regs), (k, body[k].strip())
             n_pass += 1
             i += len(group)
-        assert n_pass >= 1
+        assert n_pass >= 2, "the pass for one query and the pass for two"
