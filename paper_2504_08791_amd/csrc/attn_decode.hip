@@ -315,12 +315,17 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
             ph[r] = hi;
             pl[r] = static_cast<_Float16>(pr[r] - static_cast<float>(hi));
         }
-        const _Float16 *vt = reinterpret_cast<const _Float16 *>(&lds.vt[wave][buf][4 * g][col]);
+        // B operand: lane (col, g) wants V[key 4g + r][16 nb + col], r = 0..3, out of the row-major tile.  The LDS
+        // transpose read does that in one instruction: in each group of 16 lanes, lane i names four consecutive halves
+        // (here those of key 4g + i / 4 from column 16 nb + 4 (i % 4)) and receives, of the halves named by lanes
+        // i / 4 + 4 r, the one at position i % 4.
+        const _Float16 *vt = reinterpret_cast<const _Float16 *>(&lds.vt[wave][buf][4 * g + (col >> 2)][4 * (col & 3)]);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            half4 vb;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) vb[r] = vt[r * D + 16 * nb]; // V[key 4g + r][16 nb + col]
+            typedef short v4s __attribute__((ext_vector_type(4)));
+            const v4s vraw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) v4s *)(lds_address(vt + 16 * nb)));
+            const half4 vb = __builtin_bit_cast(half4, vraw);
             oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(ph, vb, oacc[nb], 0, 0, 0);
             oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(pl, vb, oacc[nb], 0, 0, 0);
         }
