@@ -45,6 +45,11 @@ struct PGemvArgs {
     // workgroup grp_base[c] groups of tiles (tiles, or gate/up pairs) and the first grp_extra[c] ranks one more
     uint32_t slab_magic;
     int wg_more, grp_base[2], grp_extra[2];
+    // How a slab's groups are dealt to its workgroups.  interleave != 0: rank r takes groups r, r + grp_stride[c],
+    // r + 2 grp_stride[c], ... (at any moment the workgroups then read one window of the matrix that moves through it,
+    // which loads the memory channels evenly: without it whole XCDs finish a launch 10 % apart); 0: a contiguous run
+    // (launches whose slabs are added in place: the arrival counters of a workgroup then share cache lines).
+    int interleave, grp_stride[2];
     float *part;        // n_slabs > 1: partial sums [n_slabs][n_tiles*16][T]
     unsigned *arrivals; // n_slabs > 1: per-tile arrival counters, zero between launches
 };
@@ -290,6 +295,9 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
         a.grp_extra[0] = n_groups % (q + 1);
         a.grp_base[1] = n_groups / q;
         a.grp_extra[1] = n_groups % q;
+        a.grp_stride[0] = q + 1;
+        a.grp_stride[1] = q;
+        a.interleave = (p.n_slabs == 1 || a.defer) ? 1 : 0;
     }
     if (p.n_slabs > 1) {
         // the counters sit in a region of fixed size at the start of the scratch, so that launches of
