@@ -134,7 +134,7 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
 #pragma unroll
         for (int i = 0; i < 16 / RPI; ++i) {
             const int vrow = min(k0 + RPI * i + lane / LPR, last_row);
-            dma16(Vh + static_cast<int64_t>(vrow) * D + (lane % LPR) * 8, dst + i * 1024);
+            dma16<true>(Vh + static_cast<int64_t>(vrow) * D + (lane % LPR) * 8, dst + i * 1024);
         }
     };
 
