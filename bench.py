@@ -217,6 +217,7 @@ def run_window_config(args, cfg, steps, warmup, want_cpu, with_probe, copy_calib
 
     # --- what a plain linear read reaches on this device (4 GiB, far beyond the last-level cache) ---
     stream_read_gbps = None
+    stream_read_nt_gbps = None
     if with_probe:
         probe = torch.empty(4 * 1024 ** 3, dtype=torch.uint8, device=dev)
         probe.zero_()
@@ -230,6 +231,15 @@ def run_window_config(args, cfg, steps, warmup, want_cpu, with_probe, copy_calib
         p1.record(stream)
         torch.cuda.synchronize()
         stream_read_gbps = probe.numel() * 5 / (p0.elapsed_time(p1) * 1e-3) / 1e9
+        # the same read with non-temporal loads, the way the one-token mat-vec requests its weights
+        for _ in range(2):
+            prima.stream_read_probe(probe, sink, nt=True)
+        p0.record(stream)
+        for _ in range(5):
+            prima.stream_read_probe(probe, sink, nt=True)
+        p1.record(stream)
+        torch.cuda.synchronize()
+        stream_read_nt_gbps = probe.numel() * 5 / (p0.elapsed_time(p1) * 1e-3) / 1e9
         del probe
 
     # --- per kind of launch: each replayed on its own, once per layer, between two HIP events on the
@@ -294,6 +304,7 @@ def run_window_config(args, cfg, steps, warmup, want_cpu, with_probe, copy_calib
     }
     if stream_read_gbps is not None:
         out["plain_read_gbps"] = round(stream_read_gbps, 1)  # linear 128-bit read of 4 GiB: the practical ceiling
+        out["plain_read_nt_gbps"] = round(stream_read_nt_gbps, 1)  # the same with non-temporal loads (as the one-token mat-vec reads its weights)
     if want_cpu:
         got = y.cpu().numpy().astype(np.float64)
         rms = np.sqrt((h_ref ** 2).mean(axis=1, keepdims=True))

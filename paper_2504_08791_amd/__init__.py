@@ -209,10 +209,12 @@ def window_plan_status(dims, kv_cap, T):
     return _ffi.lib().prima_window_plan_status(C.byref(d), kv_cap, T)
 
 
-def stream_read_probe(buf, sink):
-    """Measurement hook: one linear read of the uint8 tensor `buf` (discarded); `sink` any 4-byte device tensor."""
-    _ffi.check(_ffi.lib().prima_stream_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()),
-               "prima_stream_read_probe")
+def stream_read_probe(buf, sink, nt=False):
+    """Measurement hook: one linear read of the uint8 tensor `buf` (discarded); `sink` any 4-byte device tensor.
+    nt: with the non-temporal bit on the loads (prima_stream_read_probe_nt)."""
+    fn = _ffi.lib().prima_stream_read_probe_nt if nt else _ffi.lib().prima_stream_read_probe
+    _ffi.check(fn(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()),
+               "prima_stream_read_probe_nt" if nt else "prima_stream_read_probe")
 
 
 PREFILL_SMALL_TOKENS = 16   # the library's default threshold (prima_set_prefill_small_tokens)

@@ -14,7 +14,7 @@ STATUS = {0: "PRIMA_OK", 1: "PRIMA_E_NULL", 2: "PRIMA_E_SHAPE", 3: "PRIMA_E_ALIG
 EXPORTS = ["prima_q4k_gemv", "prima_gemv_workspace_bytes", "prima_q4k_dequant", "prima_attn_decode",
            "prima_attn_workspace_bytes", "prima_layer_window_decode", "prima_layer_window_decode_profiled", "prima_layer_decode_taps",
            "prima_lm_head", "prima_lm_head_workspace_bytes", "prima_workspace_bytes", "prima_status_str", "prima_abi_version",
-           "prima_window_check", "prima_stream_read_probe", "prima_layer_window_decode_batch",
+           "prima_window_check", "prima_stream_read_probe", "prima_stream_read_probe_nt", "prima_layer_window_decode_batch",
            "prima_fmt_tensor_bytes", "prima_fmt_dequant", "prima_fmt_gemv", "prima_lm_head_fmt", "prima_layer_window_decode_mixed", "prima_window_plan_status", "prima_gemv_plan_status", "prima_layer_window_decode_batch_mixed",
            "prima_q4k_gemm", "prima_gemm_workspace_bytes", "prima_gemm_workspace_bytes_ksplit", "prima_gemm_ksplit", "prima_layer_window_prefill", "prima_prefill_workspace_bytes",
            "prima_layer_window_prefill_mixed", "prima_set_prefill_small_tokens", "prima_q4k_gemv_noalloc",
@@ -107,13 +107,14 @@ def lib():
         L.prima_workspace_bytes.argtypes = [dp, i32, i32]
         L.prima_workspace_bytes.restype = sz
         L.prima_stream_read_probe.argtypes = [vp, sz, vp, vp]
+        L.prima_stream_read_probe_nt.argtypes = [vp, sz, vp, vp]
         L.prima_window_check.argtypes = [dp, i32, i32, vp, sz, vp]
         L.prima_status_str.argtypes = [C.c_int]
         L.prima_status_str.restype = C.c_char_p
         L.prima_abi_version.restype = C.c_int
         for name in ("prima_q4k_gemv", "prima_q4k_dequant", "prima_attn_decode", "prima_layer_window_decode",
                      "prima_layer_window_decode_profiled",
-                     "prima_layer_decode_taps", "prima_lm_head", "prima_window_check", "prima_stream_read_probe"):
+                     "prima_layer_decode_taps", "prima_lm_head", "prima_window_check", "prima_stream_read_probe", "prima_stream_read_probe_nt"):
             getattr(L, name).restype = C.c_int
         L.prima_gguf_tensor_bytes.argtypes = [i32, i64, i64]
         L.prima_gguf_tensor_bytes.restype = sz

@@ -118,7 +118,7 @@ prima_status launch_q4k_gemm_multi(const GemmMat *mats, int n_mats, bool pair, i
 // RoPE table [T][D/2] of (cos, sin) for the positions n_past .. n_past + T - 1 (any T)
 prima_status launch_rope_table(float *tab, int T, int D, int n_past, float theta, hipStream_t st);
 
-prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st);
+prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st, bool nt);
 prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st);
 // the RoPE table [T][D/2] of (cos, sin) and up to four regions filled with a word each (null: none) in one launch.
 // positions: null (token t sits at n_past + t) or T positions, one per token (a batch of sequences)

@@ -134,12 +134,17 @@ prima_status launch_rope_append(const prima_dims &d, float *q, const float *k, c
 // Read-only streaming probe: every thread reads 16 bytes per step with a grid-wide stride and folds them
 // into one word, so that the loads cannot be dropped.  States what this device delivers for a plain
 // linear read, next to the nominal HBM peak.
+// NT: the loads carry the non-temporal bit (bytes read once: lines marked to leave the caches first), as the weight
+// stream of the one-token mat-vec does.
+template <bool NT>
 __global__ void __launch_bounds__(256) stream_read_kernel(const uint4 *__restrict__ src, size_t n16, uint32_t *sink)
 {
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    const v4u *p = reinterpret_cast<const v4u *>(src);
     uint32_t acc = 0;
     const size_t stride = static_cast<size_t>(gridDim.x) * 256;
     for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride) {
-        const uint4 v = src[i];
+        const v4u v = NT ? __builtin_nontemporal_load(p + i) : p[i];
         acc ^= v.x ^ v.y ^ v.z ^ v.w;
     }
     if (acc == 0x9e3779b9u) sink[0] = acc; // practically never: keeps the loop alive without a store per thread
@@ -163,13 +168,15 @@ prima_status launch_swiglu(float *a, const float *u, int64_t n, hipStream_t st)
     return last_launch_status();
 }
 
-prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st)
+prima_status launch_stream_read(const void *src, size_t bytes, void *sink, hipStream_t st, bool nt)
 {
     int dev = 0, cus = 256;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0) cus = prop.multiProcessorCount;
-    hipLaunchKernelGGL(stream_read_kernel, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4 *>(src), bytes / 16,
-                       static_cast<uint32_t *>(sink));
+    if (nt) hipLaunchKernelGGL(stream_read_kernel<true>, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4 *>(src), bytes / 16,
+                               static_cast<uint32_t *>(sink));
+    else hipLaunchKernelGGL(stream_read_kernel<false>, dim3(cus * 8), dim3(256), 0, st, static_cast<const uint4 *>(src), bytes / 16,
+                            static_cast<uint32_t *>(sink));
     return last_launch_status();
 }
 

@@ -88,6 +88,21 @@ struct Piece {
     float scale, offset;
 };
 
+// a weight field, read once in a launch: non-temporal load (the line is marked to leave the caches first)
+typedef unsigned nt_v4u __attribute__((ext_vector_type(4)));
+typedef unsigned nt_v2u __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 nt_load16(const void *p)
+{
+    const nt_v4u v = __builtin_nontemporal_load(static_cast<const nt_v4u *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 nt_load8(const void *p)
+{
+    const nt_v2u v = __builtin_nontemporal_load(static_cast<const nt_v2u *>(p));
+    return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ unsigned nt_load4(const void *p) { return __builtin_nontemporal_load(static_cast<const unsigned *>(p)); }
+
 template <int FMT>
 __device__ __forceinline__ void load_raw(const uint8_t *__restrict__ W, int64_t n_rows, int64_t n_cols, int64_t row, int64_t k0, Raw<FMT> &r)
 {
@@ -95,22 +110,22 @@ __device__ __forceinline__ void load_raw(const uint8_t *__restrict__ W, int64_t 
     const int64_t blk = row * nb + (k0 >> 8);
     const int t0 = static_cast<int>(k0 & 255);
     if constexpr (FMT == PRIMA_FMT_Q8_0) {
-        r.q = *reinterpret_cast<const uint4 *>(W + row * n_cols + k0);
+        r.q = nt_load16(W + row * n_cols + k0);
         r.d = *reinterpret_cast<const unsigned short *>(W + n_rows * n_cols + ((row * n_cols + k0) >> 5) * 2);
     } else if constexpr (FMT == PRIMA_FMT_Q6_K) {
-        r.lo = *reinterpret_cast<const uint2 *>(W + blk * 128 + (t0 >> 1));
-        r.hi = *reinterpret_cast<const unsigned *>(W + 128 * n + blk * 64 + (t0 >> 2));
+        r.lo = nt_load8(W + blk * 128 + (t0 >> 1));
+        r.hi = nt_load4(W + 128 * n + blk * 64 + (t0 >> 2));
         r.sc = *reinterpret_cast<const signed char *>(W + 192 * n + blk * 16 + (t0 >> 4));
         r.d = *reinterpret_cast<const unsigned short *>(W + 208 * n + blk * 2);
     } else if constexpr (FMT == PRIMA_FMT_Q5_K) {
         r.hdr = *reinterpret_cast<const uint4 *>(W + blk * 16);
-        r.lo = *reinterpret_cast<const uint2 *>(W + 16 * n + blk * 128 + (t0 >> 1));
-        r.hi = *reinterpret_cast<const unsigned *>(W + 144 * n + blk * 32 + (t0 >> 5) * 4); // one word per 32 weights: shared by two lanes
+        r.lo = nt_load8(W + 16 * n + blk * 128 + (t0 >> 1));
+        r.hi = nt_load4(W + 144 * n + blk * 32 + (t0 >> 5) * 4); // one word per 32 weights: shared by two lanes
         r.s = t0 >> 5;
         r.half = (t0 >> 4) & 1;
     } else if constexpr (FMT == PRIMA_FMT_F16) {
-        r.a = *reinterpret_cast<const uint4 *>(W + (row * n_cols + k0) * 2);
-        r.b = *reinterpret_cast<const uint4 *>(W + (row * n_cols + k0) * 2 + 16);
+        r.a = nt_load16(W + (row * n_cols + k0) * 2);
+        r.b = nt_load16(W + (row * n_cols + k0) * 2 + 16);
     } else {
         static_assert(FMT == PRIMA_FMT_F32, "format");
         const float4 *src = reinterpret_cast<const float4 *>(W + (row * n_cols + k0) * 4);

@@ -364,7 +364,15 @@ prima_status prima_stream_read_probe(const void *src, size_t bytes, void *sink, 
     if (!src || !sink) return PRIMA_E_NULL;
     if (!aligned(src, 16) || !aligned(sink, 4)) return PRIMA_E_ALIGN;
     if (bytes < 16) return PRIMA_OK;
-    return launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream));
+    return launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream), false);
+}
+
+prima_status prima_stream_read_probe_nt(const void *src, size_t bytes, void *sink, void *hip_stream)
+{
+    if (!src || !sink) return PRIMA_E_NULL;
+    if (!aligned(src, 16) || !aligned(sink, 4)) return PRIMA_E_ALIGN;
+    if (bytes < 16) return PRIMA_OK;
+    return launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(hip_stream), true);
 }
 
 size_t prima_gemv_workspace_bytes(int64_t n_rows, int64_t n_cols, int32_t T)
