@@ -324,7 +324,7 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
         for (int nb = 0; nb < NB; ++nb) {
             typedef short v4s __attribute__((ext_vector_type(4)));
             const v4s vraw = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) v4s *)(lds_address(vt + 16 * nb)));
+                (__attribute__((address_space(3))) v4s *)(static_cast<uintptr_t>(lds_address(vt + 16 * nb))));
             const half4 vb = __builtin_bit_cast(half4, vraw);
             oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(ph, vb, oacc[nb], 0, 0, 0);
             oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x16f16(pl, vb, oacc[nb], 0, 0, 0);
