@@ -102,7 +102,9 @@ def device_profile(dims, formats=("q4_k", "q5_k", "q6_k", "q8_0", "f16", "f32"),
     vol = 2 * fmt_tensor_bytes("q4_k", rows, cols)
     bufs = [torch.empty(vol, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(max(2, int(600_000_000 // vol) + 1))]
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
-    out["T_gpu"] = vol / timed(lambda i: stream_read_probe(bufs[i % len(bufs)], sink), reps)
+    # with non-temporal loads, the way the library requests weights that a launch reads once
+    out["T_gpu"] = vol / timed(lambda i: stream_read_probe(bufs[i % len(bufs)], sink, nt=True), reps)
+    out["T_gpu_plain_loads"] = vol / timed(lambda i: stream_read_probe(bufs[i % len(bufs)], sink), reps)
     out["T_gpu_volume_bytes"] = vol
     del bufs
     # KV copy: the new token's K and V rows of one layer, device to device

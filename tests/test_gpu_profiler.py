@@ -36,6 +36,9 @@ def test_every_quantity_is_inside_its_band(measured):
     # the linear read at a tensor-like volume: between 55 % and 95 % of the peak (a plain read kernel reaches 80 %)
     assert 0.55 * HBM_PEAK < dp["T_gpu"] < 0.95 * HBM_PEAK, dp["T_gpu"]
     assert dp["T_gpu"] > dp["s_gpu"]["q4_k"] / 2.0 * 0.5625            # no mat-vec reads faster than the plain read
+    # the linear read with ordinary loads: inside the same band, and not faster than the non-temporal one beyond noise
+    assert 0.55 * HBM_PEAK < dp["T_gpu_plain_loads"] < 0.95 * HBM_PEAK, dp["T_gpu_plain_loads"]
+    assert dp["T_gpu_plain_loads"] < 1.05 * dp["T_gpu"], (dp["T_gpu_plain_loads"], dp["T_gpu"])
     # a 4 KiB copy on the device and the 4e-byte copies over the host link cost a launch or a round trip: microseconds
     assert 0.5e-6 < dp["t_kv_cpy"] < 50e-6, dp["t_kv_cpy"]
     assert 2e-6 < dp["t_ram_vram"] < 300e-6 and 2e-6 < dp["t_vram_ram"] < 300e-6, (dp["t_ram_vram"], dp["t_vram_ram"])
