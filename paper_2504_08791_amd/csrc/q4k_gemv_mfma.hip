@@ -20,13 +20,17 @@
 //  * several tokens (speculative verification, App. A.12) use the rows of the A operand for
 //    (token, digit) pairs instead: 4 tokens x 4 digits, one MFMA per sub-block for all four tokens,
 //    lane (j, g) receives the digit sums of token g with row j.  Each weight byte is unpacked once
-//    and nothing is multiplied by zeros; at 8 tokens the loop is bound by the vector ALU
-//    (4 multiply-adds per sub-block and token group for the sub-scales), at ~3.9 TB/s of weights.
+//    and nothing is multiplied by zeros; at 8 tokens the loop is bound by its instructions
+//    (4 multiply-adds per sub-block and token group for the sub-scales), at ~4.8 TB/s of weights.
 //
-// Data movement.  One 512-thread workgroup per compute unit, persistent; it owns a contiguous range
-// of 16-row tiles (with all of K whenever the activations fit in LDS); every sum has a fixed order.
+// Data movement.  One 512-thread workgroup per compute unit, persistent; it owns a share of the
+// 16-row tiles (with all of K whenever the activations fit in LDS), dealt interleaved with the other
+// workgroups' (rank, rank + ranks, ...: the workgroups then read one moving window of the matrix,
+// which loads the memory channels evenly) or, where slabs are added in place, as a contiguous run;
+// every sum has a fixed order.
 // Each wave streams its share of the weights through a private three-stage LDS ring filled by
-// 128-bit global->LDS loads (no VGPR staging): a stage is 16 rows x 2 super-blocks, requested as
+// 128-bit global->LDS loads (no VGPR staging; at one token with the non-temporal bit: a launch reads
+// every weight byte once): a stage is 16 rows x 2 super-blocks, requested as
 // runs of 288 contiguous bytes per row, laid out with an odd row stride so that the MFMA-order
 // reads (lane (j, g) reads row j) are free of bank conflicts.  Two stages are always in flight
 // per wave while the third is consumed; only s_waitcnt orders them, no barrier.  Waves take
@@ -38,7 +42,7 @@
 // stores and loads, one relaxed atomic counter per tile, reset for the next launch; no fences).
 // Several tokens: a second small kernel adds them (the last arriver would be one workgroup for
 // nearly all tiles).  The epilogue adds the residual, or applies SwiGLU to a (gate, up) pair of tiles.
-// The body is gemv_body.inc (shared with the single-launch window kernel).
+// The body is gemv_body.inc.
 #include <atomic>
 
 #include "gemv_common.h"
