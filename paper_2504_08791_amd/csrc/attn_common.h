@@ -90,32 +90,13 @@ __device__ __forceinline__ void rope_apply(float (&v)[D / 32][8], const float4 (
     }
 }
 
-// COH: the vector was written by other workgroups of the same launch: device-scope loads, waited for here
-template <int D, bool COH>
+template <int D>
 __device__ __forceinline__ void load_slices(const float *p, int c, float (&v)[D / 32][8])
 {
-    if (!COH) {
 #pragma unroll
-        for (int x = 0; x < D / 32; ++x) {
-            const float4 a = *reinterpret_cast<const float4 *>(p + 32 * x + 8 * c), b = *reinterpret_cast<const float4 *>(p + 32 * x + 8 * c + 4);
-            v[x][0] = a.x; v[x][1] = a.y; v[x][2] = a.z; v[x][3] = a.w; v[x][4] = b.x; v[x][5] = b.y; v[x][6] = b.z; v[x][7] = b.w;
-        }
-    } else {
-        static_assert(D / 32 <= 4, "eight registers named in the wait below");
-        v4f r[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) r[i] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int x = 0; x < D / 32; ++x) {
-            asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(r[2 * x]) : "v"(p + 32 * x + 8 * c) : "memory");
-            asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(r[2 * x + 1]) : "v"(p + 32 * x + 8 * c + 4) : "memory");
-        }
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]), "+v"(r[4]), "+v"(r[5]), "+v"(r[6]), "+v"(r[7]) :: "memory");
-#pragma unroll
-        for (int x = 0; x < D / 32; ++x) {
-            v[x][0] = r[2 * x][0]; v[x][1] = r[2 * x][1]; v[x][2] = r[2 * x][2]; v[x][3] = r[2 * x][3];
-            v[x][4] = r[2 * x + 1][0]; v[x][5] = r[2 * x + 1][1]; v[x][6] = r[2 * x + 1][2]; v[x][7] = r[2 * x + 1][3];
-        }
+    for (int x = 0; x < D / 32; ++x) {
+        const float4 a = *reinterpret_cast<const float4 *>(p + 32 * x + 8 * c), b = *reinterpret_cast<const float4 *>(p + 32 * x + 8 * c + 4);
+        v[x][0] = a.x; v[x][1] = a.y; v[x][2] = a.z; v[x][3] = a.w; v[x][4] = b.x; v[x][5] = b.y; v[x][6] = b.z; v[x][7] = b.w;
     }
 }
 

@@ -158,7 +158,7 @@ __global__ void __launch_bounds__(ATT_THREADS, 4) attn_decode_kernel(AttnArgs a)
 #pragma unroll
             for (int e = 0; e < 8; ++e) qv[x][e] = 0.f;
         if (q_valid) {
-            load_slices<D, false>(a.q + qoff, g, qv);
+            load_slices<D>(a.q + qoff, g, qv);
             if (a.rope_tab) rope_load<D, MODE>(a.rope_tab + (tok0 + q_t) * (D / 2), g, q_rt);
         }
         // the first tile right behind the queries: they are prepared while it is on its way

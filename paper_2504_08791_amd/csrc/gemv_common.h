@@ -58,12 +58,10 @@ struct PGemvArgs {
 // that the result arrives later, which is the point: it cannot put a wait for *all* outstanding loads
 // (the ring stages behind them included) in front of the first use.  Until the hand-written wait, which
 // names these registers as operands, nothing may touch them.
-template <bool COH> // COH: device scope (data written by other workgroups of the same launch)
 __device__ __forceinline__ v4f load16_early(const void *gptr)
 {
     v4f v;
-    if (COH) asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(v) : "v"(gptr) : "memory");
-    else asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(v) : "v"(gptr) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(v) : "v"(gptr) : "memory");
     return v;
 }
 
@@ -309,10 +307,5 @@ inline prima_status build_pass(const GemvArgs &ga, int t0, int T, void *ws, size
     }
     return PRIMA_OK;
 }
-
-// the stand-alone kernel has nothing to wait for
-struct NoSync {
-    __device__ __forceinline__ void wait() {}
-};
 
 } // namespace prima

@@ -57,9 +57,7 @@ template <int TT>
 __global__ void __launch_bounds__(GEMV_THREADS) gemv_q4k_persistent_kernel(PGemvArgs a)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    constexpr bool COH = false;
     const int wg_index = blockIdx.x;
-    NoSync sync;
     const float *const arg_x = a.x, *const arg_gain = a.gain;
     const uint8_t *const arg_W0 = a.seg[0].W, *const arg_W1 = a.seg[1].W, *const arg_W2 = a.seg[2].W;
     float *const arg_y0 = a.seg[0].y, *const arg_y1 = a.seg[1].y, *const arg_y2 = a.seg[2].y;

@@ -191,8 +191,8 @@ prima_status run_layer(const prima_dims &d, const prima_layer &L, int kv_cap, in
     return PRIMA_OK;
 }
 
-// before the first layer of a step: RoPE table, and the counters of the mat-vec, attention (and single-launch)
-// scratch zeroed, in one launch
+// before the first layer of a step: RoPE table, the counters of the mat-vec and attention scratch zeroed (and, where
+// asked, the error flag that prima_window_check reads), the attention's records set to "not written": one launch
 prima_status step_init(const prima_dims &d, void *ws, const WindowWs &w, int T, int n_past, const int *positions, bool with_sync, hipStream_t st)
 {
     // rows the longest sequence of the step holds after it: sets the attention's key ranges, hence the records it uses
